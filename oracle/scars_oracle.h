@@ -1,0 +1,92 @@
+/* CPU oracle for the skew-aware cached embedding-bag step -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, host-memory, synchronous statement of what each step of the hot path
+ * computes, written from the paper's description (Section III: a ranked skew table over all
+ * embeddings, the top entries kept on the device; Section II-B: a cached set C that removes
+ * communication but changes no value; Section II / Fig. 1: per-sample lookups in tables that
+ * live in main memory) and the plain definitions of a pooled sum and of an aggregated
+ * gradient step.  Floating point is accumulated in fp64 and rounded once.
+ *
+ * Nothing here is shared with the HIP library: no header, no helper, no constant.  Only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may load this library; the
+ * product path never does.
+ *
+ * Conventions: T tables with rows[t] rows each, global row id gid = row_base[t] + idx with
+ * row_base the exclusive prefix sum of rows; a batch is table-major CSR: offsets has T*B+1
+ * entries, bag g = t*B + b owns lookups [offsets[g], offsets[g+1]) and indices are
+ * table-local.  dtype 0 = fp32 rows, 1 = bf16 rows (uint16 storage).
+ *
+ * Every function returns 0, or ORA_ERR_INVALID_ARG / ORA_ERR_OFFSETS (nothing written), or
+ * ORA_ERR_INDEX_RANGE (outputs written as if each out-of-range lookup were absent).
+ */
+#ifndef SCARS_ORACLE_H
+#define SCARS_ORACLE_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORA_OK 0
+#define ORA_ERR_INVALID_ARG (-1)
+#define ORA_ERR_INDEX_RANGE (-5)
+#define ORA_ERR_OFFSETS (-6)
+
+/* worker threads for the loops over independent outputs (bags, unique rows); returns the count in use */
+int32_t ora_set_threads(int32_t n);
+
+/* Section IV fixes the cache by a byte budget (128 MB .. 1024 MB): k = min(N, floor(budget / row_bytes)). */
+int64_t ora_budget_rows(int64_t n_rows, int64_t row_bytes, int64_t budget_bytes);
+
+/* Skew table (Section III): counts[gid] += 1 for every lookup of the stream, duplicates included. */
+int32_t ora_histogram(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                      int64_t L, int64_t B, uint32_t* counts /* [N], accumulated into */);
+
+/* Ranked skew table -> top k (Section III): order all rows by count descending, lower gid first
+ * among equal counts; hot_gid[s] is the s-th row of that order, slot_of[gid] = s or -1. */
+int32_t ora_hot_set(int64_t N, const uint32_t* counts, int64_t k, int32_t* hot_gid /* [k] */,
+                    int32_t* slot_of /* [N] */);
+
+/* Lookup into the cached layer (Section II-B, Section IV): slot[i] = slot_of[gid_i]; positions of
+ * hits and of misses in ascending order; miss_gid[j] = gid of miss_pos[j]; n_out = {n_hit, n_miss}. */
+int32_t ora_remap(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                  int64_t L, int64_t B, const int32_t* slot_of, int32_t* slot /* [L] */,
+                  int32_t* hit_pos, int32_t* miss_pos, int32_t* miss_gid, int64_t* n_out /* [2] */);
+
+/* Pooled sum (Fig. 1 step 2 with sum pooling): out[g][:] = sum of the bag's rows read straight from
+ * the tables in main memory; no cache is involved. out is fp32 [T*B][D]. */
+int32_t ora_embedding_bag_fwd(int32_t T, const int64_t* rows, int32_t D, int32_t dtype,
+                              const void* const* tables, const int32_t* indices, const int32_t* offsets,
+                              int64_t L, int64_t B, float* out);
+
+/* Same sum, but a row whose slot_of is >= 0 is read from cache[slot] instead of its table
+ * (Section II-B: a cached row replaces the transfer, never the value). */
+int32_t ora_embedding_bag_fwd_cached(int32_t T, const int64_t* rows, int32_t D, int32_t dtype,
+                                     const void* const* tables, const int32_t* slot_of, const void* cache,
+                                     const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
+                                     float* out);
+
+/* Lookups ordered by (gid, position): sorted_gid, sorted_bag (bag of each lookup), seg_start[r] = first
+ * sorted position of the r-th distinct gid (seg_start[U] = number of valid lookups), unique_gid ascending. */
+int32_t ora_bwd_segments(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                         int64_t L, int64_t B, int32_t* sorted_gid /* [L] */, int32_t* sorted_bag /* [L] */,
+                         int32_t* seg_start /* [L+1] */, int32_t* unique_gid /* [L] */, int64_t* U);
+
+/* Aggregated gradient step on the embedding rows (the "backward" and "optimization" stages of
+ * Section IV): dW[r] = sum over lookups of r of grad_out[bag], then
+ *   optimizer 0 (SGD):     w -= lr * dW
+ *   optimizer 1 (Adagrad): G += dW^2 ; w -= lr * dW / (sqrt(G) + eps)      (element-wise, fp32 state)
+ * Only rows that are looked up change.  report = 0: tables (and state) are updated in place.
+ * report = 1: nothing is mutated; for the r-th unique gid (ascending) the fp64 values before the final
+ * rounding go to new_rows[r][:], new_state[r][:] and the summed gradient to grad_rows[r][:]
+ * (each [U][D] fp64, any may be NULL). */
+int32_t ora_embedding_bag_bwd_update(int32_t T, const int64_t* rows, int32_t D, int32_t dtype,
+                                     void* const* tables, float* const* state, int32_t optimizer,
+                                     const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
+                                     const float* grad_out, float lr, float eps, int32_t report,
+                                     double* new_rows, double* new_state, double* grad_rows);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
