@@ -1,0 +1,201 @@
+/* scars.h -- C ABI of the MI355X (gfx950) skew-aware cached embedding-bag library.
+ *
+ * The library implements, for ONE GPU's share of a recommendation-model batch, the embedding step
+ * of the communication-avoiding scheme of "Stochastic Communication Avoidance for Recommendation
+ * Systems" (arxiv 2411.01611): embedding tables live in (pinned) host memory (Section II, Fig. 1);
+ * a skew table over all embeddings is built and its top entries are kept on the device under a
+ * byte budget (Section III, Section IV); lookups that fall in that cached set C cost no transfer
+ * (Section II-B, eq. (6)), the rest are fetched over the host link; the backward pass aggregates
+ * the gradient per embedding and applies one optimizer step, hot rows on the device and cold rows
+ * in host memory (Section IV, discussion of Tables 1-4).
+ *
+ * Conventions
+ *  - T tables, rows[t] rows each, N = sum rows < 2^31.  Global row id  gid = row_base[t] + idx,
+ *    row_base = exclusive prefix sum of rows.  D = dim (same for all tables), row bytes
+ *    R = D * (4 for fp32 | 2 for bf16); R % 16 == 0 and R <= 1024.
+ *  - A batch is "jagged, table-major": offsets has T*B+1 int32 entries, offsets[0] = 0,
+ *    offsets[T*B] = L; bag g = t*B + b owns lookups [offsets[g], offsets[g+1]); indices[L] are
+ *    table-local int32 row ids.  One lookup per (sample, table) is the case offsets[g] = g.
+ *  - "DEVICE" pointers are HIP device memory, "HOST" pointers ordinary host memory, "PINNED" host
+ *    memory allocated with hipHostMalloc (device-mapped).  The caller owns every buffer; the
+ *    library allocates no device memory and frees nothing it is given.  Buffers must stay alive
+ *    until the stream work that uses them has finished.
+ *  - Every call returns SCARS_OK (0) or a negative error code and never throws.  Work is enqueued
+ *    on the caller's stream (a hipStream_t passed as void*; NULL = the default stream) and the
+ *    call returns without waiting unless stated.  Calls on one handle must be issued in stream
+ *    order; two calls on one handle must not run concurrently.
+ *  - Two errors are detected on the device and latched in the handle's status word, to be read by
+ *    scars_sync_status: SCARS_ERR_INDEX_RANGE (an index < 0 or >= rows[t]: that lookup is treated
+ *    as absent everywhere -- not counted, neither hit nor miss, adds nothing, updates nothing) and
+ *    SCARS_ERR_OFFSETS (offsets not starting at 0, not ending at L, or decreasing: outputs of that
+ *    call are unspecified, but every memory access stays inside the bound buffers).
+ */
+#ifndef SCARS_H
+#define SCARS_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SCARS_OK 0
+#define SCARS_ERR_INVALID_ARG (-1)
+#define SCARS_ERR_NOT_BUILT (-2)   /* remap / fwd / bwd / flush before a build_cache that selected a hot set */
+#define SCARS_ERR_WORKSPACE (-3)   /* bound buffers too small for the request, or nothing bound */
+#define SCARS_ERR_HIP (-4)         /* a HIP runtime call failed; text in scars_last_error */
+#define SCARS_ERR_INDEX_RANGE (-5) /* device-detected, latched */
+#define SCARS_ERR_OFFSETS (-6)     /* device-detected, latched */
+
+#define SCARS_DTYPE_F32 0
+#define SCARS_DTYPE_BF16 1
+#define SCARS_OPT_SGD 0
+#define SCARS_OPT_ADAGRAD 1
+
+#define SCARS_MAX_TABLES 1024
+#define SCARS_MAX_ROW_BYTES 1024
+
+typedef struct scars_handle scars_handle;
+
+/* Problem statement (Section II: tables in main memory; Section IV: optimizer stage). */
+typedef struct {
+    int32_t num_tables;        /* T, 1..SCARS_MAX_TABLES */
+    const int64_t* rows;       /* HOST [T], each >= 1, sum < 2^31 */
+    int32_t dim;               /* D */
+    int32_t dtype;             /* SCARS_DTYPE_*: storage type of rows; sums are always fp32 */
+    void* const* host_tables;  /* HOST [T] of PINNED pointers, table t row-major [rows[t]][D] */
+    int32_t optimizer;         /* SCARS_OPT_* */
+    float* const* host_state;  /* HOST [T] of PINNED fp32 [rows[t]][D] Adagrad accumulators; NULL for SGD */
+} scars_config;
+
+/* Sizes, in bytes, of the DEVICE buffers the caller must allocate (all 256-byte aligned). */
+typedef struct {
+    int64_t k;                  /* rows the budget buys: min(N, floor(budget_bytes / R)) */
+    int64_t counts_bytes;       /* uint32 [N]  skew table */
+    int64_t slot_of_bytes;      /* int32  [N]  gid -> cache slot or -1 */
+    int64_t hot_gid_bytes;      /* int32  [k]  slot -> gid, hottest first */
+    int64_t cache_bytes;        /* [k][D] rows in the tables' dtype */
+    int64_t state_cache_bytes;  /* fp32 [k][D] Adagrad accumulators of cached rows; 0 for SGD */
+    int64_t workspace_bytes;    /* scratch: descriptors, status word, selection and sort buffers,
+                                   staging area for rows fetched over the host link (max_L rows) */
+    /* per-batch outputs at max_L lookups / max_G bags */
+    int64_t per_lookup_bytes;   /* int32 [max_L]: slot, gid, loc, hit_pos, miss_pos, miss_gid, sorted_gid, sorted_bag, unique_gid */
+    int64_t seg_start_bytes;    /* int32 [max_L + 1] */
+    int64_t out_bytes;          /* fp32 [max_G][D] */
+} scars_sizes;
+
+typedef struct {
+    uint32_t* counts;     /* DEVICE */
+    int32_t* slot_of;     /* DEVICE */
+    int32_t* hot_gid;     /* DEVICE */
+    void* cache;          /* DEVICE */
+    float* state_cache;   /* DEVICE, NULL for SGD */
+    void* workspace;      /* DEVICE */
+    int64_t budget_bytes; /* the three arguments scars_query_sizes was called with */
+    int64_t max_L;
+    int64_t max_G;
+} scars_buffers;
+
+/* Outputs of scars_remap, all DEVICE, each int32 [L] unless noted. */
+typedef struct {
+    int32_t* slot;        /* slot_of[gid_i], -1 for a miss or an invalid lookup */
+    int32_t* gid;         /* global row id, -1 for an invalid lookup */
+    int32_t* loc;         /* where forward reads the row: slot for a hit, k + (rank in the miss list) for a miss, -1 invalid */
+    int32_t* hit_pos;     /* positions i with slot >= 0, ascending; first n_hit entries valid */
+    int32_t* miss_pos;    /* positions of misses, ascending; first n_miss entries valid */
+    int32_t* miss_gid;    /* gid of each miss, same order as miss_pos */
+    int32_t* n_hit_miss;  /* int32 [2] = {n_hit, n_miss} */
+} scars_remap_out;
+
+/* Optional outputs of scars_embedding_bag_bwd_update, all DEVICE. */
+typedef struct {
+    int32_t* sorted_gid;  /* [L] gids of valid lookups ordered by (gid, position); first n_valid entries */
+    int32_t* sorted_bag;  /* [L] bag of each sorted lookup */
+    int32_t* seg_start;   /* [L+1] first sorted position of each distinct gid; seg_start[U] = n_valid */
+    int32_t* unique_gid;  /* [L] distinct gids ascending; first U entries */
+    int32_t* n_unique;    /* int32 [2] = {U, n_valid} */
+} scars_bwd_out;
+
+/* Lifecycle.  scars_create copies the descriptor (not the tables); scars_destroy frees only the handle. */
+int32_t scars_create(const scars_config* cfg, scars_handle** out);
+int32_t scars_destroy(scars_handle* h);
+
+/* Sizes of the buffers to allocate for a byte budget (Section IV: 128 MB .. 1024 MB caches; the budget
+ * counts embedding weights only) and for batches of at most max_L lookups in max_G bags.  HOST only. */
+int32_t scars_query_sizes(const scars_handle* h, int64_t budget_bytes, int64_t max_L, int64_t max_G,
+                          scars_sizes* out);
+
+/* Hand the allocated buffers to the handle.  Copies the table descriptors into the workspace and clears
+ * the status word on `stream`; waits for that copy.  Forgets any previously built hot set. */
+int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* bufs, void* stream);
+
+/* Skew table + top-k + cache fill (Section III: "ranked skew table for all embeddings, selecting the top
+ * few embeddings for caching"; Section IV: fixed byte budget).
+ *   counts[gid] += 1 for each of the Lp lookups of the profile batch (d_indices/d_offsets DEVICE,
+ *   offsets has T*bags_per_table+1 entries);  then, unless accumulate == 2:
+ *   k = min(N, floor(budget_bytes / R)); the hot set is the first k rows in the order (count descending,
+ *   gid ascending); hot_gid[s] = s-th of them, slot_of[gid] = s or -1; cache[s] = the row's current value
+ *   read from its pinned host table (and its Adagrad accumulator into state_cache[s]).
+ *   accumulate: 0 = zero counts first; 1 = add to the existing counts, then select; 2 = add only.
+ * If the cache holds rows updated since the last flush, they are written back first.
+ * Lp = 0 with d_indices = NULL is allowed (select on the counts as they are).
+ * Errors: INVALID_ARG, WORKSPACE (budget/Lp/bags beyond what was bound), cumulative lookups >= 2^32. */
+int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t Lp,
+                          int64_t bags_per_table, int64_t budget_bytes, int32_t accumulate, void* stream);
+
+/* Rows actually cached by the last selecting scars_build_cache (HOST value, no device access); -1 if none. */
+int64_t scars_cache_rows(const scars_handle* h);
+
+/* Index -> cache-slot remap with ordered hit/miss compaction (the "lookup into the cached layer" that
+ * Section IV finds to bound the forward pass).  Fills every array of `out`. */
+int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                    const scars_remap_out* out, void* stream);
+
+/* Pooled gather-sum (Fig. 1 step 2 with sum pooling; Section II-B for the cached rows):
+ * d_out[g][:] = sum over the bag's lookups of the row, fp32, empty bag -> 0.  Hits are read from the HBM
+ * cache; misses are first fetched from the pinned host tables into the workspace's staging area (the
+ * only traffic on the host link) and read from there.  The sum runs in position order whatever the
+ * source, so the result does not depend on the budget.  `rm` must come from scars_remap on this batch. */
+int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L,
+                                int64_t B, const scars_remap_out* rm, float* d_out, void* stream);
+
+/* Backward sorted-segment scatter-add with the row update (Section IV: backward + optimization stages):
+ * lookups are ordered by (gid, position); each run of one gid sums d_grad_out[bag][:] (fp32 [T*B][D]) into
+ * dW, then  SGD: w -= lr*dW   |   Adagrad: G += dW^2, w -= lr*dW/(sqrt(G)+eps)  (element-wise).
+ * Cached rows are updated in the HBM cache (the host copy is stale until scars_flush_cache); other rows
+ * are updated in place in pinned host memory.  bf16 rows are rounded to nearest even on store.
+ * `out` may be NULL; otherwise the sorted segments are also written there. */
+int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
+                                       int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
+                                       float lr, float eps, const scars_bwd_out* out, void* stream);
+
+/* Write every cached row (and Adagrad accumulator) back to its pinned host table. */
+int32_t scars_flush_cache(scars_handle* h, void* stream);
+
+/* BLOCKS until `stream` is idle; returns the latched device-side error (then clears it) or SCARS_OK. */
+int32_t scars_sync_status(scars_handle* h, void* stream);
+
+/* Text of the last error on this handle (valid until the next call on it). */
+const char* scars_last_error(const scars_handle* h);
+
+/* Plumbing for callers without a HIP binding of their own: pinned host memory and a timed device-to-host /
+ * host-to-device copy.  scars_host_alloc uses hipHostMalloc (device-mapped, coherent). */
+int32_t scars_host_alloc(int64_t bytes, void** out);
+int32_t scars_host_free(void* p);
+int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind /* 1 = H2D, 2 = D2H, 3 = D2D */,
+                     void* stream);
+
+/* Per-kernel timing for measurement: when enabled, every kernel launch is bracketed by HIP events on the
+ * caller's stream.  scars_profile_read waits for the stream, then returns up to `cap` records
+ * (name pointer valid for the library's lifetime, launches, total milliseconds) and clears them. */
+typedef struct {
+    const char* name;
+    int64_t launches;
+    double total_ms;
+} scars_kernel_time;
+int32_t scars_profile_enable(scars_handle* h, int32_t on);
+int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out, int32_t cap, int32_t* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

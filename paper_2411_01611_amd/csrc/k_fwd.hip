@@ -1,0 +1,206 @@
+// embedding_bag_fwd: fetch of missed rows over the host link, then the pooled gather-sum.
+//
+// Fig. 1 of the paper: per-sample embeddings are looked up in main memory and sent to the GPU; Section II-B:
+// rows of the cached set C are already on the device.  Here the misses of a batch are first copied, row by
+// row, from the pinned host tables into a staging area in HBM (the only kernel that touches the host
+// link), after which every lookup -- hit or miss -- is a 16-byte-per-lane gather from HBM.  A row of R bytes
+// is read by R/16 lanes ("group"); a wave holds 64/(R/16) groups.  Short bags: one group per bag.  Long
+// bags: one wave per bag, its groups striding over the bag and combining by a fixed shuffle tree.  The
+// order of additions depends only on positions, never on where a row came from.
+#include "scars_dev.h"
+
+namespace scars {
+
+constexpr int kUnroll = 4;
+
+// ---- staging of missed rows ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
+                                                         const int32_t* __restrict__ n_hit_miss,
+                                                         const Meta* __restrict__ meta, uint4* __restrict__ staging,
+                                                         int chunks, int lpr, int64_t cap_rows) {
+    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
+    const int T = meta->num_tables;
+    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
+    __syncthreads();
+    const int64_t n = min((int64_t)n_hit_miss[1], cap_rows);
+    const int gpb = kBlock / lpr;
+    const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
+    const int64_t stride = (int64_t)gridDim.x * gpb;
+    for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
+        const uint4* src[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t j = j0 + u * stride;
+            src[u] = nullptr;
+            if (j < n) {
+                const int32_t gid = miss_gid[j];
+                const int t = upper_table(s_rbase, T, gid);
+                src[u] = (const uint4*)meta->table[t] + (int64_t)(gid - s_rbase[t]) * chunks;
+            }
+        }
+        for (int c = gl; c < chunks; c += lpr) {
+            uint4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (src[u]) v[u] = src[u][c];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (src[u]) staging[(j0 + u * stride) * chunks + c] = v[u];
+        }
+    }
+}
+
+// ---- pooled sum -------------------------------------------------------------------------------------
+template <int DTYPE> struct Chunk;   // one 16-byte piece of a row, as fp32 accumulators
+
+template <> struct Chunk<SCARS_DTYPE_F32> {
+    static constexpr int kVals = 4;
+    float v[4];
+    __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0.f; }
+    __device__ __forceinline__ void add(const uint4& r) {
+        v[0] += __uint_as_float(r.x); v[1] += __uint_as_float(r.y);
+        v[2] += __uint_as_float(r.z); v[3] += __uint_as_float(r.w);
+    }
+};
+
+template <> struct Chunk<SCARS_DTYPE_BF16> {
+    static constexpr int kVals = 8;
+    float v[8];
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    }
+    __device__ __forceinline__ void add(const uint4& r) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] += __uint_as_float(w[i] << 16);             // low half = even element
+            v[2 * i + 1] += __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+
+template <int DTYPE>
+__device__ __forceinline__ void accumulate_range(Chunk<DTYPE>& acc, int32_t first, int32_t last, int step,
+                                                 const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                 const uint4* __restrict__ staging, int32_t k, int chunks, int c,
+                                                 bool lane_on) {
+    for (int32_t i = first; i < last; i += step * kUnroll) {
+        uint4 row[kUnroll];
+        bool on[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int32_t ii = i + u * step;
+            on[u] = false;
+            if (ii < last) {
+                const int32_t l = loc[ii];
+                if (l >= 0 && lane_on) {
+                    const uint4* p = l < k ? cache + (int64_t)l * chunks : staging + (int64_t)(l - k) * chunks;
+                    row[u] = p[c];
+                    on[u] = true;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (on[u]) acc.add(row[u]);
+    }
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void store_chunk(const Chunk<DTYPE>& acc, float* __restrict__ out, int64_t g, int D, int c) {
+    float4* o = (float4*)(out + g * D + (int64_t)c * Chunk<DTYPE>::kVals);
+#pragma unroll
+    for (int q = 0; q < Chunk<DTYPE>::kVals / 4; ++q)
+        o[q] = make_float4(acc.v[4 * q], acc.v[4 * q + 1], acc.v[4 * q + 2], acc.v[4 * q + 3]);
+}
+
+// one group of LPR lanes per bag
+template <int DTYPE, int LPR>
+__global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict__ off, int64_t G, int32_t L,
+                                                       const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                       const uint4* __restrict__ staging, int32_t k, int chunks, int D,
+                                                       float* __restrict__ out) {
+    const int64_t g = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
+    const int c = threadIdx.x % LPR;
+    if (g >= G) return;
+    const int32_t a = min(max(off[g], 0), L);
+    const int32_t b = min(max(off[g + 1], a), L);
+    Chunk<DTYPE> acc;
+    acc.zero();
+    accumulate_range<DTYPE>(acc, a, b, 1, loc, cache, staging, k, chunks, c, c < chunks);
+    if (c < chunks) store_chunk<DTYPE>(acc, out, g, D, c);
+}
+
+// one wave per bag; its 64/LPR groups take every (64/LPR)-th lookup and combine by a shuffle tree
+template <int DTYPE, int LPR>
+__global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict__ off, int64_t G, int32_t L,
+                                                      const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                      const uint4* __restrict__ staging, int32_t k, int chunks, int D,
+                                                      float* __restrict__ out) {
+    constexpr int NG = kWave / LPR;
+    const int64_t g = (int64_t)blockIdx.x * (kBlock / kWave) + wave_id();
+    if (g >= G) return;
+    const int q = lane_id() / LPR, c = lane_id() % LPR;
+    const int32_t a = min(max(off[g], 0), L);
+    const int32_t b = min(max(off[g + 1], a), L);
+    Chunk<DTYPE> acc;
+    acc.zero();
+    accumulate_range<DTYPE>(acc, a + q, b, NG, loc, cache, staging, k, chunks, c, c < chunks);
+#pragma unroll
+    for (int d = kWave / 2; d >= LPR; d >>= 1) {
+#pragma unroll
+        for (int i = 0; i < Chunk<DTYPE>::kVals; ++i) acc.v[i] += __shfl_down(acc.v[i], d, 64);
+    }
+    if (q == 0 && c < chunks) store_chunk<DTYPE>(acc, out, g, D, c);
+}
+
+template <int DTYPE, int LPR>
+static void launch_pool_t(hipStream_t s, bool wave_mode, const int32_t* off, int64_t G, int64_t L, const int32_t* loc,
+                          const void* cache, const void* staging, int64_t k, int chunks, int D, float* out) {
+    if (wave_mode) {
+        hipLaunchKernelGGL((k_pool_wave<DTYPE, LPR>), dim3((unsigned)div_up(G, kBlock / kWave)), dim3(kBlock), 0, s, off,
+                           G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
+    } else {
+        hipLaunchKernelGGL((k_pool_group<DTYPE, LPR>), dim3((unsigned)div_up(G * LPR, kBlock)), dim3(kBlock), 0, s, off,
+                           G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
+    }
+}
+
+template <int DTYPE>
+static void launch_pool_d(int lpr, hipStream_t s, bool wave_mode, const int32_t* off, int64_t G, int64_t L,
+                          const int32_t* loc, const void* cache, const void* staging, int64_t k, int chunks, int D,
+                          float* out) {
+    switch (lpr) {
+#define SCARS_CASE(N) case N: launch_pool_t<DTYPE, N>(s, wave_mode, off, G, L, loc, cache, staging, k, chunks, D, out); break;
+        SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
+#undef SCARS_CASE
+    }
+}
+
+hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                      const scars_remap_out* rm, float* out) {
+    const int chunks = h->R / 16;
+    const int lpr = std::min(64, next_pow2_host(chunks));
+    const int64_t G = (int64_t)h->T * B;
+    if (L > 0 && h->k < h->N) {   // with every row cached there can be no miss
+        Timed t(h, s, "stage_misses");
+        const int gpb = kBlock / lpr;
+        const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), 256 * 8));
+        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, rm->miss_gid, rm->n_hit_miss, h->ws.meta,
+                           (uint4*)h->ws.staging, chunks, lpr, h->buf.max_L);
+    }
+    if (G > 0) {
+        const bool wave_mode = lpr < 64 && L >= G * 2 * (kWave / lpr);
+        Timed t(h, s, wave_mode ? "pool_wave" : "pool_group");
+        if (h->dtype == SCARS_DTYPE_F32)
+            launch_pool_d<SCARS_DTYPE_F32>(lpr, s, wave_mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
+                                           chunks, h->D, out);
+        else
+            launch_pool_d<SCARS_DTYPE_BF16>(lpr, s, wave_mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
+                                            chunks, h->D, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace scars

@@ -1,0 +1,156 @@
+// remap: index -> cache slot, with ordered (stable) compaction of hit and miss positions.
+//
+// Section II-B caches a set C of embeddings on the device; Section IV observes that the lookup into that
+// cached layer bounds the forward pass.  Here one pass maps every lookup to gid = row_base[t] + idx and
+// slot = slot_of[gid] (a dense int32 map, one random 4-byte read), and a three-kernel ordered compaction
+// (per-tile counts -> scan -> write) lists hits and misses in ascending position, so that the lists are
+// unique and comparable bit for bit.  loc[i] tells the forward kernel where to read the row: the cache slot
+// for a hit, k + rank-in-miss-list (a row of the staging area) for a miss.
+#include "scars_dev.h"
+
+namespace scars {
+
+constexpr int kPerWave = kScanTile / (kBlock / kWave);   // 512 consecutive lookups per wave
+constexpr int kRoundsR = kPerWave / kWave;               // 8 rounds of 64
+
+__global__ __launch_bounds__(kBlock) void k_remap_probe(const int32_t* __restrict__ idx, const int32_t* __restrict__ off,
+                                                        int64_t L, int64_t B, const Meta* __restrict__ meta,
+                                                        const int32_t* __restrict__ slot_of, int32_t* __restrict__ slot,
+                                                        int32_t* __restrict__ gid, uint32_t* __restrict__ blk_hit,
+                                                        uint32_t* __restrict__ blk_miss, int32_t* __restrict__ tstart_out,
+                                                        int32_t* __restrict__ status) {
+    __shared__ int32_t s_tstart[SCARS_MAX_TABLES + 1];
+    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
+    __shared__ uint32_t s_hit[4], s_miss[4];
+    const int T = meta->num_tables;
+    for (int t = threadIdx.x; t <= T; t += kBlock) {
+        const int32_t v = off[(int64_t)t * B];
+        s_tstart[t] = v;
+        s_rbase[t] = meta->row_base[t];
+        if (blockIdx.x == 0) tstart_out[t] = v;
+    }
+    __syncthreads();
+    const int64_t G = (int64_t)T * B;
+    const int64_t nthreads = (int64_t)gridDim.x * kBlock;
+    const int64_t gt = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (int64_t g = gt; g < G; g += nthreads)
+        if (off[g + 1] < off[g]) latch_error(status, SCARS_ERR_OFFSETS);
+    if (gt == 0 && (off[0] != 0 || (int64_t)off[G] != L)) latch_error(status, SCARS_ERR_OFFSETS);
+
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
+    uint32_t nh = 0, nm = 0;
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t i = base + r * kWave + lane_id();
+        bool hit = false, miss = false;
+        if (i < L) {
+            const int t = upper_table(s_tstart, T, (int32_t)i);
+            const int32_t row = idx[i];
+            const int32_t nrows = s_rbase[t + 1] - s_rbase[t];
+            int32_t g = -1, s = -1;
+            if (row < 0 || row >= nrows) {
+                latch_error(status, SCARS_ERR_INDEX_RANGE);
+            } else {
+                g = s_rbase[t] + row;
+                s = slot_of[g];
+                hit = s >= 0;
+                miss = !hit;
+            }
+            slot[i] = s;
+            gid[i] = g;
+        }
+        nh += (uint32_t)__popcll(ballot64(hit));
+        nm += (uint32_t)__popcll(ballot64(miss));
+    }
+    if (lane_id() == 0) { s_hit[wave_id()] = nh; s_miss[wave_id()] = nm; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk_hit[blockIdx.x] = s_hit[0] + s_hit[1] + s_hit[2] + s_hit[3];
+        blk_miss[blockIdx.x] = s_miss[0] + s_miss[1] + s_miss[2] + s_miss[3];
+    }
+}
+
+// single workgroup: exclusive scan of the per-tile counts; totals to n_hit_miss[2] (and a[n], b[n])
+__global__ __launch_bounds__(kBlock) void k_remap_scan(uint32_t* __restrict__ a, uint32_t* __restrict__ b, int n,
+                                                       int32_t* __restrict__ n_hit_miss) {
+    __shared__ uint32_t s_scan[8];
+    uint32_t ca = 0, cb = 0;
+    for (int base = 0; base < n; base += kBlock) {
+        const int i = base + threadIdx.x;
+        uint32_t va = i < n ? a[i] : 0u, vb = i < n ? b[i] : 0u, ta, tb;
+        const uint32_t ea = block_exclusive_scan(va, s_scan, &ta);
+        const uint32_t eb = block_exclusive_scan(vb, s_scan, &tb);
+        if (i < n) { a[i] = ca + ea; b[i] = cb + eb; }
+        ca += ta; cb += tb;
+    }
+    if (threadIdx.x == 0) {
+        a[n] = ca; b[n] = cb;
+        n_hit_miss[0] = (int32_t)ca;
+        n_hit_miss[1] = (int32_t)cb;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t* __restrict__ slot,
+                                                        const int32_t* __restrict__ gid, const uint32_t* __restrict__ blk_hit,
+                                                        const uint32_t* __restrict__ blk_miss, int32_t k,
+                                                        int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
+                                                        int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid) {
+    __shared__ uint32_t s_hit[4], s_miss[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
+    int32_t s[kRoundsR], g[kRoundsR];
+    uint32_t nh = 0, nm = 0;
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t i = base + r * kWave + lane_id();
+        s[r] = i < L ? slot[i] : -1;
+        g[r] = i < L ? gid[i] : -1;
+        nh += (uint32_t)__popcll(ballot64(s[r] >= 0));
+        nm += (uint32_t)__popcll(ballot64(s[r] < 0 && g[r] >= 0));
+    }
+    if (lane_id() == 0) { s_hit[wave_id()] = nh; s_miss[wave_id()] = nm; }
+    __syncthreads();
+    uint32_t hb = blk_hit[blockIdx.x], mb = blk_miss[blockIdx.x];
+    for (int w = 0; w < wave_id(); ++w) { hb += s_hit[w]; mb += s_miss[w]; }
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t i = base + r * kWave + lane_id();
+        const bool hit = s[r] >= 0, miss = s[r] < 0 && g[r] >= 0;
+        const uint64_t mh = ballot64(hit), mm = ballot64(miss);
+        if (hit) {
+            hit_pos[hb + rank_below(mh)] = (int32_t)i;
+            loc[i] = s[r];
+        } else if (miss) {
+            const uint32_t j = mb + rank_below(mm);
+            miss_pos[j] = (int32_t)i;
+            miss_gid[j] = g[r];
+            loc[i] = k + (int32_t)j;
+        } else if (i < L) {
+            loc[i] = -1;
+        }
+        hb += (uint32_t)__popcll(mh);
+        mb += (uint32_t)__popcll(mm);
+    }
+}
+
+hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
+                        const scars_remap_out* out) {
+    Workspace& ws = h->ws;
+    const int nb = (int)std::max<int64_t>(1, div_up(L, kScanTile));
+    {
+        Timed t(h, s, "remap_probe");
+        hipLaunchKernelGGL(k_remap_probe, dim3(nb), dim3(kBlock), 0, s, idx, off, L, B, ws.meta, h->buf.slot_of,
+                           out->slot, out->gid, ws.blk_hit, ws.blk_miss, ws.tstart, ws.status);
+    }
+    {
+        Timed t(h, s, "remap_scan");
+        hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hit_miss);
+    }
+    {
+        Timed t(h, s, "remap_write");
+        hipLaunchKernelGGL(k_remap_write, dim3(nb), dim3(kBlock), 0, s, L, out->slot, out->gid, ws.blk_hit, ws.blk_miss,
+                           (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos, out->miss_gid);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace scars

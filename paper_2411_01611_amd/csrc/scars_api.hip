@@ -1,0 +1,341 @@
+// C ABI of libscars: handle lifecycle, buffer binding, argument checks, and the four entry points.
+// Every device step is a kernel in the k_*.hip files; this file only validates and enqueues.
+#include <cstdio>
+#include <cstring>
+
+#include "scars_internal.h"
+
+using namespace scars;
+
+namespace scars {
+
+int32_t fail(scars_handle* h, int32_t code, const std::string& msg) {
+    if (h) h->err = msg;
+    return code;
+}
+
+int32_t hip_fail(scars_handle* h, hipError_t e, const char* what) {
+    return fail(h, SCARS_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+Timed::Timed(scars_handle* h_, hipStream_t s_, const char* n) : h(h_), s(s_), name(n) {
+    if (h && h->profile) {
+        if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+            (void)hipEventRecord(a, s);
+        } else {
+            a = b = nullptr;
+        }
+    }
+}
+
+Timed::~Timed() {
+    if (a && b) {
+        (void)hipEventRecord(b, s);
+        h->timer.pending.push_back({name, {a, b}});
+    }
+}
+
+// Lay the scratch arrays out in the caller's workspace blob.  With base == nullptr only sizes are computed.
+Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L, int64_t max_G) {
+    (void)max_G;
+    Workspace w{};
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) -> void* {
+        void* p = base ? (char*)base + off : nullptr;
+        off += align_up(std::max<int64_t>(bytes, 16), 256);
+        return p;
+    };
+    const int64_t nbN = div_up(h->N, kScanTile), nbL = std::max<int64_t>(1, div_up(max_L, kScanTile));
+    const int64_t nbS = std::max<int64_t>(1, div_up(std::max(max_L, k_cap), kSortTile));
+    w.meta = (Meta*)take(sizeof(Meta));
+    w.status = (int32_t*)take(16);
+    w.sel_hist = (uint32_t*)take(3 * kSelBins * 4);
+    w.sel_state = (uint32_t*)take(32);
+    w.blk_gt = (uint32_t*)take((nbN + 1) * 4);
+    w.blk_eq = (uint32_t*)take((nbN + 1) * 4);
+    for (int i = 0; i < 2; ++i) {
+        w.win_key[i] = (uint32_t*)take(k_cap * 4);
+        w.win_gid[i] = (int32_t*)take(k_cap * 4);
+    }
+    w.tstart = (int32_t*)take((SCARS_MAX_TABLES + 1) * 4);
+    w.blk_hit = (uint32_t*)take((nbL + 1) * 4);
+    w.blk_miss = (uint32_t*)take((nbL + 1) * 4);
+    w.sort_hist = (uint32_t*)take(256 * nbS * 4);
+    w.sort_tot = (uint32_t*)take(256 * 4);
+    for (int i = 0; i < 2; ++i) {
+        w.key_buf[i] = (uint32_t*)take(max_L * 4);
+        w.val_buf[i] = (uint32_t*)take(max_L * 4);
+    }
+    w.seg_start = (int32_t*)take((max_L + 1) * 4);
+    w.unique_gid = (int32_t*)take(max_L * 4);
+    w.n_unique = (int32_t*)take(16);
+    w.partial = (double*)take(div_up(std::max<int64_t>(max_L, 1), kSegChunk) * 2 * h->D * 8);
+    w.staging = take(max_L * h->R);
+    w.total_bytes = off;
+    return w;
+}
+
+static int64_t budget_rows(const scars_handle* h, int64_t budget_bytes) {
+    if (budget_bytes <= 0) return 0;
+    return std::min<int64_t>(h->N, budget_bytes / h->R);
+}
+
+}  // namespace scars
+
+extern "C" {
+
+int32_t scars_create(const scars_config* cfg, scars_handle** out) {
+    if (!cfg || !out) return SCARS_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (cfg->num_tables < 1 || cfg->num_tables > SCARS_MAX_TABLES || !cfg->rows || !cfg->host_tables || cfg->dim < 1)
+        return SCARS_ERR_INVALID_ARG;
+    if (cfg->dtype != SCARS_DTYPE_F32 && cfg->dtype != SCARS_DTYPE_BF16) return SCARS_ERR_INVALID_ARG;
+    if (cfg->optimizer != SCARS_OPT_SGD && cfg->optimizer != SCARS_OPT_ADAGRAD) return SCARS_ERR_INVALID_ARG;
+    if (cfg->optimizer == SCARS_OPT_ADAGRAD && !cfg->host_state) return SCARS_ERR_INVALID_ARG;
+    const int64_t R = (int64_t)cfg->dim * (cfg->dtype == SCARS_DTYPE_F32 ? 4 : 2);
+    if (R % 16 != 0 || R > SCARS_MAX_ROW_BYTES) return SCARS_ERR_INVALID_ARG;
+    scars_handle* h = new (std::nothrow) scars_handle();
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    h->T = cfg->num_tables; h->D = cfg->dim; h->dtype = cfg->dtype; h->optimizer = cfg->optimizer; h->R = (int32_t)R;
+    h->row_base.push_back(0);
+    for (int t = 0; t < h->T; ++t) {
+        if (cfg->rows[t] < 1 || !cfg->host_tables[t] ||
+            (cfg->optimizer == SCARS_OPT_ADAGRAD && !cfg->host_state[t])) { delete h; return SCARS_ERR_INVALID_ARG; }
+        h->rows.push_back(cfg->rows[t]);
+        h->N += cfg->rows[t];
+        if (h->N >= ((int64_t)1 << 31)) { delete h; return SCARS_ERR_INVALID_ARG; }
+        h->row_base.push_back(h->N);
+        h->host_tables.push_back(cfg->host_tables[t]);
+        h->host_state.push_back(cfg->optimizer == SCARS_OPT_ADAGRAD ? cfg->host_state[t] : nullptr);
+    }
+    *out = h;
+    return SCARS_OK;
+}
+
+int32_t scars_destroy(scars_handle* h) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.second.first); (void)hipEventDestroy(p.second.second); }
+    delete h;
+    return SCARS_OK;
+}
+
+int32_t scars_query_sizes(const scars_handle* h, int64_t budget_bytes, int64_t max_L, int64_t max_G, scars_sizes* out) {
+    if (!h || !out || budget_bytes < 0 || max_L < 0 || max_G < 0) return SCARS_ERR_INVALID_ARG;
+    const int64_t k = budget_rows(h, budget_bytes);
+    if (k + max_L >= ((int64_t)1 << 31) || max_G >= ((int64_t)1 << 31)) return SCARS_ERR_INVALID_ARG;
+    auto a = [](int64_t b) { return align_up(std::max<int64_t>(b, 16), 256); };
+    out->k = k;
+    out->counts_bytes = a(h->N * 4);
+    out->slot_of_bytes = a(h->N * 4);
+    out->hot_gid_bytes = a(k * 4);
+    out->cache_bytes = a(k * h->R);
+    out->state_cache_bytes = h->optimizer == SCARS_OPT_ADAGRAD ? a(k * (int64_t)h->D * 4) : 0;
+    out->workspace_bytes = carve(h, nullptr, k, max_L, max_G).total_bytes;
+    out->per_lookup_bytes = a(max_L * 4);
+    out->seg_start_bytes = a((max_L + 1) * 4);
+    out->out_bytes = a(max_G * (int64_t)h->D * 4);
+    return SCARS_OK;
+}
+
+int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!b || !b->counts || !b->slot_of || !b->workspace || b->budget_bytes < 0 || b->max_L < 0 || b->max_G < 0)
+        return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: null buffer or negative size");
+    const int64_t k = budget_rows(h, b->budget_bytes);
+    if (k + b->max_L >= ((int64_t)1 << 31)) return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: k + max_L >= 2^31");
+    if (k > 0 && (!b->hot_gid || !b->cache || (h->optimizer == SCARS_OPT_ADAGRAD && !b->state_cache)))
+        return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: cache buffers missing");
+    h->buf = *b;
+    h->k_cap = k;
+    h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);
+    h->bound = true; h->built = false; h->dirty = false; h->k = -1; h->profiled = 0;
+    Meta* m = new Meta();
+    std::memset(m, 0, sizeof(Meta));
+    for (int t = 0; t < h->T; ++t) {
+        m->table[t] = h->host_tables[t];
+        m->state[t] = h->host_state[t];
+        m->row_base[t] = (int32_t)h->row_base[t];
+    }
+    m->row_base[h->T] = (int32_t)h->row_base[h->T];
+    m->num_tables = h->T;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(h->ws.meta, m, sizeof(Meta), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = launch_fill_u32(h, s, (uint32_t*)h->ws.status, 4, 0u);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    delete m;
+    if (e != hipSuccess) { h->bound = false; return hip_fail(h, e, "bind_buffers"); }
+    return SCARS_OK;
+}
+
+static int32_t check_batch(scars_handle* h, const int32_t* idx, const int32_t* off, int64_t L, int64_t B, const char* who) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, std::string(who) + ": no buffers bound");
+    if (!off || L < 0 || B < 0 || (L > 0 && !idx)) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": null or negative argument");
+    if (L > h->buf.max_L || (int64_t)h->T * B > h->buf.max_G)
+        return fail(h, SCARS_ERR_WORKSPACE, std::string(who) + ": batch larger than the bound max_L / max_G");
+    return SCARS_OK;
+}
+
+int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t Lp,
+                          int64_t bags_per_table, int64_t budget_bytes, int32_t accumulate, void* stream) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "build_cache: no buffers bound");
+    if (accumulate < 0 || accumulate > 2 || budget_bytes < 0 || Lp < 0 || bags_per_table < 0)
+        return fail(h, SCARS_ERR_INVALID_ARG, "build_cache: bad argument");
+    const bool have_stream = Lp > 0 || d_offsets != nullptr;
+    if (have_stream) {
+        int32_t rc = check_batch(h, d_indices, d_offsets, Lp, bags_per_table, "build_cache");
+        if (rc) return rc;
+    }
+    const int64_t k = budget_rows(h, budget_bytes);
+    if (accumulate != 2 && k > h->k_cap) return fail(h, SCARS_ERR_WORKSPACE, "build_cache: budget above the bound budget");
+    const uint64_t before = accumulate == 0 ? 0 : h->profiled;
+    if (before + (uint64_t)Lp >= ((uint64_t)1 << 32))
+        return fail(h, SCARS_ERR_INVALID_ARG, "build_cache: cumulative lookups >= 2^32 would overflow the uint32 counts");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (accumulate != 2 && h->built && h->dirty) {   // keep updated hot rows before they lose their slots
+        e = launch_flush(h, s);
+        if (e != hipSuccess) return hip_fail(h, e, "build_cache(flush)");
+        h->dirty = false;
+    }
+    if (accumulate == 0) {
+        e = launch_fill_u32(h, s, h->buf.counts, h->N, 0u);
+        if (e != hipSuccess) return hip_fail(h, e, "build_cache(zero counts)");
+    }
+    if (have_stream) {
+        e = launch_histogram(h, s, d_indices, d_offsets, Lp, bags_per_table);
+        if (e != hipSuccess) return hip_fail(h, e, "build_cache(histogram)");
+    }
+    h->profiled = before + (uint64_t)Lp;
+    if (accumulate == 2) return SCARS_OK;
+    h->built = false;
+    e = launch_select_and_fill(h, s, k);
+    if (e != hipSuccess) return hip_fail(h, e, "build_cache(select)");
+    h->built = true;
+    return SCARS_OK;
+}
+
+int64_t scars_cache_rows(const scars_handle* h) { return (h && h->built) ? h->k : -1; }
+
+static int32_t check_remap_out(scars_handle* h, const scars_remap_out* o, int64_t L, const char* who) {
+    if (!o || !o->n_hit_miss || (L > 0 && (!o->slot || !o->gid || !o->loc || !o->hit_pos || !o->miss_pos || !o->miss_gid)))
+        return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": remap_out has a null array");
+    return SCARS_OK;
+}
+
+int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                    const scars_remap_out* out, void* stream) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "remap");
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "remap: build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, out, L, "remap"))) return rc;
+    hipError_t e = launch_remap(h, (hipStream_t)stream, d_indices, d_offsets, L, B, out);
+    if (e != hipSuccess) return hip_fail(h, e, "remap");
+    return SCARS_OK;
+}
+
+int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L,
+                                int64_t B, const scars_remap_out* rm, float* d_out, void* stream) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "embedding_bag_fwd");
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "embedding_bag_fwd: build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, rm, L, "embedding_bag_fwd"))) return rc;
+    if (!d_out && (int64_t)h->T * B > 0) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_fwd: null output");
+    hipError_t e = launch_fwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_out);
+    if (e != hipSuccess) return hip_fail(h, e, "embedding_bag_fwd");
+    return SCARS_OK;
+}
+
+int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
+                                       int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
+                                       float lr, float eps, const scars_bwd_out* out, void* stream) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "embedding_bag_bwd_update");
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "embedding_bag_bwd_update: build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, rm, L, "embedding_bag_bwd_update"))) return rc;
+    if (!d_grad_out && L > 0) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: null gradient");
+    if (out && (!out->n_unique || !out->seg_start || (L > 0 && (!out->sorted_gid || !out->sorted_bag || !out->unique_gid))))
+        return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: bwd_out has a null array");
+    hipError_t e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out);
+    if (e != hipSuccess) return hip_fail(h, e, "embedding_bag_bwd_update");
+    if (L > 0) h->dirty = true;
+    return SCARS_OK;
+}
+
+int32_t scars_flush_cache(scars_handle* h, void* stream) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "flush_cache: no buffers bound");
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "flush_cache: nothing cached");
+    hipError_t e = launch_flush(h, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(h, e, "flush_cache");
+    h->dirty = false;
+    return SCARS_OK;
+}
+
+int32_t scars_sync_status(scars_handle* h, void* stream) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "sync_status: no buffers bound");
+    hipStream_t s = (hipStream_t)stream;
+    int32_t st[4] = {0, 0, 0, 0};
+    hipError_t e = hipMemcpyAsync(st, h->ws.status, sizeof(st), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(h, e, "sync_status");
+    if (st[0] != 0) {
+        e = launch_fill_u32(h, s, (uint32_t*)h->ws.status, 4, 0u);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return hip_fail(h, e, "sync_status(clear)");
+        return fail(h, st[0], st[0] == SCARS_ERR_INDEX_RANGE ? "device: index out of range" : "device: bad offsets");
+    }
+    return SCARS_OK;
+}
+
+const char* scars_last_error(const scars_handle* h) { return h ? h->err.c_str() : "null handle"; }
+
+int32_t scars_host_alloc(int64_t bytes, void** out) {
+    if (!out || bytes <= 0) return SCARS_ERR_INVALID_ARG;
+    *out = nullptr;
+    hipError_t e = hipHostMalloc(out, (size_t)bytes, hipHostMallocDefault);
+    return e == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
+int32_t scars_host_free(void* p) {
+    if (!p) return SCARS_ERR_INVALID_ARG;
+    return hipHostFree(p) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
+int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind, void* stream) {
+    if (!dst || !src || bytes < 0 || kind < 1 || kind > 3) return SCARS_ERR_INVALID_ARG;
+    const hipMemcpyKind k = kind == 1 ? hipMemcpyHostToDevice : (kind == 2 ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice);
+    return hipMemcpyAsync(dst, src, (size_t)bytes, k, (hipStream_t)stream) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
+int32_t scars_profile_enable(scars_handle* h, int32_t on) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    h->profile = on != 0;
+    return SCARS_OK;
+}
+
+int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out, int32_t cap, int32_t* n_out) {
+    if (!h || !n_out || cap < 0 || (cap > 0 && !out)) return SCARS_ERR_INVALID_ARG;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(h, e, "profile_read");
+    std::vector<scars_kernel_time> acc;
+    for (auto& p : h->timer.pending) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, p.second.first, p.second.second);
+        (void)hipEventDestroy(p.second.first);
+        (void)hipEventDestroy(p.second.second);
+        bool found = false;
+        for (auto& r : acc)
+            if (std::strcmp(r.name, p.first) == 0) { r.launches += 1; r.total_ms += ms; found = true; break; }
+        if (!found) acc.push_back({p.first, 1, (double)ms});
+    }
+    h->timer.pending.clear();
+    const int32_t n = (int32_t)std::min<size_t>(acc.size(), (size_t)cap);
+    for (int32_t i = 0; i < n; ++i) out[i] = acc[i];
+    *n_out = n;
+    return SCARS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Device-side helpers for gfx950 (wave64): ballots, scans, table search, bf16 conversion, status latch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scars_internal.h"
+
+namespace scars {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+// number of set bits of m strictly below this lane
+__device__ __forceinline__ int rank_below(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
+// inclusive scan of one value per lane across the wave
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+    const int l = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(v, d, 64);
+        if (l >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan over the 256 threads of a block; *total receives the block sum. `s` is LDS scratch [8].
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s, uint32_t* total) {
+    uint32_t inc = wave_inclusive_scan(v);
+    if (lane_id() == 63) s[wave_id()] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / kWave; ++w) {
+        uint32_t t = s[w];
+        if (w < wave_id()) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+__device__ __forceinline__ void latch_error(int32_t* status, int32_t code) {
+    // status[0] holds the first error seen (0 = none); codes are negative
+    atomicCAS(status, 0, code);
+}
+
+// Largest t in [0, T) with a[t] <= x, for a non-decreasing a[0..T]; clamped so the result is always valid.
+__device__ __forceinline__ int upper_table(const int32_t* a, int T, int32_t x) {
+    int lo = 0, hi = T;  // answer in [lo, hi)
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (a[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t next_pow2_u32(uint32_t x) {
+    return x <= 1 ? 1u : 1u << (32 - __builtin_clz(x - 1));
+}
+
+}  // namespace scars
+
+namespace scars {
+inline int next_pow2_host(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+}  // namespace scars

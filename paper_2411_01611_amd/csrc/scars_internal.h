@@ -1,0 +1,128 @@
+// Internal host-side declarations shared by the translation units of libscars (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "scars.h"
+
+namespace scars {
+
+constexpr int kBlock = 256;          // threads per workgroup everywhere: 4 wave64
+constexpr int kWave = 64;
+constexpr int kScanTile = 2048;      // items per workgroup in the ordered-compaction kernels
+constexpr int kSortTile = 4096;      // items per workgroup in the radix-sort kernels
+constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
+constexpr int kSegChunk = 32;        // sorted lookups per group in the segment-reduce kernel
+
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline int64_t div_up(int64_t x, int64_t a) { return (x + a - 1) / a; }
+
+// Device-resident table descriptors (lives at the start of the workspace).
+struct Meta {
+    const void* table[SCARS_MAX_TABLES];   // pinned host row storage
+    float* state[SCARS_MAX_TABLES];        // pinned host Adagrad accumulators (or null)
+    int32_t row_base[SCARS_MAX_TABLES + 1];
+    int32_t num_tables;
+    int32_t pad[3];
+};
+
+// Everything carved out of the caller's workspace blob.
+struct Workspace {
+    Meta* meta;
+    int32_t* status;          // [4] latched device-side error word
+    // selection (build_cache)
+    uint32_t* sel_hist;       // [3][kSelBins]
+    uint32_t* sel_state;      // [8]: prefix, k_rem, (pad)
+    uint32_t* blk_gt;         // [nbN + 1]
+    uint32_t* blk_eq;         // [nbN + 1]
+    uint32_t* win_key[2];     // [k] double buffer
+    int32_t* win_gid[2];      // [k]
+    // per batch
+    int32_t* tstart;          // [T + 1] first lookup of each table (copied from offsets)
+    uint32_t* blk_hit;        // [nbL + 1]
+    uint32_t* blk_miss;       // [nbL + 1]
+    uint32_t* sort_hist;      // [256 * nbS] digit-major per-block histogram, nbS for max(max_L, k)
+    uint32_t* sort_tot;       // [256]
+    uint32_t* key_buf[2];     // [max_L]
+    uint32_t* val_buf[2];     // [max_L]
+    int32_t* seg_start;       // [max_L + 1] (used when the caller passes no bwd_out)
+    int32_t* unique_gid;      // [max_L]
+    int32_t* n_unique;        // [2]
+    double* partial;          // [nchunks][2][D] open-run partial sums (fp64) of the segment reduce
+    void* staging;            // [max_L][R] rows fetched over the host link
+    int64_t total_bytes;
+};
+
+struct KernelTimer {
+    std::vector<std::pair<const char*, std::pair<hipEvent_t, hipEvent_t>>> pending;
+};
+
+}  // namespace scars
+
+struct scars_handle {
+    // descriptor
+    int32_t T = 0, D = 0, dtype = 0, optimizer = 0;
+    int64_t N = 0;
+    int32_t R = 0;                       // row bytes
+    std::vector<int64_t> rows;
+    std::vector<int64_t> row_base;       // [T+1]
+    std::vector<void*> host_tables;
+    std::vector<float*> host_state;
+    // bound buffers
+    bool bound = false;
+    scars_buffers buf{};
+    int64_t k_cap = 0;
+    scars::Workspace ws{};
+    // state
+    bool built = false;
+    bool dirty = false;                  // cache holds rows newer than the host tables
+    int64_t k = -1;
+    uint64_t profiled = 0;               // cumulative lookups histogrammed
+    std::string err;
+    // per-kernel timing
+    bool profile = false;
+    scars::KernelTimer timer;
+};
+
+namespace scars {
+
+int32_t fail(scars_handle* h, int32_t code, const std::string& msg);
+int32_t hip_fail(scars_handle* h, hipError_t e, const char* what);
+
+// RAII bracket that records a start/stop event pair around one kernel launch when profiling is on.
+struct Timed {
+    scars_handle* h;
+    hipStream_t s;
+    const char* name;
+    hipEvent_t a = nullptr, b = nullptr;
+    Timed(scars_handle* h_, hipStream_t s_, const char* n);
+    ~Timed();
+};
+
+Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L, int64_t max_G);
+
+// ---- launchers (each enqueues on `s`; returns hipGetLastError) -------------------------------------
+// k_sort.hip
+hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n,
+                                   int bits, int* result_buffer /*0 or 1: which buffer holds the result*/);
+// k_build_cache.hip
+hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
+hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,
+                            int64_t B);
+hipError_t launch_select_and_fill(scars_handle* h, hipStream_t s, int64_t k);
+hipError_t launch_flush(scars_handle* h, hipStream_t s);
+// k_remap.hip
+hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
+                        const scars_remap_out* out);
+// k_fwd.hip
+hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                      const scars_remap_out* rm, float* out);
+// k_bwd.hip
+hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out);
+
+}  // namespace scars

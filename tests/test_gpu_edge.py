@@ -1,0 +1,246 @@
+"""Edge cases of the HIP path against the oracle: empty inputs, ties, extreme budgets, long segments,
+out-of-range indices, bad offsets."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2411_01611_amd import binding, synth
+from gpu_harness import GpuCase, assert_close
+from util import gids_of
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _custom_case(rows, D, idx, off, B, budget_rows, optimizer="sgd", dtype="f32", nprofile=0):
+    wl = synth.Workload("custom", tuple(rows), D, dtype, B, None, 1.0, budget_rows * D * (4 if dtype == "f32" else 2),
+                        optimizer)
+    c = GpuCase(wl, nprofile=nprofile, max_L=max(len(idx), 1))
+    c.batch = (torch.tensor(idx, dtype=torch.int32), torch.tensor(off, dtype=torch.int32))
+    return c
+
+
+def _run_all(c, profile_with_batch=True):
+    """build (profile = the batch itself), remap, fwd, bwd on both sides; returns GPU outputs."""
+    wl = c.wl
+    idx, off = c.batch
+    if profile_with_batch:
+        c.profile = [c.batch]
+    counts, hot, slot_of = c.build()
+    d_idx, d_off = c.dev_batch()
+    rm = c.s.remap(d_idx, d_off, wl.batch)
+    out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    g = torch.Generator().manual_seed(5)
+    grad = torch.randn(wl.num_bags, wl.dim, generator=g)
+    bo = c.s.new_bwd_out(max(idx.numel(), 1))
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), 0.01, 1e-8, bo)
+    c.s.flush_cache()
+    return rm, out, bo, grad
+
+
+def test_long_segments_cross_many_chunks():
+    """One row looked up thousands of times: its run crosses >100 reduce chunks and several sort tiles."""
+    rng = np.random.default_rng(3)
+    rows = [50, 1000]
+    B = 6000
+    idx0 = np.where(rng.random(B) < 0.7, 7, rng.integers(0, 50, B))        # 70 % of table 0 hits row 7
+    idx1 = np.where(rng.random(B) < 0.3, 999, rng.integers(0, 1000, B))    # long run at the very end of key space
+    idx = np.concatenate([idx0, idx1]).astype(np.int32)
+    off = np.arange(2 * B + 1, dtype=np.int32)
+    for opt in ("sgd", "adagrad"):
+        _say("optimizer", opt)
+        c = _custom_case(rows, 32, idx, off, B, budget_rows=100, optimizer=opt)
+        rm, out, bo, grad = _run_all(c)
+        assert c.s.sync_status() == 0
+        wl = c.wl
+        rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx, off, B)
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
+        oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1 if opt == "adagrad" else 0, idx, off, B,
+                                        grad.numpy(), np.float32(0.01), np.float32(1e-8))
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows with long segments")
+        if opt == "adagrad":
+            assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state with long segments")
+        c.close()
+
+
+def test_empty_bags_and_ragged_lengths():
+    rng = np.random.default_rng(11)
+    rows = [300, 17, 4000]
+    B = 513
+    lens = rng.integers(0, 5, 3 * B)
+    lens[:7] = 0
+    lens[-3:] = 0
+    lens[100] = 700                                    # one very long bag
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    idx = np.concatenate([rng.integers(0, rows[t], int(lens[t * B:(t + 1) * B].sum())) for t in range(3)]).astype(np.int32)
+    c = _custom_case(rows, 8, idx, off, B, budget_rows=400)
+    rm, out, bo, grad = _run_all(c)
+    assert c.s.sync_status() == 0
+    rc, want = oracle.embedding_bag_fwd(rows, [x.copy() for x in c.ora_tables], idx, off, B)
+    assert_close(out.cpu().numpy(), want, "ragged bags")
+    assert np.all(out.cpu().numpy()[lens == 0] == 0.0)
+    rc, sg, sb, ss, ug = oracle.bwd_segments(rows, idx, off, B)
+    assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
+    oracle.embedding_bag_bwd_update(rows, c.ora_tables, None, 0, idx, off, B, grad.numpy(), np.float32(0.01), np.float32(0))
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after ragged update")
+    c.close()
+
+
+def test_empty_batch():
+    rows = [10, 10]
+    B = 4
+    off = np.zeros(2 * B + 1, dtype=np.int32)
+    c = _custom_case(rows, 4, [], off, B, budget_rows=5)
+    c.profile = []
+    c.build()
+    d_off = torch.tensor(off, dtype=torch.int32, device=c.dev)
+    d_idx = torch.empty(0, dtype=torch.int32, device=c.dev)
+    rm = c.s.remap(d_idx, d_off, B)
+    assert rm.n_hit_miss.cpu().tolist() == [0, 0]
+    out = c.s.embedding_bag_fwd(d_idx, d_off, B, rm)
+    assert torch.count_nonzero(out).item() == 0
+    bo = c.s.new_bwd_out(1)
+    before = c.pinned_rows().copy()
+    c.s.embedding_bag_bwd_update(d_idx, d_off, B, rm, torch.ones(2 * B, 4, device=c.dev), 0.1, 0.0, bo)
+    c.s.flush_cache()
+    assert c.s.sync_status() == 0
+    assert bo.n_unique.cpu().tolist() == [0, 0] and int(bo.seg_start[0]) == 0
+    assert np.array_equal(c.pinned_rows(), before)
+    # all-zero counts: the hot set is the lowest ids
+    assert c.s.hot_gid().cpu().tolist() == [0, 1, 2, 3, 4]
+    c.close()
+
+
+def test_tie_classes_and_extreme_budgets():
+    rows = [3000, 2500]
+    N = sum(rows)
+    B = 4096
+    rng = np.random.default_rng(2)
+    # counts are small integers with huge tie classes; boundary falls inside a class that spans both tables
+    idx = np.concatenate([rng.integers(0, 3000, B), rng.integers(0, 2500, B)]).astype(np.int32)
+    off = np.arange(2 * B + 1, dtype=np.int32)
+    for kb in (0, 1, 2047, 2048, 2049, 4000, N - 1, N, N + 10):
+        _say("budget rows", kb)
+        c = _custom_case(rows, 4, idx, off, B, budget_rows=kb)
+        c.profile = [c.batch]
+        counts, hot, slot_of = c.build()
+        assert c.s.sync_status() == 0
+        assert c.s.cache_rows() == min(kb, N)
+        assert np.array_equal(c.s.hot_gid().cpu().numpy(), hot)
+        assert np.array_equal(c.s.slot_of().cpu().numpy(), slot_of)
+        rm = c.s.remap(*c.dev_batch(), B)
+        nh, nm = rm.n_hit_miss.cpu().tolist()
+        assert nh + nm == 2 * B
+        if kb == 0:
+            assert nh == 0          # no cache: every lookup is communicated (the paper's baseline, eq. (4))
+        if kb >= N:
+            assert nm == 0
+        c.close()
+
+
+def test_large_counts_use_all_select_passes():
+    """Counts written directly (profile of zero lookups, accumulate on preset counts) exercise the high digits."""
+    rows = [5000]
+    c = _custom_case(rows, 4, [0], [0, 1], 1, budget_rows=1234)
+    rng = np.random.default_rng(8)
+    counts = rng.integers(0, 2 ** 32, 5000, dtype=np.uint64).astype(np.uint32)
+    counts[100:200] = counts[100]                       # a tie class among large values
+    c.s.build_cache(None, None, 0, c.budget, 0)
+    c.s.counts().copy_(torch.from_numpy(counts.view(np.int32)))
+    c.s.build_cache(None, None, 0, c.budget, 1)
+    rc, hot, slot_of = oracle.hot_set(counts, 1234)
+    assert np.array_equal(c.s.hot_gid().cpu().numpy(), hot)
+    assert np.array_equal(c.s.slot_of().cpu().numpy(), slot_of)
+    c.close()
+
+
+def test_out_of_range_index_is_latched_and_treated_as_absent():
+    rows = [40, 30]
+    B = 64
+    rng = np.random.default_rng(4)
+    idx = np.concatenate([rng.integers(0, 40, B), rng.integers(0, 30, B)]).astype(np.int32)
+    idx[5] = 40
+    idx[70] = -1
+    idx[127] = 1000
+    off = np.arange(2 * B + 1, dtype=np.int32)
+    c = _custom_case(rows, 4, idx, off, B, budget_rows=20)
+    c.profile = []
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    c.s.build_cache(d_idx, d_off, B, c.budget, 0)
+    assert c.s.sync_status() == binding.ERR_INDEX_RANGE
+    assert c.s.sync_status() == 0                                   # reading clears the latch
+    rc, counts = oracle.histogram(rows, idx, off, B)
+    assert rc == oracle.ERR_INDEX_RANGE
+    assert np.array_equal(c.s.counts().cpu().numpy().view(np.uint32), counts)
+    rc, hot, slot_of = oracle.hot_set(counts, 20)
+    assert np.array_equal(c.s.hot_gid().cpu().numpy(), hot)
+    rm = c.s.remap(d_idx, d_off, B)
+    assert c.s.sync_status() == binding.ERR_INDEX_RANGE
+    rc, slot, hit, miss, mg = oracle.remap(rows, idx, off, B, slot_of)
+    assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size] and hit.size + miss.size == 2 * B - 3
+    assert np.array_equal(rm.slot.cpu().numpy(), slot)
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: mg.size], mg)
+    out = c.s.embedding_bag_fwd(d_idx, d_off, B, rm)
+    rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
+    assert rc == oracle.ERR_INDEX_RANGE
+    assert_close(out.cpu().numpy(), want, "invalid lookups add nothing")
+    grad = torch.ones(2 * B, 4)
+    bo = c.s.new_bwd_out(2 * B)
+    c.s.embedding_bag_bwd_update(d_idx, d_off, B, rm, grad.to(c.dev), 0.5, 0.0, bo)
+    c.s.flush_cache()
+    c.s.sync_status()
+    rc, sg, sb, ss, ug = oracle.bwd_segments(rows, idx, off, B)
+    assert bo.n_unique.cpu().tolist() == [ug.size, sg.size]
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
+    assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
+    oracle.embedding_bag_bwd_update(rows, c.ora_tables, None, 0, idx, off, B, grad.numpy(), np.float32(0.5), np.float32(0))
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after update with invalid lookups")
+    c.close()
+
+
+def test_bad_offsets_are_latched():
+    rows = [40, 30]
+    B = 8
+    idx = np.arange(16, dtype=np.int32) % 30
+    c = _custom_case(rows, 4, idx, np.arange(17, dtype=np.int32), B, budget_rows=10)
+    c.profile = [c.batch]
+    c.build()
+    assert c.s.sync_status() == 0
+    for bad in ([0, 1, 2, 3, 5, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16],      # decreasing
+                [1] + list(range(1, 17)),                                           # does not start at 0
+                list(range(16)) + [15]):                                            # does not end at L
+        d_off = torch.tensor(bad, dtype=torch.int32, device=c.dev)
+        d_idx = torch.tensor(idx, dtype=torch.int32, device=c.dev)
+        rm = c.s.remap(d_idx, d_off, B)
+        c.s.embedding_bag_fwd(d_idx, d_off, B, rm)          # stays in bounds whatever the offsets say
+        assert c.s.sync_status() == binding.ERR_OFFSETS
+        assert oracle.remap(rows, idx, np.array(bad, dtype=np.int32), B, c.ora_slot_of)[0] == oracle.ERR_OFFSETS
+    c.close()
+
+
+def test_rebuild_after_updates_keeps_updated_rows():
+    """A second build_cache writes updated hot rows back before it reselects."""
+    wl = synth.workload("tiny")
+    c = GpuCase(wl)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    rm = c.s.remap(d_idx, d_off, wl.batch)
+    grad = c.sampler.grads(0)
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), 0.01, 0.0)
+    oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, None, 0, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch,
+                                    grad.numpy(), np.float32(0.01), np.float32(0))
+    c.s.build_cache(None, None, 0, c.budget // 2, 1)            # reselect with half the budget, no flush call
+    assert c.s.sync_status() == 0
+    assert c.s.cache_rows() == c.k // 2
+    rm = c.s.remap(d_idx, d_off, wl.batch)
+    out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
+    assert_close(out.cpu().numpy(), want, "forward after rebuild")
+    c.close()

@@ -1,0 +1,212 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Integer outputs bit-exact; fp32 outputs within 1e-5 relative / 1e-6 absolute; bf16 rows within the admissible
+rounding interval.  Sizes span several tiles of every kernel (2048-lookup compaction tiles, 4096-pair sort
+tiles, 32-lookup reduce chunks) and end in ragged tails.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2411_01611_amd import binding, synth
+from gpu_harness import ATOL, RTOL, GpuCase, assert_bf16_within, assert_close
+from util import bag_of, gids_of
+
+CASES = {
+    "tiny": ("tiny", {}),
+    "dlrm_small": ("dlrm_onehot", {"scale": 0.004, "batch": 1500}),
+    "multi_hot_small": ("multi_hot", {"scale": 0.004, "batch": 333}),
+    "low_skew_bf16": ("low_skew", {"scale": 0.002, "batch": 700}),
+    "low_skew_uniform_bf16": ("low_skew_uniform", {"scale": 0.002, "batch": 257}),
+    "host_spill_small": ("host_spill", {"scale": 0.0005, "batch": 3000}),
+}
+
+
+def _wl(case):
+    name, kw = CASES[case]
+    return synth.workload(name, **kw)
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(params=list(CASES))
+def case(request):
+    _say("case", request.param)
+    c = GpuCase(_wl(request.param))
+    yield c
+    c.close()
+
+
+def test_build_cache_parity(case):
+    counts, hot, slot_of = case.build()
+    s = case.s
+    assert s.sync_status() == 0
+    assert s.cache_rows() == case.k
+    assert np.array_equal(s.counts().cpu().numpy().view(np.uint32), counts)
+    assert np.array_equal(s.hot_gid().cpu().numpy(), hot)
+    assert np.array_equal(s.slot_of().cpu().numpy(), slot_of)
+    rows = np.concatenate(case.ora_tables)
+    cache = s.cache().cpu()
+    cache = cache.numpy() if case.wl.dtype == "f32" else cache.view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(cache, rows[hot])
+
+
+def test_remap_parity(case):
+    case.build()
+    wl = case.wl
+    idx, off = case.batch
+    rc, slot, hit, miss, mg = oracle.remap(wl.rows, idx.numpy(), off.numpy(), wl.batch, case.ora_slot_of)
+    assert rc == 0
+    rm = case.s.remap(*case.dev_batch(), wl.batch)
+    assert case.s.sync_status() == 0
+    n = rm.n_hit_miss.cpu().numpy()
+    L = idx.numel()
+    assert n.tolist() == [hit.size, miss.size] and hit.size + miss.size == L
+    assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
+    assert np.array_equal(rm.gid.cpu().numpy()[:L], gids_of(wl, idx.numpy(), off.numpy()))
+    assert np.array_equal(rm.hit_pos.cpu().numpy()[: hit.size], hit)
+    assert np.array_equal(rm.miss_pos.cpu().numpy()[: miss.size], miss)
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
+    loc = np.where(slot >= 0, slot, 0)
+    loc[miss] = case.k + np.arange(miss.size)
+    assert np.array_equal(rm.loc.cpu().numpy()[:L], loc)
+
+
+def test_fwd_parity(case):
+    case.build()
+    wl = case.wl
+    idx, off = case.batch
+    rc, want = oracle.embedding_bag_fwd(wl.rows, case.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+    assert rc == 0
+    d_idx, d_off = case.dev_batch()
+    rm = case.s.remap(d_idx, d_off, wl.batch)
+    out = case.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    assert case.s.sync_status() == 0
+    assert_close(out.cpu().numpy(), want, "pooled output")
+    # determinism: a second run is bit-identical
+    out2 = case.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    assert torch.equal(out, out2)
+
+
+def _bwd_both(case, want_segments=True):
+    wl = case.wl
+    idx, off = case.batch
+    grad = case.sampler.grads(0)
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps if wl.optimizer == "adagrad" else 0.0)
+    opt = 1 if wl.optimizer == "adagrad" else 0
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx.numpy(), off.numpy(), wl.batch)
+    assert rc == 0
+    rc, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, case.ora_tables, case.ora_state, opt, idx.numpy(),
+                                                     off.numpy(), wl.batch, grad.numpy(), lr, eps, report=True,
+                                                     n_unique=ug.size)
+    assert rc == 0
+    before = np.concatenate(case.ora_tables).copy()
+    (rc,) = oracle.embedding_bag_bwd_update(wl.rows, case.ora_tables, case.ora_state, opt, idx.numpy(), off.numpy(),
+                                            wl.batch, grad.numpy(), lr, eps)
+    assert rc == 0
+    d_idx, d_off = case.dev_batch()
+    rm = case.s.remap(d_idx, d_off, wl.batch)
+    bo = case.s.new_bwd_out(idx.numel()) if want_segments else None
+    case.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(case.dev), float(lr), float(eps), bo)
+    case.s.flush_cache()
+    assert case.s.sync_status() == 0
+    return (sg, sb, ss, ug), (nr, ns), before, bo
+
+
+def test_bwd_parity(case):
+    case.build()
+    wl = case.wl
+    (sg, sb, ss, ug), (nr, ns), before, bo = _bwd_both(case)
+    U, nv = bo.n_unique.cpu().numpy().tolist()
+    assert U == ug.size and nv == sg.size
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+    assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+    assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+    assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+    got = case.pinned_rows()
+    want = np.concatenate(case.ora_tables)
+    touched = np.zeros(wl.total_rows, dtype=bool)
+    touched[ug] = True
+    assert np.array_equal(got[~touched], before[~touched]), "rows without a lookup must not change"
+    if wl.dtype == "f32":
+        assert_close(got, want, "updated rows")
+    else:
+        assert_bf16_within(got[ug], nr, "updated bf16 rows")
+    if wl.optimizer == "adagrad":
+        assert_close(case.pinned_state_rows(), np.concatenate(case.ora_state), "adagrad accumulators")
+
+
+def test_bwd_without_segment_outputs_gives_same_rows(case):
+    case.build()
+    _, _, _, bo = _bwd_both(case, want_segments=False)
+    assert bo is None
+    got = case.pinned_rows()
+    if case.wl.dtype == "f32":
+        assert_close(got, np.concatenate(case.ora_tables), "updated rows")
+
+
+@pytest.mark.parametrize("name", ["tiny", "multi_hot_small", "low_skew_bf16"])
+def test_source_invariance_across_budgets(name):
+    """Pooled sums and post-flush tables are identical whether rows come from the cache or the host:
+    budget 0 (every lookup misses), the workload's budget, and a budget that caches every row."""
+    wl = _wl(name)
+    outs, tabs, hits = [], [], []
+    for budget in (0, wl.budget_bytes, wl.total_rows * wl.row_bytes + 5):
+        _say("budget", budget)
+        c = GpuCase(wl, budget_bytes=budget)
+        c.build()
+        d_idx, d_off = c.dev_batch()
+        rm = c.s.remap(d_idx, d_off, wl.batch)
+        out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+        grad = c.sampler.grads(0).to(c.dev)
+        c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, wl.lr, wl.eps)
+        c.s.flush_cache()
+        assert c.s.sync_status() == 0
+        outs.append(out.cpu())
+        tabs.append(c.pinned_rows().copy())
+        hits.append(rm.n_hit_miss.cpu().tolist())
+        c.close()
+    assert hits[0][0] == 0 and hits[2][1] == 0 and hits[1][0] > 0 and hits[1][1] > 0
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert np.array_equal(tabs[0], tabs[1]) and np.array_equal(tabs[0], tabs[2])
+
+
+def test_onehot_forward_is_exact_gather():
+    wl = _wl("tiny")
+    c = GpuCase(wl)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, c.s.remap(d_idx, d_off, wl.batch)).cpu().numpy()
+    idx = c.batch[0].numpy()
+    for t in range(wl.num_tables):
+        assert np.array_equal(out[t * wl.batch:(t + 1) * wl.batch], c.ora_tables[t][idx[t * wl.batch:(t + 1) * wl.batch]])
+    c.close()
+
+
+def test_two_steps_in_a_row_match_oracle():
+    """Second step reads rows the first step updated (cache for hot rows, host for cold ones)."""
+    wl = _wl("multi_hot_small")
+    c = GpuCase(wl)
+    c.build()
+    opt = 1
+    for step in range(2):
+        idx, off = c.sampler.batch(step)
+        grad = c.sampler.grads(step)
+        rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+        oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, opt, idx.numpy(), off.numpy(), wl.batch,
+                                        grad.numpy(), np.float32(wl.lr), np.float32(wl.eps))
+        d_idx, d_off = idx.to(c.dev), off.to(c.dev)
+        rm = c.s.remap(d_idx, d_off, wl.batch)
+        out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+        assert_close(out.cpu().numpy(), want, f"step {step} output")
+        c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), wl.lr, wl.eps)
+    c.s.flush_cache()
+    assert c.s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after two steps")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after two steps")
+    c.close()

@@ -1,0 +1,87 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and its host-only logic
+(configuration checks, size queries, call-order errors) behaves.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2411_01611_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "scars.h")).read()
+    declared = set(re.findall(r"\b(scars_[a-z_]+)\s*\(", header))
+    declared -= {"scars_handle"}
+    assert declared == set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def _cfg(rows, dim, dtype=0, opt=0, tables=None, state=None):
+    T = len(rows)
+    rows_a = (C.c_int64 * T)(*rows)
+    tabs = (C.c_void_p * T)(*(tables or [0x1000] * T))
+    st = (C.c_void_p * T)(*state) if state else None
+    return binding._Config(T, rows_a, dim, dtype, tabs, opt, st), (rows_a, tabs, st)
+
+
+def test_create_rejects_bad_configurations():
+    L = binding.lib()
+    h = C.c_void_p()
+    for rows, dim, dtype, opt, tables, state in (
+        ([], 16, 0, 0, None, None),                 # no tables
+        ([10], 3, 0, 0, None, None),                # row bytes not a multiple of 16
+        ([10], 4, 1, 0, None, None),                # bf16 dim 4 = 8 bytes
+        ([10], 512, 0, 0, None, None),              # row larger than 1024 bytes
+        ([10], 16, 2, 0, None, None),               # unknown dtype
+        ([10], 16, 0, 3, None, None),               # unknown optimizer
+        ([10], 16, 0, 1, None, None),               # Adagrad without state
+        ([10, 0], 16, 0, 0, None, None),            # empty table
+        ([2 ** 30, 2 ** 30], 16, 0, 0, None, None),  # 2^31 rows
+        ([10], 16, 0, 0, [0], None),                # null table pointer
+    ):
+        cfg, keep = _cfg(rows, dim, dtype, opt, tables, state)
+        assert L.scars_create(C.byref(cfg), C.byref(h)) == binding.ERR_INVALID_ARG
+    assert L.scars_create(None, C.byref(h)) == binding.ERR_INVALID_ARG
+
+
+def test_query_sizes_and_budget_rows():
+    s = binding.Scars([1000, 3000], 64, binding.DTYPE_F32, [0x1000, 0x2000])
+    z = s.query_sizes(0, 100, 10)
+    assert z["k"] == 0
+    assert s.query_sizes(255, 100, 10)["k"] == 0                   # budget below one row
+    assert s.query_sizes(256, 100, 10)["k"] == 1
+    assert s.query_sizes(256 * 4000 + 17, 100, 10)["k"] == 4000
+    assert s.query_sizes(10 ** 12, 100, 10)["k"] == 4000
+    z = s.query_sizes(256 * 500, 5000, 2000)
+    assert z["counts_bytes"] >= 4000 * 4 and z["slot_of_bytes"] >= 4000 * 4
+    assert z["cache_bytes"] >= 500 * 256 and z["state_cache_bytes"] == 0
+    assert z["workspace_bytes"] >= 5000 * 256                      # staging for max_L rows
+    assert z["out_bytes"] >= 2000 * 64 * 4 and z["seg_start_bytes"] >= 5001 * 4
+    assert all(v % 256 == 0 for k, v in z.items() if k.endswith("_bytes"))
+    with pytest.raises(binding.ScarsError):
+        s.query_sizes(-1, 1, 1)
+    with pytest.raises(binding.ScarsError):
+        s.query_sizes(0, 2 ** 31, 1)
+    sa = binding.Scars([1000], 64, binding.DTYPE_F32, [0x1000], binding.OPT_ADAGRAD, [0x3000])
+    assert sa.query_sizes(256 * 10, 1, 1)["state_cache_bytes"] >= 10 * 256
+    sb = binding.Scars([1000], 64, binding.DTYPE_BF16, [0x1000])
+    assert sb.query_sizes(128 * 10, 1, 1)["k"] == 10
+
+
+def test_calls_before_bind_report_workspace_error():
+    L = binding.lib()
+    s = binding.Scars([100], 16, binding.DTYPE_F32, [0x1000])
+    assert L.scars_build_cache(s._h, None, None, 0, 0, 0, 0, None) == binding.ERR_WORKSPACE
+    assert L.scars_remap(s._h, None, None, 0, 0, None, None) == binding.ERR_WORKSPACE
+    assert L.scars_flush_cache(s._h, None) == binding.ERR_WORKSPACE
+    assert L.scars_sync_status(s._h, None) == binding.ERR_WORKSPACE
+    assert b"no buffers bound" in L.scars_last_error(s._h)
+    assert L.scars_cache_rows(s._h) == -1
+    assert L.scars_remap(None, None, None, 0, 0, None, None) == binding.ERR_INVALID_ARG
+    assert L.scars_destroy(None) == binding.ERR_INVALID_ARG
