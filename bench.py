@@ -1,0 +1,363 @@
+#!/usr/bin/env python3
+"""Benchmark of the cached embedding-bag hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: remap -> embedding_bag_fwd ->
+embedding_bag_bwd_update, with the workload's byte budget (hot rows in the HBM cache, cold rows in pinned host
+memory).  build_cache runs once before the timed region (it is amortised over many batches) and is reported
+separately.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2411_01611_amd import binding, synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+class Bench:
+    def __init__(self, wl: synth.Workload, budget_bytes: int):
+        self.wl = wl
+        self.dev = torch.device("cuda:0")
+        self.budget = budget_bytes
+        t0 = time.time()
+        npdt = np.float32 if wl.dtype == "f32" else np.uint16
+        self.tables, self.state = [], []
+        for t in range(wl.num_tables):
+            p = binding.PinnedArray((wl.rows[t], wl.dim), npdt)
+            self._fill(p, t)
+            self.tables.append(p)
+            if wl.optimizer == "adagrad":
+                s = binding.PinnedArray((wl.rows[t], wl.dim), np.float32)
+                self._zero(s)
+                self.state.append(s)
+        torch.cuda.synchronize()
+        log(f"tables: {wl.total_rows} rows x {wl.row_bytes} B = {wl.total_rows * wl.row_bytes / 1e9:.2f} GB pinned "
+            f"(+{len(self.state) and wl.total_rows * wl.dim * 4 / 1e9:.2f} GB state) in {time.time() - t0:.1f}s")
+        self.sampler = synth.Sampler(wl, self.dev)
+        self.s = binding.Scars(wl.rows, wl.dim, binding.DTYPE_F32 if wl.dtype == "f32" else binding.DTYPE_BF16,
+                               [p.ptr for p in self.tables],
+                               binding.OPT_ADAGRAD if wl.optimizer == "adagrad" else binding.OPT_SGD,
+                               [p.ptr for p in self.state] if self.state else None)
+
+    def _fill(self, p: binding.PinnedArray, t: int):
+        wl = self.wl
+        chunk = max(1, (1 << 27) // wl.dim)     # 128 Mi elements per chunk
+        for r0 in range(0, wl.rows[t], chunk):
+            r1 = min(wl.rows[t], r0 + chunk)
+            v = synth.row_values(wl, t, r0, r1, self.dev).contiguous()
+            p.copy_from_device(v.view(torch.int16) if wl.dtype == "bf16" else v, r0)
+            torch.cuda.synchronize()
+
+    def _zero(self, p: binding.PinnedArray):
+        rows = p.shape[0]
+        chunk = max(1, (1 << 27) // p.shape[1])
+        z = torch.zeros(min(rows, chunk), p.shape[1], dtype=torch.float32, device=self.dev)
+        for r0 in range(0, rows, chunk):
+            r1 = min(rows, r0 + chunk)
+            p.copy_from_device(z[: r1 - r0], r0)
+        torch.cuda.synchronize()
+
+    def prepare(self, n_batches: int):
+        wl = self.wl
+        self.batches = [self.sampler.batch(e) for e in range(n_batches)]
+        self.grads = [self.sampler.grads(e) for e in range(min(n_batches, 4))]
+        self.max_L = max(int(b[0].numel()) for b in self.batches)
+        prof = [self.sampler.batch(p, True) for p in range(min(wl.profile_batches, 4))]
+        self.max_L = max(self.max_L, max(int(b[0].numel()) for b in prof)) + 4096
+        self.sizes = self.s.bind_buffers(self.budget, self.max_L, wl.num_bags)
+        self.rm = self.s.new_remap_out()
+        self.out = torch.empty(wl.num_bags, wl.dim, dtype=torch.float32, device=self.dev)
+
+    def build_cache(self) -> dict:
+        wl = self.wl
+        P = wl.profile_batches
+        torch.cuda.synchronize()
+        t0 = time.time()
+        gen = 0.0
+        Lp = 0
+        self.s.build_cache(None, None, 0, self.budget, 0)
+        t_hist = 0.0
+        for p in range(P):
+            g0 = time.time()
+            idx, off = self.sampler.batch(p, True)
+            if idx.numel() > self.max_L:
+                continue
+            torch.cuda.synchronize()
+            gen += time.time() - g0
+            h0 = time.time()
+            self.s.build_cache(idx, off, wl.batch, self.budget, 2)
+            torch.cuda.synchronize()
+            t_hist += time.time() - h0
+            Lp += int(idx.numel())
+        s0 = time.time()
+        self.s.build_cache(None, None, 0, self.budget, 1)
+        torch.cuda.synchronize()
+        t_sel = time.time() - s0
+        st = self.s.sync_status()
+        assert st == 0, f"device error {st} during build_cache"
+        k = self.s.cache_rows()
+        return {"profile_lookups": Lp, "histogram_s": t_hist, "select_and_fill_s": t_sel, "k": k,
+                "histogram_Mlookups_per_s": Lp / max(t_hist, 1e-9) / 1e6,
+                "fill_host_link_GBs": k * wl.row_bytes / max(t_sel, 1e-9) / 1e9, "total_s": time.time() - t0 - gen}
+
+    def step(self, e: int):
+        wl = self.wl
+        idx, off = self.batches[e % len(self.batches)]
+        g = self.grads[e % len(self.grads)]
+        self.s.remap(idx, off, wl.batch, self.rm)
+        self.s.embedding_bag_fwd(idx, off, wl.batch, self.rm, self.out)
+        self.s.embedding_bag_bwd_update(idx, off, wl.batch, self.rm, g, wl.lr, wl.eps if wl.optimizer == "adagrad" else 0.0)
+        return int(idx.numel())
+
+    def close(self):
+        self.s.close()
+        for p in self.tables + self.state:
+            p.free()
+
+
+def measure_link(dev) -> dict:
+    """Pinned <-> device hipMemcpyAsync of 1 GiB each way: the host-link denominator."""
+    n = 1 << 30
+    host = binding.PinnedArray((n,), np.uint8)
+    d = torch.empty(n, dtype=torch.uint8, device=dev)
+    out = {}
+    for name, kind, dst, src in (("h2d_GBs", 1, d.data_ptr(), host.ptr), ("d2h_GBs", 2, host.ptr, d.data_ptr())):
+        best = 0.0
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            binding.memcpy(dst, src, n, kind)
+            b.record()
+            torch.cuda.synchronize()
+            best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
+        out[name] = best
+    host.free()
+    return out
+
+
+def calibration(dev) -> dict:
+    """Plain copy kernel of known size (1 GiB read + 1 GiB write): scales the HBM byte counters and gives the
+    box's own streaming rate beside the published peak."""
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device=dev)
+    b = torch.zeros(n, dtype=torch.uint8, device=dev)
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.calibration_copy(a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return {"copy_bytes_each_way": n, "copy_GBs": best}
+
+
+def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> dict:
+    """Bytes the method itself must move per launch of each kernel (per-lookup figures times the batch)."""
+    R, D, G = wl.row_bytes, wl.dim, wl.num_bags
+    st = 8 * D if wl.optimizer == "adagrad" else 0
+    return {
+        "pool_wave": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
+        "pool_group": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
+        "stage_misses": 2 * n_miss * R + 4 * n_miss,          # link read + HBM write
+        "seg_reduce": L * D * 4 + 8 * L + U * (2 * R + st),
+        "remap_probe": 16 * L,
+        "remap_write": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss),
+        "sort_scatter": 16 * L,
+        "sort_hist": 4 * L,
+        "bwd_pairs": 12 * L,
+    }
+
+
+def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
+    """W warm-up steps, exactly K timed steps between two synchronizes, then the same K steps again with a HIP
+    event pair around every kernel launch (recorded by the library on the launch stream)."""
+    wl = b.wl
+    for e in range(W):
+        b.step(e)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lookups = 0
+    for e in range(W, W + K):
+        lookups += b.step(e)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert b.s.sync_status() == 0
+    n_hit, n_miss = b.rm.n_hit_miss.cpu().tolist()
+
+    b.s.profile_enable(True)
+    for e in range(W, W + K):
+        b.step(e)
+    prof = b.s.profile_read()
+    b.s.profile_enable(False)
+    # unique rows (all / not cached) of the last batch, for the bytes of the segment kernel
+    bo = b.s.new_bwd_out()
+    idx, off = b.batches[(W + K - 1) % len(b.batches)]
+    b.s.embedding_bag_bwd_update(idx, off, wl.batch, b.rm, b.grads[0], wl.lr, wl.eps, bo)
+    U = int(bo.n_unique.cpu()[0])
+    U_cold = int((b.s.slot_of()[bo.unique_gid[:U].long()] < 0).sum().item())
+    torch.cuda.synchronize()
+    del bo
+
+    L_avg = lookups / K
+    alg = algorithmic_bytes(wl, L_avg, U, n_miss)
+    kern = {}
+    for name, r in prof.items():
+        avg_ms = r["total_ms"] / r["launches"]
+        kern[name] = {"launches_per_step": r["launches"] / K, "avg_ms": round(avg_ms, 5),
+                      "ms_per_step": round(r["total_ms"] / K, 5)}
+        if name in alg:
+            kern[name]["alg_GBs"] = round(alg[name] / (avg_ms * 1e-3) / 1e9, 1)
+    pool = "pool_wave" if "pool_wave" in prof else "pool_group"
+    pool_avg_s = prof[pool]["total_ms"] / prof[pool]["launches"] * 1e-3
+    achieved = alg[pool] / pool_avg_s / 1e9
+    roofline = {"kernel": pool, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": pmc_traffic(wl.name, pool),
+                "alg_bytes_per_launch": int(alg[pool]), "avg_launch_ms": round(pool_avg_s * 1e3, 5)}
+    host_link = []
+    state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
+    for name, rd, wr in (("stage_misses", n_miss * wl.row_bytes, 0),
+                         ("seg_reduce", U_cold * (wl.row_bytes + state_b), U_cold * (wl.row_bytes + state_b))):
+        if name in prof and rd > 0:
+            t_s = prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
+            t_min = max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9))
+            host_link.append({"kernel": name, "link_read_bytes": int(rd), "link_write_bytes": int(wr),
+                              "avg_launch_ms": round(t_s * 1e3, 5), "read_GBs": round(rd / t_s / 1e9, 2),
+                              "write_GBs": round(wr / t_s / 1e9, 2), "frac_of_measured_link": round(t_min / t_s, 4)})
+    return {"value": lookups / (t1 - t0), "ms_per_step": (t1 - t0) * 1e3 / K, "lookups_per_step": L_avg,
+            "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "roofline": roofline,
+            "host_link": host_link, "kernels": kern}
+
+
+def pmc_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if any."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.json")
+    try:
+        return json.load(open(path))[kernel]["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
+def cpu_baseline(b: Bench, seconds_target: float = 12.0) -> dict:
+    """The CPU oracle, as it stands, on the machine's host cores, on a bounded sample of the same workload."""
+    import oracle
+    wl = b.wl
+    cores = min(16, os.cpu_count() or 1)
+    used = oracle.set_threads(cores)
+    tabs = [p.np for p in b.tables]
+    st = [p.np for p in b.state] if b.state else None
+    opt = 1 if wl.optimizer == "adagrad" else 0
+    done_L, t_total, nb = 0, 0.0, 0
+    slot_of = b.s.slot_of().cpu().numpy()
+    while t_total < seconds_target and nb < 400:
+        idx, off = b.batches[nb % len(b.batches)]
+        idx, off = idx.cpu().numpy(), off.cpu().numpy()
+        g = b.grads[nb % len(b.grads)].cpu().numpy()
+        t0 = time.time()
+        rc1 = oracle.remap(wl.rows, idx, off, wl.batch, slot_of)[0]
+        rc2 = oracle.embedding_bag_fwd(wl.rows, tabs, idx, off, wl.batch)[0]
+        # report mode with no output arrays: everything is computed, nothing is stored or mutated
+        r = oracle.embedding_bag_bwd_update(wl.rows, tabs, st, opt, idx, off, wl.batch, g, wl.lr, wl.eps,
+                                            report=True, n_unique=0, want_outputs=False)
+        t_total += time.time() - t0
+        assert rc1 == 0 and rc2 == 0 and r[0] == 0
+        done_L += idx.shape[0]
+        nb += 1
+    return {"value": done_L / t_total, "unit": "lookups/s", "cores": used, "kind": "oracle",
+            "sample": f"{nb} batch(es) of the same workload ({done_L} lookups): oracle remap + fwd + bwd_update "
+                      f"(report mode, nothing mutated) in {t_total:.1f}s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="multi_hot", choices=synth.WORKLOAD_NAMES)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-resident", dest="resident", action="store_false",
+                    help="skip the second leg in which every row is cached")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "no GPU visible"
+    binding.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.workload(args.workload, scale=args.scale)
+    budget = wl.budget_bytes if args.budget_bytes < 0 else args.budget_bytes
+    cal = calibration(dev)
+    link = measure_link(dev)
+    log("calibration", cal, "link", link)
+
+    b = Bench(wl, budget)
+    K, W = args.steps, args.warmup
+    b.prepare(K + W)
+    bc = b.build_cache()
+    log("build_cache", bc)
+
+    leg = run_leg(b, K, W, link)
+    resident = None
+    if args.resident and budget < wl.total_rows * wl.row_bytes and wl.total_rows * wl.row_bytes * 3 < 150e9:
+        # second leg: every row cached (the paper's "hot" iteration): the same kernels, no host-link traffic
+        b.s.flush_cache()
+        torch.cuda.synchronize()
+        b.budget = wl.total_rows * wl.row_bytes
+        b.prepare(K + W)
+        b.s.build_cache(None, None, 0, b.budget, 0)
+        torch.cuda.synchronize()
+        r = run_leg(b, K, W, link)
+        resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
+                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "kernels": r["kernels"]}
+        log("cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
+
+    cpu = None
+    b.s.flush_cache()           # host tables current again before the oracle reads them
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(b)
+        log("cpu_baseline", cpu)
+
+    line = {
+        "metric": "pooled embedding lookups/sec (fwd+bwd) + achieved HBM GB/s, 1 GPU",
+        "value": leg["value"], "unit": "lookups/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": leg["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 sums", "data": "synthetic",
+        "config": {"workload": wl.name, "scale": args.scale, "tables": wl.num_tables, "rows": wl.total_rows,
+                   "dim": wl.dim, "batch": wl.batch, "lookups_per_step": leg["lookups_per_step"], "zipf_s": wl.zipf_s,
+                   "budget_bytes": budget, "cached_rows": bc["k"], "optimizer": wl.optimizer,
+                   "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],
+                   "unique_cold_rows_per_step": leg["U_cold"],
+                   "step": "remap + embedding_bag_fwd + embedding_bag_bwd_update"},
+        "roofline": leg["roofline"], "host_link": leg["host_link"],
+        "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
+                     "d2h_GBs": round(link["d2h_GBs"], 2)},
+        "cpu_baseline": cpu, "cache_resident": resident,
+        "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
+    }
+    b.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -184,6 +184,10 @@ int32_t scars_host_free(void* p);
 int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind /* 1 = H2D, 2 = D2H, 3 = D2D */,
                      void* stream);
 
+/* Measurement aid: a plain grid-stride copy kernel (k_calib_copy) of `bytes` (multiple of 16) between two DEVICE
+ * buffers, used to scale hardware byte counters against a transfer of known size. */
+int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
+
 /* Per-kernel timing for measurement: when enabled, every kernel launch is bracketed by HIP events on the
  * caller's stream.  scars_profile_read waits for the stream, then returns up to `cap` records
  * (name pointer valid for the library's lifetime, launches, total milliseconds) and clears them. */

@@ -149,7 +149,7 @@ def bwd_segments(rows, indices, offsets, B: int):
 
 def embedding_bag_bwd_update(rows, tables: Sequence[np.ndarray], state: Optional[Sequence[np.ndarray]],
                              optimizer: int, indices, offsets, B: int, grad_out: np.ndarray, lr: float,
-                             eps: float, report: bool = False, n_unique: int = 0):
+                             eps: float, report: bool = False, n_unique: int = 0, want_outputs: bool = True):
     """report=False mutates `tables`/`state` in place and returns (rc,).  report=True mutates nothing and
     returns (rc, new_rows, new_state, grad_rows) as fp64 [n_unique, D] arrays (n_unique from bwd_segments)."""
     rows = _rows(rows); indices = _i32(indices); offsets = _i32(offsets)
@@ -160,7 +160,7 @@ def embedding_bag_bwd_update(rows, tables: Sequence[np.ndarray], state: Optional
     tp = _ptr_array(tables)
     sp = _ptr_array(state) if state is not None else None
     nr = ns = gr = None
-    if report:
+    if report and want_outputs:
         nr = np.zeros((n_unique, D), dtype=np.float64)
         ns = np.zeros((n_unique, D), dtype=np.float64)
         gr = np.zeros((n_unique, D), dtype=np.float64)

@@ -25,7 +25,7 @@ EXPORTS = (
     "scars_create", "scars_destroy", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
     "scars_cache_rows", "scars_remap", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
-    "scars_memcpy", "scars_profile_enable", "scars_profile_read",
+    "scars_memcpy", "scars_calibration_copy", "scars_profile_enable", "scars_profile_read",
 )
 
 
@@ -93,6 +93,7 @@ def lib():
         L.scars_host_alloc.argtypes = [i64, C.POINTER(vp)]
         L.scars_host_free.argtypes = [vp]
         L.scars_memcpy.argtypes = [vp, vp, i64, i32, vp]
+        L.scars_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.scars_profile_enable.argtypes = [vp, i32]
         L.scars_profile_read.argtypes = [vp, vp, C.POINTER(_KernelTime), i32, C.POINTER(i32)]
         _lib = L
@@ -101,6 +102,22 @@ def lib():
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Launch the plain copy kernel on the current stream (dst, src: contiguous CUDA tensors of equal byte size)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n and n % 16 == 0
+    rc = lib().scars_calibration_copy(dst.data_ptr(), src.data_ptr(), n, _stream())
+    if rc != OK:
+        raise ScarsError(rc, "calibration copy failed")
+
+
+def memcpy(dst_ptr: int, src_ptr: int, nbytes: int, kind: int) -> None:
+    """hipMemcpyAsync on the current stream; kind 1 = host-to-device, 2 = device-to-host, 3 = device-to-device."""
+    rc = lib().scars_memcpy(dst_ptr, src_ptr, nbytes, kind, _stream())
+    if rc != OK:
+        raise ScarsError(rc, "memcpy failed")
 
 
 class PinnedArray:

@@ -23,6 +23,16 @@ hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t 
     return hipGetLastError();
 }
 
+// Plain streaming copy of 16-byte words: the known-size kernel against which HBM byte counters are scaled.
+__global__ __launch_bounds__(kBlock) void k_calib_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, int64_t n16) {
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kBlock) dst[i] = src[i];
+}
+
+hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t bytes) {
+    hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(kBlock), 0, s, (uint4*)dst, (const uint4*)src, bytes / 16);
+    return hipGetLastError();
+}
+
 // ---- (1) histogram --------------------------------------------------------------------------------
 // One thread per lookup.  The table of a lookup follows from its position: lookups of table t occupy
 // [offsets[t*B], offsets[(t+1)*B]).

@@ -16,7 +16,7 @@ constexpr int kUnroll = 4;
 // ---- staging of missed rows ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
                                                          const int32_t* __restrict__ n_hit_miss,
-                                                         const Meta* __restrict__ meta, uint4* __restrict__ staging,
+                                                         const Meta* __restrict__ meta, u32x4* __restrict__ staging,
                                                          int chunks, int lpr, int64_t cap_rows) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = meta->num_tables;
@@ -26,27 +26,24 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restri
     const int gpb = kBlock / lpr;
     const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
     const int64_t stride = (int64_t)gridDim.x * gpb;
+    const bool lane_on = gl < chunks;      // lpr >= chunks: one 16-byte piece per lane
     for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
-        const uint4* src[kUnroll];
+        u32x4 v[kUnroll];
+        bool on[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t j = j0 + u * stride;
-            src[u] = nullptr;
-            if (j < n) {
+            v[u] = (u32x4)(0u);
+            on[u] = lane_on && j < n;
+            if (on[u]) {
                 const int32_t gid = miss_gid[j];
                 const int t = upper_table(s_rbase, T, gid);
-                src[u] = (const uint4*)meta->table[t] + (int64_t)(gid - s_rbase[t]) * chunks;
+                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid - s_rbase[t]) * chunks + gl);
             }
         }
-        for (int c = gl; c < chunks; c += lpr) {
-            uint4 v[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                if (src[u]) v[u] = src[u][c];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                if (src[u]) staging[(j0 + u * stride) * chunks + c] = v[u];
-        }
+        for (int u = 0; u < kUnroll; ++u)
+            if (on[u]) staging[(j0 + u * stride) * chunks + gl] = v[u];
     }
 }
 
@@ -188,7 +185,7 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         const int gpb = kBlock / lpr;
         const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), 256 * 8));
         hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, rm->miss_gid, rm->n_hit_miss, h->ws.meta,
-                           (uint4*)h->ws.staging, chunks, lpr, h->buf.max_L);
+                           (u32x4*)h->ws.staging, chunks, lpr, h->buf.max_L);
     }
     if (G > 0) {
         const bool wave_mode = lpr < 64 && L >= G * 2 * (kWave / lpr);

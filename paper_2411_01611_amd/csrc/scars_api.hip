@@ -310,6 +310,11 @@ int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind, vo
     return hipMemcpyAsync(dst, src, (size_t)bytes, k, (hipStream_t)stream) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
 }
 
+int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream) {
+    if (!d_dst || !d_src || bytes < 0 || bytes % 16 != 0) return SCARS_ERR_INVALID_ARG;
+    return launch_calib_copy((hipStream_t)stream, d_dst, d_src, bytes) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
 int32_t scars_profile_enable(scars_handle* h, int32_t on) {
     if (!h) return SCARS_ERR_INVALID_ARG;
     h->profile = on != 0;

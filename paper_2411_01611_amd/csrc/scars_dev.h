@@ -7,6 +7,9 @@
 
 namespace scars {
 
+// 16 raw bytes as a native vector (stays in registers; HIP's uint4 struct sometimes lands in scratch)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 

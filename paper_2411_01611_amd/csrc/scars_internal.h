@@ -115,6 +115,7 @@ hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, 
                             int64_t B);
 hipError_t launch_select_and_fill(scars_handle* h, hipStream_t s, int64_t k);
 hipError_t launch_flush(scars_handle* h, hipStream_t s);
+hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t bytes);
 // k_remap.hip
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out);
