@@ -3,29 +3,29 @@
 // Section IV of the paper splits an iteration into forward, backward and optimization and attributes the
 // cost of the last two to writes of embedding rows (device memory for cached rows, host DRAM for the
 // rest).  Here: (1) pairs (gid, bag) in position order; (2) stable radix sort by gid; (3) segment heads by
-// ordered compaction (the integer outputs); (4) segment reduce in fixed chunks of kSegChunk sorted lookups
-// per lane group -- a run that lies inside one chunk is summed and applied at once, a run that crosses
-// chunk borders leaves one partial sum per chunk; (5) the chunk in which such a run starts adds the
-// partials in chunk order and applies the update.  No floating-point atomics: results are bit-stable.
+// ordered compaction (the integer outputs); (4) one lane group per distinct row sums its run of
+// gradient rows and applies the update, with the row fetched while the gradients stream in; (5) a run of
+// more than 64 lookups is summed per 64-position chunk into fp64 partials that are added in chunk order by
+// whichever piece finishes last.  No floating-point atomics: results are bit-stable.
 #include "scars_dev.h"
 
 namespace scars {
 
 // ---- (1) pairs ----------------------------------------------------------------------------------------
+// key = gid of the lookup, value = its bag.  A group of LPB lanes walks one bag's positions, so the bag id
+// needs no search; -1 (invalid lookup) becomes the largest key and sorts last.
 __global__ __launch_bounds__(kBlock) void k_bwd_pairs(const int32_t* __restrict__ gid, const int32_t* __restrict__ off,
-                                                      int64_t L, int64_t G, uint32_t* __restrict__ key,
+                                                      int32_t L, int64_t G, int lpb, uint32_t* __restrict__ key,
                                                       uint32_t* __restrict__ val) {
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= L) return;
-    // bag of position i: largest g with off[g] <= i  (empty bags share a start; the last of them owns nothing,
-    // so step to the last g whose start is <= i)
-    int64_t lo = 0, hi = G;   // answer in [lo, hi)
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if ((int64_t)off[mid] <= i) lo = mid; else hi = mid;
+    const int64_t g = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / lpb;
+    const int c = threadIdx.x % lpb;
+    if (g >= G) return;
+    const int32_t a = min(max(off[g], 0), L);
+    const int32_t b = min(max(off[g + 1], a), L);
+    for (int32_t i = a + c; i < b; i += lpb) {
+        key[i] = (uint32_t)gid[i];
+        val[i] = (uint32_t)g;
     }
-    key[i] = (uint32_t)gid[i];   // -1 (invalid lookup) becomes the largest key and sorts last
-    val[i] = (uint32_t)lo;
 }
 
 __global__ void k_bwd_empty(int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start) {
@@ -45,8 +45,12 @@ __device__ __forceinline__ bool is_head(const uint32_t* __restrict__ key, int64_
 
 // per tile: number of heads and number of valid (non-sentinel) keys
 __global__ __launch_bounds__(kBlock) void k_seg_count(const uint32_t* __restrict__ key, int64_t L,
-                                                      uint32_t* __restrict__ blk_head, uint32_t* __restrict__ blk_valid) {
+                                                      uint32_t* __restrict__ blk_head, uint32_t* __restrict__ blk_valid,
+                                                      int32_t* __restrict__ done) {
     __shared__ uint32_t s_a[4], s_b[4];
+    // clear this tile's share of the long-run completion counters (2 per chunk of kLongRunMin positions)
+    constexpr int kDonePerTile = 2 * kScanTile / kLongRunMin;
+    if (threadIdx.x < kDonePerTile) done[(int64_t)blockIdx.x * kDonePerTile + threadIdx.x] = 0;
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     uint32_t nh = 0, nv = 0;
 #pragma unroll
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
                                                       int64_t L, const uint32_t* __restrict__ blk_head,
                                                       const int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start,
                                                       int32_t* __restrict__ unique_gid, int32_t* __restrict__ sorted_gid,
-                                                      int32_t* __restrict__ sorted_bag) {
+                                                      int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run) {
     __shared__ uint32_t s_a[4];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     bool hd[kRoundsS];
@@ -105,6 +109,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
             seg_start[u] = (int32_t)j;
             unique_gid[u] = (int32_t)key[j];
         }
+        // each round is one chunk of kLongRunMin (= 64) positions: remember which run its first position is in
+        if (lane_id() == 0 && j < L) chunk_run[j / kLongRunMin] = (int32_t)(before + (hd[r] ? 1u : 0u)) - 1;
         before += (uint32_t)__popcll(m);
         if (sorted_gid && j < L) {   // caller asked for the sorted pairs as well
             sorted_gid[j] = (int32_t)key[j];
@@ -122,198 +128,243 @@ struct UpdateArgs {
     float* state_cache;
     float lr, eps;
     int D;
+    uint32_t N;      // rows in all tables: a key at or above it is never dereferenced
+    uint32_t Gm1;    // last bag: bag ids are clamped to it (both only matter after an offsets error)
 };
 
-// lane owns 4 consecutive columns [4*c, 4*c+4) of the row of `gid`; applies one optimizer step with gradient g.
-// The step is evaluated in fp64 and rounded once: Adagrad from a zero accumulator is w -= lr*g/(|g|+eps), whose
-// slope in g reaches lr/eps, so a gradient sum that is only fp32-accurate would miss a 1e-6 absolute bar.
+// Where a row lives: cache slot (HBM) or pinned host table; the Adagrad accumulator beside it.
 template <int DTYPE, int OPT>
-__device__ __forceinline__ void apply_update(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid, int c,
-                                             const double (&g)[4]) {
-    const int32_t slot = A.slot_of[gid];
-    void* wrow;
-    float* srow = nullptr;
-    if (slot >= 0) {
-        wrow = (char*)A.cache + (int64_t)slot * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
-        if (OPT == SCARS_OPT_ADAGRAD) srow = A.state_cache + (int64_t)slot * A.D;
-    } else {
-        const int t = upper_table(s_rbase, T, gid);
-        const int64_t row = gid - s_rbase[t];
-        wrow = (char*)A.meta->table[t] + row * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
-        if (OPT == SCARS_OPT_ADAGRAD) srow = A.meta->state[t] + row * A.D;
-    }
-    double w[4];
-    if (DTYPE == SCARS_DTYPE_F32) {
-        const float4 v = ((const float4*)wrow)[c];
-        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-    } else {
-        const uint2 v = ((const uint2*)wrow)[c];
-        w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xFFFF0000u);
-        w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xFFFF0000u);
-    }
-    const double lr = (double)A.lr, eps = (double)A.eps;
-    if (OPT == SCARS_OPT_SGD) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = w[i] - lr * g[i];
-    } else {
-        const float4 sv = ((const float4*)srow)[c];
-        double st[4] = {sv.x, sv.y, sv.z, sv.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            st[i] = st[i] + g[i] * g[i];
-            w[i] = w[i] - lr * g[i] / (sqrt(st[i]) + eps);
-        }
-        ((float4*)srow)[c] = make_float4((float)st[0], (float)st[1], (float)st[2], (float)st[3]);
-    }
-    if (DTYPE == SCARS_DTYPE_F32) {
-        ((float4*)wrow)[c] = make_float4((float)w[0], (float)w[1], (float)w[2], (float)w[3]);
-    } else {
-        uint2 o;
-        o.x = (uint32_t)f32_to_bf16((float)w[0]) | ((uint32_t)f32_to_bf16((float)w[1]) << 16);
-        o.y = (uint32_t)f32_to_bf16((float)w[2]) | ((uint32_t)f32_to_bf16((float)w[3]) << 16);
-        ((uint2*)wrow)[c] = o;
-    }
-}
-
-// Group of LPG lanes per chunk of kSegChunk sorted lookups; lane c owns columns [4c, 4c+4).
-// partial[(chunk*2 + side)*D + col]: side 0 = run open to the left (continues a previous chunk),
-// side 1 = run that starts in this chunk and continues into the next.
-template <int DTYPE, int OPT, int LPG>
-__global__ __launch_bounds__(kBlock) void k_seg_reduce(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
-                                                       const int32_t* __restrict__ n_unique, const float* __restrict__ grad,
-                                                       double* __restrict__ partial, UpdateArgs A) {
-    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
-    const int T = A.meta->num_tables;
-    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = A.meta->row_base[t];
-    __syncthreads();
-    const int64_t Lv = n_unique[1];
-    const int64_t chunk = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPG;
-    const int c = threadIdx.x % LPG;
-    const int64_t j0 = chunk * kSegChunk;
-    if (j0 >= Lv) return;
-    const bool lane_on = c * 4 < A.D;
-    const int64_t j1 = min(j0 + kSegChunk, Lv);
-    const uint32_t none = 0xFFFFFFFFu;
-    const uint32_t prev = j0 > 0 ? key[j0 - 1] : none;
-    const uint32_t next = j1 < Lv ? key[j1] : none;
-    uint32_t cur = key[j0];
-    bool left_open = cur == prev;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    const float4* g4 = (const float4*)grad;
-    const int dq = A.D / 4;
-    for (int64_t j = j0; j < j1; j += 4) {
-        uint32_t kk[4];
-        float4 gv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            kk[u] = none;
-            if (j + u < j1) {
-                kk[u] = key[j + u];
-                if (lane_on) gv[u] = g4[(int64_t)val[j + u] * dq + c];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (j + u < j1) {
-                if (kk[u] != cur) {
-                    // the run of `cur` ends inside this chunk
-                    if (lane_on) {
-                        if (left_open) {
-                            double* p = partial + (chunk * 2 + 0) * A.D + c * 4;
-                            p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
-                        } else {
-                            apply_update<DTYPE, OPT>(A, s_rbase, T, (int32_t)cur, c, acc);
-                        }
-                    }
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.0;
-                    cur = kk[u];
-                    left_open = false;
-                }
-                if (lane_on) { acc[0] += gv[u].x; acc[1] += gv[u].y; acc[2] += gv[u].z; acc[3] += gv[u].w; }
-            }
-        }
-    }
-    if (lane_on) {
-        const bool right_open = cur == next;
-        if (left_open) {
-            double* p = partial + (chunk * 2 + 0) * A.D + c * 4;
-            p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
-        } else if (right_open) {
-            double* p = partial + (chunk * 2 + 1) * A.D + c * 4;
-            p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
+struct RowRef {
+    void* w;
+    float* s;
+    __device__ __forceinline__ void locate(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid) {
+        const int32_t slot = A.slot_of[gid];
+        s = nullptr;
+        if (slot >= 0) {
+            w = (char*)A.cache + (int64_t)slot * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
+            if (OPT == SCARS_OPT_ADAGRAD) s = A.state_cache + (int64_t)slot * A.D;
         } else {
-            apply_update<DTYPE, OPT>(A, s_rbase, T, (int32_t)cur, c, acc);
+            const int t = upper_table(s_rbase, T, gid);
+            const int64_t row = gid - s_rbase[t];
+            w = (char*)A.meta->table[t] + row * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
+            if (OPT == SCARS_OPT_ADAGRAD) s = A.meta->state[t] + row * A.D;
+        }
+    }
+    // lane owns columns [4c, 4c+4)
+    __device__ __forceinline__ void load(int c, float (&wv)[4], float (&sv)[4]) const {
+        if (DTYPE == SCARS_DTYPE_F32) {
+            const float4 v = ((const float4*)w)[c];
+            wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
+        } else {
+            const uint2 v = ((const uint2*)w)[c];
+            wv[0] = __uint_as_float(v.x << 16); wv[1] = __uint_as_float(v.x & 0xFFFF0000u);
+            wv[2] = __uint_as_float(v.y << 16); wv[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        }
+        if (OPT == SCARS_OPT_ADAGRAD) {
+            const float4 v = ((const float4*)s)[c];
+            sv[0] = v.x; sv[1] = v.y; sv[2] = v.z; sv[3] = v.w;
+        }
+    }
+    // One optimizer step with summed gradient g, evaluated in fp64 and rounded once.  From a zero accumulator
+    // Adagrad's step is lr*g/(|g|+eps), whose slope in g reaches lr/eps, so an fp32-accurate g would miss a
+    // 1e-6 absolute bar; hence fp64 sums and fp64 arithmetic here.
+    __device__ __forceinline__ void step_and_store(const UpdateArgs& A, int c, const float (&wv)[4], const float (&sv)[4],
+                                                   const double (&g)[4]) const {
+        const double lr = (double)A.lr, eps = (double)A.eps;
+        double wn[4];
+        if (OPT == SCARS_OPT_SGD) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wn[i] = (double)wv[i] - lr * g[i];
+        } else {
+            double st[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                st[i] = (double)sv[i] + g[i] * g[i];
+                wn[i] = (double)wv[i] - lr * g[i] / (sqrt(st[i]) + eps);
+            }
+            ((float4*)s)[c] = make_float4((float)st[0], (float)st[1], (float)st[2], (float)st[3]);
+        }
+        if (DTYPE == SCARS_DTYPE_F32) {
+            ((float4*)w)[c] = make_float4((float)wn[0], (float)wn[1], (float)wn[2], (float)wn[3]);
+        } else {
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16((float)wn[0]) | ((uint32_t)f32_to_bf16((float)wn[1]) << 16);
+            o.y = (uint32_t)f32_to_bf16((float)wn[2]) | ((uint32_t)f32_to_bf16((float)wn[3]) << 16);
+            ((uint2*)w)[c] = o;
+        }
+    }
+};
+
+constexpr int kLongRun = kLongRunMin;   // runs up to this many lookups are summed by one lane group
+constexpr int kGradUnroll = 4;  // gradient rows in flight per lane group in the per-row kernel
+constexpr int kTaskUnroll = 8;  // ... and in a task of a long run (few groups, long chains: go wide)
+constexpr int kCombUnroll = 4;  // partial sums in flight when a long run is combined
+
+// sum of grad rows val[j] for j in [p0, p1), columns [4c, 4c+4), in position order, fp64; UNROLL rows in flight
+template <int UNROLL>
+__device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, const float4* __restrict__ g4, int dq, int c,
+                                          int32_t p0, int32_t p1, uint32_t Gm1, double (&acc)[4]) {
+    for (int32_t j = p0; j < p1; j += UNROLL) {
+        float4 gv[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            gv[u] = (j + u < p1) ? g4[(int64_t)min(val[j + u], Gm1) * dq + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            acc[0] += (double)gv[u].x; acc[1] += (double)gv[u].y; acc[2] += (double)gv[u].z; acc[3] += (double)gv[u].w;
         }
     }
 }
 
-// The chunk in which a border-crossing run starts collects that run's partial sums in chunk order.
+// One lane group per distinct row whose run has at most kLongRun lookups; the row (and accumulator) is
+// fetched while the gradient rows stream in.  Longer runs are left to k_seg_long.
 template <int DTYPE, int OPT, int LPG>
-__global__ __launch_bounds__(kBlock) void k_seg_fixup(const uint32_t* __restrict__ key, const int32_t* __restrict__ n_unique,
-                                                      const double* __restrict__ partial, UpdateArgs A) {
+__global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
+                                                     const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
+                                                     const float* __restrict__ grad, UpdateArgs A) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = A.meta->num_tables;
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = A.meta->row_base[t];
     __syncthreads();
-    const int64_t Lv = n_unique[1];
-    const int64_t chunk = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPG;
+    const int32_t U = n_unique[0];
     const int c = threadIdx.x % LPG;
-    const int64_t j0 = chunk * kSegChunk;
-    const int64_t j1 = j0 + kSegChunk;
-    if (j1 >= Lv) return;                       // last chunk (or beyond): nothing continues to the right
-    const uint32_t k = key[j1 - 1];
-    if (key[j1] != k) return;                   // last run of this chunk ends at the border
-    if (key[j0] == k && j0 > 0 && key[j0 - 1] == k) return;   // run started earlier: its first chunk collects
     if (c * 4 >= A.D) return;
-    const double4* p4 = (const double4*)partial;
     const int dq = A.D / 4;
-    double acc[4];
-    {
-        const double4 v = p4[(chunk * 2 + 1) * dq + c];
-        acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+    const float4* g4 = (const float4*)grad;
+    const int64_t ngroups = (int64_t)gridDim.x * (kBlock / LPG);
+    for (int64_t r = (int64_t)blockIdx.x * (kBlock / LPG) + threadIdx.x / LPG; r < U; r += ngroups) {
+        const int32_t a = seg_start[r], b = seg_start[r + 1];
+        const uint32_t gid = (uint32_t)unique_gid[r];
+        if (b - a > kLongRun || gid >= A.N) continue;
+        RowRef<DTYPE, OPT> ref;
+        ref.locate(A, s_rbase, T, (int32_t)gid);
+        float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
+        ref.load(c, wv, sv);
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        sum_grads<kGradUnroll>(val, g4, dq, c, a, b, A.Gm1, acc);
+        ref.step_and_store(A, c, wv, sv, acc);
     }
-    int64_t d = chunk + 1;
-    while (d * kSegChunk < Lv && key[d * kSegChunk] == k) {
-        double4 v[4];
-        int n = 0;
+}
+
+// Partial sums travel between compute units through agent-scope (write-through / cache-bypassing) accesses
+// instead of full fences: an agent-scope release or acquire fence on this chip writes back or invalidates the
+// whole per-XCD L2, which costs tens of microseconds per use.
+__device__ __forceinline__ void store_agent(double* p, double v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double load_agent(const double* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Runs longer than kLongRun.  One lane group per chunk of kLongRun sorted positions.  Such a run overlaps a
+// chunk either by covering its first position ("side 0") or by starting inside it and running past its end
+// ("side 1"); at most one of each per chunk.  The overlap is summed into partial[chunk][side]; the group that
+// completes a run's last outstanding piece adds that run's partials in chunk order and applies the update
+// (nobody waits: whoever finishes last combines).  done[] is indexed by the chunk in which the run starts
+// (two long runs cannot start in one chunk) and by 64-lane part for groups wider than a wave.  chunk_run[ch]
+// is the run that holds the chunk's first position.  Independent of k_seg_rows.
+template <int DTYPE, int OPT, int LPG>
+__global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                                     const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
+                                                     const int32_t* __restrict__ unique_gid, const int32_t* __restrict__ chunk_run,
+                                                     const float* __restrict__ grad, double* __restrict__ partial,
+                                                     int32_t* __restrict__ done, UpdateArgs A) {
+    // no LDS copy of the table bounds here: most groups leave after a few loads, and only the group that
+    // combines a run needs them (read from the descriptor in global memory then)
+    const int32_t* s_rbase = A.meta->row_base;
+    const int T = A.meta->num_tables;
+    const int32_t Lv = n_unique[1];
+    const int c = threadIdx.x % LPG;
+    const bool lane_on = c * 4 < A.D;
+    const int dq = A.D / 4;
+    const float4* g4 = (const float4*)grad;
+    constexpr int gpb = kBlock / LPG;
+    constexpr int kPartLanes = LPG < kWave ? LPG : kWave;          // lanes that share one completion counter
+    constexpr int kParts = LPG < kWave ? 1 : LPG / kWave;
+    const int part = c / kWave;
+    const int leader = (lane_id() / kPartLanes) * kPartLanes;       // first lane of this part inside its wave
+    const int64_t ngroups = (int64_t)gridDim.x * gpb;
+    const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
+    for (int64_t ch = (int64_t)blockIdx.x * gpb + threadIdx.x / LPG; ch < nchunks; ch += ngroups) {
+        const int32_t j0 = (int32_t)ch * kLongRun, j1 = min(j0 + kLongRun, Lv);
+        const uint32_t k0 = key[j0], k1 = key[j1 - 1];
+        const uint32_t kp = j0 > 0 ? key[j0 - 1] : ~k0;
+        const uint32_t kn = j1 < Lv ? key[j1] : ~k1;
+        const int32_t r0 = chunk_run[ch];
+        const int32_t r1 = j1 < Lv ? chunk_run[ch + 1] : 0;
+        for (int side = 0; side < 2; ++side) {
+            // a long run over this chunk must continue across one of its borders
+            const bool cand = side == 0 ? (kp == k0 || kn == k0) : (k1 != k0 && kn == k1);
+            if (!cand) continue;
+            const int32_t r = side == 0 ? r0 : r1;
+            const int32_t a = seg_start[r], b = seg_start[r + 1];
+            if (b - a <= kLongRun) continue;
+            if (lane_on) {
+                double acc[4] = {0.0, 0.0, 0.0, 0.0};
+                sum_grads<kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), A.Gm1, acc);
+                double* p = partial + ((int64_t)ch * 2 + side) * A.D + c * 4;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if ((d + u) * kSegChunk < Lv && key[(d + u) * kSegChunk] == k) {
-                v[u] = p4[((d + u) * 2 + 0) * dq + c];
-                n = u + 1;
-            } else {
-                break;
+                for (int e = 0; e < 4; ++e) store_agent(p + e, acc[e]);
             }
-        }
+            wait_stores_done();                                     // the partial sum has landed before the count
+            const int32_t first = a / kLongRun;
+            const int32_t pieces = (b - 1) / kLongRun - first + 1;
+            int32_t prev = 0;
+            if (lane_id() == leader) prev = atomicAdd(&done[first * kParts + part], 1);
+            prev = __shfl(prev, leader, kWave);
+            if (prev != pieces - 1) continue;                       // last one in combines; the others' sums have landed
+            const uint32_t gid = (uint32_t)unique_gid[r];
+            if (!lane_on || gid >= A.N) continue;
+            RowRef<DTYPE, OPT> ref;
+            ref.locate(A, s_rbase, T, (int32_t)gid);
+            float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
+            ref.load(c, wv, sv);
+            double g[4] = {0.0, 0.0, 0.0, 0.0};
+            const int first_side = (a % kLongRun) != 0 ? 1 : 0;     // the first piece starts inside its chunk?
+            for (int32_t i = 0; i < pieces; i += kCombUnroll) {
+                double v[kCombUnroll][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (u < n) { acc[0] += v[u].x; acc[1] += v[u].y; acc[2] += v[u].z; acc[3] += v[u].w; }
-        d += n;
+                for (int u = 0; u < kCombUnroll; ++u) {
+                    const int32_t ii = min(i + u, pieces - 1);
+                    const double* qq = partial + ((int64_t)(first + ii) * 2 + (ii == 0 ? first_side : 0)) * A.D + c * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[u][e] = load_agent(qq + e);
+                }
+#pragma unroll
+                for (int u = 0; u < kCombUnroll; ++u)
+                    if (i + u < pieces) { g[0] += v[u][0]; g[1] += v[u][1]; g[2] += v[u][2]; g[3] += v[u][3]; }
+            }
+            ref.step_and_store(A, c, wv, sv, g);
+        }
     }
-    apply_update<DTYPE, OPT>(A, s_rbase, T, (int32_t)k, c, acc);
 }
 
 template <int DTYPE, int OPT, int LPG>
 static void launch_reduce_t(scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val, const int32_t* nu,
-                            const float* grad, int64_t L, UpdateArgs A) {
-    const int64_t chunks = div_up(L, kSegChunk);
-    const unsigned grid = (unsigned)div_up(chunks * LPG, kBlock);
+                            const int32_t* seg_start, const int32_t* unique_gid, const float* grad, int64_t L, UpdateArgs A) {
+    Workspace& ws = h->ws;
+    const int gpb = kBlock / LPG;
+    const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), 256 * 32));
+    const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     {
-        Timed t(h, s, "seg_reduce");
-        hipLaunchKernelGGL((k_seg_reduce<DTYPE, OPT, LPG>), dim3(grid), dim3(kBlock), 0, s, key, val, nu, grad,
-                           h->ws.partial, A);
+        Timed t(h, s, "seg_long");
+        hipLaunchKernelGGL((k_seg_long<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, val, nu, seg_start,
+                           unique_gid, ws.chunk_run, grad, ws.partial, ws.task_done, A);
     }
     {
-        Timed t(h, s, "seg_fixup");
-        hipLaunchKernelGGL((k_seg_fixup<DTYPE, OPT, LPG>), dim3(grid), dim3(kBlock), 0, s, key, nu, h->ws.partial, A);
+        Timed t(h, s, "seg_rows");
+        hipLaunchKernelGGL((k_seg_rows<DTYPE, OPT, LPG>), dim3(rows_blocks), dim3(kBlock), 0, s, val, nu, seg_start,
+                           unique_gid, grad, A);
     }
 }
 
 template <int DTYPE, int OPT>
 static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val,
-                            const int32_t* nu, const float* grad, int64_t L, UpdateArgs A) {
+                            const int32_t* nu, const int32_t* seg_start, const int32_t* unique_gid, const float* grad,
+                            int64_t L, UpdateArgs A) {
     switch (lpg) {
-#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, key, val, nu, grad, L, A); break;
+#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, key, val, nu, seg_start, unique_gid, grad, L, A); break;
         SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
         SCARS_CASE(128)
 #undef SCARS_CASE
@@ -334,8 +385,9 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     }
     {
         Timed t(h, s, "bwd_pairs");
-        hipLaunchKernelGGL(k_bwd_pairs, dim3((unsigned)div_up(L, kBlock)), dim3(kBlock), 0, s, rm->gid, off, L, G,
-                           ws.key_buf[0], ws.val_buf[0]);
+        const int lpb = std::min(64, next_pow2_host((int)std::max<int64_t>(1, L / std::max<int64_t>(G, 1))));
+        hipLaunchKernelGGL(k_bwd_pairs, dim3((unsigned)div_up(G * lpb, kBlock)), dim3(kBlock), 0, s, rm->gid, off,
+                           (int32_t)L, G, lpb, ws.key_buf[0], ws.val_buf[0]);
     }
     int bits = 1;
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
@@ -347,7 +399,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int nb = (int)div_up(L, kScanTile);
     {
         Timed t(h, s, "seg_count");
-        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss);
+        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss, ws.task_done);
     }
     {
         Timed t(h, s, "seg_scan");
@@ -356,16 +408,17 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     {
         Timed t(h, s, "seg_write");
         hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, n_unique, seg_start,
-                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr);
+                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run);
     }
-    UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D};
+    UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D, (uint32_t)h->N,
+                 (uint32_t)std::max<int64_t>(G - 1, 0)};
     const int lpg = next_pow2_host(h->D / 4);
     if (h->dtype == SCARS_DTYPE_F32) {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
     } else {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
     }
     return hipGetLastError();
 }

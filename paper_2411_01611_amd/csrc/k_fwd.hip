@@ -11,7 +11,8 @@
 
 namespace scars {
 
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 4;       // rows in flight per lane group when staging misses
+constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
@@ -78,33 +79,6 @@ template <> struct Chunk<SCARS_DTYPE_BF16> {
 };
 
 template <int DTYPE>
-__device__ __forceinline__ void accumulate_range(Chunk<DTYPE>& acc, int32_t first, int32_t last, int step,
-                                                 const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
-                                                 const uint4* __restrict__ staging, int32_t k, int chunks, int c,
-                                                 bool lane_on) {
-    for (int32_t i = first; i < last; i += step * kUnroll) {
-        uint4 row[kUnroll];
-        bool on[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int32_t ii = i + u * step;
-            on[u] = false;
-            if (ii < last) {
-                const int32_t l = loc[ii];
-                if (l >= 0 && lane_on) {
-                    const uint4* p = l < k ? cache + (int64_t)l * chunks : staging + (int64_t)(l - k) * chunks;
-                    row[u] = p[c];
-                    on[u] = true;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (on[u]) acc.add(row[u]);
-    }
-}
-
-template <int DTYPE>
 __device__ __forceinline__ void store_chunk(const Chunk<DTYPE>& acc, float* __restrict__ out, int64_t g, int D, int c) {
     float4* o = (float4*)(out + g * D + (int64_t)c * Chunk<DTYPE>::kVals);
 #pragma unroll
@@ -125,7 +99,31 @@ __global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict
     const int32_t b = min(max(off[g + 1], a), L);
     Chunk<DTYPE> acc;
     acc.zero();
-    accumulate_range<DTYPE>(acc, a, b, 1, loc, cache, staging, k, chunks, c, c < chunks);
+    const bool lane_on = c < chunks;
+    // the group's lanes fetch LPR locations of the bag with one load and hand them out by shuffles, so the row
+    // addresses of a whole window are known before the first row arrives (positions are summed in order)
+    const int gl0 = (lane_id() / LPR) * LPR;                     // first lane of this group inside the wave
+    for (int32_t w0 = a; w0 < b; w0 += LPR) {
+        const int32_t n = min((int32_t)LPR, b - w0);
+        const int32_t lv = c < n ? loc[w0 + c] : -1;
+        for (int base = 0; base < n; base += kPoolUnroll) {
+            uint4 row[kPoolUnroll];
+            bool on[kPoolUnroll];
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u) {
+                const int i = base + u;
+                const int32_t l = __shfl(lv, gl0 + (i & (LPR - 1)), kWave);
+                on[u] = lane_on && i < n && l >= 0;
+                if (on[u]) {
+                    const uint4* p = l < k ? cache + (int64_t)l * chunks : staging + (int64_t)(l - k) * chunks;
+                    row[u] = p[c];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u)
+                if (on[u]) acc.add(row[u]);
+        }
+    }
     if (c < chunks) store_chunk<DTYPE>(acc, out, g, D, c);
 }
 
@@ -143,7 +141,30 @@ __global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict_
     const int32_t b = min(max(off[g + 1], a), L);
     Chunk<DTYPE> acc;
     acc.zero();
-    accumulate_range<DTYPE>(acc, a + q, b, NG, loc, cache, staging, k, chunks, c, c < chunks);
+    const bool lane_on = c < chunks;
+    // the bag's locations are fetched 64 at a time with one coalesced load and handed out by shuffles, so
+    // every row address is known before the first row arrives
+    for (int32_t w0 = a; w0 < b; w0 += kWave) {
+        const int32_t n = min(kWave, b - w0);
+        const int32_t lv = lane_id() < n ? loc[w0 + lane_id()] : -1;
+        for (int base = 0; base < n; base += NG * kPoolUnroll) {   // same trip count for every lane
+            uint4 row[kPoolUnroll];
+            bool on[kPoolUnroll];
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u) {
+                const int i = base + q + u * NG;
+                const int32_t l = __shfl(lv, i & (kWave - 1), kWave);
+                on[u] = lane_on && i < n && l >= 0;
+                if (on[u]) {
+                    const uint4* p = l < k ? cache + (int64_t)l * chunks : staging + (int64_t)(l - k) * chunks;
+                    row[u] = p[c];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u)
+                if (on[u]) acc.add(row[u]);
+        }
+    }
 #pragma unroll
     for (int d = kWave / 2; d >= LPR; d >>= 1) {
 #pragma unroll

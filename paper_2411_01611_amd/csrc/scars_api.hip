@@ -46,7 +46,7 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
         return p;
     };
     const int64_t nbN = div_up(h->N, kScanTile), nbL = std::max<int64_t>(1, div_up(max_L, kScanTile));
-    const int64_t nbS = std::max<int64_t>(1, div_up(std::max(max_L, k_cap), kSortTile));
+    const int64_t nbS = std::max<int64_t>(1, div_up(std::max(max_L, k_cap), kBlock * kSortRoundsSmall));
     w.meta = (Meta*)take(sizeof(Meta));
     w.status = (int32_t*)take(16);
     w.sel_hist = (uint32_t*)take(3 * kSelBins * 4);
@@ -60,8 +60,8 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.tstart = (int32_t*)take((SCARS_MAX_TABLES + 1) * 4);
     w.blk_hit = (uint32_t*)take((nbL + 1) * 4);
     w.blk_miss = (uint32_t*)take((nbL + 1) * 4);
-    w.sort_hist = (uint32_t*)take(256 * nbS * 4);
-    w.sort_tot = (uint32_t*)take(256 * 4);
+    w.sort_hist = (uint32_t*)take(kSortMaxBins * nbS * 4);
+    w.sort_tot = (uint32_t*)take(kSortMaxBins * 4);
     for (int i = 0; i < 2; ++i) {
         w.key_buf[i] = (uint32_t*)take(max_L * 4);
         w.val_buf[i] = (uint32_t*)take(max_L * 4);
@@ -69,7 +69,10 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.seg_start = (int32_t*)take((max_L + 1) * 4);
     w.unique_gid = (int32_t*)take(max_L * 4);
     w.n_unique = (int32_t*)take(16);
-    w.partial = (double*)take(div_up(std::max<int64_t>(max_L, 1), kSegChunk) * 2 * h->D * 8);
+    const int64_t chunks = nbL * (kScanTile / kLongRunMin);    // whole scan tiles: the counters are cleared per tile
+    w.partial = (double*)take(chunks * 2 * h->D * 8);
+    w.task_done = (int32_t*)take(chunks * 2 * 4);
+    w.chunk_run = (int32_t*)take((chunks + 1) * 4);
     w.staging = take(max_L * h->R);
     w.total_bytes = off;
     return w;

@@ -14,9 +14,11 @@ namespace scars {
 constexpr int kBlock = 256;          // threads per workgroup everywhere: 4 wave64
 constexpr int kWave = 64;
 constexpr int kScanTile = 2048;      // items per workgroup in the ordered-compaction kernels
-constexpr int kSortTile = 4096;      // items per workgroup in the radix-sort kernels
+constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1024 for inputs under 2^21 pairs,
+constexpr int kSortRoundsLarge = 8;   // 2048 above
+constexpr int kSortMaxBins = 512;     // up to 9 bits per pass
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
-constexpr int kSegChunk = 32;        // sorted lookups per group in the segment-reduce kernel
+constexpr int kLongRunMin = 64;      // runs longer than this are cut into tasks of this many lookups
 
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline int64_t div_up(int64_t x, int64_t a) { return (x + a - 1) / a; }
@@ -45,14 +47,16 @@ struct Workspace {
     int32_t* tstart;          // [T + 1] first lookup of each table (copied from offsets)
     uint32_t* blk_hit;        // [nbL + 1]
     uint32_t* blk_miss;       // [nbL + 1]
-    uint32_t* sort_hist;      // [256 * nbS] digit-major per-block histogram, nbS for max(max_L, k)
-    uint32_t* sort_tot;       // [256]
+    uint32_t* sort_hist;      // [kSortMaxBins * nbS] digit-major per-tile histogram, nbS tiles for max(max_L, k) pairs
+    uint32_t* sort_tot;       // [kSortMaxBins]
     uint32_t* key_buf[2];     // [max_L]
     uint32_t* val_buf[2];     // [max_L]
     int32_t* seg_start;       // [max_L + 1] (used when the caller passes no bwd_out)
     int32_t* unique_gid;      // [max_L]
     int32_t* n_unique;        // [2]
-    double* partial;          // [nchunks][2][D] open-run partial sums (fp64) of the segment reduce
+    double* partial;          // [chunks][2][D] fp64 partial sums of long runs, chunks of kLongRunMin sorted positions
+    int32_t* task_done;       // [chunks rounded up to whole scan tiles][2] completion counters
+    int32_t* chunk_run;       // [chunks + 1] run (segment) index that holds each chunk's first position
     void* staging;            // [max_L][R] rows fetched over the host link
     int64_t total_bytes;
 };

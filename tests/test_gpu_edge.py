@@ -42,31 +42,45 @@ def _run_all(c, profile_with_batch=True):
     return rm, out, bo, grad
 
 
-def test_long_segments_cross_many_chunks():
-    """One row looked up thousands of times: its run crosses >100 reduce chunks and several sort tiles."""
+@pytest.mark.parametrize("D,dtype,opt", [(32, "f32", "sgd"), (32, "f32", "adagrad"), (24, "f32", "adagrad"),
+                                         (256, "f32", "sgd"), (512, "bf16", "sgd"), (64, "bf16", "adagrad")])
+def test_long_segments(D, dtype, opt):
+    """Rows looked up thousands of times: runs far above the 64-lookup task size, spanning several sort tiles,
+    for lane groups narrower than, equal to and wider than a wave, and a row width that is not a power of two."""
     rng = np.random.default_rng(3)
     rows = [50, 1000]
     B = 6000
     idx0 = np.where(rng.random(B) < 0.7, 7, rng.integers(0, 50, B))        # 70 % of table 0 hits row 7
     idx1 = np.where(rng.random(B) < 0.3, 999, rng.integers(0, 1000, B))    # long run at the very end of key space
+    idx1[:130] = 500                                                         # a run of just over two tasks
+    idx1[130:195] = 501                                                      # 65 lookups: the shortest long run
+    idx1[195:259] = 502                                                      # 64 lookups: the longest short run
     idx = np.concatenate([idx0, idx1]).astype(np.int32)
     off = np.arange(2 * B + 1, dtype=np.int32)
-    for opt in ("sgd", "adagrad"):
-        _say("optimizer", opt)
-        c = _custom_case(rows, 32, idx, off, B, budget_rows=100, optimizer=opt)
-        rm, out, bo, grad = _run_all(c)
-        assert c.s.sync_status() == 0
-        wl = c.wl
-        rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx, off, B)
-        assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
-        assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
-        assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
-        oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1 if opt == "adagrad" else 0, idx, off, B,
-                                        grad.numpy(), np.float32(0.01), np.float32(1e-8))
+    _say("D", D, dtype, opt)
+    c = _custom_case(rows, D, idx, off, B, budget_rows=100, optimizer=opt, dtype=dtype)
+    rm, out, bo, grad = _run_all(c)
+    assert c.s.sync_status() == 0
+    wl = c.wl
+    rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
+    assert_close(out.cpu().numpy(), want, "forward")
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx, off, B)
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
+    assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
+    assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
+    o = 1 if opt == "adagrad" else 0
+    rc, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
+                                                     np.float32(0.01), np.float32(1e-8), report=True, n_unique=ug.size)
+    oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
+                                    np.float32(0.01), np.float32(1e-8))
+    if dtype == "f32":
         assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows with long segments")
-        if opt == "adagrad":
-            assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state with long segments")
-        c.close()
+    else:
+        from gpu_harness import assert_bf16_within
+        assert_bf16_within(c.pinned_rows()[ug], nr, "bf16 rows with long segments")
+    if opt == "adagrad":
+        assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state with long segments")
+    c.close()
 
 
 def test_empty_bags_and_ragged_lengths():
