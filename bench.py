@@ -292,6 +292,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="multi_hot", choices=synth.WORKLOAD_NAMES)
     ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--row-scale", type=float, default=None,
+                    help="shrink table rows and budget only (default 1.0; 0.5 for host_spill, whose 102 GB of "
+                         "tables exceed what one box lets a process pin, about 64 GB)")
     ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident", dest="resident", action="store_false",
@@ -304,7 +307,8 @@ def main():
     binding.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = synth.workload(args.workload, scale=args.scale)
+    row_scale = args.row_scale if args.row_scale is not None else (0.5 if args.workload == "host_spill" else 1.0)
+    wl = synth.workload(args.workload, scale=args.scale, row_scale=row_scale)
     budget = wl.budget_bytes if args.budget_bytes < 0 else args.budget_bytes
     cal = calibration(dev)
     link = measure_link(dev)
@@ -343,7 +347,7 @@ def main():
         "value": leg["value"], "unit": "lookups/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": leg["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 sums", "data": "synthetic",
-        "config": {"workload": wl.name, "scale": args.scale, "tables": wl.num_tables, "rows": wl.total_rows,
+        "config": {"workload": wl.name, "scale": args.scale, "row_scale": row_scale, "tables": wl.num_tables, "rows": wl.total_rows,
                    "dim": wl.dim, "batch": wl.batch, "lookups_per_step": leg["lookups_per_step"], "zipf_s": wl.zipf_s,
                    "budget_bytes": budget, "cached_rows": bc["k"], "optimizer": wl.optimizer,
                    "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],

@@ -86,7 +86,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
                                                       int64_t L, const uint32_t* __restrict__ blk_head,
                                                       const int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start,
                                                       int32_t* __restrict__ unique_gid, int32_t* __restrict__ sorted_gid,
-                                                      int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run) {
+                                                      int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run,
+                                                      const int32_t* __restrict__ slot_of, uint32_t N,
+                                                      int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag) {
     __shared__ uint32_t s_a[4];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     bool hd[kRoundsS];
@@ -106,8 +108,13 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
         const uint64_t m = ballot64(hd[r]);
         if (hd[r]) {
             const uint32_t u = before + (uint32_t)rank_below(m);
+            const uint32_t gk = key[j];
             seg_start[u] = (int32_t)j;
-            unique_gid[u] = (int32_t)key[j];
+            unique_gid[u] = (int32_t)gk;
+            // for the update kernel: where the row lives and which gradient row comes first, so that it can
+            // issue the row fetch and the first gradient fetch at once
+            unique_slot[u] = gk < N ? slot_of[gk] : -1;
+            first_bag[u] = val[j];
         }
         // each round is one chunk of kLongRunMin (= 64) positions: remember which run its first position is in
         if (lane_id() == 0 && j < L) chunk_run[j / kLongRunMin] = (int32_t)(before + (hd[r] ? 1u : 0u)) - 1;
@@ -137,8 +144,7 @@ template <int DTYPE, int OPT>
 struct RowRef {
     void* w;
     float* s;
-    __device__ __forceinline__ void locate(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid) {
-        const int32_t slot = A.slot_of[gid];
+    __device__ __forceinline__ void locate(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid, int32_t slot) {
         s = nullptr;
         if (slot >= 0) {
             w = (char*)A.cache + (int64_t)slot * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
@@ -221,6 +227,7 @@ __device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, cons
 template <int DTYPE, int OPT, int LPG>
 __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                                      const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
+                                                     const int32_t* __restrict__ unique_slot, const uint32_t* __restrict__ first_bag,
                                                      const float* __restrict__ grad, UpdateArgs A) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = A.meta->num_tables;
@@ -235,13 +242,17 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
     for (int64_t r = (int64_t)blockIdx.x * (kBlock / LPG) + threadIdx.x / LPG; r < U; r += ngroups) {
         const int32_t a = seg_start[r], b = seg_start[r + 1];
         const uint32_t gid = (uint32_t)unique_gid[r];
+        const int32_t slot = unique_slot[r];
+        const uint32_t bag0 = min(first_bag[r], A.Gm1);
         if (b - a > kLongRun || gid >= A.N) continue;
+        // the row, its accumulator and the first gradient row are all addressable now: one round trip
         RowRef<DTYPE, OPT> ref;
-        ref.locate(A, s_rbase, T, (int32_t)gid);
+        ref.locate(A, s_rbase, T, (int32_t)gid, slot);
         float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
         ref.load(c, wv, sv);
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        sum_grads<kGradUnroll>(val, g4, dq, c, a, b, A.Gm1, acc);
+        const float4 g0 = g4[(int64_t)bag0 * dq + c];
+        double acc[4] = {(double)g0.x, (double)g0.y, (double)g0.z, (double)g0.w};
+        if (b - a > 1) sum_grads<kGradUnroll>(val, g4, dq, c, a + 1, b, A.Gm1, acc);
         ref.step_and_store(A, c, wv, sv, acc);
     }
 }
@@ -267,8 +278,8 @@ __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmc
 template <int DTYPE, int OPT, int LPG>
 __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                      const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
-                                                     const int32_t* __restrict__ unique_gid, const int32_t* __restrict__ chunk_run,
-                                                     const float* __restrict__ grad, double* __restrict__ partial,
+                                                     const int32_t* __restrict__ unique_gid, const int32_t* __restrict__ unique_slot,
+                                                     const int32_t* __restrict__ chunk_run, const float* __restrict__ grad, double* __restrict__ partial,
                                                      int32_t* __restrict__ done, UpdateArgs A) {
     // no LDS copy of the table bounds here: most groups leave after a few loads, and only the group that
     // combines a run needs them (read from the descriptor in global memory then)
@@ -317,7 +328,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
             const uint32_t gid = (uint32_t)unique_gid[r];
             if (!lane_on || gid >= A.N) continue;
             RowRef<DTYPE, OPT> ref;
-            ref.locate(A, s_rbase, T, (int32_t)gid);
+            ref.locate(A, s_rbase, T, (int32_t)gid, unique_slot[r]);
             float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
             ref.load(c, wv, sv);
             double g[4] = {0.0, 0.0, 0.0, 0.0};
@@ -350,12 +361,12 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, const uint32_t* key,
     {
         Timed t(h, s, "seg_long");
         hipLaunchKernelGGL((k_seg_long<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, val, nu, seg_start,
-                           unique_gid, ws.chunk_run, grad, ws.partial, ws.task_done, A);
+                           unique_gid, ws.unique_slot, ws.chunk_run, grad, ws.partial, ws.task_done, A);
     }
     {
         Timed t(h, s, "seg_rows");
         hipLaunchKernelGGL((k_seg_rows<DTYPE, OPT, LPG>), dim3(rows_blocks), dim3(kBlock), 0, s, val, nu, seg_start,
-                           unique_gid, grad, A);
+                           unique_gid, ws.unique_slot, ws.first_bag, grad, A);
     }
 }
 
@@ -408,7 +419,8 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     {
         Timed t(h, s, "seg_write");
         hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, n_unique, seg_start,
-                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run);
+                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run,
+                           h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag);
     }
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};

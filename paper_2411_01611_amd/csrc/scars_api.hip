@@ -69,6 +69,8 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.seg_start = (int32_t*)take((max_L + 1) * 4);
     w.unique_gid = (int32_t*)take(max_L * 4);
     w.n_unique = (int32_t*)take(16);
+    w.unique_slot = (int32_t*)take(max_L * 4);
+    w.first_bag = (uint32_t*)take(max_L * 4);
     const int64_t chunks = nbL * (kScanTile / kLongRunMin);    // whole scan tiles: the counters are cleared per tile
     w.partial = (double*)take(chunks * 2 * h->D * 8);
     w.task_done = (int32_t*)take(chunks * 2 * 4);

@@ -54,6 +54,8 @@ struct Workspace {
     int32_t* seg_start;       // [max_L + 1] (used when the caller passes no bwd_out)
     int32_t* unique_gid;      // [max_L]
     int32_t* n_unique;        // [2]
+    int32_t* unique_slot;     // [max_L] cache slot (or -1) of each distinct row of the batch
+    uint32_t* first_bag;      // [max_L] bag of the first lookup of each distinct row
     double* partial;          // [chunks][2][D] fp64 partial sums of long runs, chunks of kLongRunMin sorted positions
     int32_t* task_done;       // [chunks rounded up to whole scan tiles][2] completion counters
     int32_t* chunk_run;       // [chunks + 1] run (segment) index that holds each chunk's first position

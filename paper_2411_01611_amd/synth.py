@@ -167,8 +167,9 @@ def _scale_to_total(rows: List[int], total: int, lo: int, hi: int) -> List[int]:
     return res
 
 
-def workload(name: str, scale: float = 1.0, seed: int = BASE_SEED, **over) -> Workload:
-    """The five benchmark workloads; `scale` < 1 shrinks rows, batch and budget together."""
+def workload(name: str, scale: float = 1.0, seed: int = BASE_SEED, row_scale: float = 1.0, **over) -> Workload:
+    """The five benchmark workloads; `scale` < 1 shrinks rows, batch and budget together, `row_scale` < 1
+    shrinks rows and budget only (same batch shape, same budget-to-bytes ratio)."""
     if name == "tiny":
         rows = [10_000] * 4
         wl = Workload(name, tuple(rows), 16, "f32", 256, None, 1.05,
@@ -199,6 +200,10 @@ def workload(name: str, scale: float = 1.0, seed: int = BASE_SEED, **over) -> Wo
         frac = wl.budget_bytes / float(wl.total_rows * wl.row_bytes)
         wl = replace(wl, rows=rows, batch=max(8, int(wl.batch * scale)),
                      budget_bytes=int(frac * sum(rows)) * wl.row_bytes)
+    if row_scale != 1.0:
+        rows = tuple(max(4, int(r * row_scale)) for r in wl.rows)
+        frac = wl.budget_bytes / float(wl.total_rows * wl.row_bytes)
+        wl = replace(wl, rows=rows, budget_bytes=int(frac * sum(rows)) * wl.row_bytes)
     if over:
         wl = replace(wl, **over)
     return wl

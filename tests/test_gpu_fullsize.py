@@ -1,0 +1,126 @@
+"""Parity at the benchmark's full size and launch configuration (workload `multi_hot`: 8 tables x 5M rows x
+dim 128 fp32, batch 4096, bags 1+Poisson(19), 2 GB cache, Adagrad), against the CPU oracle working on the same
+pinned tables.  Tables and batches are generated on the GPU by the seeded generators (as bench.py does).
+
+Checked: histogram and hot set bit-exact over all 40M rows; remap lists bit-exact; every pooled output within
+tolerance; sorted segments bit-exact; every updated row and accumulator within tolerance after a flush;
+rows without a lookup untouched (sampled); the step run again on the next batch.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2411_01611_amd import binding, synth
+from gpu_harness import assert_close
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def full():
+    dev = torch.device("cuda:0")
+    wl = synth.workload("multi_hot")
+    _say("allocating and filling", wl.total_rows * wl.row_bytes * 2 / 1e9, "GB pinned")
+    tabs, state = [], []
+    for t in range(wl.num_tables):
+        p = binding.PinnedArray((wl.rows[t], wl.dim), np.float32)
+        chunk = 1 << 20
+        for r0 in range(0, wl.rows[t], chunk):
+            r1 = min(wl.rows[t], r0 + chunk)
+            p.copy_from_device(synth.row_values(wl, t, r0, r1, dev).contiguous(), r0)
+            torch.cuda.synchronize()
+        s = binding.PinnedArray((wl.rows[t], wl.dim), np.float32)
+        s.np[...] = 0.0
+        tabs.append(p)
+        state.append(s)
+    sc = binding.Scars(wl.rows, wl.dim, binding.DTYPE_F32, [p.ptr for p in tabs], binding.OPT_ADAGRAD,
+                       [p.ptr for p in state])
+    smp = synth.Sampler(wl, dev)
+    yield wl, dev, tabs, state, sc, smp
+    sc.close()
+    for p in tabs + state:
+        p.free()
+
+
+@pytest.mark.timeout(900)
+def test_full_size_path_matches_oracle(full):
+    wl, dev, tabs, state, sc, smp = full
+    P = 8                                                     # profile batches (5.2M lookups)
+    prof = [smp.batch(p, True) for p in range(P)]
+    batches = [smp.batch(e) for e in range(2)]
+    max_L = max(int(b[0].numel()) for b in prof + batches)
+    sc.bind_buffers(wl.budget_bytes, max_L, wl.num_bags)
+    # ---- build_cache
+    counts = np.zeros(wl.total_rows, dtype=np.uint32)
+    sc.build_cache(None, None, 0, wl.budget_bytes, 0)
+    for n, (idx, off) in enumerate(prof):
+        rc, counts = oracle.histogram(wl.rows, idx.cpu().numpy(), off.cpu().numpy(), wl.batch, counts)
+        assert rc == 0
+        sc.build_cache(idx, off, wl.batch, wl.budget_bytes, 1 if n == P - 1 else 2)
+    assert sc.sync_status() == 0
+    _say("oracle hot set over", wl.total_rows, "rows")
+    k = oracle.budget_rows(wl.total_rows, wl.row_bytes, wl.budget_bytes)
+    assert k == 3_906_250 == sc.cache_rows()
+    rc, hot, slot_of = oracle.hot_set(counts, k)
+    assert np.array_equal(sc.counts().cpu().numpy().view(np.uint32), counts)
+    assert np.array_equal(sc.hot_gid().cpu().numpy(), hot)
+    assert np.array_equal(sc.slot_of().cpu().numpy(), slot_of)
+    ora_tabs = [p.np for p in tabs]          # the oracle reads the same pinned tables, in report mode, before each GPU step
+    sample = np.random.default_rng(0).integers(0, k, 4096)
+    rb = wl.row_base
+    got = sc.cache()[torch.from_numpy(sample).to(dev)].cpu().numpy()
+    for j, s in enumerate(sample):
+        g = int(hot[s]); t = int(np.searchsorted(rb, g, side="right") - 1)
+        assert np.array_equal(got[j], ora_tabs[t][g - rb[t]])
+    # ---- two steps
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps)
+    for step, (idx, off) in enumerate(batches):
+        _say("step", step)
+        hi, ho = idx.cpu().numpy(), off.cpu().numpy()
+        grad = smp.grads(step)
+        hg = grad.cpu().numpy()
+        rc, slot, hit, miss, mg = oracle.remap(wl.rows, hi, ho, wl.batch, slot_of)
+        rc2, want = oracle.embedding_bag_fwd(wl.rows, ora_tabs, hi, ho, wl.batch)
+        rc3, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, hi, ho, wl.batch)
+        rc4, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, ora_tabs, [p.np for p in state], 1, hi, ho, wl.batch,
+                                                          hg, lr, eps, report=True, n_unique=ug.size)
+        assert rc == rc2 == rc3 == rc4 == 0
+        # untouched-row sample taken before the GPU step
+        rng = np.random.default_rng(step + 1)
+        probe = rng.integers(0, wl.total_rows, 20000)
+        probe = probe[~np.isin(probe, ug)]
+        pt = np.searchsorted(rb, probe, side="right") - 1
+        before = np.stack([ora_tabs[t][g - rb[t]] for g, t in zip(probe[:2000], pt[:2000])])
+        L = idx.numel()
+        rm = sc.remap(idx, off, wl.batch)
+        out = sc.embedding_bag_fwd(idx, off, wl.batch, rm)
+        bo = sc.new_bwd_out(L)
+        sc.embedding_bag_bwd_update(idx, off, wl.batch, rm, grad, float(lr), float(eps), bo)
+        sc.flush_cache()
+        assert sc.sync_status() == 0
+        assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size] and hit.size + miss.size == L
+        assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
+        assert np.array_equal(rm.hit_pos.cpu().numpy()[: hit.size], hit)
+        assert np.array_equal(rm.miss_pos.cpu().numpy()[: miss.size], miss)
+        assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
+        assert_close(out.cpu().numpy(), want, "pooled output at full size")
+        U, nv = bo.n_unique.cpu().tolist()
+        assert U == ug.size and nv == sg.size
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+        assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+        # every touched row and accumulator (the pinned tables were updated in place by the GPU and flushed)
+        ut = np.searchsorted(rb, ug, side="right") - 1
+        for t in range(wl.num_tables):
+            sel = ut == t
+            rows_t = ug[sel] - rb[t]
+            assert_close(tabs[t].np[rows_t], nr[sel].astype(np.float32), f"updated rows of table {t}")
+            assert_close(state[t].np[rows_t], ns[sel].astype(np.float32), f"accumulators of table {t}")
+        after = np.stack([ora_tabs[t][g - rb[t]] for g, t in zip(probe[:2000], pt[:2000])])
+        assert np.array_equal(before, after), "rows without a lookup must not change"
