@@ -176,6 +176,7 @@ def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> 
     return {
         "pool_wave": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
         "pool_group": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
+        "pool_short": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
         "stage_misses": 2 * n_miss * R + 4 * n_miss,          # link read + HBM write
         "seg_reduce": L * D * 4 + 8 * L + U * (2 * R + st),
         "remap_probe": 16 * L,
@@ -225,7 +226,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
                       "ms_per_step": round(r["total_ms"] / K, 5)}
         if name in alg:
             kern[name]["alg_GBs"] = round(alg[name] / (avg_ms * 1e-3) / 1e9, 1)
-    pool = "pool_wave" if "pool_wave" in prof else "pool_group"
+    pool = [n for n in ("pool_wave", "pool_group", "pool_short") if n in prof][0]
     pool_avg_s = prof[pool]["total_ms"] / prof[pool]["launches"] * 1e-3
     achieved = alg[pool] / pool_avg_s / 1e9
     roofline = {"kernel": pool, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

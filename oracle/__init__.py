@@ -109,6 +109,19 @@ def remap(rows, indices, offsets, B: int, slot_of: np.ndarray):
     return rc, None, None, None, None
 
 
+def classify_samples(rows, indices, offsets, B: int, slot_of: np.ndarray):
+    rows = _rows(rows); indices = _i32(indices); offsets = _i32(offsets); slot_of = _i32(slot_of)
+    T = _LB(rows, offsets, B)
+    is_hot = np.empty(max(B, 1), dtype=np.int32); hot = np.empty(max(B, 1), dtype=np.int32)
+    normal = np.empty(max(B, 1), dtype=np.int32)
+    n = np.zeros(2, dtype=np.int64)
+    rc = lib().ora_classify_samples(C.c_int32(T), _p(rows), _p(indices), _p(offsets), C.c_int64(indices.shape[0]),
+                                    C.c_int64(B), _p(slot_of), _p(is_hot), _p(hot), _p(normal), _p(n))
+    if rc in (OK, ERR_INDEX_RANGE):
+        return rc, is_hot[:B].copy(), hot[: n[0]].copy(), normal[: n[1]].copy()
+    return rc, None, None, None
+
+
 def _dt(tables: Sequence[np.ndarray]) -> Tuple[int, int]:
     d = tables[0].dtype
     assert d in (np.float32, np.uint16), "rows are fp32, or bf16 held as uint16"

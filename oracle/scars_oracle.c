@@ -143,6 +143,35 @@ int32_t ora_remap(int32_t T, const int64_t* rows, const int32_t* indices, const 
     return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
 }
 
+/* ---- hot / normal samples ------------------------------------------------------------------------ */
+int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                             int64_t L, int64_t B, const int32_t* slot_of, int32_t* is_hot, int32_t* hot_ids,
+                             int32_t* normal_ids, int64_t* n_out) {
+    int rc = check_batch(T, rows, indices, offsets, L, B);
+    if (rc) return rc;
+    if (!slot_of || !n_out || (B > 0 && (!is_hot || !hot_ids || !normal_ids))) return ORA_ERR_INVALID_ARG;
+    int64_t* rb = make_row_base(T, rows);
+    int64_t nh = 0, nn = 0;
+    int bad = 0;
+    for (int64_t b = 0; b < B; ++b) {
+        int hot = 1;
+        for (int32_t t = 0; t < T; ++t) {
+            int64_t g = (int64_t)t * B + b;
+            for (int64_t i = offsets[g]; i < offsets[g + 1]; ++i) {
+                int64_t idx = indices[i];
+                if (idx < 0 || idx >= rows[t]) { bad = 1; continue; }
+                if (slot_of[rb[t] + idx] < 0) hot = 0;
+            }
+        }
+        is_hot[b] = hot;
+        if (hot) hot_ids[nh++] = (int32_t)b; else normal_ids[nn++] = (int32_t)b;
+    }
+    n_out[0] = nh;
+    n_out[1] = nn;
+    free(rb);
+    return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
+}
+
 /* ---- forward ----------------------------------------------------------------------------- */
 static int32_t fwd_impl(int32_t T, const int64_t* rows, int32_t D, int32_t dtype, const void* const* tables,
                         const int32_t* slot_of, const void* cache, const int32_t* indices,

@@ -66,6 +66,13 @@ int32_t ora_embedding_bag_fwd_cached(int32_t T, const int64_t* rows, int32_t D, 
                                      const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
                                      float* out);
 
+/* Hot / normal samples (Section III): a sample is hot when every one of its lookups, over all T tables, falls
+ * in the cached set (a sample without lookups is hot); is_hot[b] = 1/0, hot_ids / normal_ids list the sample
+ * ids of each class in ascending order, n_out = {n_hot, n_normal}. */
+int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                             int64_t L, int64_t B, const int32_t* slot_of, int32_t* is_hot /* [B] */,
+                             int32_t* hot_ids /* [B] */, int32_t* normal_ids /* [B] */, int64_t* n_out /* [2] */);
+
 /* Lookups ordered by (gid, position): sorted_gid, sorted_bag (bag of each lookup), seg_start[r] = first
  * sorted position of the r-th distinct gid (seg_start[U] = number of valid lookups), unique_gid ascending. */
 int32_t ora_bwd_segments(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,

@@ -86,22 +86,13 @@ __device__ __forceinline__ void store_chunk(const Chunk<DTYPE>& acc, float* __re
         o[q] = make_float4(acc.v[4 * q], acc.v[4 * q + 1], acc.v[4 * q + 2], acc.v[4 * q + 3]);
 }
 
-// one group of LPR lanes per bag
+// Sum of the rows at positions [a, b) by one group of LPR lanes (lane c holds 16-byte piece c of the row).
+// The group's lanes fetch LPR locations with one load and hand them out by shuffles, so the row addresses of a
+// whole window are known before the first row arrives; positions are added in order.
 template <int DTYPE, int LPR>
-__global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict__ off, int64_t G, int32_t L,
-                                                       const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
-                                                       const uint4* __restrict__ staging, int32_t k, int chunks, int D,
-                                                       float* __restrict__ out) {
-    const int64_t g = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
-    const int c = threadIdx.x % LPR;
-    if (g >= G) return;
-    const int32_t a = min(max(off[g], 0), L);
-    const int32_t b = min(max(off[g + 1], a), L);
-    Chunk<DTYPE> acc;
-    acc.zero();
-    const bool lane_on = c < chunks;
-    // the group's lanes fetch LPR locations of the bag with one load and hand them out by shuffles, so the row
-    // addresses of a whole window are known before the first row arrives (positions are summed in order)
+__device__ __forceinline__ void pool_range(Chunk<DTYPE>& acc, int32_t a, int32_t b, const int32_t* __restrict__ loc,
+                                           const uint4* __restrict__ cache, const uint4* __restrict__ staging, int32_t k,
+                                           int chunks, int c, bool lane_on) {
     const int gl0 = (lane_id() / LPR) * LPR;                     // first lane of this group inside the wave
     for (int32_t w0 = a; w0 < b; w0 += LPR) {
         const int32_t n = min((int32_t)LPR, b - w0);
@@ -124,7 +115,70 @@ __global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict
                 if (on[u]) acc.add(row[u]);
         }
     }
+}
+
+// one group of LPR lanes per bag
+template <int DTYPE, int LPR>
+__global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict__ off, int64_t G, int32_t L,
+                                                       const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                       const uint4* __restrict__ staging, int32_t k, int chunks, int D,
+                                                       float* __restrict__ out) {
+    const int64_t g = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
+    const int c = threadIdx.x % LPR;
+    if (g >= G) return;
+    const int32_t a = min(max(off[g], 0), L);
+    const int32_t b = min(max(off[g + 1], a), L);
+    Chunk<DTYPE> acc;
+    acc.zero();
+    pool_range<DTYPE, LPR>(acc, a, b, loc, cache, staging, k, chunks, c, c < chunks);
     if (c < chunks) store_chunk<DTYPE>(acc, out, g, D, c);
+}
+
+// Bags of one or two lookups (one index per sample and table): a group has nothing to overlap inside a bag, so
+// it takes kShortBags bags at once -- their offsets, then their first locations, then their first rows are
+// each fetched together.  Lookups beyond the first of a bag are added afterwards, in order.
+constexpr int kShortBags = 4;
+
+template <int DTYPE, int LPR>
+__global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict__ off, int64_t G, int32_t L,
+                                                       const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                       const uint4* __restrict__ staging, int32_t k, int chunks, int D,
+                                                       float* __restrict__ out) {
+    const int64_t TG = (G + kShortBags - 1) / kShortBags;        // groups; group gi takes bags gi, gi + TG, ...
+    const int64_t gi = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
+    const int c = threadIdx.x % LPR;
+    if (gi >= TG) return;
+    const bool lane_on = c < chunks;
+    int32_t a[kShortBags], b[kShortBags], l0[kShortBags];
+#pragma unroll
+    for (int q = 0; q < kShortBags; ++q) {
+        const int64_t g = gi + q * TG;
+        a[q] = b[q] = 0;
+        if (g < G) {
+            a[q] = min(max(off[g], 0), L);
+            b[q] = min(max(off[g + 1], a[q]), L);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kShortBags; ++q) l0[q] = b[q] > a[q] ? loc[a[q]] : -1;
+    uint4 row[kShortBags];
+#pragma unroll
+    for (int q = 0; q < kShortBags; ++q) {
+        if (lane_on && l0[q] >= 0) {
+            const uint4* p = l0[q] < k ? cache + (int64_t)l0[q] * chunks : staging + (int64_t)(l0[q] - k) * chunks;
+            row[q] = p[c];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kShortBags; ++q) {
+        const int64_t g = gi + q * TG;
+        if (g >= G) continue;
+        Chunk<DTYPE> acc;
+        acc.zero();
+        if (lane_on && l0[q] >= 0) acc.add(row[q]);
+        if (b[q] - a[q] > 1) pool_range<DTYPE, LPR>(acc, a[q] + 1, b[q], loc, cache, staging, k, chunks, c, lane_on);
+        if (lane_on) store_chunk<DTYPE>(acc, out, g, D, c);
+    }
 }
 
 // one wave per bag; its 64/LPR groups take every (64/LPR)-th lookup and combine by a shuffle tree
@@ -174,9 +228,13 @@ __global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict_
 }
 
 template <int DTYPE, int LPR>
-static void launch_pool_t(hipStream_t s, bool wave_mode, const int32_t* off, int64_t G, int64_t L, const int32_t* loc,
+static void launch_pool_t(hipStream_t s, int mode, const int32_t* off, int64_t G, int64_t L, const int32_t* loc,
                           const void* cache, const void* staging, int64_t k, int chunks, int D, float* out) {
-    if (wave_mode) {
+    if (mode == 2) {
+        const int64_t TG = div_up(G, kShortBags);
+        hipLaunchKernelGGL((k_pool_short<DTYPE, LPR>), dim3((unsigned)div_up(TG * LPR, kBlock)), dim3(kBlock), 0, s, off,
+                           G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
+    } else if (mode == 1) {
         hipLaunchKernelGGL((k_pool_wave<DTYPE, LPR>), dim3((unsigned)div_up(G, kBlock / kWave)), dim3(kBlock), 0, s, off,
                            G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
     } else {
@@ -186,11 +244,11 @@ static void launch_pool_t(hipStream_t s, bool wave_mode, const int32_t* off, int
 }
 
 template <int DTYPE>
-static void launch_pool_d(int lpr, hipStream_t s, bool wave_mode, const int32_t* off, int64_t G, int64_t L,
+static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, int64_t G, int64_t L,
                           const int32_t* loc, const void* cache, const void* staging, int64_t k, int chunks, int D,
                           float* out) {
     switch (lpr) {
-#define SCARS_CASE(N) case N: launch_pool_t<DTYPE, N>(s, wave_mode, off, G, L, loc, cache, staging, k, chunks, D, out); break;
+#define SCARS_CASE(N) case N: launch_pool_t<DTYPE, N>(s, mode, off, G, L, loc, cache, staging, k, chunks, D, out); break;
         SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
 #undef SCARS_CASE
     }
@@ -209,13 +267,14 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
                            (u32x4*)h->ws.staging, chunks, lpr, h->buf.max_L);
     }
     if (G > 0) {
-        const bool wave_mode = lpr < 64 && L >= G * 2 * (kWave / lpr);
-        Timed t(h, s, wave_mode ? "pool_wave" : "pool_group");
+        // 2: bags of one or two lookups, several bags per lane group; 1: long bags, a wave per bag; 0: a group per bag
+        const int mode = L < 2 * G ? 2 : ((lpr < 64 && L >= G * 2 * (kWave / lpr)) ? 1 : 0);
+        Timed t(h, s, mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group"));
         if (h->dtype == SCARS_DTYPE_F32)
-            launch_pool_d<SCARS_DTYPE_F32>(lpr, s, wave_mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
+            launch_pool_d<SCARS_DTYPE_F32>(lpr, s, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
                                            chunks, h->D, out);
         else
-            launch_pool_d<SCARS_DTYPE_BF16>(lpr, s, wave_mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
+            launch_pool_d<SCARS_DTYPE_BF16>(lpr, s, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
                                             chunks, h->D, out);
     }
     return hipGetLastError();

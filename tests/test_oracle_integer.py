@@ -257,3 +257,39 @@ def test_errors(ora):
     assert rc == ora.ERR_INDEX_RANGE and sg.tolist() == [0, 5] and sb.tolist() == [0, 3] and ss.tolist() == [0, 1, 2]
     neg = np.array([0, -1, 2, 1], dtype=np.int32)
     assert ora.histogram(rows, neg, off, 2)[0] == ora.ERR_INDEX_RANGE
+
+
+# ------------------------------------------------------------------ hot / normal samples (Section III)
+def test_classify_samples_brute_force_and_invariants(ora):
+    for name, kw in (("tiny", {}), ("multi_hot", {"scale": 0.01})):
+        wl = synth.workload(name, **kw)
+        s, counts, hot, slot_of = _build(ora, wl)
+        idx, off = s.batch(0)
+        idx, off = idx.numpy(), off.numpy()
+        rc, is_hot, hot_ids, normal_ids = ora.classify_samples(wl.rows, idx, off, wl.batch, slot_of)
+        assert rc == 0
+        # numpy special case: misses per sample via bincount over (bag mod B)
+        gid = gids_of(wl, idx, off)
+        sample = bag_of(off, idx.shape[0]) % wl.batch
+        misses = np.bincount(sample, weights=(slot_of[gid] < 0), minlength=wl.batch)
+        assert np.array_equal(is_hot, (misses == 0).astype(np.int32))
+        assert hot_ids.size + normal_ids.size == wl.batch
+        assert np.array_equal(hot_ids, np.nonzero(is_hot)[0]) and np.array_equal(normal_ids, np.nonzero(is_hot == 0)[0])
+        assert 0 < hot_ids.size < wl.batch or name == "multi_hot"
+        # extreme caches: everything cached -> all hot; nothing cached -> none hot (every sample has a lookup)
+        rc, h_all, a, b = ora.classify_samples(wl.rows, idx, off, wl.batch, np.arange(wl.total_rows, dtype=np.int32))
+        assert h_all.all() and b.size == 0
+        rc, h_none, a, b = ora.classify_samples(wl.rows, idx, off, wl.batch, np.full(wl.total_rows, -1, dtype=np.int32))
+        assert not h_none.any() and a.size == 0
+
+
+def test_classify_samples_hand_case(ora):
+    rows = [3, 2]
+    B = 3
+    #            table 0: sample0 [0,1]  sample1 []  sample2 [2]     table 1: sample0 [1]  sample1 []  sample2 [0]
+    off = np.array([0, 2, 2, 3, 4, 4, 5], dtype=np.int32)
+    idx = np.array([0, 1, 2, 1, 0], dtype=np.int32)
+    slot_of = np.array([0, 1, -1, 2, 3], dtype=np.int32)      # only gid 2 (table 0 row 2) is not cached
+    rc, is_hot, hot_ids, normal_ids = ora.classify_samples(rows, idx, off, B, slot_of)
+    assert rc == 0 and is_hot.tolist() == [1, 1, 0]           # a sample without lookups needs no cold row: hot
+    assert hot_ids.tolist() == [0, 1] and normal_ids.tolist() == [2]
