@@ -115,6 +115,14 @@ typedef struct {
     int32_t* n_unique;    /* int32 [2] = {U, n_valid} */
 } scars_bwd_out;
 
+/* Outputs of scars_classify_samples, all DEVICE int32. */
+typedef struct {
+    int32_t* is_hot;        /* [B] 1 if every lookup of the sample is a hit (or it has none), else 0 */
+    int32_t* hot_ids;       /* [B] ids of hot samples, ascending; first n_hot entries valid */
+    int32_t* normal_ids;    /* [B] ids of the other samples, ascending; first n_normal entries valid */
+    int32_t* n_hot_normal;  /* [2] = {n_hot, n_normal}; n_hot + n_normal = B */
+} scars_classify_out;
+
 /* Lifecycle.  scars_create copies the descriptor (not the tables); scars_destroy frees only the handle. */
 int32_t scars_create(const scars_config* cfg, scars_handle** out);
 int32_t scars_destroy(scars_handle* h);
@@ -167,6 +175,12 @@ int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const
 int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
                                        int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
                                        float lr, float eps, const scars_bwd_out* out, void* stream);
+
+/* Hot / normal samples (Section III: samples that "only need hot embeddings" versus the rest, so that
+ * mini-batches of one kind can be composed).  Sample b is hot when none of its lookups over all T tables is a
+ * miss; invalid lookups are ignored.  `rm` must come from scars_remap on this batch. */
+int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
+                               const scars_classify_out* out, void* stream);
 
 /* Write every cached row (and Adagrad accumulator) back to its pinned host table. */
 int32_t scars_flush_cache(scars_handle* h, void* stream);

@@ -23,7 +23,7 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
-    "scars_cache_rows", "scars_remap", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
+    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_profile_enable", "scars_profile_read",
 )
@@ -60,6 +60,10 @@ class _BwdOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("sorted_gid", "sorted_bag", "seg_start", "unique_gid", "n_unique")]
 
 
+class _ClassifyOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("is_hot", "hot_ids", "normal_ids", "n_hot_normal")]
+
+
 class _KernelTime(C.Structure):
     _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double)]
 
@@ -86,6 +90,7 @@ def lib():
         L.scars_embedding_bag_fwd.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, vp]
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
+        L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
         L.scars_flush_cache.argtypes = [vp, vp]
         L.scars_sync_status.argtypes = [vp, vp]
         L.scars_last_error.argtypes = [vp]
@@ -186,6 +191,17 @@ class BwdOut:
     def c(self) -> _BwdOut:
         return _BwdOut(*[t.data_ptr() for t in (self.sorted_gid, self.sorted_bag, self.seg_start, self.unique_gid,
                                                 self.n_unique)])
+
+
+@dataclass
+class ClassifyOut:
+    is_hot: torch.Tensor
+    hot_ids: torch.Tensor
+    normal_ids: torch.Tensor
+    n_hot_normal: torch.Tensor
+
+    def c(self) -> _ClassifyOut:
+        return _ClassifyOut(*[t.data_ptr() for t in (self.is_hot, self.hot_ids, self.normal_ids, self.n_hot_normal)])
 
 
 class Scars:
@@ -322,6 +338,16 @@ class Scars:
         self._check(lib().scars_embedding_bag_bwd_update(self._h, self._i32(indices), self._i32(offsets), L, B,
                                                          C.byref(c), grad_out.data_ptr(), lr, eps,
                                                          C.byref(co) if co is not None else None, _stream()))
+        return out
+
+    def classify_samples(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,
+                         out: Optional[ClassifyOut] = None) -> ClassifyOut:
+        if out is None:
+            mk = lambda m: torch.empty(max(m, 1), dtype=torch.int32, device=self.device)
+            out = ClassifyOut(mk(B), mk(B), mk(B), mk(2))
+        c, co = rm.c(), out.c()
+        self._check(lib().scars_classify_samples(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
+                                                 C.byref(co), _stream()))
         return out
 
     def flush_cache(self) -> None:

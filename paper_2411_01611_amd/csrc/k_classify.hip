@@ -1,0 +1,97 @@
+// classify_samples: hot / normal samples of a batch and their stable partition.
+//
+// Section III of the paper sorts training samples into "hot" ones, which need only cached embeddings, and
+// "normal" ones, and composes mini-batches of one kind.  A sample is hot when none of its lookups, over all
+// tables, is a miss (a sample without lookups is hot).  One thread per sample reads the slots written by
+// remap; the sample ids of each class are then listed in ascending order by the same tile-count / scan /
+// write compaction as the hit and miss lists.
+#include "scars_dev.h"
+
+namespace scars {
+
+constexpr int kPerWaveC = kScanTile / (kBlock / kWave);   // 512 consecutive samples per wave
+constexpr int kRoundsC = kPerWaveC / kWave;               // 8 rounds of 64
+
+__global__ __launch_bounds__(kBlock) void k_cls_flag(const int32_t* __restrict__ off, int32_t L, int64_t B, int T,
+                                                     const int32_t* __restrict__ slot, const int32_t* __restrict__ gid,
+                                                     int32_t* __restrict__ is_hot, uint32_t* __restrict__ blk_hot,
+                                                     uint32_t* __restrict__ blk_normal) {
+    __shared__ uint32_t s_h[4], s_n[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveC;
+    uint32_t nh = 0, nn = 0;
+#pragma unroll 1
+    for (int r = 0; r < kRoundsC; ++r) {
+        const int64_t b = base + r * kWave + lane_id();
+        bool hot = true;
+        if (b < B) {
+            for (int t = 0; t < T; ++t) {
+                const int64_t g = (int64_t)t * B + b;
+                const int32_t a = min(max(off[g], 0), L);
+                const int32_t e = min(max(off[g + 1], a), L);
+                for (int32_t i = a; i < e; ++i)
+                    if (gid[i] >= 0 && slot[i] < 0) hot = false;
+            }
+            is_hot[b] = hot ? 1 : 0;
+        }
+        nh += (uint32_t)__popcll(ballot64(b < B && hot));
+        nn += (uint32_t)__popcll(ballot64(b < B && !hot));
+    }
+    if (lane_id() == 0) { s_h[wave_id()] = nh; s_n[wave_id()] = nn; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk_hot[blockIdx.x] = s_h[0] + s_h[1] + s_h[2] + s_h[3];
+        blk_normal[blockIdx.x] = s_n[0] + s_n[1] + s_n[2] + s_n[3];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_cls_write(const int32_t* __restrict__ is_hot, int64_t B,
+                                                      const uint32_t* __restrict__ blk_hot, const uint32_t* __restrict__ blk_normal,
+                                                      int32_t* __restrict__ hot_ids, int32_t* __restrict__ normal_ids) {
+    __shared__ uint32_t s_h[4], s_n[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveC;
+    int32_t f[kRoundsC];
+    uint32_t nh = 0, nn = 0;
+#pragma unroll
+    for (int r = 0; r < kRoundsC; ++r) {
+        const int64_t b = base + r * kWave + lane_id();
+        f[r] = b < B ? is_hot[b] : -1;
+        nh += (uint32_t)__popcll(ballot64(f[r] == 1));
+        nn += (uint32_t)__popcll(ballot64(f[r] == 0));
+    }
+    if (lane_id() == 0) { s_h[wave_id()] = nh; s_n[wave_id()] = nn; }
+    __syncthreads();
+    uint32_t hb = blk_hot[blockIdx.x], nb = blk_normal[blockIdx.x];
+    for (int w = 0; w < wave_id(); ++w) { hb += s_h[w]; nb += s_n[w]; }
+#pragma unroll
+    for (int r = 0; r < kRoundsC; ++r) {
+        const int64_t b = base + r * kWave + lane_id();
+        const uint64_t mh = ballot64(f[r] == 1), mn = ballot64(f[r] == 0);
+        if (f[r] == 1) hot_ids[hb + rank_below(mh)] = (int32_t)b;
+        else if (f[r] == 0) normal_ids[nb + rank_below(mn)] = (int32_t)b;
+        hb += (uint32_t)__popcll(mh);
+        nb += (uint32_t)__popcll(mn);
+    }
+}
+
+hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                           const scars_remap_out* rm, const scars_classify_out* out) {
+    Workspace& ws = h->ws;
+    const int nb = (int)std::max<int64_t>(1, div_up(B, kScanTile));
+    {
+        Timed t(h, s, "cls_flag");
+        hipLaunchKernelGGL(k_cls_flag, dim3(nb), dim3(kBlock), 0, s, off, (int32_t)L, B, h->T, rm->slot, rm->gid,
+                           out->is_hot, ws.blk_hit, ws.blk_miss);
+    }
+    {
+        Timed t(h, s, "cls_scan");
+        hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hot_normal);
+    }
+    {
+        Timed t(h, s, "cls_write");
+        hipLaunchKernelGGL(k_cls_write, dim3(nb), dim3(kBlock), 0, s, out->is_hot, B, ws.blk_hit, ws.blk_miss,
+                           out->hot_ids, out->normal_ids);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace scars

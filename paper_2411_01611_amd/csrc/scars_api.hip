@@ -37,7 +37,6 @@ Timed::~Timed() {
 
 // Lay the scratch arrays out in the caller's workspace blob.  With base == nullptr only sizes are computed.
 Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L, int64_t max_G) {
-    (void)max_G;
     Workspace w{};
     int64_t off = 0;
     auto take = [&](int64_t bytes) -> void* {
@@ -58,8 +57,9 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
         w.win_gid[i] = (int32_t*)take(k_cap * 4);
     }
     w.tstart = (int32_t*)take((SCARS_MAX_TABLES + 1) * 4);
-    w.blk_hit = (uint32_t*)take((nbL + 1) * 4);
-    w.blk_miss = (uint32_t*)take((nbL + 1) * 4);
+    const int64_t nbLG = std::max<int64_t>(nbL, div_up(max_G, kScanTile));
+    w.blk_hit = (uint32_t*)take((nbLG + 1) * 4);
+    w.blk_miss = (uint32_t*)take((nbLG + 1) * 4);
     w.sort_hist = (uint32_t*)take(kSortMaxBins * nbS * 4);
     w.sort_tot = (uint32_t*)take(kSortMaxBins * 4);
     for (int i = 0; i < 2; ++i) {
@@ -265,6 +265,19 @@ int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices
     hipError_t e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out);
     if (e != hipSuccess) return hip_fail(h, e, "embedding_bag_bwd_update");
     if (L > 0) h->dirty = true;
+    return SCARS_OK;
+}
+
+int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
+                               const scars_classify_out* out, void* stream) {
+    int32_t rc = check_batch(h, L > 0 ? (const int32_t*)d_offsets : nullptr, d_offsets, L, B, "classify_samples");
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "classify_samples: build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, rm, L, "classify_samples"))) return rc;
+    if (!out || !out->n_hot_normal || (B > 0 && (!out->is_hot || !out->hot_ids || !out->normal_ids)))
+        return fail(h, SCARS_ERR_INVALID_ARG, "classify_samples: classify_out has a null array");
+    hipError_t e = launch_classify(h, (hipStream_t)stream, d_offsets, L, B, rm, out);
+    if (e != hipSuccess) return hip_fail(h, e, "classify_samples");
     return SCARS_OK;
 }
 

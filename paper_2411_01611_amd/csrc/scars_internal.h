@@ -45,8 +45,8 @@ struct Workspace {
     int32_t* win_gid[2];      // [k]
     // per batch
     int32_t* tstart;          // [T + 1] first lookup of each table (copied from offsets)
-    uint32_t* blk_hit;        // [nbL + 1]
-    uint32_t* blk_miss;       // [nbL + 1]
+    uint32_t* blk_hit;        // [tiles of max(max_L, max_G) + 1] per-tile counts of the ordered compactions
+    uint32_t* blk_miss;       // same
     uint32_t* sort_hist;      // [kSortMaxBins * nbS] digit-major per-tile histogram, nbS tiles for max(max_L, k) pairs
     uint32_t* sort_tot;       // [kSortMaxBins]
     uint32_t* key_buf[2];     // [max_L]
@@ -125,6 +125,11 @@ hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t 
 // k_remap.hip
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out);
+// k_remap.hip (also used by k_classify.hip): exclusive scan of two per-tile count arrays, totals to out2[0..1]
+__global__ void k_remap_scan(uint32_t* a, uint32_t* b, int n, int32_t* out2);
+// k_classify.hip
+hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                           const scars_remap_out* rm, const scars_classify_out* out);
 // k_fwd.hip
 hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, float* out);

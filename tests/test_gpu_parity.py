@@ -210,3 +210,33 @@ def test_two_steps_in_a_row_match_oracle():
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after two steps")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after two steps")
     c.close()
+
+
+def test_classify_samples_parity(case):
+    """Hot / normal samples: flags and both id lists bit-exact, n_hot + n_normal = B."""
+    case.build()
+    wl = case.wl
+    idx, off = case.batch
+    rc, is_hot, hot_ids, normal_ids = oracle.classify_samples(wl.rows, idx.numpy(), off.numpy(), wl.batch, case.ora_slot_of)
+    assert rc == 0
+    d_idx, d_off = case.dev_batch()
+    rm = case.s.remap(d_idx, d_off, wl.batch)
+    co = case.s.classify_samples(d_idx, d_off, wl.batch, rm)
+    assert case.s.sync_status() == 0
+    nh, nn = co.n_hot_normal.cpu().tolist()
+    assert nh + nn == wl.batch and nh == hot_ids.size
+    assert np.array_equal(co.is_hot.cpu().numpy()[: wl.batch], is_hot)
+    assert np.array_equal(co.hot_ids.cpu().numpy()[:nh], hot_ids)
+    assert np.array_equal(co.normal_ids.cpu().numpy()[:nn], normal_ids)
+
+
+def test_classify_samples_extreme_budgets():
+    wl = _wl("multi_hot_small")
+    for budget, all_hot in ((0, False), (wl.total_rows * wl.row_bytes, True)):
+        c = GpuCase(wl, budget_bytes=budget)
+        c.build()
+        d_idx, d_off = c.dev_batch()
+        co = c.s.classify_samples(d_idx, d_off, wl.batch, c.s.remap(d_idx, d_off, wl.batch))
+        nh, nn = co.n_hot_normal.cpu().tolist()
+        assert (nh, nn) == ((wl.batch, 0) if all_hot else (0, wl.batch))
+        c.close()
