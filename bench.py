@@ -178,7 +178,7 @@ def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> 
         "pool_group": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
         "pool_short": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
         "stage_misses": 2 * n_miss * R + 4 * n_miss,          # link read + HBM write
-        "seg_reduce": L * D * 4 + 8 * L + U * (2 * R + st),
+        "seg_rows": L * D * 4 + 8 * L + U * (2 * R + st + 12),   # with seg_long: gradient rows + row read-modify-write
         "remap_probe": 16 * L,
         "remap_write": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss),
         "sort_scatter": 16 * L,
@@ -234,9 +234,11 @@ def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
                 "alg_bytes_per_launch": int(alg[pool]), "avg_launch_ms": round(pool_avg_s * 1e3, 5)}
     host_link = []
     state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
+    # forward: every missed lookup's row is read over the link.  backward: a cold row's value comes from the copy
+    # the forward pass staged, so only its accumulator is read over the link; row and accumulator are written back
     for name, rd, wr in (("stage_misses", n_miss * wl.row_bytes, 0),
-                         ("seg_reduce", U_cold * (wl.row_bytes + state_b), U_cold * (wl.row_bytes + state_b))):
-        if name in prof and rd > 0:
+                         ("seg_rows", U_cold * state_b, U_cold * (wl.row_bytes + state_b))):
+        if name in prof and rd + wr > 0:
             t_s = prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
             t_min = max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9))
             host_link.append({"kernel": name, "link_read_bytes": int(rd), "link_write_bytes": int(wr),

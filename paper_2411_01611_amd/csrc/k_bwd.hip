@@ -5,8 +5,8 @@
 // rest).  Here: (1) pairs (gid, bag) in position order; (2) stable radix sort by gid; (3) segment heads by
 // ordered compaction (the integer outputs); (4) one lane group per distinct row sums its run of
 // gradient rows and applies the update, with the row fetched while the gradients stream in; (5) a run of
-// more than 64 lookups is summed per 64-position chunk into fp64 partials that are added in chunk order by
-// whichever piece finishes last.  No floating-point atomics: results are bit-stable.
+// more than 64 lookups is summed per 64-position chunk into fp64 partials, which a following launch adds in
+// chunk order.  No floating-point atomics: results are bit-stable.
 #include "scars_dev.h"
 
 namespace scars {
@@ -45,12 +45,8 @@ __device__ __forceinline__ bool is_head(const uint32_t* __restrict__ key, int64_
 
 // per tile: number of heads and number of valid (non-sentinel) keys
 __global__ __launch_bounds__(kBlock) void k_seg_count(const uint32_t* __restrict__ key, int64_t L,
-                                                      uint32_t* __restrict__ blk_head, uint32_t* __restrict__ blk_valid,
-                                                      int32_t* __restrict__ done) {
+                                                      uint32_t* __restrict__ blk_head, uint32_t* __restrict__ blk_valid) {
     __shared__ uint32_t s_a[4], s_b[4];
-    // clear this tile's share of the long-run completion counters (2 per chunk of kLongRunMin positions)
-    constexpr int kDonePerTile = 2 * kScanTile / kLongRunMin;
-    if (threadIdx.x < kDonePerTile) done[(int64_t)blockIdx.x * kDonePerTile + threadIdx.x] = 0;
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     uint32_t nh = 0, nv = 0;
 #pragma unroll
@@ -88,7 +84,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
                                                       int32_t* __restrict__ unique_gid, int32_t* __restrict__ sorted_gid,
                                                       int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run,
                                                       const int32_t* __restrict__ slot_of, uint32_t N,
-                                                      int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag) {
+                                                      int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag,
+                                                      const int32_t* __restrict__ off, int64_t G, const int32_t* __restrict__ gid_of,
+                                                      const int32_t* __restrict__ loc_of, int32_t k, int staged) {
     __shared__ uint32_t s_a[4];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     bool hd[kRoundsS];
@@ -113,8 +111,18 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
             unique_gid[u] = (int32_t)gk;
             // for the update kernel: where the row lives and which gradient row comes first, so that it can
             // issue the row fetch and the first gradient fetch at once
-            unique_slot[u] = gk < N ? slot_of[gk] : -1;
-            first_bag[u] = val[j];
+            int32_t src = gk < N ? slot_of[gk] : -1;
+            const uint32_t bag = val[j];
+            if (src < 0 && staged && gk < N && (int64_t)bag < G) {
+                // a cold row: the forward pass of this batch left its value in the staging area, at the location
+                // of any of its lookups; the first lookup of the run is in bag `bag`, so search that bag
+                const int32_t a = min(max(off[bag], 0), (int32_t)L);
+                const int32_t b = min(max(off[bag + 1], a), (int32_t)L);
+                for (int32_t i = a; i < b; ++i)
+                    if ((uint32_t)gid_of[i] == gk) { src = loc_of[i] >= k ? loc_of[i] : -1; break; }
+            }
+            unique_slot[u] = src;
+            first_bag[u] = bag;
         }
         // each round is one chunk of kLongRunMin (= 64) positions: remember which run its first position is in
         if (lane_id() == 0 && j < L) chunk_run[j / kLongRunMin] = (int32_t)(before + (hd[r] ? 1u : 0u)) - 1;
@@ -135,6 +143,8 @@ struct UpdateArgs {
     float* state_cache;
     float lr, eps;
     int D;
+    const void* staging;  // rows fetched by the forward pass of this batch (null when not usable)
+    int32_t k;       // cached rows: a source index >= k is row (index - k) of the staging area
     uint32_t N;      // rows in all tables: a key at or above it is never dereferenced
     uint32_t Gm1;    // last bag: bag ids are clamped to it (both only matter after an offsets error)
 };
@@ -142,27 +152,33 @@ struct UpdateArgs {
 // Where a row lives: cache slot (HBM) or pinned host table; the Adagrad accumulator beside it.
 template <int DTYPE, int OPT>
 struct RowRef {
-    void* w;
+    void* w;          // where the updated row is written
+    const void* wr;   // where its current value is read
     float* s;
-    __device__ __forceinline__ void locate(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid, int32_t slot) {
+    // src: cache slot in [0, k); k + i = cold row whose current value is row i of the staging area (the copy the
+    // forward pass of this batch fetched, so the host link carries only the write); -1 = cold row read from host
+    __device__ __forceinline__ void locate(const UpdateArgs& A, const int32_t* s_rbase, int T, int32_t gid, int32_t src) {
         s = nullptr;
-        if (slot >= 0) {
-            w = (char*)A.cache + (int64_t)slot * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
-            if (OPT == SCARS_OPT_ADAGRAD) s = A.state_cache + (int64_t)slot * A.D;
+        constexpr int kElem = DTYPE == SCARS_DTYPE_F32 ? 4 : 2;
+        if (src >= 0 && src < A.k) {
+            w = (char*)A.cache + (int64_t)src * A.D * kElem;
+            wr = w;
+            if (OPT == SCARS_OPT_ADAGRAD) s = A.state_cache + (int64_t)src * A.D;
         } else {
             const int t = upper_table(s_rbase, T, gid);
             const int64_t row = gid - s_rbase[t];
-            w = (char*)A.meta->table[t] + row * A.D * (DTYPE == SCARS_DTYPE_F32 ? 4 : 2);
+            w = (char*)A.meta->table[t] + row * A.D * kElem;
+            wr = (src >= A.k && A.staging) ? (const void*)((const char*)A.staging + (int64_t)(src - A.k) * A.D * kElem) : w;
             if (OPT == SCARS_OPT_ADAGRAD) s = A.meta->state[t] + row * A.D;
         }
     }
     // lane owns columns [4c, 4c+4)
     __device__ __forceinline__ void load(int c, float (&wv)[4], float (&sv)[4]) const {
         if (DTYPE == SCARS_DTYPE_F32) {
-            const float4 v = ((const float4*)w)[c];
+            const float4 v = ((const float4*)wr)[c];
             wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
         } else {
-            const uint2 v = ((const uint2*)w)[c];
+            const uint2 v = ((const uint2*)wr)[c];
             wv[0] = __uint_as_float(v.x << 16); wv[1] = __uint_as_float(v.x & 0xFFFF0000u);
             wv[2] = __uint_as_float(v.y << 16); wv[3] = __uint_as_float(v.y & 0xFFFF0000u);
         }
@@ -204,20 +220,26 @@ struct RowRef {
 constexpr int kLongRun = kLongRunMin;   // runs up to this many lookups are summed by one lane group
 constexpr int kGradUnroll = 4;  // gradient rows in flight per lane group in the per-row kernel
 constexpr int kTaskUnroll = 8;  // ... and in a task of a long run (few groups, long chains: go wide)
-constexpr int kCombUnroll = 4;  // partial sums in flight when a long run is combined
+constexpr int kCombUnroll = 16; // partial sums in flight when a long run is combined
 
 // sum of grad rows val[j] for j in [p0, p1), columns [4c, 4c+4), in position order, fp64; UNROLL rows in flight
 template <int UNROLL>
 __device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, const float4* __restrict__ g4, int dq, int c,
                                           int32_t p0, int32_t p1, uint32_t Gm1, double (&acc)[4]) {
     for (int32_t j = p0; j < p1; j += UNROLL) {
+        // indices are clamped instead of guarded so that all bag loads, then all gradient loads, are issued
+        // back to back (a guarded load would wait for the previous one); surplus rows are not added
+        uint32_t bag[UNROLL];
         float4 gv[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            gv[u] = (j + u < p1) ? g4[(int64_t)min(val[j + u], Gm1) * dq + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < UNROLL; ++u) bag[u] = min(val[min(j + u, p1 - 1)], Gm1);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) gv[u] = g4[(int64_t)bag[u] * dq + c];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            acc[0] += (double)gv[u].x; acc[1] += (double)gv[u].y; acc[2] += (double)gv[u].z; acc[3] += (double)gv[u].w;
+            if (j + u < p1) {
+                acc[0] += (double)gv[u].x; acc[1] += (double)gv[u].y; acc[2] += (double)gv[u].z; acc[3] += (double)gv[u].w;
+            }
         }
     }
 }
@@ -257,44 +279,21 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
     }
 }
 
-// Partial sums travel between compute units through agent-scope (write-through / cache-bypassing) accesses
-// instead of full fences: an agent-scope release or acquire fence on this chip writes back or invalidates the
-// whole per-XCD L2, which costs tens of microseconds per use.
-__device__ __forceinline__ void store_agent(double* p, double v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double load_agent(const double* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// Runs longer than kLongRun.  One lane group per chunk of kLongRun sorted positions.  Such a run overlaps a
-// chunk either by covering its first position ("side 0") or by starting inside it and running past its end
-// ("side 1"); at most one of each per chunk.  The overlap is summed into partial[chunk][side]; the group that
-// completes a run's last outstanding piece adds that run's partials in chunk order and applies the update
-// (nobody waits: whoever finishes last combines).  done[] is indexed by the chunk in which the run starts
-// (two long runs cannot start in one chunk) and by 64-lane part for groups wider than a wave.  chunk_run[ch]
-// is the run that holds the chunk's first position.  Independent of k_seg_rows.
-template <int DTYPE, int OPT, int LPG>
+// Runs longer than kLongRun, first half: one lane group per chunk of kLongRun sorted positions.  Such a run
+// overlaps a chunk either by covering its first position ("side 0") or by starting inside it and running past
+// its end ("side 1"); at most one of each per chunk.  The overlap is summed into partial[chunk][side].
+// chunk_run[ch] is the run that holds the chunk's first position.  Independent of k_seg_rows.
+template <int LPG>
 __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                      const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
-                                                     const int32_t* __restrict__ unique_gid, const int32_t* __restrict__ unique_slot,
-                                                     const int32_t* __restrict__ chunk_run, const float* __restrict__ grad, double* __restrict__ partial,
-                                                     int32_t* __restrict__ done, UpdateArgs A) {
-    // no LDS copy of the table bounds here: most groups leave after a few loads, and only the group that
-    // combines a run needs them (read from the descriptor in global memory then)
-    const int32_t* s_rbase = A.meta->row_base;
-    const int T = A.meta->num_tables;
+                                                     const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
+                                                     double* __restrict__ partial, int D, uint32_t Gm1) {
     const int32_t Lv = n_unique[1];
     const int c = threadIdx.x % LPG;
-    const bool lane_on = c * 4 < A.D;
-    const int dq = A.D / 4;
+    const bool lane_on = c * 4 < D;
+    const int dq = D / 4;
     const float4* g4 = (const float4*)grad;
     constexpr int gpb = kBlock / LPG;
-    constexpr int kPartLanes = LPG < kWave ? LPG : kWave;          // lanes that share one completion counter
-    constexpr int kParts = LPG < kWave ? 1 : LPG / kWave;
-    const int part = c / kWave;
-    const int leader = (lane_id() / kPartLanes) * kPartLanes;       // first lane of this part inside its wave
     const int64_t ngroups = (int64_t)gridDim.x * gpb;
     const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
     for (int64_t ch = (int64_t)blockIdx.x * gpb + threadIdx.x / LPG; ch < nchunks; ch += ngroups) {
@@ -307,44 +306,65 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
         for (int side = 0; side < 2; ++side) {
             // a long run over this chunk must continue across one of its borders
             const bool cand = side == 0 ? (kp == k0 || kn == k0) : (k1 != k0 && kn == k1);
-            if (!cand) continue;
+            if (!cand || !lane_on) continue;
             const int32_t r = side == 0 ? r0 : r1;
             const int32_t a = seg_start[r], b = seg_start[r + 1];
             if (b - a <= kLongRun) continue;
-            if (lane_on) {
-                double acc[4] = {0.0, 0.0, 0.0, 0.0};
-                sum_grads<kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), A.Gm1, acc);
-                double* p = partial + ((int64_t)ch * 2 + side) * A.D + c * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) store_agent(p + e, acc[e]);
-            }
-            wait_stores_done();                                     // the partial sum has landed before the count
-            const int32_t first = a / kLongRun;
-            const int32_t pieces = (b - 1) / kLongRun - first + 1;
-            int32_t prev = 0;
-            if (lane_id() == leader) prev = atomicAdd(&done[first * kParts + part], 1);
-            prev = __shfl(prev, leader, kWave);
-            if (prev != pieces - 1) continue;                       // last one in combines; the others' sums have landed
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            sum_grads<kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
+            double* p = partial + ((int64_t)ch * 2 + side) * D + c * 4;
+            p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
+        }
+    }
+}
+
+// Second half, in a launch of its own so that the partial sums need no fences or atomics: the group of the
+// chunk in which a long run starts adds that run's partials in chunk order and applies the update.
+template <int DTYPE, int OPT, int LPG>
+__global__ __launch_bounds__(kBlock) void k_seg_combine(const uint32_t* __restrict__ key, const int32_t* __restrict__ n_unique,
+                                                        const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
+                                                        const int32_t* __restrict__ unique_slot, const int32_t* __restrict__ chunk_run,
+                                                        const double* __restrict__ partial, UpdateArgs A) {
+    const int32_t* s_rbase = A.meta->row_base;   // read from the descriptor: only the few combining groups need it
+    const int T = A.meta->num_tables;
+    const int32_t Lv = n_unique[1];
+    const int c = threadIdx.x % LPG;
+    if (c * 4 >= A.D) return;
+    constexpr int gpb = kBlock / LPG;
+    const int64_t ngroups = (int64_t)gridDim.x * gpb;
+    const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
+    for (int64_t ch = (int64_t)blockIdx.x * gpb + threadIdx.x / LPG; ch < nchunks; ch += ngroups) {
+        const int32_t j0 = (int32_t)ch * kLongRun, j1 = min(j0 + kLongRun, Lv);
+        if (j1 >= Lv) continue;                                  // a long run that starts here runs past j1
+        const uint32_t k0 = key[j0], k1 = key[j1 - 1], kn = key[j1];
+        const uint32_t kp = j0 > 0 ? key[j0 - 1] : ~k0;
+        for (int side = 0; side < 2; ++side) {
+            // side 0: a run that starts exactly at the chunk's first position; side 1: one that starts inside
+            const bool cand = side == 0 ? (kp != k0 && kn == k0) : (k1 != k0 && kn == k1);
+            if (!cand) continue;
+            const int32_t r = side == 0 ? chunk_run[ch] : chunk_run[ch + 1];
+            const int32_t a = seg_start[r], b = seg_start[r + 1];
+            if (b - a <= kLongRun) continue;
             const uint32_t gid = (uint32_t)unique_gid[r];
-            if (!lane_on || gid >= A.N) continue;
+            if (gid >= A.N) continue;
             RowRef<DTYPE, OPT> ref;
             ref.locate(A, s_rbase, T, (int32_t)gid, unique_slot[r]);
             float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
             ref.load(c, wv, sv);
+            const int32_t pieces = (b - 1) / kLongRun - (int32_t)ch + 1;
             double g[4] = {0.0, 0.0, 0.0, 0.0};
-            const int first_side = (a % kLongRun) != 0 ? 1 : 0;     // the first piece starts inside its chunk?
             for (int32_t i = 0; i < pieces; i += kCombUnroll) {
-                double v[kCombUnroll][4];
+                double2 v[kCombUnroll][2];
 #pragma unroll
                 for (int u = 0; u < kCombUnroll; ++u) {
                     const int32_t ii = min(i + u, pieces - 1);
-                    const double* qq = partial + ((int64_t)(first + ii) * 2 + (ii == 0 ? first_side : 0)) * A.D + c * 4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[u][e] = load_agent(qq + e);
+                    const double2* qq = (const double2*)(partial + ((int64_t)(ch + ii) * 2 + (ii == 0 ? side : 0)) * A.D + c * 4);
+                    v[u][0] = qq[0];
+                    v[u][1] = qq[1];
                 }
 #pragma unroll
                 for (int u = 0; u < kCombUnroll; ++u)
-                    if (i + u < pieces) { g[0] += v[u][0]; g[1] += v[u][1]; g[2] += v[u][2]; g[3] += v[u][3]; }
+                    if (i + u < pieces) { g[0] += v[u][0].x; g[1] += v[u][0].y; g[2] += v[u][1].x; g[3] += v[u][1].y; }
             }
             ref.step_and_store(A, c, wv, sv, g);
         }
@@ -360,8 +380,13 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, const uint32_t* key,
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     {
         Timed t(h, s, "seg_long");
-        hipLaunchKernelGGL((k_seg_long<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, val, nu, seg_start,
-                           unique_gid, ws.unique_slot, ws.chunk_run, grad, ws.partial, ws.task_done, A);
+        hipLaunchKernelGGL((k_seg_long<LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, val, nu, seg_start, ws.chunk_run,
+                           grad, ws.partial, A.D, A.Gm1);
+    }
+    {
+        Timed t(h, s, "seg_combine");
+        hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
+                           unique_gid, ws.unique_slot, ws.chunk_run, ws.partial, A);
     }
     {
         Timed t(h, s, "seg_rows");
@@ -385,6 +410,9 @@ static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, const uint3
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out) {
     Workspace& ws = h->ws;
+    // rows fetched by this batch's forward pass are still in the staging area: cold rows are read from there
+    const bool use_staged = h->staged_valid && h->staged_loc == rm->loc;
+    h->staged_valid = false;   // this call changes the rows
     int32_t* n_unique = out ? out->n_unique : ws.n_unique;
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
     int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
@@ -410,7 +438,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int nb = (int)div_up(L, kScanTile);
     {
         Timed t(h, s, "seg_count");
-        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss, ws.task_done);
+        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss);
     }
     {
         Timed t(h, s, "seg_scan");
@@ -420,9 +448,11 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         Timed t(h, s, "seg_write");
         hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, n_unique, seg_start,
                            unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run,
-                           h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag);
+                           h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid, rm->loc,
+                           (int32_t)h->k, use_staged ? 1 : 0);
     }
-    UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D, (uint32_t)h->N,
+    UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
+                 use_staged ? ws.staging : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};
     const int lpg = next_pow2_host(h->D / 4);
     if (h->dtype == SCARS_DTYPE_F32) {

@@ -28,23 +28,22 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restri
     const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
     const int64_t stride = (int64_t)gridDim.x * gpb;
     const bool lane_on = gl < chunks;      // lpr >= chunks: one 16-byte piece per lane
+    if (!lane_on || n <= 0) return;
     for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
+        // row numbers are clamped instead of guarded so that the gid loads, then the row loads over the link,
+        // are all issued back to back; only rows below n are written
+        int32_t gid[kUnroll];
         u32x4 v[kUnroll];
-        bool on[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) gid[u] = miss_gid[min(j0 + u * stride, n - 1)];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int64_t j = j0 + u * stride;
-            v[u] = (u32x4)(0u);
-            on[u] = lane_on && j < n;
-            if (on[u]) {
-                const int32_t gid = miss_gid[j];
-                const int t = upper_table(s_rbase, T, gid);
-                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid - s_rbase[t]) * chunks + gl);
-            }
+            const int t = upper_table(s_rbase, T, gid[u]);
+            v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            if (on[u]) staging[(j0 + u * stride) * chunks + gl] = v[u];
+            if (j0 + u * stride < n) staging[(j0 + u * stride) * chunks + gl] = v[u];
     }
 }
 
@@ -259,6 +258,8 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int64_t G = (int64_t)h->T * B;
+    h->staged_valid = L > 0 && h->k < h->N;
+    h->staged_loc = rm->loc;
     if (L > 0 && h->k < h->N) {   // with every row cached there can be no miss
         Timed t(h, s, "stage_misses");
         const int gpb = kBlock / lpr;

@@ -39,25 +39,36 @@ __global__ __launch_bounds__(kBlock) void k_remap_probe(const int32_t* __restric
 
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
     uint32_t nh = 0, nm = 0;
+    // positions are clamped instead of guarded so that the index loads of all rounds, then the slot probes of
+    // all rounds, are issued back to back; only positions below L are written and counted
+    int32_t row[kRoundsR], g[kRoundsR], sl[kRoundsR];
+    const int64_t last = L - 1;
+    if (L > 0) {
+#pragma unroll
+        for (int r = 0; r < kRoundsR; ++r) row[r] = idx[min(base + r * kWave + lane_id(), last)];
+#pragma unroll
+        for (int r = 0; r < kRoundsR; ++r) {
+            const int64_t i = min(base + r * kWave + lane_id(), last);
+            const int t = upper_table(s_tstart, T, (int32_t)i);
+            const int32_t nrows = s_rbase[t + 1] - s_rbase[t];
+            g[r] = (row[r] < 0 || row[r] >= nrows) ? -1 : s_rbase[t] + row[r];
+        }
+#pragma unroll
+        for (int r = 0; r < kRoundsR; ++r) sl[r] = slot_of[max(g[r], 0)];
+    }
 #pragma unroll
     for (int r = 0; r < kRoundsR; ++r) {
         const int64_t i = base + r * kWave + lane_id();
         bool hit = false, miss = false;
         if (i < L) {
-            const int t = upper_table(s_tstart, T, (int32_t)i);
-            const int32_t row = idx[i];
-            const int32_t nrows = s_rbase[t + 1] - s_rbase[t];
-            int32_t g = -1, s = -1;
-            if (row < 0 || row >= nrows) {
+            if (g[r] < 0) {
                 latch_error(status, SCARS_ERR_INDEX_RANGE);
-            } else {
-                g = s_rbase[t] + row;
-                s = slot_of[g];
-                hit = s >= 0;
-                miss = !hit;
+                sl[r] = -1;
             }
-            slot[i] = s;
-            gid[i] = g;
+            hit = sl[r] >= 0;
+            miss = g[r] >= 0 && !hit;
+            slot[i] = sl[r];
+            gid[i] = g[r];
         }
         nh += (uint32_t)__popcll(ballot64(hit));
         nm += (uint32_t)__popcll(ballot64(miss));

@@ -73,7 +73,6 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.first_bag = (uint32_t*)take(max_L * 4);
     const int64_t chunks = nbL * (kScanTile / kLongRunMin);    // whole scan tiles: the counters are cleared per tile
     w.partial = (double*)take(chunks * 2 * h->D * 8);
-    w.task_done = (int32_t*)take(chunks * 2 * 4);
     w.chunk_run = (int32_t*)take((chunks + 1) * 4);
     w.staging = take(max_L * h->R);
     w.total_bytes = off;
@@ -153,7 +152,7 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     h->buf = *b;
     h->k_cap = k;
     h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);
-    h->bound = true; h->built = false; h->dirty = false; h->k = -1; h->profiled = 0;
+    h->bound = true; h->built = false; h->dirty = false; h->k = -1; h->profiled = 0; h->staged_valid = false;
     Meta* m = new Meta();
     std::memset(m, 0, sizeof(Meta));
     for (int t = 0; t < h->T; ++t) {
@@ -215,6 +214,7 @@ int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32
     h->profiled = before + (uint64_t)Lp;
     if (accumulate == 2) return SCARS_OK;
     h->built = false;
+    h->staged_valid = false;
     e = launch_select_and_fill(h, s, k);
     if (e != hipSuccess) return hip_fail(h, e, "build_cache(select)");
     h->built = true;
@@ -235,6 +235,7 @@ int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_
     if (rc) return rc;
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "remap: build_cache has not selected a hot set");
     if ((rc = check_remap_out(h, out, L, "remap"))) return rc;
+    if (out->loc == h->staged_loc) h->staged_valid = false;   // these arrays no longer describe the staged batch
     hipError_t e = launch_remap(h, (hipStream_t)stream, d_indices, d_offsets, L, B, out);
     if (e != hipSuccess) return hip_fail(h, e, "remap");
     return SCARS_OK;

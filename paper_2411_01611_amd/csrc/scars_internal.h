@@ -57,7 +57,6 @@ struct Workspace {
     int32_t* unique_slot;     // [max_L] cache slot (or -1) of each distinct row of the batch
     uint32_t* first_bag;      // [max_L] bag of the first lookup of each distinct row
     double* partial;          // [chunks][2][D] fp64 partial sums of long runs, chunks of kLongRunMin sorted positions
-    int32_t* task_done;       // [chunks rounded up to whole scan tiles][2] completion counters
     int32_t* chunk_run;       // [chunks + 1] run (segment) index that holds each chunk's first position
     void* staging;            // [max_L][R] rows fetched over the host link
     int64_t total_bytes;
@@ -88,6 +87,8 @@ struct scars_handle {
     bool dirty = false;                  // cache holds rows newer than the host tables
     int64_t k = -1;
     uint64_t profiled = 0;               // cumulative lookups histogrammed
+    bool staged_valid = false;           // the staging area holds the missed rows of the batch whose remap wrote staged_loc
+    const int32_t* staged_loc = nullptr;
     std::string err;
     // per-kernel timing
     bool profile = false;

@@ -258,3 +258,40 @@ def test_rebuild_after_updates_keeps_updated_rows():
     rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
     assert_close(out.cpu().numpy(), want, "forward after rebuild")
     c.close()
+
+
+def test_backward_never_reads_stale_staged_rows():
+    """The backward pass may take cold rows from the staging area filled by the forward pass of the same batch,
+    but not after the arrays were reused for another batch, nor after the rows were already updated once."""
+    wl = synth.workload("multi_hot", scale=0.004, batch=200)
+    c = GpuCase(wl)
+    c.build()
+    s = c.s
+    A, B2 = c.sampler.batch(0), c.sampler.batch(1)
+    grad = c.sampler.grads(0)
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps)
+    rm = s.new_remap_out()
+    dA, dB = [t.to(c.dev) for t in A], [t.to(c.dev) for t in B2]
+
+    def ora_step(batch):
+        oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1, batch[0].numpy(), batch[1].numpy(), wl.batch,
+                                        grad.numpy(), lr, eps)
+
+    # forward of A, then the same arrays are remapped for B and B is updated: A's staged rows must not be used
+    s.remap(dA[0], dA[1], wl.batch, rm)
+    s.embedding_bag_fwd(dA[0], dA[1], wl.batch, rm)
+    s.remap(dB[0], dB[1], wl.batch, rm)
+    s.embedding_bag_bwd_update(dB[0], dB[1], wl.batch, rm, grad.to(c.dev), float(lr), float(eps))
+    ora_step(B2)
+    # forward + backward of A (staged rows used), then a second backward of A without a new forward
+    s.remap(dA[0], dA[1], wl.batch, rm)
+    s.embedding_bag_fwd(dA[0], dA[1], wl.batch, rm)
+    s.embedding_bag_bwd_update(dA[0], dA[1], wl.batch, rm, grad.to(c.dev), float(lr), float(eps))
+    ora_step(A)
+    s.embedding_bag_bwd_update(dA[0], dA[1], wl.batch, rm, grad.to(c.dev), float(lr), float(eps))
+    ora_step(A)
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after interleaved batches")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after interleaved batches")
+    c.close()
