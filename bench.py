@@ -6,7 +6,7 @@ embedding_bag_bwd_update, with the workload's byte budget (hot rows in the HBM c
 memory).  build_cache runs once before the timed region (it is amortised over many batches) and is reported
 separately.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--resident] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -300,8 +300,9 @@ def main():
                          "tables exceed what one box lets a process pin, about 64 GB)")
     ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-resident", dest="resident", action="store_false",
-                    help="skip the second leg in which every row is cached")
+    ap.add_argument("--resident", action="store_true",
+                    help="add a second leg in which every row is cached (the paper's 'hot' iteration): same kernels, "
+                         "no host-link traffic; reported under cache_resident")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
