@@ -109,6 +109,15 @@ def remap(rows, indices, offsets, B: int, slot_of: np.ndarray):
     return rc, None, None, None, None
 
 
+def coalesce(miss_gid: np.ndarray):
+    miss_gid = _i32(miss_gid)
+    n = miss_gid.shape[0]
+    uq = np.empty(max(n, 1), dtype=np.int32); inv = np.empty(max(n, 1), dtype=np.int32)
+    U = np.zeros(1, dtype=np.int64)
+    rc = lib().ora_coalesce(C.c_int64(n), _p(miss_gid), _p(uq), _p(inv), _p(U))
+    return rc, uq[: int(U[0])].copy(), inv[:n].copy()
+
+
 def classify_samples(rows, indices, offsets, B: int, slot_of: np.ndarray):
     rows = _rows(rows); indices = _i32(indices); offsets = _i32(offsets); slot_of = _i32(slot_of)
     T = _LB(rows, offsets, B)

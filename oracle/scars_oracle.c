@@ -143,6 +143,32 @@ int32_t ora_remap(int32_t T, const int64_t* rows, const int32_t* indices, const 
     return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
 }
 
+/* ---- coalescing: unique missed rows and the per-lookup index into them ------------------------- */
+typedef struct { int32_t gid; int32_t j; } miss_item;
+
+static int cmp_miss(const void* a, const void* b) {
+    const miss_item* x = (const miss_item*)a;
+    const miss_item* y = (const miss_item*)b;
+    if (x->gid != y->gid) return x->gid < y->gid ? -1 : 1;
+    if (x->j != y->j) return x->j < y->j ? -1 : 1;
+    return 0;
+}
+
+int32_t ora_coalesce(int64_t n_miss, const int32_t* miss_gid, int32_t* unique_gid, int32_t* inverse, int64_t* U) {
+    if (n_miss < 0 || !U || (n_miss > 0 && (!miss_gid || !unique_gid || !inverse))) return ORA_ERR_INVALID_ARG;
+    miss_item* m = (miss_item*)malloc(sizeof(miss_item) * (size_t)(n_miss > 0 ? n_miss : 1));
+    for (int64_t j = 0; j < n_miss; ++j) { m[j].gid = miss_gid[j]; m[j].j = (int32_t)j; }
+    qsort(m, (size_t)n_miss, sizeof(miss_item), cmp_miss);
+    int64_t u = 0;
+    for (int64_t s = 0; s < n_miss; ++s) {
+        if (s == 0 || m[s].gid != m[s - 1].gid) unique_gid[u++] = m[s].gid;
+        inverse[m[s].j] = (int32_t)(u - 1);
+    }
+    *U = u;
+    free(m);
+    return ORA_OK;
+}
+
 /* ---- hot / normal samples ------------------------------------------------------------------------ */
 int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
                              int64_t L, int64_t B, const int32_t* slot_of, int32_t* is_hot, int32_t* hot_ids,

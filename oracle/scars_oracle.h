@@ -66,6 +66,12 @@ int32_t ora_embedding_bag_fwd_cached(int32_t T, const int64_t* rows, int32_t D, 
                                      const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
                                      float* out);
 
+/* Coalescing (Section II-A, eq. (1)-(3)): instead of one embedding per lookup, send the list of UNIQUE missed
+ * embeddings of the batch plus, per lookup, an index into that list.  unique_gid = the distinct values of
+ * miss_gid in ascending order, inverse[j] = position of miss_gid[j] in it, *U = their number. */
+int32_t ora_coalesce(int64_t n_miss, const int32_t* miss_gid, int32_t* unique_gid /* [n_miss] */,
+                     int32_t* inverse /* [n_miss] */, int64_t* U);
+
 /* Hot / normal samples (Section III): a sample is hot when every one of its lookups, over all T tables, falls
  * in the cached set (a sample without lookups is hot); is_hot[b] = 1/0, hot_ids / normal_ids list the sample
  * ids of each class in ascending order, n_out = {n_hot, n_normal}. */

@@ -293,3 +293,30 @@ def test_classify_samples_hand_case(ora):
     rc, is_hot, hot_ids, normal_ids = ora.classify_samples(rows, idx, off, B, slot_of)
     assert rc == 0 and is_hot.tolist() == [1, 1, 0]           # a sample without lookups needs no cold row: hot
     assert hot_ids.tolist() == [0, 1] and normal_ids.tolist() == [2]
+
+
+# ------------------------------------------------------------------ coalescing (Section II-A)
+def test_coalesce_matches_numpy_unique(ora):
+    rng = np.random.default_rng(0)
+    for n, hi in ((0, 5), (1, 5), (1000, 50), (5000, 10 ** 6)):
+        mg = rng.integers(0, hi, n).astype(np.int32)
+        rc, uq, inv = ora.coalesce(mg)
+        assert rc == 0
+        ref_u, ref_inv = np.unique(mg, return_inverse=True)
+        assert np.array_equal(uq, ref_u) and np.array_equal(inv, ref_inv)
+        assert np.array_equal(uq[inv], mg)                      # the list plus the indices reproduce every lookup
+
+
+def test_coalesced_cost_matches_expected_communication(ora):
+    # eq. (2)/(3): with nothing cached every lookup is a miss, and the coalesced transfer is the b indices plus
+    # sum_e 1 - (1 - P(e))^b unique embeddings per feature
+    wl = synth.workload("tiny", batch=4096)
+    s = synth.Sampler(wl)
+    idx, off = s.batch(0)
+    none = np.full(wl.total_rows, -1, dtype=np.int32)
+    rc, slot, hit, miss, mg = ora.remap(wl.rows, idx.numpy(), off.numpy(), wl.batch, none)
+    assert miss.size == idx.numel()                             # eq. (4): b * d lookups communicated without coalescing
+    rc, uq, inv = ora.coalesce(mg)
+    EU = sum(float(np.sum(1.0 - (1.0 - s.row_probs(t).numpy()) ** wl.batch)) for t in range(wl.num_tables))
+    assert abs(uq.size - EU) < 5 * math.sqrt(EU)
+    assert uq.size < 0.5 * miss.size                            # Zipf 1.05 at b = 4096: coalescing more than halves it
