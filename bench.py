@@ -32,8 +32,9 @@ def log(*a):
 
 
 class Bench:
-    def __init__(self, wl: synth.Workload, budget_bytes: int):
+    def __init__(self, wl: synth.Workload, budget_bytes: int, coalesce: bool = False):
         self.wl = wl
+        self.coalesce = coalesce
         self.dev = torch.device("cuda:0")
         self.budget = budget_bytes
         t0 = time.time()
@@ -82,7 +83,7 @@ class Bench:
         prof = [self.sampler.batch(p, True) for p in range(min(wl.profile_batches, 4))]
         self.max_L = max(self.max_L, max(int(b[0].numel()) for b in prof)) + 4096
         self.sizes = self.s.bind_buffers(self.budget, self.max_L, wl.num_bags)
-        self.rm = self.s.new_remap_out()
+        self.rm = self.s.new_remap_out(coalesce=self.coalesce)
         self.out = torch.empty(wl.num_bags, wl.dim, dtype=torch.float32, device=self.dev)
 
     def build_cache(self) -> dict:
@@ -202,6 +203,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
     t1 = time.perf_counter()
     assert b.s.sync_status() == 0
     n_hit, n_miss = b.rm.n_hit_miss.cpu().tolist()
+    n_staged = b.rm.n_unique_miss.cpu().tolist()[0] if b.coalesce else n_miss   # rows fetched over the link
 
     b.s.profile_enable(True)
     for e in range(W, W + K):
@@ -236,7 +238,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
     state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
     # forward: every missed lookup's row is read over the link.  backward: a cold row's value comes from the copy
     # the forward pass staged, so only its accumulator is read over the link; row and accumulator are written back
-    for name, rd, wr in (("stage_misses", n_miss * wl.row_bytes, 0),
+    for name, rd, wr in (("stage_misses", n_staged * wl.row_bytes, 0),
                          ("seg_rows", U_cold * state_b, U_cold * (wl.row_bytes + state_b))):
         if name in prof and rd + wr > 0:
             t_s = prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
@@ -245,7 +247,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
                               "avg_launch_ms": round(t_s * 1e3, 5), "read_GBs": round(rd / t_s / 1e9, 2),
                               "write_GBs": round(wr / t_s / 1e9, 2), "frac_of_measured_link": round(t_min / t_s, 4)})
     return {"value": lookups / (t1 - t0), "ms_per_step": (t1 - t0) * 1e3 / K, "lookups_per_step": L_avg,
-            "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "roofline": roofline,
+            "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "n_miss": n_miss, "n_staged": n_staged, "roofline": roofline,
             "host_link": host_link, "kernels": kern}
 
 
@@ -299,6 +301,8 @@ def main():
                     help="shrink table rows and budget only (default 1.0; 0.5 for host_spill, whose 102 GB of "
                          "tables exceed what one box lets a process pin, about 64 GB)")
     ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
+    ap.add_argument("--coalesce", action="store_true",
+                    help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--resident", action="store_true",
                     help="add a second leg in which every row is cached (the paper's 'hot' iteration): same kernels, "
@@ -318,7 +322,7 @@ def main():
     link = measure_link(dev)
     log("calibration", cal, "link", link)
 
-    b = Bench(wl, budget)
+    b = Bench(wl, budget, args.coalesce)
     K, W = args.steps, args.warmup
     b.prepare(K + W)
     bc = b.build_cache()
@@ -355,7 +359,8 @@ def main():
                    "dim": wl.dim, "batch": wl.batch, "lookups_per_step": leg["lookups_per_step"], "zipf_s": wl.zipf_s,
                    "budget_bytes": budget, "cached_rows": bc["k"], "optimizer": wl.optimizer,
                    "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],
-                   "unique_cold_rows_per_step": leg["U_cold"],
+                   "unique_cold_rows_per_step": leg["U_cold"], "missed_lookups_per_step": leg["n_miss"],
+                   "rows_fetched_over_link_per_step": leg["n_staged"], "coalesce": args.coalesce,
                    "step": "remap + embedding_bag_fwd + embedding_bag_bwd_update"},
         "roofline": leg["roofline"], "host_link": leg["host_link"],
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),

@@ -104,6 +104,13 @@ typedef struct {
     int32_t* miss_pos;    /* positions of misses, ascending; first n_miss entries valid */
     int32_t* miss_gid;    /* gid of each miss, same order as miss_pos */
     int32_t* n_hit_miss;  /* int32 [2] = {n_hit, n_miss} */
+    /* Optional coalescing (Section II-A: send each distinct embedding of the batch once, plus per-lookup indices).
+     * Both NULL: one staged row per missed lookup, loc as above.  Both set: unique_miss_gid [L] receives the
+     * distinct missed gids in ascending order (first n_unique_miss[0] entries), n_unique_miss int32 [2] =
+     * {U_miss, n_miss}, and loc of a miss = k + (index of its gid in unique_miss_gid): forward then fetches each
+     * distinct cold row once over the host link. */
+    int32_t* unique_miss_gid;
+    int32_t* n_unique_miss;
 } scars_remap_out;
 
 /* Optional outputs of scars_embedding_bag_bwd_update, all DEVICE. */

@@ -53,7 +53,8 @@ class _Buffers(C.Structure):
 
 
 class _RemapOut(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("slot", "gid", "loc", "hit_pos", "miss_pos", "miss_gid", "n_hit_miss")]
+    _fields_ = [(n, C.c_void_p) for n in ("slot", "gid", "loc", "hit_pos", "miss_pos", "miss_gid", "n_hit_miss",
+                                          "unique_miss_gid", "n_unique_miss")]
 
 
 class _BwdOut(C.Structure):
@@ -174,10 +175,14 @@ class RemapOut:
     miss_pos: torch.Tensor
     miss_gid: torch.Tensor
     n_hit_miss: torch.Tensor
+    unique_miss_gid: Optional[torch.Tensor] = None     # set both to have remap coalesce the missed rows
+    n_unique_miss: Optional[torch.Tensor] = None
 
     def c(self) -> _RemapOut:
+        opt = lambda t: t.data_ptr() if t is not None else None
         return _RemapOut(*[t.data_ptr() for t in (self.slot, self.gid, self.loc, self.hit_pos, self.miss_pos,
-                                                  self.miss_gid, self.n_hit_miss)])
+                                                  self.miss_gid, self.n_hit_miss)],
+                         opt(self.unique_miss_gid), opt(self.n_unique_miss))
 
 
 @dataclass
@@ -262,10 +267,11 @@ class Scars:
         self.max_L, self.max_G, self.budget_bytes, self.device = max_L, max_G, budget_bytes, dev
         return sz
 
-    def new_remap_out(self, L: Optional[int] = None) -> RemapOut:
+    def new_remap_out(self, L: Optional[int] = None, coalesce: bool = False) -> RemapOut:
         n = max(self.max_L if L is None else L, 1)
         mk = lambda m: torch.empty(m, dtype=torch.int32, device=self.device)
-        return RemapOut(mk(n), mk(n), mk(n), mk(n), mk(n), mk(n), mk(2))
+        return RemapOut(mk(n), mk(n), mk(n), mk(n), mk(n), mk(n), mk(2), mk(n) if coalesce else None,
+                        mk(2) if coalesce else None)
 
     def new_bwd_out(self, L: Optional[int] = None) -> BwdOut:
         n = max(self.max_L if L is None else L, 1)
@@ -309,9 +315,10 @@ class Scars:
     def cache_rows(self) -> int:
         return int(lib().scars_cache_rows(self._h))
 
-    def remap(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, out: Optional[RemapOut] = None) -> RemapOut:
+    def remap(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, out: Optional[RemapOut] = None,
+              coalesce: bool = False) -> RemapOut:
         L = int(indices.numel())
-        out = out or self.new_remap_out(L)
+        out = out or self.new_remap_out(L, coalesce)
         c = out.c()
         self._check(lib().scars_remap(self._h, self._i32(indices), self._i32(offsets), L, B, C.byref(c), _stream()))
         return out

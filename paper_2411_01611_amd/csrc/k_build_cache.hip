@@ -332,7 +332,7 @@ hipError_t launch_select_and_fill(scars_handle* h, hipStream_t s, int64_t k) {
         uint32_t* keys[2] = {ws.win_key[0], ws.win_key[1]};
         uint32_t* vals[2] = {(uint32_t*)ws.win_gid[0], (uint32_t*)ws.win_gid[1]};
         int res = 0;
-        hipError_t e = launch_radix_sort_pairs(h, s, keys, vals, k, 32, &res);
+        hipError_t e = launch_radix_sort_pairs(h, s, keys, vals, k, nullptr, 32, &res);
         if (e != hipSuccess) return e;
         {
             Timed t(h, s, "slot_scatter");

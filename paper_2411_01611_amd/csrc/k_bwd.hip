@@ -431,7 +431,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     int bits = 1;
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
     int res = 0;
-    hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, bits, &res);
+    hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
     if (e != hipSuccess) return e;
     const uint32_t* key = ws.key_buf[res];
     const uint32_t* val = ws.val_buf[res];

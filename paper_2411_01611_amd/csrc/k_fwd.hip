@@ -16,14 +16,14 @@ constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
-                                                         const int32_t* __restrict__ n_hit_miss,
+                                                         const int32_t* __restrict__ d_count,
                                                          const Meta* __restrict__ meta, u32x4* __restrict__ staging,
                                                          int chunks, int lpr, int64_t cap_rows) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = meta->num_tables;
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
     __syncthreads();
-    const int64_t n = min((int64_t)n_hit_miss[1], cap_rows);
+    const int64_t n = min((int64_t)*d_count, cap_rows);
     const int gpb = kBlock / lpr;
     const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
     const int64_t stride = (int64_t)gridDim.x * gpb;
@@ -264,7 +264,10 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         Timed t(h, s, "stage_misses");
         const int gpb = kBlock / lpr;
         const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), 256 * 8));
-        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, rm->miss_gid, rm->n_hit_miss, h->ws.meta,
+        // one row per missed lookup, or (after a coalescing remap) one per distinct missed row
+        const int32_t* list = rm->unique_miss_gid ? rm->unique_miss_gid : rm->miss_gid;
+        const int32_t* count = rm->unique_miss_gid ? rm->n_unique_miss : rm->n_hit_miss + 1;
+        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, list, count, h->ws.meta,
                            (u32x4*)h->ws.staging, chunks, lpr, h->buf.max_L);
     }
     if (G > 0) {

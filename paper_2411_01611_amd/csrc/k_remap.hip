@@ -143,6 +143,80 @@ __global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t
     }
 }
 
+__global__ void k_um_empty(int32_t* __restrict__ n_unique_miss) {
+    if (threadIdx.x < 2) n_unique_miss[threadIdx.x] = 0;
+}
+
+// ---- coalescing of the missed rows (Section II-A of the paper) -------------------------------------------
+// Instead of one staged row per missed lookup, the distinct missed rows are listed once (ascending gid) and
+// every missed lookup's loc points at its row in that list: pairs (gid, miss rank) are sorted by gid, run heads
+// are compacted into unique_miss_gid, and each pair writes loc[miss_pos[rank]] = k + (index of its run).
+__global__ __launch_bounds__(kBlock) void k_um_prepare(const int32_t* __restrict__ miss_gid, const int32_t* __restrict__ n_hit_miss,
+                                                       uint32_t* __restrict__ key, uint32_t* __restrict__ val) {
+    const int64_t n = n_hit_miss[1];
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < n; j += (int64_t)gridDim.x * kBlock) {
+        key[j] = (uint32_t)miss_gid[j];
+        val[j] = (uint32_t)j;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_um_count(const uint32_t* __restrict__ key, const int32_t* __restrict__ n_hit_miss,
+                                                     uint32_t* __restrict__ blk_head, uint32_t* __restrict__ blk_n) {
+    __shared__ uint32_t s_a[4], s_b[4];
+    const int64_t n = n_hit_miss[1];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
+    uint32_t nh = 0, nv = 0;
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t j = base + r * kWave + lane_id();
+        const bool in = j < n;
+        const bool head = in && (j == 0 || key[j - 1] != key[j]);
+        nh += (uint32_t)__popcll(ballot64(head));
+        nv += (uint32_t)__popcll(ballot64(in));
+    }
+    if (lane_id() == 0) { s_a[wave_id()] = nh; s_b[wave_id()] = nv; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk_head[blockIdx.x] = s_a[0] + s_a[1] + s_a[2] + s_a[3];
+        blk_n[blockIdx.x] = s_b[0] + s_b[1] + s_b[2] + s_b[3];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_um_write(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                                     const int32_t* __restrict__ n_hit_miss, const uint32_t* __restrict__ blk_head,
+                                                     int32_t k, const int32_t* __restrict__ miss_pos,
+                                                     int32_t* __restrict__ unique_miss_gid, int32_t* __restrict__ loc) {
+    __shared__ uint32_t s_a[4];
+    const int64_t n = n_hit_miss[1];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
+    uint32_t kk[kRoundsR];
+    bool hd[kRoundsR];
+    uint32_t nh = 0;
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t j = base + r * kWave + lane_id();
+        kk[r] = j < n ? key[j] : 0u;
+        hd[r] = j < n && (j == 0 || key[j - 1] != kk[r]);
+        nh += (uint32_t)__popcll(ballot64(hd[r]));
+    }
+    if (lane_id() == 0) s_a[wave_id()] = nh;
+    __syncthreads();
+    uint32_t before = blk_head[blockIdx.x];
+    for (int w = 0; w < wave_id(); ++w) before += s_a[w];
+#pragma unroll
+    for (int r = 0; r < kRoundsR; ++r) {
+        const int64_t j = base + r * kWave + lane_id();
+        const uint64_t m = ballot64(hd[r]);
+        if (j < n) {
+            // index of this pair's run = heads at or before j, minus one
+            const uint32_t u = before + (uint32_t)rank_below(m) + (hd[r] ? 1u : 0u) - 1u;
+            if (hd[r]) unique_miss_gid[u] = (int32_t)kk[r];
+            loc[miss_pos[val[j]]] = k + (int32_t)u;
+        }
+        before += (uint32_t)__popcll(m);
+    }
+}
+
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out) {
     Workspace& ws = h->ws;
@@ -160,6 +234,36 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         Timed t(h, s, "remap_write");
         hipLaunchKernelGGL(k_remap_write, dim3(nb), dim3(kBlock), 0, s, L, out->slot, out->gid, ws.blk_hit, ws.blk_miss,
                            (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos, out->miss_gid);
+    }
+    if (out->unique_miss_gid && L > 0 && h->k < h->N) {
+        const int grid = (int)std::min<int64_t>(div_up(L, kBlock), 256 * 8);
+        {
+            Timed t(h, s, "um_prepare");
+            hipLaunchKernelGGL(k_um_prepare, dim3(grid), dim3(kBlock), 0, s, out->miss_gid, out->n_hit_miss, ws.key_buf[0],
+                               ws.val_buf[0]);
+        }
+        int bits = 1;
+        while (bits < 32 && ((int64_t)1 << bits) < h->N) ++bits;      // gids are below N
+        int res = 0;
+        hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, out->n_hit_miss + 1, bits, &res);
+        if (e != hipSuccess) return e;
+        {
+            Timed t(h, s, "um_count");
+            hipLaunchKernelGGL(k_um_count, dim3(nb), dim3(kBlock), 0, s, ws.key_buf[res], out->n_hit_miss, ws.blk_hit,
+                               ws.blk_miss);
+        }
+        {
+            Timed t(h, s, "um_scan");
+            hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_unique_miss);
+        }
+        {
+            Timed t(h, s, "um_write");
+            hipLaunchKernelGGL(k_um_write, dim3(nb), dim3(kBlock), 0, s, ws.key_buf[res], ws.val_buf[res], out->n_hit_miss,
+                               ws.blk_hit, (int32_t)h->k, out->miss_pos, out->unique_miss_gid, out->loc);
+        }
+    } else if (out->unique_miss_gid) {
+        Timed t(h, s, "um_empty");   // nothing can miss: the list is empty
+        hipLaunchKernelGGL(k_um_empty, dim3(1), dim3(kWave), 0, s, out->n_unique_miss);
     }
     return hipGetLastError();
 }

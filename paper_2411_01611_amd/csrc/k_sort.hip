@@ -16,9 +16,10 @@ constexpr int kWaves = kBlock / kWave;
 
 // hist is digit-major: hist[d * nb + tile]
 template <int ROUNDS>
-__global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict__ keys, int64_t n, int shift, int dbits,
-                                                      uint32_t* __restrict__ hist, int nb) {
+__global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict__ keys, int64_t n, const int32_t* __restrict__ d_n,
+                                                      int shift, int dbits, uint32_t* __restrict__ hist, int nb) {
     __shared__ uint32_t s_hist[kMaxBins];
+    if (d_n) n = min(n, (int64_t)max(*d_n, 0));    // the pair count may live on the device (n is then its bound)
     const int bins = 1 << dbits;
     const uint32_t mask = (uint32_t)bins - 1u;
     for (int d = threadIdx.x; d < bins; d += kBlock) s_hist[d] = 0;
@@ -53,9 +54,11 @@ __global__ __launch_bounds__(kBlock) void k_sort_scan(uint32_t* __restrict__ his
 template <int ROUNDS>
 __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin,
                                                          uint32_t* __restrict__ kout, uint32_t* __restrict__ vout,
-                                                         int64_t n, int shift, int dbits, const uint32_t* __restrict__ hist,
-                                                         const uint32_t* __restrict__ tot, int nb) {
+                                                         int64_t n, const int32_t* __restrict__ d_n, int shift, int dbits,
+                                                         const uint32_t* __restrict__ hist, const uint32_t* __restrict__ tot, int nb) {
     constexpr int kTile = kBlock * ROUNDS;
+    if (d_n) n = min(n, (int64_t)max(*d_n, 0));
+    if ((int64_t)blockIdx.x * kTile >= n) return;   // whole workgroup: nothing of this tile is in use
     constexpr int kPerWave = kWave * ROUNDS;
     __shared__ uint32_t s_key[kTile];
     __shared__ uint32_t s_val[kTile];
@@ -153,7 +156,8 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
 }
 
 template <int ROUNDS>
-static void sort_passes(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n, int bits, int* cur) {
+static void sort_passes(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n, const int32_t* d_n,
+                        int bits, int* cur) {
     const int nb = (int)div_up(n, kBlock * ROUNDS);
     const int passes = (int)div_up(bits, 9);
     const int dbits = (int)div_up(bits, passes);
@@ -161,7 +165,7 @@ static void sort_passes(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32
         const int shift = p * dbits;
         {
             Timed t(h, s, "sort_hist");
-            hipLaunchKernelGGL((k_sort_hist<ROUNDS>), dim3(nb), dim3(kBlock), 0, s, key[*cur], n, shift, dbits,
+            hipLaunchKernelGGL((k_sort_hist<ROUNDS>), dim3(nb), dim3(kBlock), 0, s, key[*cur], n, d_n, shift, dbits,
                                h->ws.sort_hist, nb);
         }
         {
@@ -171,19 +175,19 @@ static void sort_passes(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32
         {
             Timed t(h, s, "sort_scatter");
             hipLaunchKernelGGL((k_sort_scatter<ROUNDS>), dim3(nb), dim3(kBlock), 0, s, key[*cur], val[*cur], key[*cur ^ 1],
-                               val[*cur ^ 1], n, shift, dbits, h->ws.sort_hist, h->ws.sort_tot, nb);
+                               val[*cur ^ 1], n, d_n, shift, dbits, h->ws.sort_hist, h->ws.sort_tot, nb);
         }
         *cur ^= 1;
     }
 }
 
 hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n,
-                                   int bits, int* result_buffer) {
+                                   const int32_t* d_n, int bits, int* result_buffer) {
     int cur = 0;
     if (n > 0) {
         // small inputs: small tiles, so that there are enough workgroups to fill the chip
-        if (n < ((int64_t)1 << 21)) sort_passes<kSortRoundsSmall>(h, s, key, val, n, bits, &cur);
-        else sort_passes<kSortRoundsLarge>(h, s, key, val, n, bits, &cur);
+        if (n < ((int64_t)1 << 21)) sort_passes<kSortRoundsSmall>(h, s, key, val, n, d_n, bits, &cur);
+        else sort_passes<kSortRoundsLarge>(h, s, key, val, n, d_n, bits, &cur);
     }
     *result_buffer = cur;
     return hipGetLastError();

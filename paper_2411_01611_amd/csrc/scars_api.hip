@@ -226,6 +226,8 @@ int64_t scars_cache_rows(const scars_handle* h) { return (h && h->built) ? h->k 
 static int32_t check_remap_out(scars_handle* h, const scars_remap_out* o, int64_t L, const char* who) {
     if (!o || !o->n_hit_miss || (L > 0 && (!o->slot || !o->gid || !o->loc || !o->hit_pos || !o->miss_pos || !o->miss_gid)))
         return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": remap_out has a null array");
+    if ((o->unique_miss_gid == nullptr) != (o->n_unique_miss == nullptr))
+        return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": unique_miss_gid and n_unique_miss go together");
     return SCARS_OK;
 }
 

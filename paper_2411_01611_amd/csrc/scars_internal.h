@@ -115,7 +115,8 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
 // ---- launchers (each enqueues on `s`; returns hipGetLastError) -------------------------------------
 // k_sort.hip
 hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n,
-                                   int bits, int* result_buffer /*0 or 1: which buffer holds the result*/);
+                                   const int32_t* d_n /*device-side pair count bounded by n, or null*/, int bits,
+                                   int* result_buffer /*0 or 1: which buffer holds the result*/);
 // k_build_cache.hip
 hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
 hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,

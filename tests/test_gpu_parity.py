@@ -240,3 +240,64 @@ def test_classify_samples_extreme_budgets():
         nh, nn = co.n_hot_normal.cpu().tolist()
         assert (nh, nn) == ((wl.batch, 0) if all_hot else (0, wl.batch))
         c.close()
+
+
+def test_coalesced_remap_and_forward(case):
+    """Section II-A coalescing: distinct missed rows listed once (bit-exact against the oracle), every missed
+    lookup pointing into that list; forward and the following backward give the same values as without it."""
+    case.build()
+    wl = case.wl
+    idx, off = case.batch
+    rc, slot, hit, miss, mg = oracle.remap(wl.rows, idx.numpy(), off.numpy(), wl.batch, case.ora_slot_of)
+    rc, uq, inv = oracle.coalesce(mg)
+    assert rc == 0
+    d_idx, d_off = case.dev_batch()
+    L = idx.numel()
+    plain = case.s.remap(d_idx, d_off, wl.batch)
+    out_plain = case.s.embedding_bag_fwd(d_idx, d_off, wl.batch, plain)
+    rm = case.s.remap(d_idx, d_off, wl.batch, coalesce=True)
+    assert case.s.sync_status() == 0
+    assert rm.n_unique_miss.cpu().tolist() == [uq.size, miss.size]
+    assert np.array_equal(rm.unique_miss_gid.cpu().numpy()[: uq.size], uq)
+    loc = rm.loc.cpu().numpy()[:L]
+    assert np.array_equal(loc[miss], case.k + inv)
+    assert np.array_equal(loc[hit], slot[hit])
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)       # the per-lookup lists are unchanged
+    out = case.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    assert torch.equal(out, out_plain)
+    rc, want = oracle.embedding_bag_fwd(wl.rows, case.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+    assert_close(out.cpu().numpy(), want, "pooled output with coalesced misses")
+    # backward right after this forward takes cold rows from the coalesced staging area
+    grad = case.sampler.grads(0)
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps if wl.optimizer == "adagrad" else 0.0)
+    opt = 1 if wl.optimizer == "adagrad" else 0
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx.numpy(), off.numpy(), wl.batch)
+    rc, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, case.ora_tables, case.ora_state, opt, idx.numpy(),
+                                                     off.numpy(), wl.batch, grad.numpy(), lr, eps, report=True,
+                                                     n_unique=ug.size)
+    oracle.embedding_bag_bwd_update(wl.rows, case.ora_tables, case.ora_state, opt, idx.numpy(), off.numpy(), wl.batch,
+                                    grad.numpy(), lr, eps)
+    case.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(case.dev), float(lr), float(eps))
+    case.s.flush_cache()
+    assert case.s.sync_status() == 0
+    if wl.dtype == "f32":
+        assert_close(case.pinned_rows(), np.concatenate(case.ora_tables), "rows after coalesced step")
+    else:
+        assert_bf16_within(case.pinned_rows()[ug], nr, "bf16 rows after coalesced step")
+
+
+def test_coalescing_without_cache_matches_expected_unique():
+    """No cache at all (the paper's coalescing-only setting): every lookup misses and the staged rows are the
+    batch's distinct rows."""
+    wl = _wl("host_spill_small")
+    c = GpuCase(wl, budget_bytes=0)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    rm = c.s.remap(d_idx, d_off, wl.batch, coalesce=True)
+    U, n_miss = rm.n_unique_miss.cpu().tolist()
+    gid = gids_of(wl, c.batch[0].numpy(), c.batch[1].numpy())
+    assert n_miss == gid.size and U == np.unique(gid).size and U < 0.6 * n_miss
+    out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
+    assert_close(out.cpu().numpy(), want, "coalesced forward without a cache")
+    c.close()
