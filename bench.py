@@ -116,7 +116,7 @@ class Bench:
         k = self.s.cache_rows()
         return {"profile_lookups": Lp, "histogram_s": t_hist, "select_and_fill_s": t_sel, "k": k,
                 "histogram_Mlookups_per_s": Lp / max(t_hist, 1e-9) / 1e6,
-                "fill_host_link_GBs": k * wl.row_bytes / max(t_sel, 1e-9) / 1e9, "total_s": time.time() - t0 - gen}
+                "fill_host_link_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_sel, 1e-9) / 1e9, "total_s": time.time() - t0 - gen}
 
     def step(self, e: int):
         wl = self.wl

@@ -189,6 +189,13 @@ int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices
 int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
                                const scars_classify_out* out, void* stream);
 
+/* Use of the cache by portion (the measurement of Fig. 4 in Section IV: samples of a mini-batch that touch each
+ * successive part of the hotness-ordered cache).  d_usage[p], DEVICE int32 [n_portions] with n_portions <= 64,
+ * receives the number of samples having at least one lookup whose slot lies in
+ * [p * portion_rows, (p + 1) * portion_rows).  `rm` must come from scars_remap on this batch. */
+int32_t scars_portion_usage(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
+                            int64_t portion_rows, int32_t n_portions, int32_t* d_usage, void* stream);
+
 /* Write every cached row (and Adagrad accumulator) back to its pinned host table. */
 int32_t scars_flush_cache(scars_handle* h, void* stream);
 

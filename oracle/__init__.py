@@ -131,6 +131,15 @@ def classify_samples(rows, indices, offsets, B: int, slot_of: np.ndarray):
     return rc, None, None, None
 
 
+def portion_usage(rows, indices, offsets, B: int, slot_of: np.ndarray, portion_rows: int, n_portions: int):
+    rows = _rows(rows); indices = _i32(indices); offsets = _i32(offsets); slot_of = _i32(slot_of)
+    T = _LB(rows, offsets, B)
+    usage = np.zeros(n_portions, dtype=np.int32)
+    rc = lib().ora_portion_usage(C.c_int32(T), _p(rows), _p(indices), _p(offsets), C.c_int64(indices.shape[0]),
+                                 C.c_int64(B), _p(slot_of), C.c_int64(portion_rows), C.c_int32(n_portions), _p(usage))
+    return rc, usage
+
+
 def _dt(tables: Sequence[np.ndarray]) -> Tuple[int, int]:
     d = tables[0].dtype
     assert d in (np.float32, np.uint16), "rows are fp32, or bf16 held as uint16"

@@ -198,6 +198,35 @@ int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indi
     return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
 }
 
+/* ---- cache use by portion ------------------------------------------------------------------------ */
+int32_t ora_portion_usage(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                          int64_t L, int64_t B, const int32_t* slot_of, int64_t portion_rows, int32_t n_portions,
+                          int32_t* usage) {
+    int rc = check_batch(T, rows, indices, offsets, L, B);
+    if (rc) return rc;
+    if (!slot_of || portion_rows < 1 || n_portions < 1 || !usage) return ORA_ERR_INVALID_ARG;
+    int64_t* rb = make_row_base(T, rows);
+    char* seen = (char*)malloc((size_t)n_portions);
+    int bad = 0;
+    for (int32_t p = 0; p < n_portions; ++p) usage[p] = 0;
+    for (int64_t b = 0; b < B; ++b) {
+        memset(seen, 0, (size_t)n_portions);
+        for (int32_t t = 0; t < T; ++t) {
+            int64_t g = (int64_t)t * B + b;
+            for (int64_t i = offsets[g]; i < offsets[g + 1]; ++i) {
+                int64_t idx = indices[i];
+                if (idx < 0 || idx >= rows[t]) { bad = 1; continue; }
+                int64_t s = slot_of[rb[t] + idx];
+                if (s >= 0 && s / portion_rows < n_portions) seen[s / portion_rows] = 1;
+            }
+        }
+        for (int32_t p = 0; p < n_portions; ++p) usage[p] += seen[p];
+    }
+    free(seen);
+    free(rb);
+    return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
+}
+
 /* ---- forward ----------------------------------------------------------------------------- */
 static int32_t fwd_impl(int32_t T, const int64_t* rows, int32_t D, int32_t dtype, const void* const* tables,
                         const int32_t* slot_of, const void* cache, const int32_t* indices,

@@ -79,6 +79,14 @@ int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indi
                              int64_t L, int64_t B, const int32_t* slot_of, int32_t* is_hot /* [B] */,
                              int32_t* hot_ids /* [B] */, int32_t* normal_ids /* [B] */, int64_t* n_out /* [2] */);
 
+/* Use of the cache by portion (the measurement behind Fig. 4 of Section IV: how many samples of a mini-batch
+ * touch each successive portion of the hotness-ordered cache).  Portion p holds slots
+ * [p * portion_rows, (p+1) * portion_rows); usage[p] = number of samples with at least one lookup whose slot
+ * falls in portion p (slots at or beyond n_portions * portion_rows are not counted). */
+int32_t ora_portion_usage(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
+                          int64_t L, int64_t B, const int32_t* slot_of, int64_t portion_rows, int32_t n_portions,
+                          int32_t* usage /* [n_portions] */);
+
 /* Lookups ordered by (gid, position): sorted_gid, sorted_bag (bag of each lookup), seg_start[r] = first
  * sorted position of the r-th distinct gid (seg_start[U] = number of valid lookups), unique_gid ascending. */
 int32_t ora_bwd_segments(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,

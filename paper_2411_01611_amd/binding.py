@@ -23,7 +23,7 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
-    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
+    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_profile_enable", "scars_profile_read",
 )
@@ -92,6 +92,7 @@ def lib():
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
         L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
+        L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
         L.scars_flush_cache.argtypes = [vp, vp]
         L.scars_sync_status.argtypes = [vp, vp]
         L.scars_last_error.argtypes = [vp]
@@ -356,6 +357,14 @@ class Scars:
         self._check(lib().scars_classify_samples(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
                                                  C.byref(co), _stream()))
         return out
+
+    def portion_usage(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut, portion_rows: int,
+                      n_portions: int) -> torch.Tensor:
+        usage = torch.empty(n_portions, dtype=torch.int32, device=self.device)
+        c = rm.c()
+        self._check(lib().scars_portion_usage(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
+                                              portion_rows, n_portions, usage.data_ptr(), _stream()))
+        return usage
 
     def flush_cache(self) -> None:
         self._check(lib().scars_flush_cache(self._h, _stream()))

@@ -73,6 +73,43 @@ __global__ __launch_bounds__(kBlock) void k_cls_write(const int32_t* __restrict_
     }
 }
 
+// Use of the cache by portion (the measurement behind Fig. 4 of the paper): usage[p] = samples with at least one
+// lookup whose slot lies in [p * portion_rows, (p + 1) * portion_rows).  One thread per sample builds a bit mask
+// of the portions it touches; one integer atomic per wave and portion.
+__global__ __launch_bounds__(kBlock) void k_portion_usage(const int32_t* __restrict__ off, int32_t L, int64_t B, int T,
+                                                          const int32_t* __restrict__ slot, int32_t portion_rows,
+                                                          int n_portions, int32_t* __restrict__ usage) {
+    const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    uint64_t mask = 0;
+    if (b < B) {
+        for (int t = 0; t < T; ++t) {
+            const int64_t g = (int64_t)t * B + b;
+            const int32_t a = min(max(off[g], 0), L);
+            const int32_t e = min(max(off[g + 1], a), L);
+            for (int32_t i = a; i < e; ++i) {
+                const int32_t s = slot[i];
+                if (s >= 0 && s / portion_rows < n_portions) mask |= 1ull << (s / portion_rows);
+            }
+        }
+    }
+    for (int p = 0; p < n_portions; ++p) {
+        const int c = __popcll(ballot64((mask >> p) & 1ull));
+        if (c && lane_id() == 0) atomicAdd(&usage[p], c);
+    }
+}
+
+hipError_t launch_portion_usage(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                                const scars_remap_out* rm, int64_t portion_rows, int32_t n_portions, int32_t* usage) {
+    hipError_t e = launch_fill_u32(h, s, (uint32_t*)usage, n_portions, 0u);
+    if (e != hipSuccess) return e;
+    if (B > 0) {
+        Timed t(h, s, "portion_usage");
+        hipLaunchKernelGGL(k_portion_usage, dim3((unsigned)div_up(B, kBlock)), dim3(kBlock), 0, s, off, (int32_t)L, B, h->T,
+                           rm->slot, (int32_t)std::min<int64_t>(portion_rows, 0x7fffffff), n_portions, usage);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                            const scars_remap_out* rm, const scars_classify_out* out) {
     Workspace& ws = h->ws;

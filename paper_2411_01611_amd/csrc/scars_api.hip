@@ -284,6 +284,19 @@ int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_
     return SCARS_OK;
 }
 
+int32_t scars_portion_usage(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
+                            int64_t portion_rows, int32_t n_portions, int32_t* d_usage, void* stream) {
+    int32_t rc = check_batch(h, L > 0 ? (const int32_t*)d_offsets : nullptr, d_offsets, L, B, "portion_usage");
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "portion_usage: build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, rm, L, "portion_usage"))) return rc;
+    if (portion_rows < 1 || n_portions < 1 || n_portions > 64 || !d_usage)
+        return fail(h, SCARS_ERR_INVALID_ARG, "portion_usage: portion_rows >= 1, 1 <= n_portions <= 64, usage not null");
+    hipError_t e = launch_portion_usage(h, (hipStream_t)stream, d_offsets, L, B, rm, portion_rows, n_portions, d_usage);
+    if (e != hipSuccess) return hip_fail(h, e, "portion_usage");
+    return SCARS_OK;
+}
+
 int32_t scars_flush_cache(scars_handle* h, void* stream) {
     if (!h) return SCARS_ERR_INVALID_ARG;
     if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "flush_cache: no buffers bound");

@@ -132,6 +132,8 @@ __global__ void k_remap_scan(uint32_t* a, uint32_t* b, int n, int32_t* out2);
 // k_classify.hip
 hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                            const scars_remap_out* rm, const scars_classify_out* out);
+hipError_t launch_portion_usage(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                                const scars_remap_out* rm, int64_t portion_rows, int32_t n_portions, int32_t* usage);
 // k_fwd.hip
 hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, float* out);

@@ -99,6 +99,8 @@ class Workload:
     eps: float = 1e-8
     profile_batches: int = 64
     seed: int = BASE_SEED
+    rank_dist: str = "zipf"         # "zipf" (exponent zipf_s; uniform ids when zipf_s is None), "exp", "halfnormal"
+    rank_scale: float = 0.02        # exp: p(j) ~ exp(-j / (rank_scale * N_t)); halfnormal: p(j) ~ exp(-j^2 / (2 (rank_scale * N_t)^2))
 
     @property
     def num_tables(self) -> int:
@@ -187,6 +189,11 @@ def workload(name: str, scale: float = 1.0, seed: int = BASE_SEED, row_scale: fl
                                200_000_000, 1_000, 40_000_000)
         wl = Workload(name, tuple(rows), 128, "f32", 65_536, None, 1.2,
                       16_000_000_000, "sgd", profile_batches=16, seed=seed)
+    elif name in ("multi_hot_exp", "multi_hot_halfnormal"):
+        # the multi-hot shape with the paper's two other rank distributions (end of Section II-B)
+        rows = [5_000_000] * 8
+        wl = Workload(name, tuple(rows), 128, "f32", 4096, 19.0, None, 2_000_000_000, "adagrad", seed=seed,
+                      rank_dist="exp" if name.endswith("exp") else "halfnormal", rank_scale=0.02)
     elif name in ("low_skew", "low_skew_uniform"):
         rows = _scale_to_total(_log_uniform_rows(seed, 26, 1_000, 10_000_000),
                                50_000_000, 1_000, 10_000_000)
@@ -209,7 +216,8 @@ def workload(name: str, scale: float = 1.0, seed: int = BASE_SEED, row_scale: fl
     return wl
 
 
-WORKLOAD_NAMES = ("tiny", "dlrm_onehot", "multi_hot", "host_spill", "low_skew", "low_skew_uniform")
+WORKLOAD_NAMES = ("tiny", "dlrm_onehot", "multi_hot", "host_spill", "low_skew", "low_skew_uniform",
+                  "multi_hot_exp", "multi_hot_halfnormal")
 
 
 # --------------------------------------------------------------------------------------
@@ -221,8 +229,21 @@ def zipf_probs(n: int, s: float, device="cpu") -> torch.Tensor:
     return w / w.sum()
 
 
+def rank_weights(n: int, dist: str, param: float, device="cpu") -> torch.Tensor:
+    """Unnormalised weight of rank j = 1..n.  Zipf, exponential and half-normal are the three rank
+    distributions the paper analyses at the end of Section II-B (it calls Criteo closest to half-normal)."""
+    j = torch.arange(1, n + 1, dtype=torch.float64, device=device)
+    if dist == "zipf":
+        return j.pow_(-param)
+    if dist == "exp":
+        return torch.exp(-(j - 1) / (param * n))
+    if dist == "halfnormal":
+        return torch.exp(-((j - 1) ** 2) / (2.0 * (param * n) ** 2))
+    raise ValueError(f"unknown rank distribution {dist!r}")
+
+
 def _zipf_cdf(n: int, s: float, device) -> torch.Tensor:
-    c = torch.cumsum(torch.arange(1, n + 1, dtype=torch.float64, device=device).pow_(-s), 0)
+    c = torch.cumsum(rank_weights(n, "zipf", s, device), 0)
     return c / c[-1]
 
 
@@ -255,20 +276,30 @@ class Sampler:
             self._perm[t] = torch.argsort(k, stable=True).to(torch.int32)
         return self._perm[t]
 
+    def _dist(self):
+        wl = self.wl
+        return ("zipf", wl.zipf_s) if wl.rank_dist == "zipf" else (wl.rank_dist, wl.rank_scale)
+
     def cdf(self, t: int) -> torch.Tensor:
-        key = (self.wl.rows[t], self.wl.zipf_s)
+        key = (self.wl.rows[t],) + self._dist()
         if key not in self._cdf:
-            self._cdf[key] = _zipf_cdf(key[0], key[1], self.device)
+            c = torch.cumsum(rank_weights(key[0], key[1], key[2], self.device), 0)
+            self._cdf[key] = c / c[-1]
         return self._cdf[key]
 
     def row_probs(self, t: int) -> torch.Tensor:
         """P(e) for every row id of table t (Section II-A's P(e)), fp64, on CPU."""
         n = self.wl.rows[t]
-        if self.wl.zipf_s is None:
+        if self._uniform():
             return torch.full((n,), 1.0 / n, dtype=torch.float64)
+        d, prm = self._dist()
+        w = rank_weights(n, d, prm)
         p = torch.empty(n, dtype=torch.float64)
-        p[self.permutation(t).cpu().long()] = zipf_probs(n, self.wl.zipf_s)
+        p[self.permutation(t).cpu().long()] = w / w.sum()
         return p
+
+    def _uniform(self) -> bool:
+        return self.wl.rank_dist == "zipf" and self.wl.zipf_s is None
 
     def lengths(self, batch_id: int, t: int, profile: bool) -> torch.Tensor:
         B = self.wl.batch
@@ -288,7 +319,7 @@ class Sampler:
             key = stream_key(wl.seed, S_PROFILE_IDX if profile else S_EVAL_IDX, batch_id, t)
             u = uniform01(key, torch.arange(m, device=self.device))
             n = wl.rows[t]
-            if wl.zipf_s is None:
+            if self._uniform():
                 idx = (u * n).to(torch.int64).clamp_(max=n - 1).to(torch.int32)
             else:
                 rank = torch.searchsorted(self.cdf(t), u, right=False).clamp_(max=n - 1)

@@ -301,3 +301,17 @@ def test_coalescing_without_cache_matches_expected_unique():
     rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
     assert_close(out.cpu().numpy(), want, "coalesced forward without a cache")
     c.close()
+
+
+def test_portion_usage_parity(case):
+    case.build()
+    wl = case.wl
+    idx, off = case.batch
+    portion, nport = max(1, case.k // 5), 7           # the last portions lie beyond the cache: zero use
+    rc, want = oracle.portion_usage(wl.rows, idx.numpy(), off.numpy(), wl.batch, case.ora_slot_of, portion, nport)
+    assert rc == 0
+    d_idx, d_off = case.dev_batch()
+    rm = case.s.remap(d_idx, d_off, wl.batch)
+    got = case.s.portion_usage(d_idx, d_off, wl.batch, rm, portion, nport)
+    assert case.s.sync_status() == 0
+    assert np.array_equal(got.cpu().numpy(), want)

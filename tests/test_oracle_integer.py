@@ -320,3 +320,23 @@ def test_coalesced_cost_matches_expected_communication(ora):
     EU = sum(float(np.sum(1.0 - (1.0 - s.row_probs(t).numpy()) ** wl.batch)) for t in range(wl.num_tables))
     assert abs(uq.size - EU) < 5 * math.sqrt(EU)
     assert uq.size < 0.5 * miss.size                            # Zipf 1.05 at b = 4096: coalescing more than halves it
+
+
+# ------------------------------------------------------------------ cache use by portion (Fig. 4)
+def test_portion_usage_brute_force(ora):
+    wl = synth.workload("multi_hot", scale=0.01)
+    s, counts, hot, slot_of = _build(ora, wl)
+    idx, off = s.batch(0)
+    idx, off = idx.numpy(), off.numpy()
+    k = hot.size
+    portion, nport = max(1, k // 4), 4
+    rc, usage = ora.portion_usage(wl.rows, idx, off, wl.batch, slot_of, portion, nport)
+    assert rc == 0
+    gid = gids_of(wl, idx, off)
+    sample = bag_of(off, idx.shape[0]) % wl.batch
+    sl = slot_of[gid]
+    ok = (sl >= 0) & (sl // portion < nport)
+    pairs = np.unique(np.stack([sample[ok], sl[ok] // portion], 1), axis=0)      # distinct (sample, portion)
+    assert np.array_equal(usage, np.bincount(pairs[:, 1], minlength=nport))
+    assert usage.max() <= wl.batch
+    assert usage[0] >= usage[-1]                 # slots are in hotness order: the first portion is used most
