@@ -188,19 +188,36 @@ def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> 
     }
 
 
-def run_leg(b: Bench, K: int, W: int, link: dict) -> dict:
+def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> dict:
     """W warm-up steps, exactly K timed steps between two synchronizes, then the same K steps again with a HIP
     event pair around every kernel launch (recorded by the library on the launch stream)."""
     wl = b.wl
     for e in range(W):
         b.step(e)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
     lookups = 0
-    for e in range(W, W + K):
-        lookups += b.step(e)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if use_graph:
+        # the K steps allocate nothing and never wait on the host: capture them once, time one replay
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for e in range(W, W + K):
+                    lookups += b.step(e)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        del g
+    else:
+        t0 = time.perf_counter()
+        for e in range(W, W + K):
+            lookups += b.step(e)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     assert b.s.sync_status() == 0
     n_hit, n_miss = b.rm.n_hit_miss.cpu().tolist()
     n_staged = b.rm.n_unique_miss.cpu().tolist()[0] if b.coalesce else n_miss   # rows fetched over the link
@@ -301,6 +318,11 @@ def main():
                     help="shrink table rows and budget only (default 1.0; 0.5 for host_spill, whose 102 GB of "
                          "tables exceed what one box lets a process pin, about 64 GB)")
     ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
+    ap.add_argument("--also", default="dlrm_onehot,low_skew,host_spill",
+                    help="comma-separated other workloads to run briefly afterwards and report under other_workloads "
+                         "('none' to skip)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the K timed steps into one HIP graph and time its replay instead of K eager steps")
     ap.add_argument("--coalesce", action="store_true",
                     help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -315,22 +337,37 @@ def main():
     binding.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    row_scale = args.row_scale if args.row_scale is not None else (0.5 if args.workload == "host_spill" else 1.0)
-    wl = synth.workload(args.workload, scale=args.scale, row_scale=row_scale)
-    budget = wl.budget_bytes if args.budget_bytes < 0 else args.budget_bytes
     cal = calibration(dev)
     link = measure_link(dev)
     log("calibration", cal, "link", link)
+    line = run_workload(args.workload, args, args.steps, args.warmup, cal, link, not args.no_cpu_baseline, args.resident)
+    others = {}
+    for name in [w for w in args.also.split(",") if w and w != "none" and w != args.workload]:
+        # the other single-GPU workloads, shorter: parity-sized and link/latency-bound cases for context
+        torch.cuda.empty_cache()
+        r = run_workload(name, args, min(args.steps, 10), min(args.warmup, 3), cal, link, False, False)
+        others[name] = {"value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "dtype": r["dtype"],
+                        "config": {k: r["config"][k] for k in ("row_scale", "rows", "dim", "batch", "lookups_per_step",
+                                                                "hit_rate", "budget_bytes", "optimizer")},
+                        "roofline": r["roofline"], "host_link": r["host_link"]}
+    line["other_workloads"] = others
+    print(json.dumps(line), flush=True)
+
+
+def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cpu: bool, with_resident: bool) -> dict:
+    dev = torch.device("cuda:0")
+    row_scale = args.row_scale if args.row_scale is not None else (0.5 if name == "host_spill" else 1.0)
+    wl = synth.workload(name, scale=args.scale, row_scale=row_scale)
+    budget = wl.budget_bytes if (args.budget_bytes < 0 or name != args.workload) else args.budget_bytes
 
     b = Bench(wl, budget, args.coalesce)
-    K, W = args.steps, args.warmup
     b.prepare(K + W)
     bc = b.build_cache()
-    log("build_cache", bc)
+    log(name, "build_cache", bc)
 
-    leg = run_leg(b, K, W, link)
+    leg = run_leg(b, K, W, link, args.graph)
     resident = None
-    if args.resident and budget < wl.total_rows * wl.row_bytes and wl.total_rows * wl.row_bytes * 3 < 150e9:
+    if with_resident and budget < wl.total_rows * wl.row_bytes and wl.total_rows * wl.row_bytes * 3 < 150e9:
         # second leg: every row cached (the paper's "hot" iteration): the same kernels, no host-link traffic
         b.s.flush_cache()
         torch.cuda.synchronize()
@@ -338,17 +375,18 @@ def main():
         b.prepare(K + W)
         b.s.build_cache(None, None, 0, b.budget, 0)
         torch.cuda.synchronize()
-        r = run_leg(b, K, W, link)
+        r = run_leg(b, K, W, link, args.graph)
         resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
                     "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "kernels": r["kernels"]}
-        log("cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
+        log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
 
     cpu = None
     b.s.flush_cache()           # host tables current again before the oracle reads them
     torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if with_cpu:
         cpu = cpu_baseline(b)
-        log("cpu_baseline", cpu)
+        log(name, "cpu_baseline", cpu)
+    log(name, "lookups/s", f"{leg['value']:.4g}", "ms/step", f"{leg['ms_per_step']:.4f}")
 
     line = {
         "metric": "pooled embedding lookups/sec (fwd+bwd) + achieved HBM GB/s, 1 GPU",
@@ -361,6 +399,7 @@ def main():
                    "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],
                    "unique_cold_rows_per_step": leg["U_cold"], "missed_lookups_per_step": leg["n_miss"],
                    "rows_fetched_over_link_per_step": leg["n_staged"], "coalesce": args.coalesce,
+                   "launch": "hip graph of the K steps" if args.graph else "eager",
                    "step": "remap + embedding_bag_fwd + embedding_bag_bwd_update"},
         "roofline": leg["roofline"], "host_link": leg["host_link"],
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
@@ -369,7 +408,8 @@ def main():
         "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
     }
     b.close()
-    print(json.dumps(line), flush=True)
+    del b
+    return line
 
 
 if __name__ == "__main__":

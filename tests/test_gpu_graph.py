@@ -1,0 +1,83 @@
+"""The three per-batch calls allocate nothing and never wait on the host, so a step can be captured into a HIP
+graph and replayed.  Each replay is checked against eager results, with eager work between the replays."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2411_01611_amd import synth
+from gpu_harness import GpuCase, assert_close
+
+
+def test_graph_replay_of_remap_and_forward_matches_eager():
+    wl = synth.workload("multi_hot", scale=0.004, batch=333)
+    c = GpuCase(wl)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    rm = c.s.new_remap_out()
+    out = torch.zeros(wl.num_bags, wl.dim, device=c.dev)
+    # eager reference
+    c.s.remap(d_idx, d_off, wl.batch, rm)
+    c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm, out)
+    torch.cuda.synchronize()
+    ref_out, ref_loc, ref_n = out.clone(), rm.loc.clone(), rm.n_hit_miss.clone()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            c.s.remap(d_idx, d_off, wl.batch, rm)
+            c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm, out)
+    torch.cuda.current_stream().wait_stream(side)
+    other = c.sampler.batch(1)
+    for rep in range(3):
+        out.fill_(-1.0)
+        rm.loc.fill_(-7)
+        # eager work on another batch between replays (disturbs the shared workspace on purpose)
+        o_idx, o_off = other[0].to(c.dev), other[1].to(c.dev)
+        rm2 = c.s.remap(o_idx, o_off, wl.batch)
+        c.s.embedding_bag_fwd(o_idx, o_off, wl.batch, rm2)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out), f"replay {rep}"
+        L = d_idx.numel()
+        assert torch.equal(rm.loc[:L], ref_loc[:L]) and torch.equal(rm.n_hit_miss, ref_n)
+    assert c.s.sync_status() == 0
+    c.close()
+
+
+def test_graph_replay_of_a_training_step_matches_oracle():
+    wl = synth.workload("multi_hot", scale=0.004, batch=333)
+    c = GpuCase(wl)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    idx, off = c.batch
+    grad = c.sampler.grads(0)
+    d_grad = grad.to(c.dev)
+    rm = c.s.new_remap_out()
+    out = torch.zeros(wl.num_bags, wl.dim, device=c.dev)
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            c.s.remap(d_idx, d_off, wl.batch, rm)
+            c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm, out)
+            c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, d_grad, float(lr), float(eps))
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+        oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1, idx.numpy(), off.numpy(), wl.batch,
+                                        grad.numpy(), lr, eps)
+        g.replay()
+        torch.cuda.synchronize()
+        assert_close(out.cpu().numpy(), want, f"forward of replay {rep}")
+    c.s.flush_cache()
+    assert c.s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after three replayed steps")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after three replayed steps")
+    c.close()
