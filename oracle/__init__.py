@@ -140,6 +140,22 @@ def portion_usage(rows, indices, offsets, B: int, slot_of: np.ndarray, portion_r
     return rc, usage
 
 
+def epoch_cost(T: int, counts: np.ndarray, n_samples: int, k: int, M: float, a: float, d: float, Q: float):
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    cost = C.c_double(0.0); b = C.c_double(0.0)
+    rc = lib().ora_epoch_cost(C.c_int32(T), C.c_int64(counts.shape[0]), _p(counts), C.c_int64(n_samples), C.c_int64(k),
+                              C.c_double(M), C.c_double(a), C.c_double(d), C.c_double(Q), C.byref(cost), C.byref(b))
+    return rc, cost.value, b.value
+
+
+def plan_brute(T: int, counts: np.ndarray, n_samples: int, k_max: int, M: float, a: float, d: float, Q: float):
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    bk = C.c_int64(0); bc = C.c_double(0.0)
+    rc = lib().ora_plan_brute(C.c_int32(T), C.c_int64(counts.shape[0]), _p(counts), C.c_int64(n_samples), C.c_int64(k_max),
+                              C.c_double(M), C.c_double(a), C.c_double(d), C.c_double(Q), C.byref(bk), C.byref(bc))
+    return rc, bk.value, bc.value
+
+
 def _dt(tables: Sequence[np.ndarray]) -> Tuple[int, int]:
     d = tables[0].dtype
     assert d in (np.float32, np.uint16), "rows are fp32, or bf16 held as uint16"

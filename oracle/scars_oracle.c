@@ -227,6 +227,43 @@ int32_t ora_portion_usage(int32_t T, const int64_t* rows, const int32_t* indices
     return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
 }
 
+/* ---- expected communication per epoch (eq. (6), (7)) ---------------------------------------------- */
+int32_t ora_epoch_cost(int32_t T, int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k, double M, double a,
+                       double d, double Q, double* cost, double* b_out) {
+    if (T < 1 || N < 1 || !counts || n_samples < 1 || k < 0 || k > N || a <= 0.0 || d <= 0.0 || !cost)
+        return ORA_ERR_INVALID_ARG;
+    const double b = (M - (double)k * d) / a;
+    if (!(b >= 1.0)) return ORA_ERR_INVALID_ARG;
+    int32_t* hot = (int32_t*)malloc(sizeof(int32_t) * (size_t)(k > 0 ? k : 1));
+    int32_t* slot_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int rc = ora_hot_set(N, counts, k, hot, slot_of);
+    if (rc) { free(hot); free(slot_of); return rc; }
+    double sum = 0.0;
+    for (int64_t e = 0; e < N; ++e) {
+        if (slot_of[e] >= 0) continue;                       /* cached: no transfer */
+        double p = (double)counts[e] / (double)n_samples;
+        if (p > 1.0) p = 1.0;
+        sum += 1.0 - pow(1.0 - p, b);
+    }
+    *cost = (double)T * Q + (Q / b) * d * sum;
+    if (b_out) *b_out = b;
+    free(hot);
+    free(slot_of);
+    return ORA_OK;
+}
+
+int32_t ora_plan_brute(int32_t T, int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k_max, double M, double a,
+                       double d, double Q, int64_t* best_k, double* best_cost) {
+    if (!best_k || !best_cost || k_max < 0 || k_max > N) return ORA_ERR_INVALID_ARG;
+    int found = 0;
+    for (int64_t k = 0; k <= k_max; ++k) {
+        double c, b;
+        if (ora_epoch_cost(T, N, counts, n_samples, k, M, a, d, Q, &c, &b) != ORA_OK) continue;
+        if (!found || c < *best_cost) { *best_cost = c; *best_k = k; found = 1; }
+    }
+    return found ? ORA_OK : ORA_ERR_INVALID_ARG;
+}
+
 /* ---- forward ----------------------------------------------------------------------------- */
 static int32_t fwd_impl(int32_t T, const int64_t* rows, int32_t D, int32_t dtype, const void* const* tables,
                         const int32_t* slot_of, const void* cache, const int32_t* indices,

@@ -87,6 +87,19 @@ int32_t ora_portion_usage(int32_t T, const int64_t* rows, const int32_t* indices
                           int64_t L, int64_t B, const int32_t* slot_of, int64_t portion_rows, int32_t n_portions,
                           int32_t* usage /* [n_portions] */);
 
+/* Expected communication per epoch with a cached set (Section II-B, eq. (6) with the batch size of eq. (7)).
+ * P(e) = min(1, counts[e] / n_samples) (eq. (1)'s probability that a random sample refers to e, estimated from
+ * the skew table); C = the first k rows in the order (count descending, lower id first);
+ * b = (M - k*d) / a (eq. (7), real-valued; the call fails with ORA_ERR_INVALID_ARG if b < 1);
+ *   cost = T*Q + (Q / b) * d * sum_{e not in C} (1 - (1 - P(e))^b)        (eq. (6), summed over the T features;
+ * the first term is the indices, the second the embeddings, both in parameters).  *b_out receives b. */
+int32_t ora_epoch_cost(int32_t T, int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k, double M, double a,
+                       double d, double Q, double* cost, double* b_out);
+
+/* Brute force over every feasible k in [0, k_max]: the k with the smallest ora_epoch_cost (lowest k on ties). */
+int32_t ora_plan_brute(int32_t T, int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k_max, double M, double a,
+                       double d, double Q, int64_t* best_k, double* best_cost);
+
 /* Lookups ordered by (gid, position): sorted_gid, sorted_bag (bag of each lookup), seg_start[r] = first
  * sorted position of the r-th distinct gid (seg_start[U] = number of valid lookups), unique_gid ascending. */
 int32_t ora_bwd_segments(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
