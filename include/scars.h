@@ -196,6 +196,32 @@ int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_
 int32_t scars_portion_usage(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
                             int64_t portion_rows, int32_t n_portions, int32_t* d_usage, void* stream);
 
+/* Budget chooser from the paper's expected-communication model (Section II-B).  With P(e) estimated from the
+ * skew table as min(1, counts[e] / profile_samples), C = the first k rows of the ranking, d = dim and the batch
+ * size tied to the cache by eq. (7), b = (M - k d) / a, an epoch of Q samples communicates (eq. (6), summed
+ * over the T features, in parameters)
+ *     cost(k) = T Q + (Q / b) d sum_{e not in C} (1 - (1 - P(e))^b).
+ * Both calls BLOCK (one small kernel builds the rows-per-count table, the rest is host arithmetic). */
+typedef struct {
+    double device_params;      /* M: parameters that fit on the device */
+    double per_sample_params;  /* a: parameters (weights share + activations) one sample of the batch needs */
+    double samples_per_epoch;  /* Q */
+    int64_t profile_samples;   /* samples behind the counts now in the skew table */
+} scars_plan_in;
+
+typedef struct {
+    int64_t best_k;            /* rows to cache: the k with the smallest cost among those examined */
+    double best_cost, best_batch;
+    double cost_no_cache, batch_no_cache;   /* k = 0: coalescing only, eq. (5) */
+    int64_t k_max;             /* largest k that still leaves room for one sample (b >= 1) */
+} scars_plan_out;
+
+/* cost(k) and its batch size for one k; INVALID_ARG if b < 1. */
+int32_t scars_epoch_cost(scars_handle* h, const scars_plan_in* in, int64_t k, double* cost, double* batch, void* stream);
+
+/* Search over k in [0, k_max]: every k when k_max <= 4096, otherwise count-class borders and a narrowing grid. */
+int32_t scars_plan_cache(scars_handle* h, const scars_plan_in* in, scars_plan_out* out, void* stream);
+
 /* Write every cached row (and Adagrad accumulator) back to its pinned host table. */
 int32_t scars_flush_cache(scars_handle* h, void* stream);
 

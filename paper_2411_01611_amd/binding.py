@@ -23,7 +23,8 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
-    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
+    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_epoch_cost",
+    "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_profile_enable", "scars_profile_read",
 )
@@ -65,6 +66,16 @@ class _ClassifyOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("is_hot", "hot_ids", "normal_ids", "n_hot_normal")]
 
 
+class _PlanIn(C.Structure):
+    _fields_ = [("device_params", C.c_double), ("per_sample_params", C.c_double), ("samples_per_epoch", C.c_double),
+                ("profile_samples", C.c_int64)]
+
+
+class _PlanOut(C.Structure):
+    _fields_ = [("best_k", C.c_int64), ("best_cost", C.c_double), ("best_batch", C.c_double), ("cost_no_cache", C.c_double),
+                ("batch_no_cache", C.c_double), ("k_max", C.c_int64)]
+
+
 class _KernelTime(C.Structure):
     _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double)]
 
@@ -93,6 +104,8 @@ def lib():
                                                      C.POINTER(_BwdOut), vp]
         L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
         L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
+        L.scars_epoch_cost.argtypes = [vp, C.POINTER(_PlanIn), i64, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+        L.scars_plan_cache.argtypes = [vp, C.POINTER(_PlanIn), C.POINTER(_PlanOut), vp]
         L.scars_flush_cache.argtypes = [vp, vp]
         L.scars_sync_status.argtypes = [vp, vp]
         L.scars_last_error.argtypes = [vp]
@@ -365,6 +378,18 @@ class Scars:
         self._check(lib().scars_portion_usage(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
                                               portion_rows, n_portions, usage.data_ptr(), _stream()))
         return usage
+
+    def epoch_cost(self, M: float, a: float, Q: float, profile_samples: int, k: int):
+        """(cost, batch size) of eq. (6)/(7) for k cached rows, from the skew table now on the device.  Blocks."""
+        pin = _PlanIn(M, a, Q, profile_samples)
+        cost, b = C.c_double(0.0), C.c_double(0.0)
+        self._check(lib().scars_epoch_cost(self._h, C.byref(pin), k, C.byref(cost), C.byref(b), _stream()))
+        return cost.value, b.value
+
+    def plan_cache(self, M: float, a: float, Q: float, profile_samples: int) -> Dict[str, float]:
+        pin, po = _PlanIn(M, a, Q, profile_samples), _PlanOut()
+        self._check(lib().scars_plan_cache(self._h, C.byref(pin), C.byref(po), _stream()))
+        return {n: getattr(po, n) for n, _ in _PlanOut._fields_}
 
     def flush_cache(self) -> None:
         self._check(lib().scars_flush_cache(self._h, _stream()))

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscars.so")
-SOURCES = ["scars_api.hip", "k_sort.hip", "k_build_cache.hip", "k_remap.hip", "k_classify.hip", "k_fwd.hip", "k_bwd.hip"]
+SOURCES = ["scars_api.hip", "k_sort.hip", "k_build_cache.hip", "k_remap.hip", "k_classify.hip", "k_plan.hip", "k_fwd.hip", "k_bwd.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

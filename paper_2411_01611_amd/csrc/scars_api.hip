@@ -1,7 +1,10 @@
 // C ABI of libscars: handle lifecycle, buffer binding, argument checks, and the four entry points.
 // Every device step is a kernel in the k_*.hip files; this file only validates and enqueues.
+#include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 
 #include "scars_internal.h"
 
@@ -74,6 +77,7 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     const int64_t chunks = nbL * (kScanTile / kLongRunMin);    // whole scan tiles: the counters are cleared per tile
     w.partial = (double*)take(chunks * 2 * h->D * 8);
     w.chunk_run = (int32_t*)take((chunks + 1) * 4);
+    w.plan_cc = (uint32_t*)take((kPlanBins + kPlanBigCap + 4) * 4);
     w.staging = take(max_L * h->R);
     w.total_bytes = off;
     return w;
@@ -294,6 +298,99 @@ int32_t scars_portion_usage(scars_handle* h, const int32_t* d_offsets, int64_t L
         return fail(h, SCARS_ERR_INVALID_ARG, "portion_usage: portion_rows >= 1, 1 <= n_portions <= 64, usage not null");
     hipError_t e = launch_portion_usage(h, (hipStream_t)stream, d_offsets, L, B, rm, portion_rows, n_portions, d_usage);
     if (e != hipSuccess) return hip_fail(h, e, "portion_usage");
+    return SCARS_OK;
+}
+
+// rows per count value from the device skew table, hottest class first
+static int32_t load_classes(scars_handle* h, hipStream_t s, std::vector<std::pair<uint32_t, int64_t>>* classes) {
+    hipError_t e = launch_count_of_counts(h, s);
+    if (e != hipSuccess) return hip_fail(h, e, "plan(count of counts)");
+    std::vector<uint32_t> host(kPlanBins + kPlanBigCap + 4);
+    e = hipMemcpyAsync(host.data(), h->ws.plan_cc, host.size() * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(h, e, "plan(copy)");
+    const uint32_t n_big = host[kPlanBins + kPlanBigCap];
+    if (n_big > (uint32_t)kPlanBigCap) return fail(h, SCARS_ERR_WORKSPACE, "plan: too many rows with a count of 65536 or more");
+    std::vector<uint32_t> big(host.begin() + kPlanBins, host.begin() + kPlanBins + n_big);
+    std::sort(big.begin(), big.end(), std::greater<uint32_t>());
+    classes->clear();
+    for (size_t i = 0; i < big.size();) {
+        size_t j = i;
+        while (j < big.size() && big[j] == big[i]) ++j;
+        classes->push_back({big[i], (int64_t)(j - i)});
+        i = j;
+    }
+    for (int c = kPlanBins - 1; c >= 0; --c)
+        if (host[c]) classes->push_back({(uint32_t)c, (int64_t)host[c]});
+    return SCARS_OK;
+}
+
+static int32_t check_plan(scars_handle* h, const scars_plan_in* in) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "plan: no buffers bound");
+    if (!in || !(in->device_params > 0.0) || !(in->per_sample_params > 0.0) || !(in->samples_per_epoch > 0.0) ||
+        in->profile_samples < 1)
+        return fail(h, SCARS_ERR_INVALID_ARG, "plan: parameters must be positive");
+    return SCARS_OK;
+}
+
+int32_t scars_epoch_cost(scars_handle* h, const scars_plan_in* in, int64_t k, double* cost, double* batch, void* stream) {
+    int32_t rc = check_plan(h, in);
+    if (rc) return rc;
+    if (k < 0 || k > h->N || !cost) return fail(h, SCARS_ERR_INVALID_ARG, "epoch_cost: k out of range or null output");
+    std::vector<std::pair<uint32_t, int64_t>> classes;
+    if ((rc = load_classes(h, (hipStream_t)stream, &classes))) return rc;
+    double b = 0.0;
+    const double c = plan_cost(classes, h->T, in->profile_samples, k, in->device_params, in->per_sample_params, (double)h->D,
+                               in->samples_per_epoch, &b);
+    if (batch) *batch = b;
+    if (!std::isfinite(c)) return fail(h, SCARS_ERR_INVALID_ARG, "epoch_cost: no room for a batch of one sample (b < 1)");
+    *cost = c;
+    return SCARS_OK;
+}
+
+int32_t scars_plan_cache(scars_handle* h, const scars_plan_in* in, scars_plan_out* out, void* stream) {
+    int32_t rc = check_plan(h, in);
+    if (rc) return rc;
+    if (!out) return fail(h, SCARS_ERR_INVALID_ARG, "plan_cache: null output");
+    std::vector<std::pair<uint32_t, int64_t>> classes;
+    if ((rc = load_classes(h, (hipStream_t)stream, &classes))) return rc;
+    const double M = in->device_params, a = in->per_sample_params, d = (double)h->D, Q = in->samples_per_epoch;
+    // feasible k: b = (M - k d) / a >= 1
+    const double kf = std::floor((M - a) / d);
+    if (kf < 0.0) return fail(h, SCARS_ERR_INVALID_ARG, "plan_cache: the device cannot hold a batch of one sample");
+    const int64_t k_max = (int64_t)std::min<double>((double)h->N, kf);
+    auto cost = [&](int64_t k, double* b) { return plan_cost(classes, h->T, in->profile_samples, k, M, a, d, Q, b); };
+    int64_t best_k = 0;
+    double best_b = 0.0, best = cost(0, &best_b);
+    auto consider = [&](int64_t k) {
+        double b;
+        const double c = cost(k, &b);
+        if (c < best || (c == best && k < best_k)) { best = c; best_k = k; best_b = b; }
+    };
+    if (k_max <= 4096) {
+        for (int64_t k = 1; k <= k_max; ++k) consider(k);           // small tables: every k
+    } else {
+        // class borders, then three rounds of a 64-point grid narrowing around the best point
+        int64_t before = 0;
+        for (const auto& cl : classes) {
+            before += cl.second;
+            if (before <= k_max && classes.size() <= 4096) consider(before);
+        }
+        int64_t lo = 0, hi = k_max;
+        for (int round = 0; round < 4; ++round) {
+            const int64_t step = std::max<int64_t>(1, (hi - lo) / 64);
+            for (int64_t k = lo; k <= hi; k += step) consider(k);
+            consider(hi);
+            lo = std::max<int64_t>(0, best_k - step);
+            hi = std::min<int64_t>(k_max, best_k + step);
+        }
+    }
+    out->best_k = best_k;
+    out->best_cost = best;
+    out->best_batch = best_b;
+    out->cost_no_cache = cost(0, &out->batch_no_cache);
+    out->k_max = k_max;
     return SCARS_OK;
 }
 

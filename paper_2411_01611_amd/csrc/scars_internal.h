@@ -18,6 +18,8 @@ constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1
 constexpr int kSortRoundsLarge = 8;   // 2048 above
 constexpr int kSortMaxBins = 512;     // up to 9 bits per pass
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
+constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
+constexpr int kPlanBigCap = 4096;
 constexpr int kLongRunMin = 64;      // runs longer than this are cut into tasks of this many lookups
 
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -58,6 +60,7 @@ struct Workspace {
     uint32_t* first_bag;      // [max_L] bag of the first lookup of each distinct row
     double* partial;          // [chunks][2][D] fp64 partial sums of long runs, chunks of kLongRunMin sorted positions
     int32_t* chunk_run;       // [chunks + 1] run (segment) index that holds each chunk's first position
+    uint32_t* plan_cc;        // [kPlanBins] rows per count value, [kPlanBigCap] counts at or above kPlanBins, [4] their number
     void* staging;            // [max_L][R] rows fetched over the host link
     int64_t total_bytes;
 };
@@ -134,6 +137,10 @@ hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, i
                            const scars_remap_out* rm, const scars_classify_out* out);
 hipError_t launch_portion_usage(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                                 const scars_remap_out* rm, int64_t portion_rows, int32_t n_portions, int32_t* usage);
+// k_plan.hip
+hipError_t launch_count_of_counts(scars_handle* h, hipStream_t s);
+double plan_cost(const std::vector<std::pair<uint32_t, int64_t>>& classes, int T, int64_t n_samples, int64_t k, double M,
+                 double a, double d, double Q, double* b_out);
 // k_fwd.hip
 hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, float* out);

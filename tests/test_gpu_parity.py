@@ -315,3 +315,91 @@ def test_portion_usage_parity(case):
     got = case.s.portion_usage(d_idx, d_off, wl.batch, rm, portion, nport)
     assert case.s.sync_status() == 0
     assert np.array_equal(got.cpu().numpy(), want)
+
+
+# ---- budget chooser: eq. (6)/(7) on the device skew table -------------------------------------------------
+def _plan_params(case, frac):
+    """M holds `frac` of the rows next to a batch; a makes the batch a few thousand samples when nothing is cached."""
+    wl = case.wl
+    d = float(wl.dim)
+    M = wl.total_rows * d * frac
+    a = M / 4096.0
+    return M, a, d, 1.0e6, len(case.profile) * wl.batch
+
+
+@pytest.mark.parametrize("frac", [0.3, 2.0])
+def test_epoch_cost_parity(case, frac):
+    counts, _, _ = case.build()
+    wl = case.wl
+    M, a, d, Q, S = _plan_params(case, frac)
+    kf = int(min(wl.total_rows, (M - a) // d))
+    for k in sorted({0, 1, case.k, kf // 2, kf}):
+        _say("epoch_cost", wl.name, "k", k)
+        rc, want, b_want = oracle.epoch_cost(wl.num_tables, counts, S, k, M, a, d, Q)
+        assert rc == 0
+        got, b = case.s.epoch_cost(M, a, Q, S, k)
+        assert abs(b - b_want) <= 1e-12 * b_want
+        assert abs(got - want) <= 1e-10 * want            # same fp64 terms, summed per count class instead of per row
+    if kf < wl.total_rows:                                # one row more leaves no room for a sample: refused by both
+        assert oracle.epoch_cost(wl.num_tables, counts, S, kf + 1, M, a, d, Q)[0] != 0
+        with pytest.raises(binding.ScarsError):
+            case.s.epoch_cost(M, a, Q, S, kf + 1)
+
+
+def test_plan_cache_matches_brute_force():
+    # a table small enough that the oracle can try every k; the library examines every k as well
+    wl = synth.workload("tiny", rows=(1500, 900, 600), budget_bytes=1 << 16)
+    c = GpuCase(wl, nprofile=8)
+    counts, _, _ = c.build()
+    for frac in (0.2, 0.6, 3.0):
+        M, a, d, Q, S = _plan_params(c, frac)
+        a = M / 512.0
+        kf = int(min(wl.total_rows, (M - a) // d))
+        _say("plan_cache", "frac", frac, "k_max", kf)
+        rc, bk, bc = oracle.plan_brute(wl.num_tables, counts, S, kf, M, a, d, Q)
+        assert rc == 0
+        p = c.s.plan_cache(M, a, Q, S)
+        assert p["k_max"] == kf
+        assert abs(p["best_cost"] - bc) <= 1e-10 * bc
+        if p["best_k"] != bk:                             # only a tie up to summation order may move the argmin
+            assert abs(oracle.epoch_cost(wl.num_tables, counts, S, int(p["best_k"]), M, a, d, Q)[1] - bc) <= 1e-10 * bc
+        rc, c0, b0 = oracle.epoch_cost(wl.num_tables, counts, S, 0, M, a, d, Q)
+        assert abs(p["cost_no_cache"] - c0) <= 1e-10 * c0 and abs(p["batch_no_cache"] - b0) <= 1e-12 * b0
+        assert abs(p["best_batch"] - (M - p["best_k"] * d) / a) <= 1e-9
+    c.close()
+
+
+def test_plan_cache_grid_search_is_no_worse_than_sampled_k(case):
+    # beyond 4096 candidate rows the search is a narrowing grid: its result must not lose to any k the oracle samples
+    counts, _, _ = case.build()
+    wl = case.wl
+    M, a, d, Q, S = _plan_params(case, 0.5)
+    p = case.s.plan_cache(M, a, Q, S)
+    rc, want, _ = oracle.epoch_cost(wl.num_tables, counts, S, int(p["best_k"]), M, a, d, Q)
+    assert rc == 0 and abs(p["best_cost"] - want) <= 1e-10 * want
+    kf = int(p["k_max"])
+    for k in np.unique(np.linspace(0, kf, 41).astype(np.int64)):
+        rc, ck, _ = oracle.epoch_cost(wl.num_tables, counts, S, int(k), M, a, d, Q)
+        assert rc == 0 and p["best_cost"] <= ck * (1 + 1e-10)
+
+
+def test_epoch_cost_with_counts_beyond_the_binned_range():
+    # counts written straight into the device skew table: many rows of one small count (the one-atomic-per-wave
+    # path), rows in the globally binned range, and rows whose count exceeds 65535 (kept as a list)
+    wl = synth.workload("tiny", rows=(7000, 3000))
+    c = GpuCase(wl, nprofile=1)
+    N = wl.total_rows
+    u = synth.uniform01(synth.stream_key(wl.seed, 77), torch.arange(N, dtype=torch.int64)).numpy()
+    counts = np.where(u < 0.7, 3, np.where(u < 0.9, (u * 60000).astype(np.int64), (u * 3.0e6).astype(np.int64))).astype(np.uint32)
+    counts[:640] = 0
+    assert (counts >= 65536).sum() > 100 and ((counts >= 2048) & (counts < 65536)).sum() > 100
+    c.s.counts().copy_(torch.from_numpy(counts.view(np.int32)))
+    S, d, Q = 4_000_000, float(wl.dim), 1.0e6
+    M = N * d * 0.5
+    a = M / 1000.0
+    for k in (0, 5, 800, 3000):
+        rc, want, _ = oracle.epoch_cost(wl.num_tables, counts, S, k, M, a, d, Q)
+        assert rc == 0
+        got, _ = c.s.epoch_cost(M, a, Q, S, k)
+        assert abs(got - want) <= 1e-10 * want
+    c.close()
