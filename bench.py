@@ -167,7 +167,16 @@ def calibration(dev) -> dict:
         e1.record()
         torch.cuda.synchronize()
         best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    return {"copy_bytes_each_way": n, "copy_GBs": best}
+    sink = torch.empty(binding.CALIB_SINK_BYTES, dtype=torch.uint8, device=dev)
+    best_r = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.calibration_read(a, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best_r = max(best_r, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return {"copy_bytes_each_way": n, "copy_GBs": best, "read_GBs": best_r}
 
 
 def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> dict:
@@ -402,7 +411,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
                    "launch": "hip graph of the K steps" if args.graph else "eager",
                    "step": "remap + embedding_bag_fwd + embedding_bag_bwd_update"},
         "roofline": leg["roofline"], "host_link": leg["host_link"],
-        "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
+        "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
                      "d2h_GBs": round(link["d2h_GBs"], 2)},
         "cpu_baseline": cpu, "cache_resident": resident,
         "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},

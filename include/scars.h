@@ -67,6 +67,12 @@ typedef struct {
     float* const* host_state;  /* HOST [T] of PINNED fp32 [rows[t]][D] Adagrad accumulators; NULL for SGD */
 } scars_config;
 
+/* Launch tuning; results never depend on it.  The ordered compactions (hit/miss lists, run starts, sample lists)
+ * count per tile of 2048 items, then need each tile's start: with few tiles the writing kernel adds up the counts
+ * of the tiles before its own, beyond the limit a separate scan kernel runs first.  A limit of 0 always scans. */
+#define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 1024, at most 4096 */
+int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value);
+
 /* Sizes, in bytes, of the DEVICE buffers the caller must allocate (all 256-byte aligned). */
 typedef struct {
     int64_t k;                  /* rows the budget buys: min(N, floor(budget_bytes / R)) */
@@ -241,6 +247,12 @@ int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind /* 
 /* Measurement aid: a plain grid-stride copy kernel (k_calib_copy) of `bytes` (multiple of 16) between two DEVICE
  * buffers, used to scale hardware byte counters against a transfer of known size. */
 int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
+
+/* Measurement aid: a plain grid-stride read-only kernel over `bytes` (multiple of 16) of a DEVICE buffer; each
+ * thread folds what it read into one 32-bit word of `d_sink` (DEVICE, at least SCARS_CALIB_SINK_BYTES).  Gives the
+ * box's streaming read rate, the practical ceiling of a gather. */
+#define SCARS_CALIB_SINK_BYTES (4 << 20)
+int32_t scars_calibration_read(const void* d_src, int64_t bytes, void* d_sink, void* stream);
 
 /* Per-kernel timing for measurement: when enabled, every kernel launch is bracketed by HIP events on the
  * caller's stream.  scars_profile_read waits for the stream, then returns up to `cap` records

@@ -22,11 +22,11 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
-    "scars_create", "scars_destroy", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
+    "scars_create", "scars_destroy", "scars_set_tuning", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
     "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_epoch_cost",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
-    "scars_memcpy", "scars_calibration_copy", "scars_profile_enable", "scars_profile_read",
+    "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_profile_enable", "scars_profile_read",
 )
 
 
@@ -93,6 +93,7 @@ def lib():
         vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
         L.scars_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
         L.scars_destroy.argtypes = [vp]
+        L.scars_set_tuning.argtypes = [vp, i32, i64]
         L.scars_query_sizes.argtypes = [vp, i64, i64, i64, C.POINTER(_Sizes)]
         L.scars_bind_buffers.argtypes = [vp, C.POINTER(_Buffers), vp]
         L.scars_build_cache.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
@@ -114,6 +115,7 @@ def lib():
         L.scars_host_free.argtypes = [vp]
         L.scars_memcpy.argtypes = [vp, vp, i64, i32, vp]
         L.scars_calibration_copy.argtypes = [vp, vp, i64, vp]
+        L.scars_calibration_read.argtypes = [vp, i64, vp, vp]
         L.scars_profile_enable.argtypes = [vp, i32]
         L.scars_profile_read.argtypes = [vp, vp, C.POINTER(_KernelTime), i32, C.POINTER(i32)]
         _lib = L
@@ -122,6 +124,19 @@ def lib():
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+CALIB_SINK_BYTES = 4 << 20
+TUNE_FUSED_SCAN_MAX_TILES = 1
+
+
+def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Launch the plain read-only kernel on the current stream (sink: CUDA tensor of at least CALIB_SINK_BYTES)."""
+    n = src.numel() * src.element_size()
+    assert n % 16 == 0 and sink.numel() * sink.element_size() >= CALIB_SINK_BYTES
+    rc = lib().scars_calibration_read(src.data_ptr(), n, sink.data_ptr(), _stream())
+    if rc != OK:
+        raise ScarsError(rc, "calibration read failed")
 
 
 def calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
@@ -378,6 +393,9 @@ class Scars:
         self._check(lib().scars_portion_usage(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
                                               portion_rows, n_portions, usage.data_ptr(), _stream()))
         return usage
+
+    def set_tuning(self, which: int, value: int) -> None:
+        self._check(lib().scars_set_tuning(self._h, which, value))
 
     def epoch_cost(self, M: float, a: float, Q: float, profile_samples: int, k: int):
         """(cost, batch size) of eq. (6)/(7) for k cached rows, from the skew table now on the device.  Blocks."""

@@ -33,6 +33,27 @@ hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t 
     return hipGetLastError();
 }
 
+// Plain streaming read: every 16-byte word is loaded once and folded into one word per thread (written to `sink`,
+// gridDim * kBlock words), so the box's read-only rate can stand beside the copy rate.
+constexpr int kCalibReadGrid = 256 * 16;
+__global__ __launch_bounds__(kBlock) void k_calib_read(const u32x4* __restrict__ src, int64_t n16, uint32_t* __restrict__ sink) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    sink[(int64_t)blockIdx.x * kBlock + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
+hipError_t launch_calib_read(hipStream_t s, const void* src, int64_t bytes, void* sink) {
+    hipLaunchKernelGGL(k_calib_read, dim3(kCalibReadGrid), dim3(kBlock), 0, s, (const u32x4*)src, bytes / 16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
 // ---- (1) histogram --------------------------------------------------------------------------------
 // One thread per lookup.  The table of a lookup follows from its position: lookups of table t occupy
 // [offsets[t*B], offsets[(t+1)*B]).

@@ -80,14 +80,15 @@ __global__ __launch_bounds__(kBlock) void k_seg_scan(uint32_t* __restrict__ a, u
 
 __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                       int64_t L, const uint32_t* __restrict__ blk_head,
-                                                      const int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start,
+                                                      const uint32_t* __restrict__ blk_valid, int scanned,
+                                                      int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start,
                                                       int32_t* __restrict__ unique_gid, int32_t* __restrict__ sorted_gid,
                                                       int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run,
                                                       const int32_t* __restrict__ slot_of, uint32_t N,
                                                       int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag,
                                                       const int32_t* __restrict__ off, int64_t G, const int32_t* __restrict__ gid_of,
                                                       const int32_t* __restrict__ loc_of, int32_t k, int staged) {
-    __shared__ uint32_t s_a[4];
+    __shared__ uint32_t s_a[4], s_red[8];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     bool hd[kRoundsS];
     uint32_t nh = 0;
@@ -98,7 +99,12 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
     }
     if (lane_id() == 0) s_a[wave_id()] = nh;
     __syncthreads();
-    uint32_t before = blk_head[blockIdx.x];
+    uint32_t before, bv, n_runs, n_valid;
+    const bool last = tile_prefix2(blk_head, blk_valid, blockIdx.x, gridDim.x, scanned != 0, s_red, n_unique, &before, &bv,
+                                   &n_runs, &n_valid);
+    // one entry past the last run start: the number of valid pairs
+    if (last && threadIdx.x == 0) seg_start[n_runs] = (int32_t)n_valid;
+    if (scanned && blockIdx.x == 0 && threadIdx.x == 0) seg_start[n_unique[0]] = n_unique[1];
     for (int w = 0; w < wave_id(); ++w) before += s_a[w];
 #pragma unroll
     for (int r = 0; r < kRoundsS; ++r) {
@@ -132,7 +138,6 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
             sorted_bag[j] = (int32_t)val[j];
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) seg_start[n_unique[0]] = n_unique[1];
 }
 
 // ---- (4)/(5) segment reduce and update --------------------------------------------------------------------
@@ -440,13 +445,15 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         Timed t(h, s, "seg_count");
         hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss);
     }
-    {
+    const bool scan = nb > h->fused_scan_max_tiles;   // few tiles: the writer adds up the tile counts itself
+    if (scan) {
         Timed t(h, s, "seg_scan");
         hipLaunchKernelGGL(k_seg_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, n_unique);
     }
     {
         Timed t(h, s, "seg_write");
-        hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, n_unique, seg_start,
+        hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, ws.blk_miss, scan ? 1 : 0,
+                           n_unique, seg_start,
                            unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run,
                            h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid, rm->loc,
                            (int32_t)h->k, use_staged ? 1 : 0);

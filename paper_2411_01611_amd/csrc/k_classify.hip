@@ -46,8 +46,9 @@ __global__ __launch_bounds__(kBlock) void k_cls_flag(const int32_t* __restrict__
 
 __global__ __launch_bounds__(kBlock) void k_cls_write(const int32_t* __restrict__ is_hot, int64_t B,
                                                       const uint32_t* __restrict__ blk_hot, const uint32_t* __restrict__ blk_normal,
+                                                      int scanned, int32_t* __restrict__ n_hot_normal,
                                                       int32_t* __restrict__ hot_ids, int32_t* __restrict__ normal_ids) {
-    __shared__ uint32_t s_h[4], s_n[4];
+    __shared__ uint32_t s_h[4], s_n[4], s_red[8];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveC;
     int32_t f[kRoundsC];
     uint32_t nh = 0, nn = 0;
@@ -60,7 +61,8 @@ __global__ __launch_bounds__(kBlock) void k_cls_write(const int32_t* __restrict_
     }
     if (lane_id() == 0) { s_h[wave_id()] = nh; s_n[wave_id()] = nn; }
     __syncthreads();
-    uint32_t hb = blk_hot[blockIdx.x], nb = blk_normal[blockIdx.x];
+    uint32_t hb, nb, th, tn;
+    tile_prefix2(blk_hot, blk_normal, blockIdx.x, gridDim.x, scanned != 0, s_red, n_hot_normal, &hb, &nb, &th, &tn);
     for (int w = 0; w < wave_id(); ++w) { hb += s_h[w]; nb += s_n[w]; }
 #pragma unroll
     for (int r = 0; r < kRoundsC; ++r) {
@@ -119,14 +121,15 @@ hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, i
         hipLaunchKernelGGL(k_cls_flag, dim3(nb), dim3(kBlock), 0, s, off, (int32_t)L, B, h->T, rm->slot, rm->gid,
                            out->is_hot, ws.blk_hit, ws.blk_miss);
     }
-    {
+    const bool scan = nb > h->fused_scan_max_tiles;   // few tiles: the writer adds up the tile counts itself
+    if (scan) {
         Timed t(h, s, "cls_scan");
         hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hot_normal);
     }
     {
         Timed t(h, s, "cls_write");
         hipLaunchKernelGGL(k_cls_write, dim3(nb), dim3(kBlock), 0, s, out->is_hot, B, ws.blk_hit, ws.blk_miss,
-                           out->hot_ids, out->normal_ids);
+                           scan ? 1 : 0, out->n_hot_normal, out->hot_ids, out->normal_ids);
     }
     return hipGetLastError();
 }

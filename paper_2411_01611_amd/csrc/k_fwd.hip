@@ -13,6 +13,7 @@ namespace scars {
 
 constexpr int kUnroll = 4;       // rows in flight per lane group when staging misses
 constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
+constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
@@ -88,7 +89,7 @@ __device__ __forceinline__ void store_chunk(const Chunk<DTYPE>& acc, float* __re
 // Sum of the rows at positions [a, b) by one group of LPR lanes (lane c holds 16-byte piece c of the row).
 // The group's lanes fetch LPR locations with one load and hand them out by shuffles, so the row addresses of a
 // whole window are known before the first row arrives; positions are added in order.
-template <int DTYPE, int LPR>
+template <int DTYPE, int LPR, int UNROLL>
 __device__ __forceinline__ void pool_range(Chunk<DTYPE>& acc, int32_t a, int32_t b, const int32_t* __restrict__ loc,
                                            const uint4* __restrict__ cache, const uint4* __restrict__ staging, int32_t k,
                                            int chunks, int c, bool lane_on) {
@@ -96,11 +97,11 @@ __device__ __forceinline__ void pool_range(Chunk<DTYPE>& acc, int32_t a, int32_t
     for (int32_t w0 = a; w0 < b; w0 += LPR) {
         const int32_t n = min((int32_t)LPR, b - w0);
         const int32_t lv = c < n ? loc[w0 + c] : -1;
-        for (int base = 0; base < n; base += kPoolUnroll) {
-            uint4 row[kPoolUnroll];
-            bool on[kPoolUnroll];
+        for (int base = 0; base < n; base += UNROLL) {
+            uint4 row[UNROLL];
+            bool on[UNROLL];
 #pragma unroll
-            for (int u = 0; u < kPoolUnroll; ++u) {
+            for (int u = 0; u < UNROLL; ++u) {
                 const int i = base + u;
                 const int32_t l = __shfl(lv, gl0 + (i & (LPR - 1)), kWave);
                 on[u] = lane_on && i < n && l >= 0;
@@ -110,7 +111,7 @@ __device__ __forceinline__ void pool_range(Chunk<DTYPE>& acc, int32_t a, int32_t
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kPoolUnroll; ++u)
+            for (int u = 0; u < UNROLL; ++u)
                 if (on[u]) acc.add(row[u]);
         }
     }
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(kBlock) void k_pool_group(const int32_t* __restrict
     const int32_t b = min(max(off[g + 1], a), L);
     Chunk<DTYPE> acc;
     acc.zero();
-    pool_range<DTYPE, LPR>(acc, a, b, loc, cache, staging, k, chunks, c, c < chunks);
+    pool_range<DTYPE, LPR, kPoolUnroll>(acc, a, b, loc, cache, staging, k, chunks, c, c < chunks);
     if (c < chunks) store_chunk<DTYPE>(acc, out, g, D, c);
 }
 
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict
         Chunk<DTYPE> acc;
         acc.zero();
         if (lane_on && l0[q] >= 0) acc.add(row[q]);
-        if (b[q] - a[q] > 1) pool_range<DTYPE, LPR>(acc, a[q] + 1, b[q], loc, cache, staging, k, chunks, c, lane_on);
+        if (b[q] - a[q] > 1) pool_range<DTYPE, LPR, kShortTailUnroll>(acc, a[q] + 1, b[q], loc, cache, staging, k, chunks, c, lane_on);
         if (lane_on) store_chunk<DTYPE>(acc, out, g, D, c);
     }
 }

@@ -103,10 +103,11 @@ __global__ __launch_bounds__(kBlock) void k_remap_scan(uint32_t* __restrict__ a,
 
 __global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t* __restrict__ slot,
                                                         const int32_t* __restrict__ gid, const uint32_t* __restrict__ blk_hit,
-                                                        const uint32_t* __restrict__ blk_miss, int32_t k,
+                                                        const uint32_t* __restrict__ blk_miss, int scanned,
+                                                        int32_t* __restrict__ n_hit_miss, int32_t k,
                                                         int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
                                                         int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid) {
-    __shared__ uint32_t s_hit[4], s_miss[4];
+    __shared__ uint32_t s_hit[4], s_miss[4], s_red[8];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
     int32_t s[kRoundsR], g[kRoundsR];
     uint32_t nh = 0, nm = 0;
@@ -120,7 +121,8 @@ __global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t
     }
     if (lane_id() == 0) { s_hit[wave_id()] = nh; s_miss[wave_id()] = nm; }
     __syncthreads();
-    uint32_t hb = blk_hit[blockIdx.x], mb = blk_miss[blockIdx.x];
+    uint32_t hb, mb, th, tm;
+    tile_prefix2(blk_hit, blk_miss, blockIdx.x, gridDim.x, scanned != 0, s_red, n_hit_miss, &hb, &mb, &th, &tm);
     for (int w = 0; w < wave_id(); ++w) { hb += s_hit[w]; mb += s_miss[w]; }
 #pragma unroll
     for (int r = 0; r < kRoundsR; ++r) {
@@ -184,9 +186,11 @@ __global__ __launch_bounds__(kBlock) void k_um_count(const uint32_t* __restrict_
 
 __global__ __launch_bounds__(kBlock) void k_um_write(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                      const int32_t* __restrict__ n_hit_miss, const uint32_t* __restrict__ blk_head,
-                                                     int32_t k, const int32_t* __restrict__ miss_pos,
+                                                     const uint32_t* __restrict__ blk_n, int scanned,
+                                                     int32_t* __restrict__ n_unique_miss, int32_t k,
+                                                     const int32_t* __restrict__ miss_pos,
                                                      int32_t* __restrict__ unique_miss_gid, int32_t* __restrict__ loc) {
-    __shared__ uint32_t s_a[4];
+    __shared__ uint32_t s_a[4], s_red[8];
     const int64_t n = n_hit_miss[1];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
     uint32_t kk[kRoundsR];
@@ -201,7 +205,8 @@ __global__ __launch_bounds__(kBlock) void k_um_write(const uint32_t* __restrict_
     }
     if (lane_id() == 0) s_a[wave_id()] = nh;
     __syncthreads();
-    uint32_t before = blk_head[blockIdx.x];
+    uint32_t before, bn, ta, tb;
+    tile_prefix2(blk_head, blk_n, blockIdx.x, gridDim.x, scanned != 0, s_red, n_unique_miss, &before, &bn, &ta, &tb);
     for (int w = 0; w < wave_id(); ++w) before += s_a[w];
 #pragma unroll
     for (int r = 0; r < kRoundsR; ++r) {
@@ -226,14 +231,16 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         hipLaunchKernelGGL(k_remap_probe, dim3(nb), dim3(kBlock), 0, s, idx, off, L, B, ws.meta, h->buf.slot_of,
                            out->slot, out->gid, ws.blk_hit, ws.blk_miss, ws.tstart, ws.status);
     }
-    {
+    const bool scan = nb > h->fused_scan_max_tiles;   // few tiles: the writer adds up the tile counts itself
+    if (scan) {
         Timed t(h, s, "remap_scan");
         hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hit_miss);
     }
     {
         Timed t(h, s, "remap_write");
         hipLaunchKernelGGL(k_remap_write, dim3(nb), dim3(kBlock), 0, s, L, out->slot, out->gid, ws.blk_hit, ws.blk_miss,
-                           (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos, out->miss_gid);
+                           scan ? 1 : 0, out->n_hit_miss, (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos,
+                           out->miss_gid);
     }
     if (out->unique_miss_gid && L > 0 && h->k < h->N) {
         const int grid = (int)std::min<int64_t>(div_up(L, kBlock), 256 * 8);
@@ -252,14 +259,15 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
             hipLaunchKernelGGL(k_um_count, dim3(nb), dim3(kBlock), 0, s, ws.key_buf[res], out->n_hit_miss, ws.blk_hit,
                                ws.blk_miss);
         }
-        {
+        if (scan) {
             Timed t(h, s, "um_scan");
             hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_unique_miss);
         }
         {
             Timed t(h, s, "um_write");
             hipLaunchKernelGGL(k_um_write, dim3(nb), dim3(kBlock), 0, s, ws.key_buf[res], ws.val_buf[res], out->n_hit_miss,
-                               ws.blk_hit, (int32_t)h->k, out->miss_pos, out->unique_miss_gid, out->loc);
+                               ws.blk_hit, ws.blk_miss, scan ? 1 : 0, out->n_unique_miss, (int32_t)h->k, out->miss_pos,
+                               out->unique_miss_gid, out->loc);
         }
     } else if (out->unique_miss_gid) {
         Timed t(h, s, "um_empty");   // nothing can miss: the list is empty

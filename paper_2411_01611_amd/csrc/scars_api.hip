@@ -120,6 +120,16 @@ int32_t scars_create(const scars_config* cfg, scars_handle** out) {
     return SCARS_OK;
 }
 
+int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
+    if (!h) return SCARS_ERR_INVALID_ARG;
+    if (value < 0 || value > (1 << 20)) return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: value out of range");
+    switch (which) {
+        case SCARS_TUNE_FUSED_SCAN_MAX_TILES: h->fused_scan_max_tiles = (int)std::min<int64_t>(value, 4096); break;
+        default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
+    }
+    return SCARS_OK;
+}
+
 int32_t scars_destroy(scars_handle* h) {
     if (!h) return SCARS_ERR_INVALID_ARG;
     for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.second.first); (void)hipEventDestroy(p.second.second); }
@@ -444,6 +454,11 @@ int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind, vo
 int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream) {
     if (!d_dst || !d_src || bytes < 0 || bytes % 16 != 0) return SCARS_ERR_INVALID_ARG;
     return launch_calib_copy((hipStream_t)stream, d_dst, d_src, bytes) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
+int32_t scars_calibration_read(const void* d_src, int64_t bytes, void* d_sink, void* stream) {
+    if (!d_src || !d_sink || bytes < 0 || bytes % 16 != 0) return SCARS_ERR_INVALID_ARG;
+    return launch_calib_read((hipStream_t)stream, d_src, bytes, d_sink) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
 }
 
 int32_t scars_profile_enable(scars_handle* h, int32_t on) {

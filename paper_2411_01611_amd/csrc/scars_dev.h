@@ -48,6 +48,53 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
     return base + inc - v;
 }
 
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Start of tile t in a two-list compaction, from the per-tile counts a[], b[] of nt tiles.  With `scanned` a scan
+// kernel has already turned the counts into exclusive prefixes (and written the totals).  Otherwise the counts are
+// raw: the workgroup adds up the tiles before its own (a few loads per thread while nt is small; the host picks the
+// scan kernel beyond that), and the workgroup of the last tile also writes the two totals to n_out[0..1].
+// Every thread of the workgroup must call; s_red is LDS scratch [8].  Returns true in that last workgroup, with the
+// totals in *ta, *tb.
+__device__ __forceinline__ bool tile_prefix2(const uint32_t* __restrict__ a, const uint32_t* __restrict__ b, int t, int nt,
+                                             bool scanned, uint32_t* s_red, int32_t* __restrict__ n_out, uint32_t* pa,
+                                             uint32_t* pb, uint32_t* ta, uint32_t* tb) {
+    if (scanned) {
+        *pa = a[t];
+        *pb = b[t];
+        return false;
+    }
+    uint32_t sa = 0, sb = 0;
+    for (int i = threadIdx.x; i < t; i += kBlock) {
+        sa += a[i];
+        sb += b[i];
+    }
+    sa = wave_sum(sa);
+    sb = wave_sum(sb);
+    if (lane_id() == 0) {
+        s_red[wave_id()] = sa;
+        s_red[4 + wave_id()] = sb;
+    }
+    __syncthreads();
+    sa = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    sb = s_red[4] + s_red[5] + s_red[6] + s_red[7];
+    __syncthreads();
+    *pa = sa;
+    *pb = sb;
+    if (t != nt - 1) return false;
+    *ta = sa + a[t];
+    *tb = sb + b[t];
+    if (threadIdx.x == 0 && n_out) {
+        n_out[0] = (int32_t)*ta;
+        n_out[1] = (int32_t)*tb;
+    }
+    return true;
+}
+
 __device__ __forceinline__ void latch_error(int32_t* status, int32_t code) {
     // status[0] holds the first error seen (0 = none); codes are negative
     atomicCAS(status, 0, code);

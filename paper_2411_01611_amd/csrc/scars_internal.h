@@ -93,6 +93,8 @@ struct scars_handle {
     bool staged_valid = false;           // the staging area holds the missed rows of the batch whose remap wrote staged_loc
     const int32_t* staged_loc = nullptr;
     std::string err;
+    // launch tuning (scars_set_tuning)
+    int fused_scan_max_tiles = 1024;     // compaction: up to this many tiles the writer sums the tile counts itself
     // per-kernel timing
     bool profile = false;
     scars::KernelTimer timer;
@@ -127,6 +129,7 @@ hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, 
 hipError_t launch_select_and_fill(scars_handle* h, hipStream_t s, int64_t k);
 hipError_t launch_flush(scars_handle* h, hipStream_t s);
 hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t bytes);
+hipError_t launch_calib_read(hipStream_t s, const void* src, int64_t bytes, void* sink);
 // k_remap.hip
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out);

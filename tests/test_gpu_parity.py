@@ -34,10 +34,18 @@ def _say(*a):
     print(*a, flush=True)
 
 
-@pytest.fixture(params=list(CASES))
+# "/scan": the same case with the separate scan kernels of the compactions forced (by default so few tiles add up
+# their counts in the writing kernels)
+VARIANTS = list(CASES) + ["tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan"]
+
+
+@pytest.fixture(params=VARIANTS)
 def case(request):
     _say("case", request.param)
-    c = GpuCase(_wl(request.param))
+    name, _, variant = request.param.partition("/")
+    c = GpuCase(_wl(name))
+    if variant == "scan":
+        c.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
     yield c
     c.close()
 
