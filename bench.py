@@ -6,7 +6,7 @@ embedding_bag_bwd_update, with the workload's byte budget (hot rows in the HBM c
 memory).  build_cache runs once before the timed region (it is amortised over many batches) and is reported
 separately.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--resident] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--no-resident] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -127,6 +127,11 @@ class Bench:
         self.s.embedding_bag_bwd_update(idx, off, wl.batch, self.rm, g, wl.lr, wl.eps if wl.optimizer == "adagrad" else 0.0)
         return int(idx.numel())
 
+    def fwd_only(self, e: int):
+        idx, off = self.batches[e % len(self.batches)]
+        self.s.remap(idx, off, self.wl.batch, self.rm)
+        self.s.embedding_bag_fwd(idx, off, self.wl.batch, self.rm, self.out)
+
     def close(self):
         self.s.close()
         for p in self.tables + self.state:
@@ -244,6 +249,15 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     U_cold = int((b.s.slot_of()[bo.unique_gid[:U].long()] < 0).sum().item())
     torch.cuda.synchronize()
     del bo
+    # the gather kernel without the update kernel before it: inside a step it also pays for the write-back of the
+    # rows the previous backward pass left dirty in the caches, so its own rate is measured on remap + forward only
+    for e in range(W):
+        b.fwd_only(e)
+    b.s.profile_enable(True)
+    for e in range(W, W + K):
+        b.fwd_only(e)
+    prof_fwd = b.s.profile_read()
+    b.s.profile_enable(False)
 
     L_avg = lookups / K
     alg = algorithmic_bytes(wl, L_avg, U, n_miss)
@@ -260,6 +274,12 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     roofline = {"kernel": pool, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": pmc_traffic(wl.name, pool),
                 "alg_bytes_per_launch": int(alg[pool]), "avg_launch_ms": round(pool_avg_s * 1e3, 5)}
+    alone_s = prof_fwd[pool]["total_ms"] / prof_fwd[pool]["launches"] * 1e-3
+    roofline["forward_alone"] = {"avg_launch_ms": round(alone_s * 1e3, 5), "achieved": round(alg[pool] / alone_s / 1e9, 1),
+                                 "frac": round(alg[pool] / alone_s / 1e9 / HBM_PEAK_GBS, 4)}
+    calls = {c: round(sum(v["ms_per_step"] for n, v in kern.items() if n.startswith(pre)), 5)
+             for c, pre in (("remap", ("remap_", "um_")), ("embedding_bag_fwd", ("stage_", "pool_")),
+                            ("embedding_bag_bwd_update", ("bwd_", "sort_", "seg_")))}
     host_link = []
     state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
     # forward: every missed lookup's row is read over the link.  backward: a cold row's value comes from the copy
@@ -274,7 +294,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
                               "write_GBs": round(wr / t_s / 1e9, 2), "frac_of_measured_link": round(t_min / t_s, 4)})
     return {"value": lookups / (t1 - t0), "ms_per_step": (t1 - t0) * 1e3 / K, "lookups_per_step": L_avg,
             "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "n_miss": n_miss, "n_staged": n_staged, "roofline": roofline,
-            "host_link": host_link, "kernels": kern}
+            "host_link": host_link, "kernels": kern, "calls_ms": calls}
 
 
 def pmc_traffic(workload: str, kernel: str):
@@ -335,9 +355,11 @@ def main():
     ap.add_argument("--coalesce", action="store_true",
                     help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--resident", action="store_true",
-                    help="add a second leg in which every row is cached (the paper's 'hot' iteration): same kernels, "
-                         "no host-link traffic; reported under cache_resident")
+    ap.add_argument("--no-resident", dest="resident", action="store_false",
+                    help="skip the second leg in which every row is cached (the paper's 'hot' iteration): same "
+                         "kernels, no host-link traffic; reported under cache_resident")
+    ap.add_argument("--resident", dest="resident", action="store_true", help="(default) run that second leg")
+    ap.set_defaults(resident=True)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -386,7 +408,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         torch.cuda.synchronize()
         r = run_leg(b, K, W, link, args.graph)
         resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
-                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "kernels": r["kernels"]}
+                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "calls_ms": r["calls_ms"],
+                    "kernels": r["kernels"]}
         log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
 
     cpu = None
@@ -414,7 +437,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
                      "d2h_GBs": round(link["d2h_GBs"], 2)},
         "cpu_baseline": cpu, "cache_resident": resident,
-        "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
+        "calls_ms": leg["calls_ms"], "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
     }
     b.close()
     del b
