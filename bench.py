@@ -257,7 +257,25 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     for e in range(W, W + K):
         b.fwd_only(e)
     prof_fwd = b.s.profile_read()
+    # ... and with cold caches: a 1 GiB read-only sweep between remap and forward evicts L2 and Infinity Cache
+    sweep = torch.empty(1 << 30, dtype=torch.uint8, device=b.dev)
+    sink = torch.empty(binding.CALIB_SINK_BYTES, dtype=torch.uint8, device=b.dev)
+    for e in range(W, W + K):
+        idx, off = b.batches[e % len(b.batches)]
+        b.s.remap(idx, off, wl.batch, b.rm)
+        binding.calibration_read(sweep, sink)
+        b.s.embedding_bag_fwd(idx, off, wl.batch, b.rm, b.out)
+    prof_cold = b.s.profile_read()
     b.s.profile_enable(False)
+    del sweep, sink
+    # per-step spread: the same K steps once more, each between its own pair of events
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    for i, e in enumerate(range(W, W + K)):
+        evs[i][0].record()
+        b.step(e)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(c) for a, c in evs)
 
     L_avg = lookups / K
     alg = algorithmic_bytes(wl, L_avg, U, n_miss)
@@ -277,6 +295,9 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     alone_s = prof_fwd[pool]["total_ms"] / prof_fwd[pool]["launches"] * 1e-3
     roofline["forward_alone"] = {"avg_launch_ms": round(alone_s * 1e3, 5), "achieved": round(alg[pool] / alone_s / 1e9, 1),
                                  "frac": round(alg[pool] / alone_s / 1e9 / HBM_PEAK_GBS, 4)}
+    cold_s = prof_cold[pool]["total_ms"] / prof_cold[pool]["launches"] * 1e-3
+    roofline["forward_cold_caches"] = {"avg_launch_ms": round(cold_s * 1e3, 5), "achieved": round(alg[pool] / cold_s / 1e9, 1),
+                                       "frac": round(alg[pool] / cold_s / 1e9 / HBM_PEAK_GBS, 4)}
     calls = {c: round(sum(v["ms_per_step"] for n, v in kern.items() if n.startswith(pre)), 5)
              for c, pre in (("remap", ("remap_", "um_")), ("embedding_bag_fwd", ("stage_", "pool_")),
                             ("embedding_bag_bwd_update", ("bwd_", "sort_", "seg_")))}
@@ -294,7 +315,8 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
                               "write_GBs": round(wr / t_s / 1e9, 2), "frac_of_measured_link": round(t_min / t_s, 4)})
     return {"value": lookups / (t1 - t0), "ms_per_step": (t1 - t0) * 1e3 / K, "lookups_per_step": L_avg,
             "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "n_miss": n_miss, "n_staged": n_staged, "roofline": roofline,
-            "host_link": host_link, "kernels": kern, "calls_ms": calls}
+            "host_link": host_link, "kernels": kern, "calls_ms": calls,
+            "ms_per_step_median": round(per_step[len(per_step) // 2], 5), "ms_per_step_min": round(per_step[0], 5)}
 
 
 def pmc_traffic(workload: str, kernel: str):
@@ -315,25 +337,43 @@ def cpu_baseline(b: Bench, seconds_target: float = 12.0) -> dict:
     tabs = [p.np for p in b.tables]
     st = [p.np for p in b.state] if b.state else None
     opt = 1 if wl.optimizer == "adagrad" else 0
-    done_L, t_total, nb = 0, 0.0, 0
     slot_of = b.s.slot_of().cpu().numpy()
-    while t_total < seconds_target and nb < 400:
-        idx, off = b.batches[nb % len(b.batches)]
-        idx, off = idx.cpu().numpy(), off.cpu().numpy()
-        g = b.grads[nb % len(b.grads)].cpu().numpy()
-        t0 = time.time()
-        rc1 = oracle.remap(wl.rows, idx, off, wl.batch, slot_of)[0]
-        rc2 = oracle.embedding_bag_fwd(wl.rows, tabs, idx, off, wl.batch)[0]
-        # report mode with no output arrays: everything is computed, nothing is stored or mutated
-        r = oracle.embedding_bag_bwd_update(wl.rows, tabs, st, opt, idx, off, wl.batch, g, wl.lr, wl.eps,
-                                            report=True, n_unique=0, want_outputs=False)
-        t_total += time.time() - t0
-        assert rc1 == 0 and rc2 == 0 and r[0] == 0
-        done_L += idx.shape[0]
-        nb += 1
+
+    def run(seconds: float, max_batches: int):
+        done_L, t_total, nb = 0, 0.0, 0
+        while t_total < seconds and nb < max_batches:
+            idx, off = b.batches[nb % len(b.batches)]
+            idx, off = idx.cpu().numpy(), off.cpu().numpy()
+            g = b.grads[nb % len(b.grads)].cpu().numpy()
+            t0 = time.time()
+            rc1 = oracle.remap(wl.rows, idx, off, wl.batch, slot_of)[0]
+            rc2 = oracle.embedding_bag_fwd(wl.rows, tabs, idx, off, wl.batch)[0]
+            # report mode with no output arrays: everything is computed, nothing is stored or mutated
+            r = oracle.embedding_bag_bwd_update(wl.rows, tabs, st, opt, idx, off, wl.batch, g, wl.lr, wl.eps,
+                                                report=True, n_unique=0, want_outputs=False)
+            t_total += time.time() - t0
+            assert rc1 == 0 and rc2 == 0 and r[0] == 0
+            done_L += idx.shape[0]
+            nb += 1
+        return done_L, t_total, nb
+
+    done_L, t_total, nb = run(seconds_target, 400)
+    oracle.set_threads(1)
+    one_L, one_t, one_nb = run(4.0, 50)
+    oracle.set_threads(cores)
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     return {"value": done_L / t_total, "unit": "lookups/s", "cores": used, "kind": "oracle",
             "sample": f"{nb} batch(es) of the same workload ({done_L} lookups): oracle remap + fwd + bwd_update "
-                      f"(report mode, nothing mutated) in {t_total:.1f}s"}
+                      f"(report mode, nothing mutated) in {t_total:.1f}s",
+            "value_1_thread": one_L / one_t, "sample_1_thread": f"{one_nb} batch(es) in {one_t:.1f}s",
+            "cpu_model": model, "host_cpus_visible": os.cpu_count()}
 
 
 def main():
@@ -408,6 +448,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         torch.cuda.synchronize()
         r = run_leg(b, K, W, link, args.graph)
         resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
+                    "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
                     "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "calls_ms": r["calls_ms"],
                     "kernels": r["kernels"]}
         log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
@@ -437,6 +478,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
                      "d2h_GBs": round(link["d2h_GBs"], 2)},
         "cpu_baseline": cpu, "cache_resident": resident,
+        "ms_per_step_median": leg["ms_per_step_median"], "ms_per_step_min": leg["ms_per_step_min"],
         "calls_ms": leg["calls_ms"], "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
     }
     b.close()
