@@ -71,3 +71,28 @@ def test_caching_lowers_cost_at_fixed_batch_and_tradeoff_exists(ora):
     assert rc == 0 and 0 < bk < 1500
     c0 = ora.epoch_cost(T, counts[:2000], S, 0, 2000 * d * 0.6, 200.0, d, Q)[1]
     assert bc < c0
+
+
+def test_growth_with_five_times_rows_and_batch_stays_below_five(ora):
+    # end of Section II-B: with 5x the embeddings and 5x the batch, sending each distinct embedding once grows the
+    # per-batch communication by less than the 5x of sending every looked-up embedding; least for the light-tailed
+    # rank distributions.  The paper does not give its parameters; these are ours: one feature, 2*10^5 -> 10^6 rows,
+    # b = 2048 -> 10240, d = 64, Zipf exponent 1, exponential and half-normal with a scale of 2000 ranks (absolute,
+    # so the added rows extend the tail).  Evaluated with the oracle's eq. (6) at k = 0 and Q = b (one batch).
+    N0, b0, d, S = 200_000, 2048.0, 64.0, 10 ** 9
+    j = lambda n: np.arange(n, dtype=np.float64)
+    dists = {"zipf": lambda n: 1.0 / (j(n) + 1.0),
+             "exp": lambda n: np.exp(-j(n) / 2000.0),
+             "halfnormal": lambda n: np.exp(-(j(n) / 2000.0) ** 2 / 2.0)}
+    growth = {}
+    for name, w in dists.items():
+        cost = []
+        for n, b in ((N0, b0), (5 * N0, 5 * b0)):
+            p = w(n)
+            counts = np.round(p / p.sum() * S).astype(np.uint32)
+            rc, c, bb = ora.epoch_cost(1, counts, S, 0, b * 1000.0, 1000.0, d, b)
+            assert rc == 0 and abs(bb - b) < 1e-9
+            cost.append(c)
+        growth[name] = cost[1] / cost[0]
+    assert growth["exp"] < growth["zipf"] < 5.0 and growth["halfnormal"] < growth["zipf"]
+    assert growth["exp"] < 3.0 and growth["halfnormal"] < 3.0

@@ -2,6 +2,7 @@
 import math
 
 import numpy as np
+import pytest
 import torch
 
 from paper_2411_01611_amd import synth
@@ -101,3 +102,25 @@ def test_rows_and_grads():
     assert abs(float(g.mean())) < 0.03 and abs(float(g.std()) - 1.0) < 0.03
     wb = synth.make_tables_cpu(synth.workload("low_skew", scale=0.001))
     assert wb[0].dtype == torch.bfloat16
+
+
+@pytest.mark.parametrize("dist", ["exp", "halfnormal"])
+def test_exponential_and_half_normal_rank_distributions(dist):
+    # closed forms over ranks j = 0..n-1 with scale 0.02 n, and drawn frequencies that follow them
+    wl = synth.workload("tiny", batch=200_000, rank_dist=dist, rank_scale=0.02)
+    s = synth.Sampler(wl)
+    t, n = 1, wl.rows[1]
+    p = s.row_probs(t).numpy()
+    j = np.arange(n, dtype=np.float64)
+    w = np.exp(-j / (0.02 * n)) if dist == "exp" else np.exp(-(j ** 2) / (2.0 * (0.02 * n) ** 2))
+    want_sorted = w / w.sum()
+    assert np.allclose(np.sort(p)[::-1], want_sorted, rtol=1e-12, atol=1e-300)
+    idx, off = s.batch(0)
+    a, b = int(off[t * wl.batch]), int(off[(t + 1) * wl.batch])
+    cnt = np.bincount(idx[a:b].numpy(), minlength=n).astype(np.float64)
+    m = b - a
+    for e in np.argsort(-p)[:20]:
+        assert abs(cnt[e] - m * p[e]) < 5 * math.sqrt(m * p[e] * (1 - p[e]))
+    # almost all mass sits in the first few scale lengths: rows far down the ranking are never drawn
+    cold = np.argsort(-p)[int(0.5 * n):]
+    assert cnt[cold].sum() == 0
