@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 from paper_2411_01611_amd import binding, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+PRESORT_MIN_L = 1 << 17  # batches this large start the backward sort in remap, on the library's side stream
 
 
 def log(*a):
@@ -251,6 +252,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     del bo
     # the gather kernel without the update kernel before it: inside a step it also pays for the write-back of the
     # rows the previous backward pass left dirty in the caches, so its own rate is measured on remap + forward only
+    b.s.set_tuning(binding.TUNE_PRESORT, 0)     # no backward pass follows: nothing to prepare beside the forward pass
     for e in range(W):
         b.fwd_only(e)
     b.s.profile_enable(True)
@@ -267,6 +269,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
         b.s.embedding_bag_fwd(idx, off, wl.batch, b.rm, b.out)
     prof_cold = b.s.profile_read()
     b.s.profile_enable(False)
+    b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
     del sweep, sink
     # per-step spread: the same K steps once more, each between its own pair of events
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -395,6 +398,10 @@ def main():
     ap.add_argument("--coalesce", action="store_true",
                     help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-presort", dest="presort", action="store_false",
+                    help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
+                         "remap on the library's side stream, beside the forward pass")
+    ap.set_defaults(presort=True)
     ap.add_argument("--no-resident", dest="resident", action="store_false",
                     help="skip the second leg in which every row is cached (the paper's 'hot' iteration): same "
                          "kernels, no host-link traffic; reported under cache_resident")
@@ -432,6 +439,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     budget = wl.budget_bytes if (args.budget_bytes < 0 or name != args.workload) else args.budget_bytes
 
     b = Bench(wl, budget, args.coalesce)
+    b.presort = bool(args.presort)
+    b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
     b.prepare(K + W)
     bc = b.build_cache()
     log(name, "build_cache", bc)
@@ -472,7 +481,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
                    "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],
                    "unique_cold_rows_per_step": leg["U_cold"], "missed_lookups_per_step": leg["n_miss"],
                    "rows_fetched_over_link_per_step": leg["n_staged"], "coalesce": args.coalesce,
-                   "launch": "hip graph of the K steps" if args.graph else "eager",
+                   "launch": ("hip graph of the K steps" if args.graph else "eager") +
+                             (", backward sort started by remap on the library's side stream" if args.presort else ""),
                    "step": "remap + embedding_bag_fwd + embedding_bag_bwd_update"},
         "roofline": leg["roofline"], "host_link": leg["host_link"],
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),

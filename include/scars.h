@@ -71,6 +71,20 @@ typedef struct {
  * count per tile of 2048 items, then need each tile's start: with few tiles the writing kernel adds up the counts
  * of the tiles before its own, beyond the limit a separate scan kernel runs first.  A limit of 0 always scans. */
 #define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 1024, at most 4096 */
+/* Value n > 0: for batches of at least n lookups, when the cache is smaller than the tables, scars_remap also starts
+ * the integer half of the backward pass of the same batch (pairs, sort, run starts; it needs the remap outputs only)
+ * on a stream the library owns (default priority, created on first use), so that it runs while
+ * scars_embedding_bag_fwd waits on the host link for the missed rows.  scars_embedding_bag_bwd_update makes the
+ * caller's stream wait for it and uses it when it is called for that batch (same remap_out arrays, offsets, L and
+ * B), after that batch's forward pass, and without a scars_bwd_out; otherwise it sorts again itself.  The next call
+ * of remap, build_cache, sync_status or bwd_update waits for outstanding side-stream work first.  The two
+ * cross-stream waits cost some 10-20 us per step: not worth it for small batches.  Under HIP graph capture the side
+ * stream joins the capture: end the capture after the bwd_update (or sync_status) that joins it back.  Default 0. */
+#define SCARS_TUNE_PRESORT 2
+
+/* Host-side counters (never reset); -1 for an unknown counter. */
+#define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */
+int64_t scars_get_counter(const scars_handle* h, int32_t which);
 int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value);
 
 /* Sizes, in bytes, of the DEVICE buffers the caller must allocate (all 256-byte aligned). */

@@ -22,7 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
-    "scars_create", "scars_destroy", "scars_set_tuning", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
+    "scars_create", "scars_destroy", "scars_set_tuning", "scars_get_counter", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
     "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_epoch_cost",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
@@ -94,6 +94,8 @@ def lib():
         L.scars_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
         L.scars_destroy.argtypes = [vp]
         L.scars_set_tuning.argtypes = [vp, i32, i64]
+        L.scars_get_counter.argtypes = [vp, i32]
+        L.scars_get_counter.restype = i64
         L.scars_query_sizes.argtypes = [vp, i64, i64, i64, C.POINTER(_Sizes)]
         L.scars_bind_buffers.argtypes = [vp, C.POINTER(_Buffers), vp]
         L.scars_build_cache.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
@@ -127,7 +129,8 @@ def _stream() -> int:
 
 
 CALIB_SINK_BYTES = 4 << 20
-TUNE_FUSED_SCAN_MAX_TILES = 1
+TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT = 1, 2
+COUNTER_PREPARED_USED = 1
 
 
 def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:
@@ -396,6 +399,9 @@ class Scars:
 
     def set_tuning(self, which: int, value: int) -> None:
         self._check(lib().scars_set_tuning(self._h, which, value))
+
+    def get_counter(self, which: int) -> int:
+        return int(lib().scars_get_counter(self._h, which))
 
     def epoch_cost(self, M: float, a: float, Q: float, profile_samples: int, k: int):
         """(cost, batch size) of eq. (6)/(7) for k cached rows, from the skew table now on the device.  Blocks."""

@@ -412,21 +412,16 @@ static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, const uint3
     }
 }
 
-hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
-                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out) {
+// Integer half of the backward pass: (gid, bag) pairs, their sort, the run starts.  It depends on the remap outputs
+// only, not on the gradient, so it may run on another stream while the forward pass runs.  `staged`: cold rows take
+// their current value from the staging area (the forward pass of the same batch fills it).
+hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out) {
     Workspace& ws = h->ws;
-    // rows fetched by this batch's forward pass are still in the staging area: cold rows are read from there
-    const bool use_staged = h->staged_valid && h->staged_loc == rm->loc;
-    h->staged_valid = false;   // this call changes the rows
     int32_t* n_unique = out ? out->n_unique : ws.n_unique;
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
     int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
     const int64_t G = (int64_t)h->T * B;
-    if (L == 0) {
-        Timed t(h, s, "bwd_empty");
-        hipLaunchKernelGGL(k_bwd_empty, dim3(1), dim3(kWave), 0, s, n_unique, seg_start);
-        return hipGetLastError();
-    }
     {
         Timed t(h, s, "bwd_pairs");
         const int lpb = std::min(64, next_pow2_host((int)std::max<int64_t>(1, L / std::max<int64_t>(G, 1))));
@@ -438,26 +433,58 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     int res = 0;
     hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
     if (e != hipSuccess) return e;
+    *res_out = res;
     const uint32_t* key = ws.key_buf[res];
     const uint32_t* val = ws.val_buf[res];
     const int nb = (int)div_up(L, kScanTile);
     {
         Timed t(h, s, "seg_count");
-        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_hit, ws.blk_miss);
+        hipLaunchKernelGGL(k_seg_count, dim3(nb), dim3(kBlock), 0, s, key, L, ws.blk_seg_a, ws.blk_seg_b);
     }
     const bool scan = nb > h->fused_scan_max_tiles;   // few tiles: the writer adds up the tile counts itself
     if (scan) {
         Timed t(h, s, "seg_scan");
-        hipLaunchKernelGGL(k_seg_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, n_unique);
+        hipLaunchKernelGGL(k_seg_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_seg_a, ws.blk_seg_b, nb, n_unique);
     }
     {
         Timed t(h, s, "seg_write");
-        hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_hit, ws.blk_miss, scan ? 1 : 0,
-                           n_unique, seg_start,
-                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run,
-                           h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid, rm->loc,
-                           (int32_t)h->k, use_staged ? 1 : 0);
+        hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_seg_a, ws.blk_seg_b, scan ? 1 : 0,
+                           n_unique, seg_start, unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr,
+                           ws.chunk_run, h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid,
+                           rm->loc, (int32_t)h->k, staged ? 1 : 0);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out) {
+    Workspace& ws = h->ws;
+    // rows fetched by this batch's forward pass are still in the staging area: cold rows are read from there
+    const bool use_staged = h->staged_valid && h->staged_loc == rm->loc;
+    h->staged_valid = false;   // this call changes the rows
+    int32_t* n_unique = out ? out->n_unique : ws.n_unique;
+    int32_t* seg_start = out ? out->seg_start : ws.seg_start;
+    int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
+    const int64_t G = (int64_t)h->T * B;
+    // segments prepared on the side stream by the remap of this very batch (the caller's stream has already been
+    // made to wait for them); they are in the workspace arrays, built for staged cold rows when misses are possible
+    const bool prepared = h->presort_valid && h->presort_gid == rm->gid && h->presort_loc == rm->loc &&
+                          h->presort_off == off && h->presort_L == L && h->presort_B == B && !out &&
+                          h->presort_staged == use_staged;
+    h->presort_valid = false;
+    if (L == 0) {
+        Timed t(h, s, "bwd_empty");
+        hipLaunchKernelGGL(k_bwd_empty, dim3(1), dim3(kWave), 0, s, n_unique, seg_start);
+        return hipGetLastError();
+    }
+    int res = h->presort_res;
+    if (prepared) ++h->n_prepared_used;
+    if (!prepared) {
+        hipError_t e = launch_bwd_segments(h, s, off, L, B, rm, use_staged, out, &res);
+        if (e != hipSuccess) return e;
+    }
+    const uint32_t* key = ws.key_buf[res];
+    const uint32_t* val = ws.val_buf[res];
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
                  use_staged ? ws.staging : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};

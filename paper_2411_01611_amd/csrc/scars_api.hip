@@ -77,10 +77,31 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     const int64_t chunks = nbL * (kScanTile / kLongRunMin);    // whole scan tiles: the counters are cleared per tile
     w.partial = (double*)take(chunks * 2 * h->D * 8);
     w.chunk_run = (int32_t*)take((chunks + 1) * 4);
+    w.blk_seg_a = (uint32_t*)take((nbLG + 1) * 4);
+    w.blk_seg_b = (uint32_t*)take((nbLG + 1) * 4);
     w.plan_cc = (uint32_t*)take((kPlanBins + kPlanBigCap + 4) * 4);
     w.staging = take(max_L * h->R);
     w.total_bytes = off;
     return w;
+}
+
+// Make stream s wait for work enqueued on the side stream, if any is outstanding.
+static hipError_t side_join(scars_handle* h, hipStream_t s) {
+    if (!h->side_pending) return hipSuccess;
+    h->side_pending = false;
+    return hipStreamWaitEvent(s, h->ev_join, 0);
+}
+
+// Make the side stream (created on first use, default priority) wait for everything enqueued on s so far.
+static hipError_t side_fork(scars_handle* h, hipStream_t s) {
+    hipError_t e = hipSuccess;
+    if (!h->side) {
+        if ((e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming)) != hipSuccess) return e;
+    }
+    if ((e = hipEventRecord(h->ev_fork, s)) != hipSuccess) return e;
+    return hipStreamWaitEvent(h->side, h->ev_fork, 0);
 }
 
 static int64_t budget_rows(const scars_handle* h, int64_t budget_bytes) {
@@ -122,16 +143,31 @@ int32_t scars_create(const scars_config* cfg, scars_handle** out) {
 
 int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
     if (!h) return SCARS_ERR_INVALID_ARG;
-    if (value < 0 || value > (1 << 20)) return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: value out of range");
+    if (value < 0 || value >= ((int64_t)1 << 31)) return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: value out of range");
     switch (which) {
         case SCARS_TUNE_FUSED_SCAN_MAX_TILES: h->fused_scan_max_tiles = (int)std::min<int64_t>(value, 4096); break;
+        case SCARS_TUNE_PRESORT: h->presort_min_L = value; break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
     return SCARS_OK;
 }
 
+int64_t scars_get_counter(const scars_handle* h, int32_t which) {
+    if (!h) return -1;
+    switch (which) {
+        case SCARS_COUNTER_PREPARED_USED: return h->n_prepared_used;
+        default: return -1;
+    }
+}
+
 int32_t scars_destroy(scars_handle* h) {
     if (!h) return SCARS_ERR_INVALID_ARG;
+    if (h->side) {
+        (void)hipStreamSynchronize(h->side);
+        (void)hipStreamDestroy(h->side);
+        (void)hipEventDestroy(h->ev_fork);
+        (void)hipEventDestroy(h->ev_join);
+    }
     for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.second.first); (void)hipEventDestroy(p.second.second); }
     delete h;
     return SCARS_OK;
@@ -163,6 +199,9 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     if (k + b->max_L >= ((int64_t)1 << 31)) return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: k + max_L >= 2^31");
     if (k > 0 && (!b->hot_gid || !b->cache || (h->optimizer == SCARS_OPT_ADAGRAD && !b->state_cache)))
         return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: cache buffers missing");
+    if (h->side) (void)hipStreamSynchronize(h->side);   // nothing may still be using the buffers bound before
+    h->side_pending = false;
+    h->presort_valid = false;
     h->buf = *b;
     h->k_cap = k;
     h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);
@@ -211,7 +250,9 @@ int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32
     if (before + (uint64_t)Lp >= ((uint64_t)1 << 32))
         return fail(h, SCARS_ERR_INVALID_ARG, "build_cache: cumulative lookups >= 2^32 would overflow the uint32 counts");
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = hipSuccess;
+    hipError_t e = side_join(h, s);   // segments being prepared on the side stream read slot_of and the sort buffers
+    if (e != hipSuccess) return hip_fail(h, e, "build_cache(join)");
+    h->presort_valid = false;
     if (accumulate != 2 && h->built && h->dirty) {   // keep updated hot rows before they lose their slots
         e = launch_flush(h, s);
         if (e != hipSuccess) return hip_fail(h, e, "build_cache(flush)");
@@ -252,8 +293,25 @@ int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "remap: build_cache has not selected a hot set");
     if ((rc = check_remap_out(h, out, L, "remap"))) return rc;
     if (out->loc == h->staged_loc) h->staged_valid = false;   // these arrays no longer describe the staged batch
-    hipError_t e = launch_remap(h, (hipStream_t)stream, d_indices, d_offsets, L, B, out);
+    hipStream_t s = (hipStream_t)stream;
+    // segments still being prepared on the side stream read the previous batch's arrays and the sort buffers
+    hipError_t e = side_join(h, s);
+    if (e != hipSuccess) return hip_fail(h, e, "remap(join)");
+    h->presort_valid = false;
+    e = launch_remap(h, s, d_indices, d_offsets, L, B, out);
     if (e != hipSuccess) return hip_fail(h, e, "remap");
+    // worth it only when a link-bound staging kernel will leave the GPU idle (misses are possible)
+    if (h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {
+        if ((e = side_fork(h, s)) != hipSuccess) return hip_fail(h, e, "remap(fork)");
+        const bool staged = h->k < h->N;   // misses are possible: the forward pass will stage them
+        e = launch_bwd_segments(h, h->side, d_offsets, L, B, out, staged, nullptr, &h->presort_res);
+        if (e == hipSuccess) e = hipEventRecord(h->ev_join, h->side);
+        if (e != hipSuccess) return hip_fail(h, e, "remap(backward segments)");
+        h->side_pending = true;
+        h->presort_valid = true;
+        h->presort_gid = out->gid; h->presort_loc = out->loc; h->presort_off = d_offsets;
+        h->presort_L = L; h->presort_B = B; h->presort_staged = staged;
+    }
     return SCARS_OK;
 }
 
@@ -279,7 +337,8 @@ int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices
     if (!d_grad_out && L > 0) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: null gradient");
     if (out && (!out->n_unique || !out->seg_start || (L > 0 && (!out->sorted_gid || !out->sorted_bag || !out->unique_gid))))
         return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: bwd_out has a null array");
-    hipError_t e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out);
+    hipError_t e = side_join(h, (hipStream_t)stream);
+    if (e == hipSuccess) e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out);
     if (e != hipSuccess) return hip_fail(h, e, "embedding_bag_bwd_update");
     if (L > 0) h->dirty = true;
     return SCARS_OK;
@@ -419,7 +478,8 @@ int32_t scars_sync_status(scars_handle* h, void* stream) {
     if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "sync_status: no buffers bound");
     hipStream_t s = (hipStream_t)stream;
     int32_t st[4] = {0, 0, 0, 0};
-    hipError_t e = hipMemcpyAsync(st, h->ws.status, sizeof(st), hipMemcpyDeviceToHost, s);
+    hipError_t e = side_join(h, s);   // side-stream kernels latch errors too
+    if (e == hipSuccess) e = hipMemcpyAsync(st, h->ws.status, sizeof(st), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(h, e, "sync_status");
     if (st[0] != 0) {
@@ -470,6 +530,7 @@ int32_t scars_profile_enable(scars_handle* h, int32_t on) {
 int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out, int32_t cap, int32_t* n_out) {
     if (!h || !n_out || cap < 0 || (cap > 0 && !out)) return SCARS_ERR_INVALID_ARG;
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess && h->side) e = hipStreamSynchronize(h->side);
     if (e != hipSuccess) return hip_fail(h, e, "profile_read");
     std::vector<scars_kernel_time> acc;
     for (auto& p : h->timer.pending) {

@@ -60,6 +60,8 @@ struct Workspace {
     uint32_t* first_bag;      // [max_L] bag of the first lookup of each distinct row
     double* partial;          // [chunks][2][D] fp64 partial sums of long runs, chunks of kLongRunMin sorted positions
     int32_t* chunk_run;       // [chunks + 1] run (segment) index that holds each chunk's first position
+    uint32_t* blk_seg_a;      // [tiles+1] x2: tile counters of the backward pass's run-start compaction (its own pair:
+    uint32_t* blk_seg_b;      //   that half of the pass may run on the side stream beside calls that use blk_hit/blk_miss)
     uint32_t* plan_cc;        // [kPlanBins] rows per count value, [kPlanBigCap] counts at or above kPlanBins, [4] their number
     void* staging;            // [max_L][R] rows fetched over the host link
     int64_t total_bytes;
@@ -93,7 +95,18 @@ struct scars_handle {
     bool staged_valid = false;           // the staging area holds the missed rows of the batch whose remap wrote staged_loc
     const int32_t* staged_loc = nullptr;
     std::string err;
+    // side stream: the integer half of the backward pass can be started by remap and run beside the forward pass
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool side_pending = false;           // ev_join has been recorded and no stream has been made to wait for it yet
+    bool presort_valid = false;          // the workspace holds the segments of the batch described below
+    const int32_t *presort_gid = nullptr, *presort_loc = nullptr, *presort_off = nullptr;
+    int64_t presort_L = 0, presort_B = 0;
+    bool presort_staged = false;
+    int presort_res = 0;
+    int64_t n_prepared_used = 0;         // bwd_update calls that used segments prepared on the side stream
     // launch tuning (scars_set_tuning)
+    int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
     int fused_scan_max_tiles = 1024;     // compaction: up to this many tiles the writer sums the tile counts itself
     // per-kernel timing
     bool profile = false;
@@ -150,5 +163,7 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
 // k_bwd.hip
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out);
+hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
+                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out);
 
 }  // namespace scars

@@ -4,7 +4,8 @@ pinned tables.  Tables and batches are generated on the GPU by the seeded genera
 
 Checked: histogram and hot set bit-exact over all 40M rows; remap lists bit-exact; every pooled output within
 tolerance; sorted segments bit-exact; every updated row and accumulator within tolerance after a flush;
-rows without a lookup untouched (sampled); the step run again on the next batch.
+rows without a lookup untouched (sampled); the step run again on the next batch, and a third time in bench.py's
+launch configuration (backward sort started by remap on the side stream, no segment outputs).
 """
 import numpy as np
 import pytest
@@ -52,7 +53,7 @@ def test_full_size_path_matches_oracle(full):
     wl, dev, tabs, state, sc, smp = full
     P = 8                                                     # profile batches (5.2M lookups)
     prof = [smp.batch(p, True) for p in range(P)]
-    batches = [smp.batch(e) for e in range(2)]
+    batches = [smp.batch(e) for e in range(3)]
     max_L = max(int(b[0].numel()) for b in prof + batches)
     sc.bind_buffers(wl.budget_bytes, max_L, wl.num_bags)
     # ---- build_cache
@@ -77,7 +78,8 @@ def test_full_size_path_matches_oracle(full):
     for j, s in enumerate(sample):
         g = int(hot[s]); t = int(np.searchsorted(rb, g, side="right") - 1)
         assert np.array_equal(got[j], ora_tabs[t][g - rb[t]])
-    # ---- two steps
+    # ---- three steps; the last one in bench.py's launch configuration: remap also starts the backward pass's sort on
+    # the library's side stream, and no segment outputs are requested
     lr, eps = np.float32(wl.lr), np.float32(wl.eps)
     for step, (idx, off) in enumerate(batches):
         _say("step", step)
@@ -97,24 +99,28 @@ def test_full_size_path_matches_oracle(full):
         pt = np.searchsorted(rb, probe, side="right") - 1
         before = np.stack([ora_tabs[t][g - rb[t]] for g, t in zip(probe[:2000], pt[:2000])])
         L = idx.numel()
+        presort = step == 2
+        sc.set_tuning(binding.TUNE_PRESORT, 131072 if presort else 0)
         rm = sc.remap(idx, off, wl.batch)
         out = sc.embedding_bag_fwd(idx, off, wl.batch, rm)
-        bo = sc.new_bwd_out(L)
+        bo = None if presort else sc.new_bwd_out(L)
         sc.embedding_bag_bwd_update(idx, off, wl.batch, rm, grad, float(lr), float(eps), bo)
         sc.flush_cache()
         assert sc.sync_status() == 0
+        assert sc.get_counter(binding.COUNTER_PREPARED_USED) == (1 if presort else 0)
         assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size] and hit.size + miss.size == L
         assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
         assert np.array_equal(rm.hit_pos.cpu().numpy()[: hit.size], hit)
         assert np.array_equal(rm.miss_pos.cpu().numpy()[: miss.size], miss)
         assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
         assert_close(out.cpu().numpy(), want, "pooled output at full size")
-        U, nv = bo.n_unique.cpu().tolist()
-        assert U == ug.size and nv == sg.size
-        assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
-        assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
-        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
-        assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+        if bo is not None:
+            U, nv = bo.n_unique.cpu().tolist()
+            assert U == ug.size and nv == sg.size
+            assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+            assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+            assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+            assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
         # every touched row and accumulator (the pinned tables were updated in place by the GPU and flushed)
         ut = np.searchsorted(rb, ug, side="right") - 1
         for t in range(wl.num_tables):

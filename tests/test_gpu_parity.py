@@ -36,7 +36,10 @@ def _say(*a):
 
 # "/scan": the same case with the separate scan kernels of the compactions forced (by default so few tiles add up
 # their counts in the writing kernels)
-VARIANTS = list(CASES) + ["tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan"]
+# "/presort": remap starts the backward pass's sort on the library's side stream
+VARIANTS = list(CASES) + ["tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan",
+                          "tiny/presort", "multi_hot_small/presort", "host_spill_small/presort", "low_skew_bf16/presort",
+                          "dlrm_small/presort"]
 
 
 @pytest.fixture(params=VARIANTS)
@@ -46,6 +49,8 @@ def case(request):
     c = GpuCase(_wl(name))
     if variant == "scan":
         c.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
+    if variant == "presort":
+        c.s.set_tuning(binding.TUNE_PRESORT, 1)
     yield c
     c.close()
 
@@ -410,4 +415,104 @@ def test_epoch_cost_with_counts_beyond_the_binned_range():
         assert rc == 0
         got, _ = c.s.epoch_cost(M, a, Q, S, k)
         assert abs(got - want) <= 1e-10 * want
+    c.close()
+
+
+# ---- backward sort started by remap on the library's side stream -------------------------------------------
+def _room(wl):
+    """Lookups to bind for: well above any batch the sampler draws."""
+    return int(wl.num_bags * (1.0 + (wl.bag_lambda or 0.0)) * 1.3) + 1024
+
+
+def _presort_steps(c, steps, budget_note):
+    """steps x (remap, forward, backward without segment outputs) on both sides; rows compared after a flush."""
+    wl = c.wl
+    opt = 1 if wl.optimizer == "adagrad" else 0
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps if opt else 0.0)
+    for step in range(steps):
+        idx, off = c.sampler.batch(step)
+        grad = c.sampler.grads(step)
+        rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+        assert rc == 0
+        (rc,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, opt, idx.numpy(), off.numpy(), wl.batch,
+                                                grad.numpy(), lr, eps)
+        assert rc == 0
+        d_idx, d_off = idx.to(c.dev), off.to(c.dev)
+        rm = c.s.remap(d_idx, d_off, wl.batch)
+        out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+        c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), float(lr), float(eps))
+        if wl.dtype == "f32":
+            assert_close(out.cpu().numpy(), want, f"{budget_note} step {step} output")
+    c.s.flush_cache()
+    assert c.s.sync_status() == 0
+    if wl.dtype == "f32":
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), f"{budget_note} rows")
+        if opt:
+            assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), f"{budget_note} accumulators")
+
+
+@pytest.mark.parametrize("name", ["tiny", "multi_hot_small", "host_spill_small", "dlrm_small"])
+@pytest.mark.parametrize("budget", ["own", "none", "all"])
+def test_presort_steps_match_oracle(name, budget):
+    wl = _wl(name)
+    bb = {"own": None, "none": 0, "all": wl.total_rows * wl.row_bytes}[budget]
+    _say("presort", name, budget)
+    c = GpuCase(wl, budget_bytes=bb, max_L=_room(wl))
+    c.s.set_tuning(binding.TUNE_PRESORT, 1)
+    c.build()
+    _presort_steps(c, 3, f"{name}/{budget}")
+    # every backward pass used the prepared segments; with every row cached nothing is prepared (no link to hide behind)
+    assert c.s.get_counter(binding.COUNTER_PREPARED_USED) == (0 if budget == "all" else 3)
+    c.close()
+
+
+def test_presort_falls_back_when_the_calls_do_not_line_up():
+    """The prepared segments are used only for remap -> forward -> backward of one batch without segment outputs;
+    every other order sorts again and gives the same rows."""
+    wl = _wl("multi_hot_small")
+    c = GpuCase(wl, max_L=_room(wl))
+    c.s.set_tuning(binding.TUNE_PRESORT, 1)
+    c.build()
+    opt, lr, eps = 1, np.float32(wl.lr), np.float32(wl.eps)
+    used = lambda: c.s.get_counter(binding.COUNTER_PREPARED_USED)
+
+    def oracle_step(step):
+        idx, off = c.sampler.batch(step)
+        (rc,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, opt, idx.numpy(), off.numpy(), wl.batch,
+                                                c.sampler.grads(step).numpy(), lr, eps)
+        assert rc == 0
+        return idx.to(c.dev), off.to(c.dev), c.sampler.grads(step).to(c.dev)
+
+    # (1) backward without a forward pass: cold rows must come from the host, not from a stale staging area
+    i0, o0, g0 = oracle_step(0)
+    rm = c.s.remap(i0, o0, wl.batch)
+    c.s.embedding_bag_bwd_update(i0, o0, wl.batch, rm, g0, float(lr), float(eps))
+    assert used() == 0
+    # (2) segment outputs requested: sorted in line, outputs bit-exact
+    i1, o1, g1 = oracle_step(1)
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, i1.cpu().numpy(), o1.cpu().numpy(), wl.batch)
+    rm = c.s.remap(i1, o1, wl.batch)
+    c.s.embedding_bag_fwd(i1, o1, wl.batch, rm)
+    bo = c.s.new_bwd_out(i1.numel())
+    c.s.embedding_bag_bwd_update(i1, o1, wl.batch, rm, g1, float(lr), float(eps), bo)
+    assert used() == 0
+    assert np.array_equal(bo.unique_gid.cpu().numpy()[: ug.size], ug) and np.array_equal(bo.seg_start.cpu().numpy()[: ug.size + 1], ss)
+    # (3) two remaps, then the step of the second batch with other output arrays than the first
+    i2, o2, g2 = oracle_step(2)
+    rm_a = c.s.remap(i0, o0, wl.batch)
+    rm_b = c.s.remap(i2, o2, wl.batch, c.s.new_remap_out())
+    c.s.embedding_bag_fwd(i2, o2, wl.batch, rm_b)
+    c.s.embedding_bag_bwd_update(i2, o2, wl.batch, rm_b, g2, float(lr), float(eps))
+    assert used() == 1
+    # (4) a step whose backward pass is given the first remap's arrays: they describe another batch's preparation
+    i3, o3, g3 = oracle_step(3)
+    rm_c = c.s.remap(i3, o3, wl.batch, rm_a)
+    c.s.embedding_bag_fwd(i3, o3, wl.batch, rm_c)
+    c.s.remap(i2, o2, wl.batch, rm_b)                                   # prepares batch 2 again; batch 3's is gone
+    c.s.embedding_bag_bwd_update(i3, o3, wl.batch, rm_c, g3, float(lr), float(eps))
+    assert used() == 1
+    c.s.flush_cache()
+    assert c.s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after mixed call orders")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after mixed call orders")
     c.close()
