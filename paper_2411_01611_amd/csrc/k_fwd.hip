@@ -12,7 +12,7 @@
 namespace scars {
 
 constexpr int kUnroll = 4;       // rows in flight per lane group when staging misses
-constexpr int kStageBlocks = 256;  // workgroups of the staging kernel
+constexpr int kStageBlocks = 128;  // workgroups of the staging kernel
 constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
@@ -265,8 +265,9 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     if (L > 0 && h->k < h->N) {   // with every row cached there can be no miss
         Timed t(h, s, "stage_misses");
         const int gpb = kBlock / lpr;
-        // one workgroup per compute unit is far more than the host link needs in flight (256 x 8 groups x 4 rows), and
-        // it leaves most wave slots free for work on other streams while this kernel waits on the link
+        // 128 workgroups hold far more than the host link needs in flight (128 x 256 lanes x 4 x 16 bytes = 2 MB) and
+        // leave half the compute units, and most wave slots, to work on other streams while this kernel waits on the
+        // link (kernels sharing a compute unit with it run several times slower: its host reads fill the memory queues)
         const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), kStageBlocks));
         // one row per missed lookup, or (after a coalescing remap) one per distinct missed row
         const int32_t* list = rm->unique_miss_gid ? rm->unique_miss_gid : rm->miss_gid;
