@@ -7,7 +7,7 @@ import torch
 pytestmark = pytest.mark.gpu
 
 import oracle
-from paper_2411_01611_amd import synth
+from paper_2411_01611_amd import binding, synth
 from gpu_harness import GpuCase, assert_close
 
 
@@ -49,9 +49,13 @@ def test_graph_replay_of_remap_and_forward_matches_eager():
     c.close()
 
 
-def test_graph_replay_of_a_training_step_matches_oracle():
+@pytest.mark.parametrize("presort", [0, 1])
+def test_graph_replay_of_a_training_step_matches_oracle(presort):
+    """presort: remap starts the backward sort on the library's side stream, which joins the capture and is joined
+    back by bwd_update before the capture ends."""
     wl = synth.workload("multi_hot", scale=0.004, batch=333)
     c = GpuCase(wl)
+    c.s.set_tuning(binding.TUNE_PRESORT, presort)
     c.build()
     d_idx, d_off = c.dev_batch()
     idx, off = c.batch
@@ -80,4 +84,5 @@ def test_graph_replay_of_a_training_step_matches_oracle():
     assert c.s.sync_status() == 0
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after three replayed steps")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after three replayed steps")
+    assert c.s.get_counter(binding.COUNTER_PREPARED_USED) == presort     # decided once, at capture time
     c.close()
