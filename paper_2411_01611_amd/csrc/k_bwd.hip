@@ -224,26 +224,36 @@ struct RowRef {
 
 constexpr int kLongRun = kLongRunMin;   // runs up to this many lookups are summed by one lane group
 constexpr int kGradUnroll = 4;  // gradient rows in flight per lane group in the per-row kernel
-constexpr int kTaskUnroll = 8;  // ... and in a task of a long run (few groups, long chains: go wide)
+constexpr int kTaskUnroll = 16;  // ... and in a task of a long run (few groups, long chains: go wide)
 constexpr int kCombUnroll = 16; // partial sums in flight when a long run is combined
 
-// sum of grad rows val[j] for j in [p0, p1), columns [4c, 4c+4), in position order, fp64; UNROLL rows in flight
-template <int UNROLL>
+// Sum of the gradient rows val[j], j in [p0, p1), columns [4c, 4c+4), in position order, fp64.  The group's lanes
+// fetch a window of bag ids with one load and hand them out by shuffles, so every gradient row address of a trip is
+// known at once (bag ids and rows are otherwise two dependent round trips per trip); UNROLL rows in flight.  Every
+// lane of the group must call, also lanes beyond the row (c >= dq: they read the last piece and their sums are
+// never stored).  Indices are clamped instead of guarded so that the loads are issued back to back.
+template <int LPG, int UNROLL>
 __device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, const float4* __restrict__ g4, int dq, int c,
                                           int32_t p0, int32_t p1, uint32_t Gm1, double (&acc)[4]) {
-    for (int32_t j = p0; j < p1; j += UNROLL) {
-        // indices are clamped instead of guarded so that all bag loads, then all gradient loads, are issued
-        // back to back (a guarded load would wait for the previous one); surplus rows are not added
-        uint32_t bag[UNROLL];
-        float4 gv[UNROLL];
+    constexpr int W = LPG < kWave ? LPG : kWave;                 // positions one load of the group covers
+    const int wl = LPG < kWave ? c : lane_id();                  // this lane's place in the window
+    const int gl0 = LPG < kWave ? (lane_id() / LPG) * LPG : 0;   // first lane of the group inside the wave
+    const int cc = min(c, dq - 1);
+    for (int32_t w0 = p0; w0 < p1; w0 += W) {
+        const int32_t n = min((int32_t)W, p1 - w0);
+        const uint32_t bv = min(val[min(w0 + wl, p1 - 1)], Gm1);
+        for (int base = 0; base < n; base += UNROLL) {
+            float4 gv[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) bag[u] = min(val[min(j + u, p1 - 1)], Gm1);
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t bag = __shfl(bv, gl0 + min(base + u, n - 1), kWave);
+                gv[u] = g4[(int64_t)bag * dq + cc];
+            }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) gv[u] = g4[(int64_t)bag[u] * dq + c];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (j + u < p1) {
-                acc[0] += (double)gv[u].x; acc[1] += (double)gv[u].y; acc[2] += (double)gv[u].z; acc[3] += (double)gv[u].w;
+            for (int u = 0; u < UNROLL; ++u) {
+                if (base + u < n) {
+                    acc[0] += (double)gv[u].x; acc[1] += (double)gv[u].y; acc[2] += (double)gv[u].z; acc[3] += (double)gv[u].w;
+                }
             }
         }
     }
@@ -262,8 +272,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
     __syncthreads();
     const int32_t U = n_unique[0];
     const int c = threadIdx.x % LPG;
-    if (c * 4 >= A.D) return;
     const int dq = A.D / 4;
+    const bool lane_on = c < dq;              // lanes beyond the row stay: they hand out bag ids in sum_grads
+    const int cc = min(c, dq - 1);
     const float4* g4 = (const float4*)grad;
     const int64_t ngroups = (int64_t)gridDim.x * (kBlock / LPG);
     for (int64_t r = (int64_t)blockIdx.x * (kBlock / LPG) + threadIdx.x / LPG; r < U; r += ngroups) {
@@ -276,11 +287,11 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
         RowRef<DTYPE, OPT> ref;
         ref.locate(A, s_rbase, T, (int32_t)gid, slot);
         float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
-        ref.load(c, wv, sv);
-        const float4 g0 = g4[(int64_t)bag0 * dq + c];
+        ref.load(cc, wv, sv);
+        const float4 g0 = g4[(int64_t)bag0 * dq + cc];
         double acc[4] = {(double)g0.x, (double)g0.y, (double)g0.z, (double)g0.w};
-        if (b - a > 1) sum_grads<kGradUnroll>(val, g4, dq, c, a + 1, b, A.Gm1, acc);
-        ref.step_and_store(A, c, wv, sv, acc);
+        if (b - a > 1) sum_grads<LPG, kGradUnroll>(val, g4, dq, c, a + 1, b, A.Gm1, acc);
+        if (lane_on) ref.step_and_store(A, c, wv, sv, acc);
     }
 }
 
@@ -311,14 +322,16 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
         for (int side = 0; side < 2; ++side) {
             // a long run over this chunk must continue across one of its borders
             const bool cand = side == 0 ? (kp == k0 || kn == k0) : (k1 != k0 && kn == k1);
-            if (!cand || !lane_on) continue;
+            if (!cand) continue;              // (the same for every lane of the group)
             const int32_t r = side == 0 ? r0 : r1;
             const int32_t a = seg_start[r], b = seg_start[r + 1];
             if (b - a <= kLongRun) continue;
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            sum_grads<kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
-            double* p = partial + ((int64_t)ch * 2 + side) * D + c * 4;
-            p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
+            sum_grads<LPG, kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
+            if (lane_on) {
+                double* p = partial + ((int64_t)ch * 2 + side) * D + c * 4;
+                p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
+            }
         }
     }
 }
