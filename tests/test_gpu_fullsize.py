@@ -130,3 +130,108 @@ def test_full_size_path_matches_oracle(full):
             assert_close(state[t].np[rows_t], ns[sel].astype(np.float32), f"accumulators of table {t}")
         after = np.stack([ora_tabs[t][g - rb[t]] for g, t in zip(probe[:2000], pt[:2000])])
         assert np.array_equal(before, after), "rows without a lookup must not change"
+
+
+def _full_size_sgd_step(wl, P):
+    """One SGD workload at the size bench.py runs it: build_cache over P profile batches, then one batch through
+    remap, forward and backward -- integer outputs bit-exact, pooled sums and every updated row within tolerance --
+    the backward pass a second time in bench.py's launch configuration (sort started by remap on the side stream)."""
+    from gpu_harness import assert_bf16_within
+    dev = torch.device("cuda:0")
+    bf16 = wl.dtype == "bf16"
+    tabs = []
+    for t in range(wl.num_tables):
+        p = binding.PinnedArray((wl.rows[t], wl.dim), np.uint16 if bf16 else np.float32)
+        chunk = max(1, (1 << 27) // wl.dim)
+        for r0 in range(0, wl.rows[t], chunk):
+            r1 = min(wl.rows[t], r0 + chunk)
+            v = synth.row_values(wl, t, r0, r1, dev).contiguous()
+            p.copy_from_device(v.view(torch.int16) if bf16 else v, r0)
+            torch.cuda.synchronize()
+        tabs.append(p)
+    sc = binding.Scars(wl.rows, wl.dim, binding.DTYPE_BF16 if bf16 else binding.DTYPE_F32, [p.ptr for p in tabs],
+                       binding.OPT_SGD, None)
+    smp = synth.Sampler(wl, dev)
+    prof = [smp.batch(p, True) for p in range(P)]
+    idx, off = smp.batch(0)
+    max_L = max(int(b[0].numel()) for b in prof + [(idx, off)])
+    sc.bind_buffers(wl.budget_bytes, max_L, wl.num_bags)
+    counts = np.zeros(wl.total_rows, dtype=np.uint32)
+    sc.build_cache(None, None, 0, wl.budget_bytes, 0)
+    for n, (pi, po) in enumerate(prof):
+        rc, counts = oracle.histogram(wl.rows, pi.cpu().numpy(), po.cpu().numpy(), wl.batch, counts)
+        assert rc == 0
+        sc.build_cache(pi, po, wl.batch, wl.budget_bytes, 1 if n == P - 1 else 2)
+    assert sc.sync_status() == 0
+    k = oracle.budget_rows(wl.total_rows, wl.row_bytes, wl.budget_bytes)
+    assert k == sc.cache_rows()
+    _say(wl.name, "oracle hot set over", wl.total_rows, "rows, k =", k)
+    rc, hot, slot_of = oracle.hot_set(counts, k)
+    assert np.array_equal(sc.counts().cpu().numpy().view(np.uint32), counts)
+    assert np.array_equal(sc.hot_gid().cpu().numpy(), hot)
+    assert np.array_equal(sc.slot_of().cpu().numpy(), slot_of)
+    ora_tabs = [p.np for p in tabs]
+    hi, ho = idx.cpu().numpy(), off.cpu().numpy()
+    grad = smp.grads(0)
+    lr = np.float32(wl.lr)
+    _say(wl.name, "oracle step")
+    rc, slot, hit, miss, mg = oracle.remap(wl.rows, hi, ho, wl.batch, slot_of)
+    rc2, want = oracle.embedding_bag_fwd(wl.rows, ora_tabs, hi, ho, wl.batch)
+    rc3, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, hi, ho, wl.batch)
+    rc4, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, ora_tabs, None, 0, hi, ho, wl.batch, grad.cpu().numpy(), lr,
+                                                      np.float32(0.0), report=True, n_unique=ug.size)
+    assert rc == rc2 == rc3 == rc4 == 0
+    L = idx.numel()
+    # (1) the integer outputs need only the remap and the sort: take them from a backward call with lr = 0, which
+    # rewrites every touched row with its own value
+    rm = sc.remap(idx, off, wl.batch)
+    out = sc.embedding_bag_fwd(idx, off, wl.batch, rm)
+    bo = sc.new_bwd_out(L)
+    sc.embedding_bag_bwd_update(idx, off, wl.batch, rm, grad, 0.0, 0.0, bo)
+    assert sc.sync_status() == 0
+    assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size] and hit.size + miss.size == L
+    assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
+    assert np.array_equal(rm.hit_pos.cpu().numpy()[: hit.size], hit)
+    assert np.array_equal(rm.miss_pos.cpu().numpy()[: miss.size], miss)
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
+    assert_close(out.cpu().numpy(), want, f"pooled output, {wl.name} at full size")
+    U, nv = bo.n_unique.cpu().tolist()
+    assert U == ug.size and nv == sg.size
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+    assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+    assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+    assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+    del bo
+    # (2) the real step, as bench.py launches it
+    sc.set_tuning(binding.TUNE_PRESORT, 131072)
+    rm = sc.remap(idx, off, wl.batch, rm)
+    sc.embedding_bag_fwd(idx, off, wl.batch, rm, out)
+    sc.embedding_bag_bwd_update(idx, off, wl.batch, rm, grad, float(lr), 0.0)
+    sc.flush_cache()
+    assert sc.sync_status() == 0
+    assert sc.get_counter(binding.COUNTER_PREPARED_USED) == (1 if L >= 131072 and k < wl.total_rows else 0)
+    rb = wl.row_base
+    ut = np.searchsorted(rb, ug, side="right") - 1
+    for t in range(wl.num_tables):
+        sel = ut == t
+        if bf16:
+            assert_bf16_within(tabs[t].np[ug[sel] - rb[t]], nr[sel], f"updated bf16 rows of table {t}")
+        else:
+            assert_close(tabs[t].np[ug[sel] - rb[t]], nr[sel].astype(np.float32), f"updated rows of table {t}")
+    sc.close()
+    for p in tabs:
+        p.free()
+    return max_L
+
+
+@pytest.mark.timeout(900)
+def test_full_size_low_skew_bf16_matches_oracle():
+    """26 bf16 tables, 50M rows x dim 64, batch 16384, bags 1+Poisson(9), Zipf 0.5, 10 % of rows cached: 4.3M lookups
+    per batch, so the sort runs its large tiles and the compactions span more than two thousand tiles."""
+    assert _full_size_sgd_step(synth.workload("low_skew"), 4) > (1 << 21)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_dlrm_onehot_matches_oracle():
+    """26 fp32 tables of 10 to 10M rows x dim 64, batch 2048, one index per table and sample, Zipf 1.1, 5 % cached."""
+    _full_size_sgd_step(synth.workload("dlrm_onehot"), 8)
