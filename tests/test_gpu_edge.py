@@ -295,3 +295,64 @@ def test_backward_never_reads_stale_staged_rows():
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after interleaved batches")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after interleaved batches")
     c.close()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_match_oracle(seed):
+    """Random small problems: 1 to 6 tables of 1 to 5000 rows, row widths that are and are not powers of two, both
+    storage types and optimizers, bag lengths 0 to 12 (with empty bags and duplicates), budgets from nothing to
+    everything.  The whole path against the oracle: integers bit-exact, sums and rows within tolerance."""
+    from gpu_harness import assert_bf16_within
+    rng = np.random.default_rng(1000 + seed)
+    T = int(rng.integers(1, 7))
+    rows = [int(rng.choice([1, 2, 3, 17, 256, 1000, 5000])) for _ in range(T)]
+    dtype = "bf16" if seed % 4 == 3 else "f32"
+    D = int(rng.choice([8, 16, 24, 40, 64, 128] if dtype == "bf16" else [4, 8, 12, 16, 20, 32, 64, 100, 128]))
+    opt = "adagrad" if seed % 2 else "sgd"
+    B = int(rng.choice([1, 2, 63, 64, 65, 300, 1111]))
+    max_len = int(rng.choice([1, 2, 5, 12]))
+    lens = rng.integers(0, max_len + 1, T * B) if max_len > 1 else np.ones(T * B, dtype=np.int64)
+    off = np.zeros(T * B + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    parts = []
+    for t in range(T):
+        n = int(off[(t + 1) * B] - off[t * B])
+        skew = rng.random(n) < 0.5                               # half the lookups go to a few popular rows
+        parts.append(np.where(skew, rng.integers(0, min(rows[t], 3), n), rng.integers(0, rows[t], n)))
+    idx = np.concatenate(parts).astype(np.int32) if parts else np.zeros(0, dtype=np.int32)
+    N = sum(rows)
+    k = int(rng.choice([0, 1, N // 3, N]))
+    _say("seed", seed, "T", T, "rows", rows, "D", D, dtype, opt, "B", B, "L", idx.size, "k", k)
+    c = _custom_case(rows, D, idx, off, B, budget_rows=k, optimizer=opt, dtype=dtype)
+    rm, out, bo, grad = _run_all(c)
+    assert c.s.sync_status() == 0
+    wl = c.wl
+    L = idx.size
+    rc, slot, hit, miss, mg = oracle.remap(wl.rows, idx, off, B, c.ora_slot_of)
+    assert rc == 0 and rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size]
+    assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
+    assert np.array_equal(rm.hit_pos.cpu().numpy()[: hit.size], hit)
+    assert np.array_equal(rm.miss_pos.cpu().numpy()[: miss.size], miss)
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
+    rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
+    assert_close(out.cpu().numpy(), want, "forward")
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx, off, B)
+    U, nv = bo.n_unique.cpu().tolist()
+    assert U == ug.size and nv == sg.size
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+    assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+    assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+    assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+    o = 1 if opt == "adagrad" else 0
+    rc, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
+                                                     np.float32(0.01), np.float32(1e-8), report=True, n_unique=ug.size)
+    (rc2,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
+                                             np.float32(0.01), np.float32(1e-8))
+    assert rc == 0 and rc2 == 0
+    if dtype == "f32":
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+    else:
+        assert_bf16_within(c.pinned_rows()[ug], nr, "bf16 rows")
+    if opt == "adagrad":
+        assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
+    c.close()
