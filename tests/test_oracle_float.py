@@ -191,3 +191,68 @@ def test_bwd_bf16_rows_round_to_nearest_even(ora):
     assert np.array_equal(got, want)                      # torch's fp32->bf16 cast is round-to-nearest-even
     ref_w, _ = _torch_step(wl, tables, idx, off, grad, "sgd", float(np.float32(0.01)), 0.0)
     np.testing.assert_allclose(nr, torch.cat(ref_w).numpy()[ug], rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_against_numpy_brute_force(ora, seed):
+    """Random small problems (1-6 tables of 1-5000 rows, widths that are not powers of two, empty bags, duplicates,
+    both optimizers): every oracle step against its definition written with numpy on global row ids."""
+    rng = np.random.default_rng(500 + seed)
+    T = int(rng.integers(1, 7))
+    rows = [int(rng.choice([1, 2, 3, 17, 256, 1000, 5000])) for _ in range(T)]
+    D = int(rng.choice([4, 8, 12, 20, 32, 100]))
+    B = int(rng.choice([1, 2, 63, 65, 300]))
+    lens = rng.integers(0, 7, T * B)
+    off = np.zeros(T * B + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    idx = np.concatenate([rng.integers(0, min(rows[t], 4) if rng.random() < 0.5 else rows[t],
+                                       int(off[(t + 1) * B] - off[t * B])) for t in range(T)]).astype(np.int32)
+    L, N = idx.size, sum(rows)
+    rb = np.concatenate([[0], np.cumsum(rows)])
+    bag = np.repeat(np.arange(T * B), lens)
+    gid = (rb[bag // B] + idx).astype(np.int64)
+    tables = [rng.uniform(-1, 1, (r, D)).astype(np.float32) for r in rows]
+    W = np.concatenate(tables).astype(np.float64)
+    # histogram and hot set
+    rc, counts = ora.histogram(rows, idx, off, B)
+    assert rc == 0 and np.array_equal(counts, np.bincount(gid, minlength=N).astype(np.uint32))
+    k = int(rng.integers(0, N + 1))
+    rc, hot, slot_of = ora.hot_set(counts, k)
+    order = np.lexsort((np.arange(N), -counts.astype(np.int64)))[:k]
+    assert rc == 0 and np.array_equal(hot, order)
+    inv = np.full(N, -1, dtype=np.int32)
+    inv[order] = np.arange(k, dtype=np.int32)
+    assert np.array_equal(slot_of, inv)
+    # remap
+    rc, slot, hit, miss, mg = ora.remap(rows, idx, off, B, slot_of)
+    assert rc == 0 and np.array_equal(slot, inv[gid])
+    assert np.array_equal(hit, np.nonzero(inv[gid] >= 0)[0]) and np.array_equal(miss, np.nonzero(inv[gid] < 0)[0])
+    assert np.array_equal(mg, gid[miss])
+    # forward
+    want = np.zeros((T * B, D), dtype=np.float64)
+    np.add.at(want, bag, W[gid])
+    rc, out = ora.embedding_bag_fwd(rows, tables, idx, off, B)
+    assert rc == 0 and np.allclose(out, want.astype(np.float32), rtol=1e-6, atol=1e-7)
+    # segments
+    rc, sg, sb, ss, ug = ora.bwd_segments(rows, idx, off, B)
+    o = np.argsort(gid, kind="stable")
+    assert np.array_equal(sg, gid[o]) and np.array_equal(sb, bag[o])
+    assert np.array_equal(ug, np.unique(gid)) and np.array_equal(ss[:-1], np.searchsorted(gid[o], ug)) and ss[-1] == L
+    # backward, both optimizers
+    grad = rng.standard_normal((T * B, D)).astype(np.float32)
+    dW = np.zeros((N, D), dtype=np.float64)
+    np.add.at(dW, gid, grad[bag].astype(np.float64))
+    lr, eps = np.float32(0.05), np.float32(1e-8)
+    mine = [t.copy() for t in tables]
+    (rc,) = ora.embedding_bag_bwd_update(rows, mine, None, 0, idx, off, B, grad, lr, np.float32(0.0))
+    assert rc == 0 and np.array_equal(np.concatenate(mine), (W - float(lr) * dW).astype(np.float32))
+    mine = [t.copy() for t in tables]
+    G0 = rng.uniform(0, 2, (N, D)).astype(np.float32)
+    st = [G0[rb[t]:rb[t + 1]].copy() for t in range(T)]
+    (rc,) = ora.embedding_bag_bwd_update(rows, mine, st, 1, idx, off, B, grad, lr, eps)
+    Gn = G0.astype(np.float64) + dW * dW
+    touched = np.zeros(N, dtype=bool)
+    touched[gid] = True
+    Wn = np.where(touched[:, None], W - float(lr) * dW / (np.sqrt(Gn) + float(eps)), W)
+    assert rc == 0 and np.array_equal(np.concatenate(st), np.where(touched[:, None], Gn, G0).astype(np.float32))
+    assert np.allclose(np.concatenate(mine), Wn.astype(np.float32), rtol=1e-7, atol=1e-8)
