@@ -17,8 +17,7 @@ __global__ __launch_bounds__(kBlock) void k_remap_probe(const int32_t* __restric
                                                         int64_t L, int64_t B, const Meta* __restrict__ meta,
                                                         const int32_t* __restrict__ slot_of, int32_t* __restrict__ slot,
                                                         int32_t* __restrict__ gid, uint32_t* __restrict__ blk_hit,
-                                                        uint32_t* __restrict__ blk_miss, int32_t* __restrict__ tstart_out,
-                                                        int32_t* __restrict__ status) {
+                                                        uint32_t* __restrict__ blk_miss, int32_t* __restrict__ status) {
     __shared__ int32_t s_tstart[SCARS_MAX_TABLES + 1];
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     __shared__ uint32_t s_hit[4], s_miss[4];
@@ -27,7 +26,6 @@ __global__ __launch_bounds__(kBlock) void k_remap_probe(const int32_t* __restric
         const int32_t v = off[(int64_t)t * B];
         s_tstart[t] = v;
         s_rbase[t] = meta->row_base[t];
-        if (blockIdx.x == 0) tstart_out[t] = v;
     }
     __syncthreads();
     const int64_t G = (int64_t)T * B;
@@ -229,7 +227,7 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
     {
         Timed t(h, s, "remap_probe");
         hipLaunchKernelGGL(k_remap_probe, dim3(nb), dim3(kBlock), 0, s, idx, off, L, B, ws.meta, h->buf.slot_of,
-                           out->slot, out->gid, ws.blk_hit, ws.blk_miss, ws.tstart, ws.status);
+                           out->slot, out->gid, ws.blk_hit, ws.blk_miss, ws.status);
     }
     const bool scan = nb > h->fused_scan_max_tiles;   // few tiles: the writer adds up the tile counts itself
     if (scan) {

@@ -11,7 +11,7 @@
 
 namespace scars {
 
-constexpr int kMaxBins = 512;
+constexpr int kMaxBins = kSortMaxBins;
 constexpr int kWaves = kBlock / kWave;
 
 // hist is digit-major: hist[d * nb + tile]

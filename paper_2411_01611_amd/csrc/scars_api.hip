@@ -59,7 +59,6 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
         w.win_key[i] = (uint32_t*)take(k_cap * 4);
         w.win_gid[i] = (int32_t*)take(k_cap * 4);
     }
-    w.tstart = (int32_t*)take((SCARS_MAX_TABLES + 1) * 4);
     const int64_t nbLG = std::max<int64_t>(nbL, div_up(max_G, kScanTile));
     w.blk_hit = (uint32_t*)take((nbLG + 1) * 4);
     w.blk_miss = (uint32_t*)take((nbLG + 1) * 4);

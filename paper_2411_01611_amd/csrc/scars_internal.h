@@ -46,7 +46,6 @@ struct Workspace {
     uint32_t* win_key[2];     // [k] double buffer
     int32_t* win_gid[2];      // [k]
     // per batch
-    int32_t* tstart;          // [T + 1] first lookup of each table (copied from offsets)
     uint32_t* blk_hit;        // [tiles of max(max_L, max_G) + 1] per-tile counts of the ordered compactions
     uint32_t* blk_miss;       // same
     uint32_t* sort_hist;      // [kSortMaxBins * nbS] digit-major per-tile histogram, nbS tiles for max(max_L, k) pairs
