@@ -356,3 +356,59 @@ def test_random_shapes_match_oracle(seed):
     if opt == "adagrad":
         assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
     c.close()
+
+
+def test_one_huge_bag_and_one_row_looked_up_a_hundred_thousand_times():
+    """A single bag of 300k lookups beside an empty one (the wave-per-bag kernel loops thousands of times) in which
+    one row takes a third of the lookups (a run of ~100k positions: thousands of partial sums to combine)."""
+    rng = np.random.default_rng(21)
+    rows, B, L = [2000], 2, 300_000
+    idx = np.where(rng.random(L) < 0.33, 1234, rng.integers(0, 2000, L)).astype(np.int32)
+    off = np.array([0, L, L], dtype=np.int32)
+    for opt in ("sgd", "adagrad"):
+        _say("huge bag", opt)
+        c = _custom_case(rows, 32, idx, off, B, budget_rows=500, optimizer=opt)
+        rm, out, bo, grad = _run_all(c)
+        assert c.s.sync_status() == 0
+        rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
+        # 150k terms per lane group added one after the other in fp32 (sums reach several hundred) against an fp64
+        # sum: rounding grows with the length of the bag, the 1e-5 bar is for bags of the workloads' lengths
+        assert np.allclose(out.cpu().numpy(), want, rtol=1e-3, atol=1e-3)
+        assert np.all(out.cpu().numpy()[1] == 0.0)
+        rc, sg, sb, ss, ug = oracle.bwd_segments(c.wl.rows, idx, off, B)
+        U, nv = bo.n_unique.cpu().tolist()
+        assert U == ug.size and nv == L
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+        o = 1 if opt == "adagrad" else 0
+        (rc,) = oracle.embedding_bag_bwd_update(c.wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
+                                                np.float32(0.01), np.float32(1e-8))
+        assert rc == 0
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after a huge bag")
+        if o:
+            assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after a huge bag")
+        c.close()
+
+
+def test_a_thousand_tables():
+    """SCARS_MAX_TABLES tables of one to four rows: table search and per-table descriptors at their limit."""
+    rng = np.random.default_rng(22)
+    T, B = 1024, 3
+    rows = [int(r) for r in rng.integers(1, 5, T)]
+    lens = rng.integers(0, 3, T * B)
+    off = np.zeros(T * B + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    idx = np.concatenate([rng.integers(0, rows[t], int(off[(t + 1) * B] - off[t * B])) for t in range(T)]).astype(np.int32)
+    c = _custom_case(rows, 8, idx, off, B, budget_rows=sum(rows) // 2, optimizer="adagrad")
+    rm, out, bo, grad = _run_all(c)
+    assert c.s.sync_status() == 0
+    rc, slot, hit, miss, mg = oracle.remap(c.wl.rows, idx, off, B, c.ora_slot_of)
+    assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size]
+    assert np.array_equal(rm.slot.cpu().numpy()[: idx.size], slot)
+    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
+    rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
+    assert_close(out.cpu().numpy(), want, "forward over 1024 tables")
+    (rc,) = oracle.embedding_bag_bwd_update(c.wl.rows, c.ora_tables, c.ora_state, 1, idx, off, B, grad.numpy(),
+                                            np.float32(0.01), np.float32(1e-8))
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows over 1024 tables")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators over 1024 tables")
+    c.close()
