@@ -390,20 +390,20 @@ __global__ __launch_bounds__(kBlock) void k_seg_combine(const uint32_t* __restri
 }
 
 template <int DTYPE, int OPT, int LPG>
-static void launch_reduce_t(scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val, const int32_t* nu,
+static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, const uint32_t* key, const uint32_t* val, const int32_t* nu,
                             const int32_t* seg_start, const int32_t* unique_gid, const float* grad, int64_t L, UpdateArgs A) {
     Workspace& ws = h->ws;
     const int gpb = kBlock / LPG;
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), 256 * 32));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     {
-        Timed t(h, s, "seg_long");
-        hipLaunchKernelGGL((k_seg_long<LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, val, nu, seg_start, ws.chunk_run,
+        Timed t(h, s2, "seg_long");
+        hipLaunchKernelGGL((k_seg_long<LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s2, key, val, nu, seg_start, ws.chunk_run,
                            grad, ws.partial, A.D, A.Gm1);
     }
     {
-        Timed t(h, s, "seg_combine");
-        hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
+        Timed t(h, s2, "seg_combine");
+        hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s2, key, nu, seg_start,
                            unique_gid, ws.unique_slot, ws.chunk_run, ws.partial, A);
     }
     {
@@ -414,11 +414,11 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, const uint32_t* key,
 }
 
 template <int DTYPE, int OPT>
-static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val,
+static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, hipStream_t s2, const uint32_t* key, const uint32_t* val,
                             const int32_t* nu, const int32_t* seg_start, const int32_t* unique_gid, const float* grad,
                             int64_t L, UpdateArgs A) {
     switch (lpg) {
-#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, key, val, nu, seg_start, unique_gid, grad, L, A); break;
+#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, s2, key, val, nu, seg_start, unique_gid, grad, L, A); break;
         SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
         SCARS_CASE(128)
 #undef SCARS_CASE
@@ -502,12 +502,25 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
                  use_staged ? ws.staging : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};
     const int lpg = next_pow2_host(h->D / 4);
+    // long runs (HBM-bound) beside the per-row kernel (bound by the host link while rows are cold)
+    hipStream_t s2 = s;
+    const bool split = h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
+    if (split) {
+        hipError_t e = side_fork(h, s);
+        if (e != hipSuccess) return e;
+        s2 = h->side;
+    }
     if (h->dtype == SCARS_DTYPE_F32) {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
     } else {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+    }
+    if (split) {
+        hipError_t e = hipEventRecord(h->ev_join, h->side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, h->ev_join, 0);
+        if (e != hipSuccess) return e;
     }
     return hipGetLastError();
 }

@@ -92,7 +92,7 @@ static hipError_t side_join(scars_handle* h, hipStream_t s) {
 }
 
 // Make the side stream (created on first use, default priority) wait for everything enqueued on s so far.
-static hipError_t side_fork(scars_handle* h, hipStream_t s) {
+hipError_t side_fork(scars_handle* h, hipStream_t s) {
     hipError_t e = hipSuccess;
     if (!h->side) {
         if ((e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking)) != hipSuccess) return e;

@@ -115,6 +115,8 @@ struct scars_handle {
 namespace scars {
 
 int32_t fail(scars_handle* h, int32_t code, const std::string& msg);
+// scars_api.hip: make the library's side stream wait for everything enqueued on s so far
+hipError_t side_fork(scars_handle* h, hipStream_t s);
 int32_t hip_fail(scars_handle* h, hipError_t e, const char* what);
 
 // RAII bracket that records a start/stop event pair around one kernel launch when profiling is on.
