@@ -282,6 +282,12 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
 
     L_avg = lookups / K
     alg = algorithmic_bytes(wl, L_avg, U, n_miss)
+    if "pool_short_staged" in prof:
+        # one index per bag, side-stream option: bags whose row is cached are pooled by one launch while the missed
+        # rows are fetched, the others by a second launch after the fetch; the bytes split with the bags
+        whole = alg["pool_short"]
+        alg["pool_short"] = whole * n_hit / max(1, n_hit + n_miss)
+        alg["pool_short_staged"] = whole - alg["pool_short"]
     kern = {}
     for name, r in prof.items():
         avg_ms = r["total_ms"] / r["launches"]

@@ -79,7 +79,9 @@ typedef struct {
  * B), after that batch's forward pass, and without a scars_bwd_out; otherwise it sorts again itself.  The next call
  * of remap, build_cache, sync_status or bwd_update waits for outstanding side-stream work first.  For the same
  * batches bwd_update also runs its long-run kernels (HBM-bound) on that stream beside the per-row kernel (bound by
- * the host link while it writes cold rows) and joins them before it returns.  The two
+ * the host link while it writes cold rows) and joins them before it returns; and scars_embedding_bag_fwd, when bags
+ * hold one lookup on average, pools the bags that need no fetched row on a further stream beside the fetch of the
+ * missed rows, joined before it returns.  The two
  * cross-stream waits cost some 10-20 us per step: not worth it for small batches.  Under HIP graph capture the side
  * stream joins the capture: end the capture after the bwd_update (or sync_status) that joins it back.  Default 0. */
 #define SCARS_TUNE_PRESORT 2

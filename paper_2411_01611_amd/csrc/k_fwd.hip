@@ -144,7 +144,9 @@ template <int DTYPE, int LPR>
 __global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict__ off, int64_t G, int32_t L,
                                                        const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
                                                        const uint4* __restrict__ staging, int32_t k, int chunks, int D,
-                                                       float* __restrict__ out) {
+                                                       float* __restrict__ out, int filter) {
+    // filter 0: every bag.  1: only bags that need no staged row (empty, or one lookup that hit the cache): these do
+    // not depend on the fetch of the missed rows.  2: only the other bags.
     const int64_t TG = (G + kShortBags - 1) / kShortBags;        // groups; group gi takes bags gi, gi + TG, ...
     const int64_t gi = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LPR;
     const int c = threadIdx.x % LPR;
@@ -162,10 +164,16 @@ __global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict
     }
 #pragma unroll
     for (int q = 0; q < kShortBags; ++q) l0[q] = b[q] > a[q] ? loc[a[q]] : -1;
+    bool take[kShortBags];
+#pragma unroll
+    for (int q = 0; q < kShortBags; ++q) {
+        const bool no_staged = b[q] - a[q] <= 1 && l0[q] < k;     // (an invalid lookup has location -1)
+        take[q] = gi + q * TG < G && (filter == 0 || (filter == 1) == no_staged);
+    }
     uint4 row[kShortBags];
 #pragma unroll
     for (int q = 0; q < kShortBags; ++q) {
-        if (lane_on && l0[q] >= 0) {
+        if (take[q] && lane_on && l0[q] >= 0) {
             const uint4* p = l0[q] < k ? cache + (int64_t)l0[q] * chunks : staging + (int64_t)(l0[q] - k) * chunks;
             row[q] = p[c];
         }
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict
 #pragma unroll
     for (int q = 0; q < kShortBags; ++q) {
         const int64_t g = gi + q * TG;
-        if (g >= G) continue;
+        if (!take[q]) continue;
         Chunk<DTYPE> acc;
         acc.zero();
         if (lane_on && l0[q] >= 0) acc.add(row[q]);
@@ -230,11 +238,11 @@ __global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict_
 
 template <int DTYPE, int LPR>
 static void launch_pool_t(hipStream_t s, int mode, const int32_t* off, int64_t G, int64_t L, const int32_t* loc,
-                          const void* cache, const void* staging, int64_t k, int chunks, int D, float* out) {
+                          const void* cache, const void* staging, int64_t k, int chunks, int D, float* out, int filter) {
     if (mode == 2) {
         const int64_t TG = div_up(G, kShortBags);
         hipLaunchKernelGGL((k_pool_short<DTYPE, LPR>), dim3((unsigned)div_up(TG * LPR, kBlock)), dim3(kBlock), 0, s, off,
-                           G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
+                           G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out, filter);
     } else if (mode == 1) {
         hipLaunchKernelGGL((k_pool_wave<DTYPE, LPR>), dim3((unsigned)div_up(G, kBlock / kWave)), dim3(kBlock), 0, s, off,
                            G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
@@ -247,9 +255,9 @@ static void launch_pool_t(hipStream_t s, int mode, const int32_t* off, int64_t G
 template <int DTYPE>
 static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, int64_t G, int64_t L,
                           const int32_t* loc, const void* cache, const void* staging, int64_t k, int chunks, int D,
-                          float* out) {
+                          float* out, int filter) {
     switch (lpr) {
-#define SCARS_CASE(N) case N: launch_pool_t<DTYPE, N>(s, mode, off, G, L, loc, cache, staging, k, chunks, D, out); break;
+#define SCARS_CASE(N) case N: launch_pool_t<DTYPE, N>(s, mode, off, G, L, loc, cache, staging, k, chunks, D, out, filter); break;
         SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
 #undef SCARS_CASE
     }
@@ -262,6 +270,32 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int64_t G = (int64_t)h->T * B;
     h->staged_valid = L > 0 && h->k < h->N;
     h->staged_loc = rm->loc;
+    // 2: bags of one or two lookups, several bags per lane group; 1: long bags, a wave per bag; 0: a group per bag
+    const int mode = L < 2 * G ? 2 : ((lpr < 64 && L >= G * 2 * (kWave / lpr)) ? 1 : 0);
+    auto pool = [&](hipStream_t st, int filter, const char* name) {
+        Timed t(h, st, name);
+        if (h->dtype == SCARS_DTYPE_F32)
+            launch_pool_d<SCARS_DTYPE_F32>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k, chunks,
+                                           h->D, out, filter);
+        else
+            launch_pool_d<SCARS_DTYPE_BF16>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k, chunks,
+                                            h->D, out, filter);
+    };
+    // With the side-stream option and short bags, the bags that need no staged row (the hits of a one-index-per-bag
+    // batch) are pooled on the side stream while the missed rows are still being fetched; the rest follow the fetch.
+    const bool split = mode == 2 && G > 0 && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
+    if (split) {   // a stream of its own: the side stream may still be busy with the backward pass's sort
+        hipError_t e = hipSuccess;
+        if (!h->pool_stream) {
+            if ((e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking)) != hipSuccess) return e;
+            if ((e = hipEventCreateWithFlags(&h->ev_pool_fork, hipEventDisableTiming)) != hipSuccess) return e;
+            if ((e = hipEventCreateWithFlags(&h->ev_pool_join, hipEventDisableTiming)) != hipSuccess) return e;
+        }
+        if ((e = hipEventRecord(h->ev_pool_fork, s)) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(h->pool_stream, h->ev_pool_fork, 0)) != hipSuccess) return e;
+        pool(h->pool_stream, 1, "pool_short");
+        if ((e = hipEventRecord(h->ev_pool_join, h->pool_stream)) != hipSuccess) return e;
+    }
     if (L > 0 && h->k < h->N) {   // with every row cached there can be no miss
         Timed t(h, s, "stage_misses");
         const int gpb = kBlock / lpr;
@@ -275,16 +309,10 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, list, count, h->ws.meta,
                            (u32x4*)h->ws.staging, chunks, lpr, h->buf.max_L);
     }
-    if (G > 0) {
-        // 2: bags of one or two lookups, several bags per lane group; 1: long bags, a wave per bag; 0: a group per bag
-        const int mode = L < 2 * G ? 2 : ((lpr < 64 && L >= G * 2 * (kWave / lpr)) ? 1 : 0);
-        Timed t(h, s, mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group"));
-        if (h->dtype == SCARS_DTYPE_F32)
-            launch_pool_d<SCARS_DTYPE_F32>(lpr, s, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
-                                           chunks, h->D, out);
-        else
-            launch_pool_d<SCARS_DTYPE_BF16>(lpr, s, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k,
-                                            chunks, h->D, out);
+    if (G > 0) pool(s, split ? 2 : 0, split ? "pool_short_staged" : (mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group")));
+    if (split) {   // the output is complete, in the caller's stream order, when this call returns
+        hipError_t e = hipStreamWaitEvent(s, h->ev_pool_join, 0);
+        if (e != hipSuccess) return e;
     }
     return hipGetLastError();
 }

@@ -161,6 +161,12 @@ int64_t scars_get_counter(const scars_handle* h, int32_t which) {
 
 int32_t scars_destroy(scars_handle* h) {
     if (!h) return SCARS_ERR_INVALID_ARG;
+    if (h->pool_stream) {
+        (void)hipStreamSynchronize(h->pool_stream);
+        (void)hipStreamDestroy(h->pool_stream);
+        (void)hipEventDestroy(h->ev_pool_fork);
+        (void)hipEventDestroy(h->ev_pool_join);
+    }
     if (h->side) {
         (void)hipStreamSynchronize(h->side);
         (void)hipStreamDestroy(h->side);
@@ -530,6 +536,7 @@ int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out
     if (!h || !n_out || cap < 0 || (cap > 0 && !out)) return SCARS_ERR_INVALID_ARG;
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e == hipSuccess && h->side) e = hipStreamSynchronize(h->side);
+    if (e == hipSuccess && h->pool_stream) e = hipStreamSynchronize(h->pool_stream);
     if (e != hipSuccess) return hip_fail(h, e, "profile_read");
     std::vector<scars_kernel_time> acc;
     for (auto& p : h->timer.pending) {

@@ -97,6 +97,8 @@ struct scars_handle {
     // side stream: the integer half of the backward pass can be started by remap and run beside the forward pass
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipStream_t pool_stream = nullptr;   // forward pass: bags that need no fetched row, pooled beside the fetch
+    hipEvent_t ev_pool_fork = nullptr, ev_pool_join = nullptr;
     bool side_pending = false;           // ev_join has been recorded and no stream has been made to wait for it yet
     bool presort_valid = false;          // the workspace holds the segments of the batch described below
     const int32_t *presort_gid = nullptr, *presort_loc = nullptr, *presort_off = nullptr;
