@@ -85,3 +85,24 @@ def test_calls_before_bind_report_workspace_error():
     assert L.scars_cache_rows(s._h) == -1
     assert L.scars_remap(None, None, None, 0, 0, None, None) == binding.ERR_INVALID_ARG
     assert L.scars_destroy(None) == binding.ERR_INVALID_ARG
+
+
+def test_tuning_counters_and_planning_calls_check_their_arguments():
+    L = binding.lib()
+    s = binding.Scars([100], 16, binding.DTYPE_F32, [0x1000])
+    s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
+    s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 10 ** 6)          # clamped to the documented maximum
+    s.set_tuning(binding.TUNE_PRESORT, 131072)
+    s.set_tuning(binding.TUNE_PRESORT, 0)
+    for which, value in ((99, 1), (binding.TUNE_PRESORT, -1), (binding.TUNE_PRESORT, 2 ** 31)):
+        assert L.scars_set_tuning(s._h, which, value) == binding.ERR_INVALID_ARG
+    assert L.scars_set_tuning(None, binding.TUNE_PRESORT, 1) == binding.ERR_INVALID_ARG
+    assert s.get_counter(binding.COUNTER_PREPARED_USED) == 0
+    assert L.scars_get_counter(s._h, 99) == -1 and L.scars_get_counter(None, 1) == -1
+    # planning before any buffer is bound
+    pin = binding._PlanIn(1e6, 1e3, 1e5, 100)
+    po = binding._PlanOut()
+    cost, b = C.c_double(0.0), C.c_double(0.0)
+    assert L.scars_plan_cache(s._h, C.byref(pin), C.byref(po), None) == binding.ERR_WORKSPACE
+    assert L.scars_epoch_cost(s._h, C.byref(pin), 0, C.byref(cost), C.byref(b), None) == binding.ERR_WORKSPACE
+    assert L.scars_plan_cache(None, C.byref(pin), C.byref(po), None) == binding.ERR_INVALID_ARG
