@@ -1,5 +1,7 @@
 """Edge cases of the HIP path against the oracle: empty inputs, ties, extreme budgets, long segments,
 out-of-range indices, bad offsets."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -411,4 +413,45 @@ def test_a_thousand_tables():
                                             np.float32(0.01), np.float32(1e-8))
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows over 1024 tables")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators over 1024 tables")
+    c.close()
+
+
+def test_call_order_and_size_errors_leave_outputs_alone():
+    """Errors the host can see are returned before anything is enqueued: no hot set selected yet, a batch larger than
+    the buffers were bound for, a budget above the bound one, null arrays."""
+    wl = synth.workload("tiny")
+    c = GpuCase(wl)                                   # bound, nothing built
+    d_idx, d_off = c.dev_batch()
+    L = d_idx.numel()
+    rm = c.s.new_remap_out()
+    rm.slot.fill_(-77)
+    out = torch.full((wl.num_bags, wl.dim), 3.5, device=c.dev)
+    grad = c.sampler.grads(0).to(c.dev)
+
+    def code(fn):
+        with pytest.raises(binding.ScarsError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: c.s.remap(d_idx, d_off, wl.batch, rm)) == binding.ERR_NOT_BUILT
+    assert code(lambda: c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm, out)) == binding.ERR_NOT_BUILT
+    assert code(lambda: c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01)) == binding.ERR_NOT_BUILT
+    assert code(lambda: c.s.flush_cache()) == binding.ERR_NOT_BUILT
+    assert code(lambda: c.s.build_cache(d_idx, d_off, wl.batch, c.budget * 2, 0)) == binding.ERR_WORKSPACE
+    c.build()
+    big_idx = torch.cat([d_idx] * 40)                 # far more lookups than max_L
+    big_off = torch.arange(0, wl.num_bags + 1, dtype=torch.int32, device=c.dev) * 40
+    assert code(lambda: c.s.remap(big_idx, big_off, wl.batch, rm)) == binding.ERR_WORKSPACE
+    assert code(lambda: c.s.remap(d_idx, d_off, wl.batch * 1000, rm)) == binding.ERR_WORKSPACE   # more bags than max_G
+    Lb = binding.lib()
+    assert Lb.scars_remap(c.s._h, d_idx.data_ptr(), d_off.data_ptr(), L, wl.batch, None, None) == binding.ERR_INVALID_ARG
+    assert Lb.scars_remap(c.s._h, None, d_off.data_ptr(), L, wl.batch, C.byref(rm.c()), None) == binding.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert c.s.sync_status() == 0
+    assert bool((rm.slot == -77).all()) and bool((out == 3.5).all())      # nothing was written
+    # and the same arrays work once the call is valid
+    c.s.remap(d_idx, d_off, wl.batch, rm)
+    c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm, out)
+    rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
+    assert_close(out.cpu().numpy(), want, "forward after the refused calls")
     c.close()
