@@ -131,6 +131,18 @@ def classify_samples(rows, indices, offsets, B: int, slot_of: np.ndarray):
     return rc, None, None, None
 
 
+def partition_batch(T: int, indices, offsets, B: int, ids):
+    """Sub-batch of the samples `ids` (ascending): (rc, sub_indices, sub_offsets)."""
+    indices = _i32(indices); offsets = _i32(offsets); ids = _i32(ids)
+    L, n = indices.shape[0], ids.shape[0]
+    sub_idx = np.empty(max(L, 1), dtype=np.int32)
+    sub_off = np.empty(T * n + 1, dtype=np.int32)
+    Ls = C.c_int64(0)
+    rc = lib().ora_partition_batch(C.c_int32(T), _p(indices), _p(offsets), C.c_int64(L), C.c_int64(B), _p(ids),
+                                   C.c_int64(n), _p(sub_idx), _p(sub_off), C.byref(Ls))
+    return rc, sub_idx[: Ls.value], sub_off
+
+
 def portion_usage(rows, indices, offsets, B: int, slot_of: np.ndarray, portion_rows: int, n_portions: int):
     rows = _rows(rows); indices = _i32(indices); offsets = _i32(offsets); slot_of = _i32(slot_of)
     T = _LB(rows, offsets, B)

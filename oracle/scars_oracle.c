@@ -198,6 +198,31 @@ int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indi
     return bad ? ORA_ERR_INDEX_RANGE : ORA_OK;
 }
 
+/* ---- sub-batch of selected samples ---------------------------------------------------------------
+ * Section III: hot and normal samples are trained in separate mini-batches.  The sub-batch of the samples
+ * ids[0..n) (ascending sample numbers) keeps the table-major layout with n samples per table: its bag
+ * t*n + j is bag t*B + ids[j] of the batch, lookups in their original order. */
+int32_t ora_partition_batch(int32_t T, const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
+                            const int32_t* ids, int64_t n, int32_t* sub_indices, int32_t* sub_offsets, int64_t* L_sub) {
+    if (T < 1 || B < 0 || L < 0 || n < 0 || n > B || !offsets || !sub_offsets || !L_sub || (n > 0 && !ids) ||
+        (L > 0 && (!indices || !sub_indices)))
+        return ORA_ERR_INVALID_ARG;
+    for (int64_t j = 0; j < n; ++j)
+        if (ids[j] < 0 || ids[j] >= B || (j > 0 && ids[j] <= ids[j - 1])) return ORA_ERR_INVALID_ARG;
+    int64_t pos = 0;
+    sub_offsets[0] = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t g = (int64_t)t * B + ids[j];
+            if (offsets[g] < 0 || offsets[g + 1] < offsets[g] || offsets[g + 1] > L) return ORA_ERR_OFFSETS;
+            for (int64_t i = offsets[g]; i < offsets[g + 1]; ++i) sub_indices[pos++] = indices[i];
+            sub_offsets[(int64_t)t * n + j + 1] = (int32_t)pos;
+        }
+    }
+    *L_sub = pos;
+    return ORA_OK;
+}
+
 /* ---- cache use by portion ------------------------------------------------------------------------ */
 int32_t ora_portion_usage(int32_t T, const int64_t* rows, const int32_t* indices, const int32_t* offsets,
                           int64_t L, int64_t B, const int32_t* slot_of, int64_t portion_rows, int32_t n_portions,

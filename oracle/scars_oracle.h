@@ -79,6 +79,11 @@ int32_t ora_classify_samples(int32_t T, const int64_t* rows, const int32_t* indi
                              int64_t L, int64_t B, const int32_t* slot_of, int32_t* is_hot /* [B] */,
                              int32_t* hot_ids /* [B] */, int32_t* normal_ids /* [B] */, int64_t* n_out /* [2] */);
 
+/* Section III, separate mini-batches of hot and normal samples: the sub-batch of samples ids[0..n) (ascending),
+ * table-major with n samples per table, lookups in their original order.  sub_offsets has T*n + 1 entries. */
+int32_t ora_partition_batch(int32_t T, const int32_t* indices, const int32_t* offsets, int64_t L, int64_t B,
+                            const int32_t* ids, int64_t n, int32_t* sub_indices, int32_t* sub_offsets, int64_t* L_sub);
+
 /* Use of the cache by portion (the measurement behind Fig. 4 of Section IV: how many samples of a mini-batch
  * touch each successive portion of the hotness-ordered cache).  Portion p holds slots
  * [p * portion_rows, (p+1) * portion_rows); usage[p] = number of samples with at least one lookup whose slot

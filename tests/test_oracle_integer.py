@@ -340,3 +340,45 @@ def test_portion_usage_brute_force(ora):
     assert np.array_equal(usage, np.bincount(pairs[:, 1], minlength=nport))
     assert usage.max() <= wl.batch
     assert usage[0] >= usage[-1]                 # slots are in hotness order: the first portion is used most
+
+
+def test_partition_batch_brute_force_and_invariants(ora):
+    """Sub-batch of selected samples (Section III): python-list brute force; hot and normal sub-batches together hold
+    every lookup once; the forward sums of a sub-batch are the selected rows of the full batch's sums (bit for bit:
+    same lookups, same order); a hot sub-batch has no miss."""
+    wl = synth.workload("tiny", batch=97, bag_lambda=0.7)      # 1 + Poisson(0.7) lookups per bag, four tables
+    s = synth.Sampler(wl)
+    idx, off = (a.numpy() for a in s.batch(0))
+    T, B = wl.num_tables, wl.batch
+    rc, counts = ora.histogram(wl.rows, *(a.numpy() for a in s.batch(1, True)), B)
+    k = wl.total_rows // 4
+    rc, hot, slot_of = ora.hot_set(counts, k)
+    rc, is_hot, hot_ids, normal_ids = ora.classify_samples(wl.rows, idx, off, B, slot_of)
+    assert rc == 0 and 0 < hot_ids.size < B
+    subs = {}
+    for name, ids in (("hot", hot_ids), ("normal", normal_ids), ("all", np.arange(B, dtype=np.int32)),
+                      ("none", np.zeros(0, dtype=np.int32))):
+        rc, si, so = ora.partition_batch(T, idx, off, B, ids)
+        assert rc == 0
+        want_i, want_o = [], [0]
+        for t in range(T):
+            for j in ids:
+                g = t * B + int(j)
+                want_i += idx[off[g]:off[g + 1]].tolist()
+                want_o.append(len(want_i))
+        assert si.tolist() == want_i and so.tolist() == want_o
+        subs[name] = (si, so, ids)
+    assert np.array_equal(subs["all"][0], idx) and np.array_equal(subs["all"][1], off)
+    assert subs["hot"][0].size + subs["normal"][0].size == idx.size
+    tables = [t.numpy() for t in synth.make_tables_cpu(wl)]
+    rc, full = ora.embedding_bag_fwd(wl.rows, tables, idx, off, B)
+    for name in ("hot", "normal"):
+        si, so, ids = subs[name]
+        rc, out = ora.embedding_bag_fwd(wl.rows, tables, si, so, ids.size)
+        sel = (np.arange(T)[:, None] * B + ids[None, :]).reshape(-1)
+        assert rc == 0 and np.array_equal(out, full[sel])
+    rc, slot, hit, miss, mg = ora.remap(wl.rows, subs["hot"][0], subs["hot"][1], hot_ids.size, slot_of)
+    assert rc == 0 and miss.size == 0
+    # refused: ids not ascending, out of range
+    assert ora.partition_batch(T, idx, off, B, np.array([3, 3], dtype=np.int32))[0] != 0
+    assert ora.partition_batch(T, idx, off, B, np.array([B], dtype=np.int32))[0] != 0
