@@ -213,6 +213,20 @@ int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices
 int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
                                const scars_classify_out* out, void* stream);
 
+/* Sub-batch of selected samples (Section III: hot and normal samples are trained in separate mini-batches).  d_ids
+ * (DEVICE int32, ascending sample numbers below B, e.g. hot_ids or normal_ids of scars_classify_samples) and *d_n
+ * (DEVICE int32: how many of them, e.g. &n_hot_normal[0]) select the samples; the sub-batch keeps the table-major
+ * layout with n samples per table: its bag t*n + j is bag t*B + d_ids[j] of the batch, lookups in their original
+ * order, so its pooled sums are the selected rows of the batch's, bit for bit.  n stays on the device: read
+ * n_lookups_bags back (or n_hot_normal) to call the per-batch entry points on the sub-batch with B = n. */
+typedef struct {
+    int32_t* indices;         /* DEVICE int32 [L]: first n_lookups entries valid */
+    int32_t* offsets;         /* DEVICE int32 [T*B + 1]: first T*n + 1 entries valid */
+    int32_t* n_lookups_bags;  /* DEVICE int32 [2] = {lookups, bags = T*n} of the sub-batch */
+} scars_subbatch_out;
+int32_t scars_partition_batch(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                              const int32_t* d_ids, const int32_t* d_n, const scars_subbatch_out* out, void* stream);
+
 /* Use of the cache by portion (the measurement of Fig. 4 in Section IV: samples of a mini-batch that touch each
  * successive part of the hotness-ordered cache).  d_usage[p], DEVICE int32 [n_portions] with n_portions <= 64,
  * receives the number of samples having at least one lookup whose slot lies in

@@ -23,7 +23,7 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_set_tuning", "scars_get_counter", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
-    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_portion_usage", "scars_epoch_cost",
+    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_partition_batch", "scars_portion_usage", "scars_epoch_cost",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_profile_enable", "scars_profile_read",
@@ -66,6 +66,10 @@ class _ClassifyOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("is_hot", "hot_ids", "normal_ids", "n_hot_normal")]
 
 
+class _SubbatchOut(C.Structure):
+    _fields_ = [("indices", C.c_void_p), ("offsets", C.c_void_p), ("n_lookups_bags", C.c_void_p)]
+
+
 class _PlanIn(C.Structure):
     _fields_ = [("device_params", C.c_double), ("per_sample_params", C.c_double), ("samples_per_epoch", C.c_double),
                 ("profile_samples", C.c_int64)]
@@ -106,6 +110,7 @@ def lib():
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
         L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
+        L.scars_partition_batch.argtypes = [vp, vp, vp, i64, i64, vp, vp, C.POINTER(_SubbatchOut), vp]
         L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
         L.scars_epoch_cost.argtypes = [vp, C.POINTER(_PlanIn), i64, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
         L.scars_plan_cache.argtypes = [vp, C.POINTER(_PlanIn), C.POINTER(_PlanOut), vp]
@@ -388,6 +393,19 @@ class Scars:
         self._check(lib().scars_classify_samples(self._h, self._i32(offsets), int(indices.numel()), B, C.byref(c),
                                                  C.byref(co), _stream()))
         return out
+
+    def partition_batch(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, ids: torch.Tensor, n: torch.Tensor):
+        """Sub-batch of the samples ids[:n] (n: 1-element int32 CUDA tensor, e.g. cls.n_hot_normal[0:1]).
+        Returns (sub_indices [L], sub_offsets [T*B+1], n_lookups_bags [2]); only the leading parts are valid."""
+        L = int(indices.numel())
+        sub_idx = torch.empty(max(L, 1), dtype=torch.int32, device=self.device)
+        sub_off = torch.empty(self.T * B + 1, dtype=torch.int32, device=self.device)
+        cnt = torch.zeros(2, dtype=torch.int32, device=self.device)
+        assert ids.is_cuda and ids.dtype == torch.int32 and n.is_cuda and n.dtype == torch.int32
+        c = _SubbatchOut(sub_idx.data_ptr(), sub_off.data_ptr(), cnt.data_ptr())
+        self._check(lib().scars_partition_batch(self._h, self._i32(indices), self._i32(offsets), L, B, ids.data_ptr(),
+                                                n.data_ptr(), C.byref(c), _stream()))
+        return sub_idx, sub_off, cnt
 
     def portion_usage(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut, portion_rows: int,
                       n_portions: int) -> torch.Tensor:

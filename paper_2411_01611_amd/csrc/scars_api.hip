@@ -362,6 +362,18 @@ int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_
     return SCARS_OK;
 }
 
+int32_t scars_partition_batch(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                              const int32_t* d_ids, const int32_t* d_n, const scars_subbatch_out* out, void* stream) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "partition_batch");
+    if (rc) return rc;
+    if (!d_n || (B > 0 && !d_ids)) return fail(h, SCARS_ERR_INVALID_ARG, "partition_batch: null sample list");
+    if (!out || !out->offsets || !out->n_lookups_bags || (L > 0 && !out->indices))
+        return fail(h, SCARS_ERR_INVALID_ARG, "partition_batch: subbatch_out has a null array");
+    hipError_t e = launch_partition(h, (hipStream_t)stream, d_indices, d_offsets, L, B, d_ids, d_n, out);
+    if (e != hipSuccess) return hip_fail(h, e, "partition_batch");
+    return SCARS_OK;
+}
+
 int32_t scars_portion_usage(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
                             int64_t portion_rows, int32_t n_portions, int32_t* d_usage, void* stream) {
     int32_t rc = check_batch(h, L > 0 ? (const int32_t*)d_offsets : nullptr, d_offsets, L, B, "portion_usage");

@@ -156,6 +156,8 @@ hipError_t launch_classify(scars_handle* h, hipStream_t s, const int32_t* off, i
                            const scars_remap_out* rm, const scars_classify_out* out);
 hipError_t launch_portion_usage(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                                 const scars_remap_out* rm, int64_t portion_rows, int32_t n_portions, int32_t* usage);
+hipError_t launch_partition(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
+                            const int32_t* ids, const int32_t* d_n, const scars_subbatch_out* out);
 // k_plan.hip
 hipError_t launch_count_of_counts(scars_handle* h, hipStream_t s);
 double plan_cost(const std::vector<std::pair<uint32_t, int64_t>>& classes, int T, int64_t n_samples, int64_t k, double M,

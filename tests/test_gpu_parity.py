@@ -516,3 +516,65 @@ def test_presort_falls_back_when_the_calls_do_not_line_up():
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after mixed call orders")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after mixed call orders")
     c.close()
+
+
+# ---- sub-batches of hot and normal samples (Section III) ---------------------------------------------------------
+@pytest.mark.parametrize("name,budget_frac", [("tiny", 0.25), ("dlrm_small", 0.3), ("multi_hot_small", 0.9),
+                                              ("host_spill_small", 0.1), ("low_skew_bf16", 0.95)])
+@pytest.mark.parametrize("scan", [False, True])
+def test_partition_batch_parity_and_hot_subbatch_never_misses(name, budget_frac, scan):
+    wl = _wl(name)
+    c = GpuCase(wl, budget_bytes=int(wl.total_rows * budget_frac) * wl.row_bytes)
+    if scan:
+        c.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
+    c.build()
+    T, B = wl.num_tables, wl.batch
+    idx, off = c.batch
+    d_idx, d_off = c.dev_batch()
+    rm = c.s.remap(d_idx, d_off, B)
+    full = c.s.embedding_bag_fwd(d_idx, d_off, B, rm).clone()
+    cls = c.s.classify_samples(d_idx, d_off, B, rm)
+    rc, is_hot, hot_ids, normal_ids = oracle.classify_samples(wl.rows, idx.numpy(), off.numpy(), B, c.ora_slot_of)
+    assert rc == 0
+    _say("partition", name, "hot samples", hot_ids.size, "of", B)
+    for which, ids_dev, ids_ref in ((0, cls.hot_ids, hot_ids), (1, cls.normal_ids, normal_ids)):
+        rc, want_i, want_o = oracle.partition_batch(T, idx.numpy(), off.numpy(), B, ids_ref)
+        assert rc == 0
+        sub_i, sub_o, cnt = c.s.partition_batch(d_idx, d_off, B, ids_dev, cls.n_hot_normal[which:which + 1])
+        assert c.s.sync_status() == 0
+        n = ids_ref.size
+        assert cnt.cpu().tolist() == [want_i.size, T * n]
+        assert np.array_equal(sub_o.cpu().numpy()[: T * n + 1], want_o)
+        assert np.array_equal(sub_i.cpu().numpy()[: want_i.size], want_i)
+        if n == 0:
+            continue
+        # the sub-batch through the per-batch calls, with B = n
+        s_idx, s_off = sub_i[: want_i.size].contiguous(), sub_o[: T * n + 1].contiguous()
+        rm_s = c.s.remap(s_idx, s_off, n)
+        out_s = c.s.embedding_bag_fwd(s_idx, s_off, n, rm_s)
+        assert c.s.sync_status() == 0
+        sel = (torch.arange(T)[:, None] * B + torch.from_numpy(ids_ref.astype(np.int64))[None, :]).reshape(-1).to(c.dev)
+        assert torch.equal(out_s, full[sel]), "a sub-batch's sums are the selected rows of the batch's, bit for bit"
+        if which == 0:
+            assert rm_s.n_hit_miss.cpu().tolist() == [want_i.size, 0]      # a hot sub-batch never touches the host link
+    c.close()
+
+
+def test_partition_batch_of_nothing_and_of_everything():
+    wl = _wl("multi_hot_small")
+    c = GpuCase(wl)
+    c.build()
+    T, B = wl.num_tables, wl.batch
+    idx, off = c.batch
+    d_idx, d_off = c.dev_batch()
+    ids = torch.arange(B, dtype=torch.int32, device=c.dev)
+    for n in (0, B):
+        nt = torch.tensor([n], dtype=torch.int32, device=c.dev)
+        sub_i, sub_o, cnt = c.s.partition_batch(d_idx, d_off, B, ids, nt)
+        assert c.s.sync_status() == 0
+        if n == 0:
+            assert cnt.cpu().tolist() == [0, 0] and int(sub_o[0]) == 0
+        else:
+            assert cnt.cpu().tolist() == [idx.numel(), T * B]
+            assert torch.equal(sub_i[: idx.numel()].cpu(), idx) and torch.equal(sub_o.cpu(), off)
+    c.close()
