@@ -257,6 +257,12 @@ typedef struct {
 /* cost(k) and its batch size for one k; INVALID_ARG if b < 1. */
 int32_t scars_epoch_cost(scars_handle* h, const scars_plan_in* in, int64_t k, double* cost, double* batch, void* stream);
 
+/* The paper's test for caching one more embedding (eq. (8)-(12)): with the first k rows of the ranking cached and e'
+ * the next one, b = (M - k d) / a, b' = b - d / a, communication per epoch falls iff
+ *     *lhs = 1 - (1 - P(e'))^b  >=  *t1 = sum_{e not in C'} (b (1 - (1 - P(e))^b') - b' (1 - (1 - P(e))^b)) / b'.
+ * INVALID_ARG if k >= N or b' < 1.  BLOCKS like the other two. */
+int32_t scars_caching_gain(scars_handle* h, const scars_plan_in* in, int64_t k, double* lhs, double* t1, void* stream);
+
 /* Search over k in [0, k_max]: every k when k_max <= 4096, otherwise count-class borders and a narrowing grid. */
 int32_t scars_plan_cache(scars_handle* h, const scars_plan_in* in, scars_plan_out* out, void* stream);
 

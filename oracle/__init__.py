@@ -160,6 +160,14 @@ def epoch_cost(T: int, counts: np.ndarray, n_samples: int, k: int, M: float, a: 
     return rc, cost.value, b.value
 
 
+def caching_gain(counts: np.ndarray, n_samples: int, k: int, M: float, a: float, d: float):
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    lhs = C.c_double(0.0); t1 = C.c_double(0.0)
+    rc = lib().ora_caching_gain(C.c_int64(counts.shape[0]), _p(counts), C.c_int64(n_samples), C.c_int64(k), C.c_double(M),
+                                C.c_double(a), C.c_double(d), C.byref(lhs), C.byref(t1))
+    return rc, lhs.value, t1.value
+
+
 def plan_brute(T: int, counts: np.ndarray, n_samples: int, k_max: int, M: float, a: float, d: float, Q: float):
     counts = np.ascontiguousarray(counts, dtype=np.uint32)
     bk = C.c_int64(0); bc = C.c_double(0.0)

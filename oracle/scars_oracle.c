@@ -289,6 +289,35 @@ int32_t ora_plan_brute(int32_t T, int64_t N, const uint32_t* counts, int64_t n_s
     return found ? ORA_OK : ORA_ERR_INVALID_ARG;
 }
 
+/* Caching one more embedding e' (eq. (8)-(12)): with C = the first k rows of the ranking, e' = the next one,
+ * b = (M - k d) / a and b' = b - d / a, communication per epoch falls iff
+ *     1 - (1 - P(e'))^b  >=  t1 = sum_{e not in C'} (b (1 - (1 - P(e))^b') - b' (1 - (1 - P(e))^b)) / b'. */
+int32_t ora_caching_gain(int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k, double M, double a, double d,
+                         double* lhs, double* t1) {
+    if (N < 1 || !counts || n_samples < 1 || k < 0 || k >= N || a <= 0.0 || d <= 0.0 || !lhs || !t1)
+        return ORA_ERR_INVALID_ARG;
+    const double b = (M - (double)k * d) / a, b2 = b - d / a;
+    if (!(b2 >= 1.0)) return ORA_ERR_INVALID_ARG;
+    int32_t* hot = (int32_t*)malloc(sizeof(int32_t) * (size_t)(k + 1));
+    int32_t* slot_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int rc = ora_hot_set(N, counts, k + 1, hot, slot_of);          /* C' = first k + 1 rows; e' = the last of them */
+    if (rc) { free(hot); free(slot_of); return rc; }
+    double pe = (double)counts[hot[k]] / (double)n_samples;
+    if (pe > 1.0) pe = 1.0;
+    *lhs = 1.0 - pow(1.0 - pe, b);
+    double sum = 0.0;
+    for (int64_t e = 0; e < N; ++e) {
+        if (slot_of[e] >= 0) continue;
+        double p = (double)counts[e] / (double)n_samples;
+        if (p > 1.0) p = 1.0;
+        sum += (b * (1.0 - pow(1.0 - p, b2)) - b2 * (1.0 - pow(1.0 - p, b))) / b2;
+    }
+    *t1 = sum;
+    free(hot);
+    free(slot_of);
+    return ORA_OK;
+}
+
 /* ---- forward ----------------------------------------------------------------------------- */
 static int32_t fwd_impl(int32_t T, const int64_t* rows, int32_t D, int32_t dtype, const void* const* tables,
                         const int32_t* slot_of, const void* cache, const int32_t* indices,

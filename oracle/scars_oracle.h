@@ -102,6 +102,11 @@ int32_t ora_epoch_cost(int32_t T, int64_t N, const uint32_t* counts, int64_t n_s
                        double d, double Q, double* cost, double* b_out);
 
 /* Brute force over every feasible k in [0, k_max]: the k with the smallest ora_epoch_cost (lowest k on ties). */
+/* Eq. (8)-(12): the test for caching one more embedding.  C = first k rows of the ranking, e' the next one;
+ * *lhs = 1 - (1 - P(e'))^b, *t1 as in eq. (12) with b' = b - d / a.  Communication per epoch falls iff lhs >= t1. */
+int32_t ora_caching_gain(int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k, double M, double a, double d,
+                         double* lhs, double* t1);
+
 int32_t ora_plan_brute(int32_t T, int64_t N, const uint32_t* counts, int64_t n_samples, int64_t k_max, double M, double a,
                        double d, double Q, int64_t* best_k, double* best_cost);
 

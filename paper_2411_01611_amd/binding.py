@@ -24,6 +24,7 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_set_tuning", "scars_get_counter", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
     "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_partition_batch", "scars_portion_usage", "scars_epoch_cost",
+    "scars_caching_gain",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_profile_enable", "scars_profile_read",
@@ -113,6 +114,7 @@ def lib():
         L.scars_partition_batch.argtypes = [vp, vp, vp, i64, i64, vp, vp, C.POINTER(_SubbatchOut), vp]
         L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
         L.scars_epoch_cost.argtypes = [vp, C.POINTER(_PlanIn), i64, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+        L.scars_caching_gain.argtypes = [vp, C.POINTER(_PlanIn), i64, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
         L.scars_plan_cache.argtypes = [vp, C.POINTER(_PlanIn), C.POINTER(_PlanOut), vp]
         L.scars_flush_cache.argtypes = [vp, vp]
         L.scars_sync_status.argtypes = [vp, vp]
@@ -427,6 +429,13 @@ class Scars:
         cost, b = C.c_double(0.0), C.c_double(0.0)
         self._check(lib().scars_epoch_cost(self._h, C.byref(pin), k, C.byref(cost), C.byref(b), _stream()))
         return cost.value, b.value
+
+    def caching_gain(self, M: float, a: float, profile_samples: int, k: int):
+        """(lhs, t1) of eq. (11)/(12) for caching the row ranked k + 1 on top of the first k.  Blocks."""
+        pin = _PlanIn(M, a, 1.0, profile_samples)
+        lhs, t1 = C.c_double(0.0), C.c_double(0.0)
+        self._check(lib().scars_caching_gain(self._h, C.byref(pin), k, C.byref(lhs), C.byref(t1), _stream()))
+        return lhs.value, t1.value
 
     def plan_cache(self, M: float, a: float, Q: float, profile_samples: int) -> Dict[str, float]:
         pin, po = _PlanIn(M, a, Q, profile_samples), _PlanOut()

@@ -435,6 +435,32 @@ int32_t scars_epoch_cost(scars_handle* h, const scars_plan_in* in, int64_t k, do
     return SCARS_OK;
 }
 
+int32_t scars_caching_gain(scars_handle* h, const scars_plan_in* in, int64_t k, double* lhs, double* t1, void* stream) {
+    int32_t rc = check_plan(h, in);
+    if (rc) return rc;
+    if (k < 0 || k >= h->N || !lhs || !t1) return fail(h, SCARS_ERR_INVALID_ARG, "caching_gain: k out of range or null output");
+    const double M = in->device_params, a = in->per_sample_params, d = (double)h->D;
+    const double b = (M - (double)k * d) / a, b2 = b - d / a;
+    if (!(b2 >= 1.0)) return fail(h, SCARS_ERR_INVALID_ARG, "caching_gain: no room for a batch of one sample with one more row cached");
+    std::vector<std::pair<uint32_t, int64_t>> classes;
+    if ((rc = load_classes(h, (hipStream_t)stream, &classes))) return rc;
+    // rows are ranked by count: the first k are cached, the next one is e', the rest stay outside C'
+    double sum = 0.0, pe = 0.0;
+    int64_t before = 0;
+    for (const auto& cl : classes) {
+        const int64_t cached = std::min<int64_t>(std::max<int64_t>(k + 1 - before, 0), cl.second);
+        const double p = std::min(1.0, (double)cl.first / (double)in->profile_samples);
+        if (before <= k && k < before + cl.second) pe = p;       // e' is in this class
+        before += cl.second;
+        const int64_t rest = cl.second - cached;
+        if (rest > 0 && cl.first > 0)
+            sum += (double)rest * (b * (1.0 - std::pow(1.0 - p, b2)) - b2 * (1.0 - std::pow(1.0 - p, b))) / b2;
+    }
+    *lhs = 1.0 - std::pow(1.0 - pe, b);
+    *t1 = sum;
+    return SCARS_OK;
+}
+
 int32_t scars_plan_cache(scars_handle* h, const scars_plan_in* in, scars_plan_out* out, void* stream) {
     int32_t rc = check_plan(h, in);
     if (rc) return rc;

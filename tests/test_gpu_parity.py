@@ -578,3 +578,18 @@ def test_partition_batch_of_nothing_and_of_everything():
             assert cnt.cpu().tolist() == [idx.numel(), T * B]
             assert torch.equal(sub_i[: idx.numel()].cpu(), idx) and torch.equal(sub_o.cpu(), off)
     c.close()
+
+
+def test_caching_gain_parity(case):
+    """eq. (11)/(12) from the device skew table against the oracle's per-row sums."""
+    counts, _, _ = case.build()
+    wl = case.wl
+    M, a, d, Q, S = _plan_params(case, 0.5)
+    kf = int(min(wl.total_rows - 1, (M - a - d) // d))
+    for k in sorted({0, 1, case.k, kf // 2, kf}):
+        rc, lhs, t1 = oracle.caching_gain(counts, S, k, M, a, d)
+        assert rc == 0
+        g_lhs, g_t1 = case.s.caching_gain(M, a, S, k)
+        assert abs(g_lhs - lhs) <= 1e-12 and abs(g_t1 - t1) <= 1e-10 * max(1.0, abs(t1))
+    with pytest.raises(binding.ScarsError):
+        case.s.caching_gain(M, a, S, wl.total_rows)

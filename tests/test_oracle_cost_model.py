@@ -96,3 +96,43 @@ def test_growth_with_five_times_rows_and_batch_stays_below_five(ora):
         growth[name] = cost[1] / cost[0]
     assert growth["exp"] < growth["zipf"] < 5.0 and growth["halfnormal"] < growth["zipf"]
     assert growth["exp"] < 3.0 and growth["halfnormal"] < 3.0
+
+
+def test_caching_one_more_row_criterion_agrees_with_the_cost_difference(ora):
+    # eq. (11)/(12) is eq. (8) <= 0 rearranged: lhs >= t1 exactly when the epoch cost of eq. (6) does not rise from k
+    # to k + 1 cached rows; and t1 against its definition written with numpy.  Two settings: a skewed table with
+    # a > d (the regime in which the paper says caching generally helps: it does, at every k), and a flat table with
+    # a < d, where giving up batch size for one more row does not pay until most rows are cached.
+    wl = synth.workload("tiny")
+    s = synth.Sampler(wl)
+    skewed = None
+    for p in range(8):
+        idx, off = s.batch(p, True)
+        rc, skewed = ora.histogram(wl.rows, idx.numpy(), off.numpy(), wl.batch, skewed)
+    skewed = skewed[:3000]
+    d, Q, T = 16.0, 1.0e6, 1
+    outcomes = {}
+    for name, counts, S, M, a, ks in (("skewed, a > d", skewed, 8 * wl.batch, 3000 * d * 0.6, 150.0, (0, 1, 5, 50, 200)),
+                                      ("flat, a < d", np.ones(3000, dtype=np.uint32), 3000, 3000 * d * 0.5, 5.0,
+                                       (0, 100, 500, 1000, 1400))):
+        order = np.lexsort((np.arange(counts.size), -counts.astype(np.int64)))
+        P = np.minimum(1.0, counts.astype(np.float64) / S)
+        seen = []
+        for k in ks:
+            rc, lhs, t1 = ora.caching_gain(counts, S, k, M, a, d)
+            assert rc == 0
+            b = (M - k * d) / a
+            b2 = b - d / a
+            rest = P[order[k + 1:]]
+            t1_ref = np.sum((b * (1 - (1 - rest) ** b2) - b2 * (1 - (1 - rest) ** b)) / b2)
+            assert abs(lhs - (1 - (1 - P[order[k]]) ** b)) < 1e-14 and abs(t1 - t1_ref) <= 1e-9 * max(1.0, abs(t1_ref))
+            c0 = ora.epoch_cost(T, counts, S, k, M, a, d, Q)[1]
+            c1 = ora.epoch_cost(T, counts, S, k + 1, M, a, d, Q)[1]
+            assert abs(c1 - c0) > 1e-9 * c0 and (lhs >= t1) == (c1 <= c0)
+            seen.append(bool(lhs >= t1))
+        outcomes[name] = seen
+    assert outcomes["skewed, a > d"] == [True] * 5
+    assert outcomes["flat, a < d"] == [False, False, False, True, True]
+    # refused: nothing left to cache, or no room for a batch of one after caching one more
+    assert ora.caching_gain(skewed, 8 * wl.batch, 3000, 1e6, 10.0, d)[0] != 0
+    assert ora.caching_gain(skewed, 8 * wl.batch, 10, 10 * d + 20.0, 10.0, d)[0] != 0
