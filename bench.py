@@ -452,14 +452,24 @@ def main():
                                                                 "hit_rate", "budget_bytes", "optimizer")},
                         "roofline": r["roofline"], "host_link": r["host_link"]}
     line["other_workloads"] = others
+    if args.also != "none" and args.workload != "low_skew_uniform":
+        # the gather roofline reference: uniform ids over 6.4 GB of rows, every row cached (no reuse for the caches
+        # to serve, so algorithmic bytes are close to HBM bytes)
+        torch.cuda.empty_cache()
+        r = run_workload("low_skew_uniform", args, min(args.steps, 10), min(args.warmup, 3), cal, link, False, False, True)
+        line["gather_reference"] = {"workload": "low_skew_uniform, every row cached", "value": r["value"], "unit": r["unit"],
+                                    "ms_per_step": r["ms_per_step"], "roofline": r["roofline"]}
     print(json.dumps(line), flush=True)
 
 
-def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cpu: bool, with_resident: bool) -> dict:
+def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cpu: bool, with_resident: bool,
+                 all_cached: bool = False) -> dict:
     dev = torch.device("cuda:0")
     row_scale = args.row_scale if args.row_scale is not None else (0.5 if name == "host_spill" else 1.0)
     wl = synth.workload(name, scale=args.scale, row_scale=row_scale)
     budget = wl.budget_bytes if (args.budget_bytes < 0 or name != args.workload) else args.budget_bytes
+    if all_cached:
+        budget = wl.total_rows * wl.row_bytes
 
     b = Bench(wl, budget, args.coalesce)
     b.presort = bool(args.presort)
