@@ -593,3 +593,16 @@ def test_caching_gain_parity(case):
         assert abs(g_lhs - lhs) <= 1e-12 and abs(g_t1 - t1) <= 1e-10 * max(1.0, abs(t1))
     with pytest.raises(binding.ScarsError):
         case.s.caching_gain(M, a, S, wl.total_rows)
+
+
+@pytest.mark.parametrize("name", ["multi_hot_small", "host_spill_small"])
+def test_twenty_steps_with_the_side_streams_match_oracle(name):
+    """A longer run with every side-stream path on (sort started by remap, long runs beside the per-row kernel, cached
+    bags pooled beside the fetch): rows and accumulators after twenty steps."""
+    wl = _wl(name)
+    c = GpuCase(wl, max_L=_room(wl))
+    c.s.set_tuning(binding.TUNE_PRESORT, 1)
+    c.build()
+    _presort_steps(c, 20, f"{name}, twenty steps")
+    assert c.s.get_counter(binding.COUNTER_PREPARED_USED) == 20
+    c.close()
