@@ -112,12 +112,24 @@ class Bench:
         self.s.build_cache(None, None, 0, self.budget, 1)
         torch.cuda.synchronize()
         t_sel = time.time() - s0
+        # the same selection once more with a HIP event pair around every kernel: select, rank sort and fill apart
+        self.s.profile_enable(True)
+        self.s.build_cache(None, None, 0, self.budget, 1)
+        prof = self.s.profile_read()
+        self.s.profile_enable(False)
+        ms = lambda *names: sum(v["total_ms"] for n, v in prof.items() if n.startswith(names))
+        t_select = ms("sel_", "win_", "scan_two", "fill") * 1e-3
+        t_rank = ms("sort_", "slot_scatter") * 1e-3
+        t_fill = ms("cache_fill") * 1e-3
         st = self.s.sync_status()
         assert st == 0, f"device error {st} during build_cache"
         k = self.s.cache_rows()
         return {"profile_lookups": Lp, "histogram_s": t_hist, "select_and_fill_s": t_sel, "k": k,
                 "histogram_Mlookups_per_s": Lp / max(t_hist, 1e-9) / 1e6,
-                "fill_host_link_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_sel, 1e-9) / 1e9, "total_s": time.time() - t0 - gen}
+                "fill_host_link_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_sel, 1e-9) / 1e9,
+                "select_s": t_select, "select_Mrows_per_s": wl.total_rows / max(t_select, 1e-9) / 1e6, "rank_sort_s": t_rank,
+                "fill_s": t_fill, "fill_kernel_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_fill, 1e-9) / 1e9,
+                "kernels_ms": {n: round(v["total_ms"], 4) for n, v in prof.items()}, "total_s": t_hist + t_sel}
 
     def step(self, e: int):
         wl = self.wl
