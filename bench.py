@@ -207,6 +207,7 @@ def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> 
         "pool_short": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
         "stage_misses": 2 * n_miss * R + 4 * n_miss,          # link read + HBM write
         "seg_rows": L * D * 4 + 8 * L + U * (2 * R + st + 12),   # with seg_long: gradient rows + row read-modify-write
+        "seg_rows_long": L * D * 4 + 8 * L + U * (2 * R + st + 12),   # small batches: both in one launch
         "remap_probe": 16 * L,
         "remap_write": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss),
         "sort_scatter": 16 * L,
@@ -344,7 +345,8 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     # forward: every missed lookup's row is read over the link.  backward: a cold row's value comes from the copy
     # the forward pass staged, so only its accumulator is read over the link; row and accumulator are written back
     for name, rd, wr in (("stage_misses", n_staged * wl.row_bytes, 0),
-                         ("seg_rows", U_cold * state_b, U_cold * (wl.row_bytes + state_b))):
+                         ("seg_rows", U_cold * state_b, U_cold * (wl.row_bytes + state_b)),
+                         ("seg_rows_long", U_cold * state_b, U_cold * (wl.row_bytes + state_b))):
         if name in prof and rd + wr > 0:
             t_s = prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
             t_min = max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9))
@@ -433,6 +435,9 @@ def main():
     ap.add_argument("--coalesce", action="store_true",
                     help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-long-max-l", type=int, default=-1,
+                    help="largest batch (lookups) whose backward pass updates long runs and the other rows in one "
+                         "launch (default: the library's, every batch; 0 = never)")
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
@@ -486,6 +491,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     b = Bench(wl, budget, args.coalesce)
     b.presort = bool(args.presort)
     b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
+    if args.fused_long_max_l >= 0:
+        b.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, args.fused_long_max_l)
     b.prepare(K + W)
     bc = b.build_cache()
     log(name, "build_cache", bc)

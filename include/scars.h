@@ -85,6 +85,11 @@ typedef struct {
  * cross-stream waits cost some 10-20 us per step: not worth it for small batches.  Under HIP graph capture the side
  * stream joins the capture: end the capture after the bwd_update (or sync_status) that joins it back.  Default 0. */
 #define SCARS_TUNE_PRESORT 2
+/* Batches of at most this many lookups sum the long runs (more than 64 lookups of one row) and update the other rows
+ * in one launch of the backward pass instead of two: the two jobs touch disjoint rows, and sharing a launch hides the
+ * shorter one's chain of dependent memory round trips.  Not used while SCARS_TUNE_PRESORT runs the long runs on the
+ * side stream.  0 = never (two launches). */
+#define SCARS_TUNE_FUSED_LONG_MAX_L 3           /* default 2^31 - 1: every batch */
 
 /* Host-side counters (never reset); -1 for an unknown counter. */
 #define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */

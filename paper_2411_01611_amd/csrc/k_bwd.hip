@@ -226,6 +226,7 @@ constexpr int kLongRun = kLongRunMin;   // runs up to this many lookups are summ
 constexpr int kGradUnroll = 4;  // gradient rows in flight per lane group in the per-row kernel
 constexpr int kTaskUnroll = 16;  // ... and in a task of a long run (few groups, long chains: go wide)
 constexpr int kCombUnroll = 16; // partial sums in flight when a long run is combined
+constexpr int64_t kFusedWideMaxL = 1 << 17;   // shared launch: batches up to this size take the wide long-run part
 
 // Sum of the gradient rows val[j], j in [p0, p1), columns [4c, 4c+4), in position order, fp64.  The group's lanes
 // fetch a window of bag ids with one load and hand them out by shuffles, so every gradient row address of a trip is
@@ -261,11 +262,13 @@ __device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, cons
 
 // One lane group per distinct row whose run has at most kLongRun lookups; the row (and accumulator) is
 // fetched while the gradient rows stream in.  Longer runs are left to k_seg_long.
+// `block` of `nblocks` workgroups share the rows (the kernel's own grid, or the part of a fused grid that does this).
 template <int DTYPE, int OPT, int LPG>
-__global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
-                                                     const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
-                                                     const int32_t* __restrict__ unique_slot, const uint32_t* __restrict__ first_bag,
-                                                     const float* __restrict__ grad, UpdateArgs A) {
+__device__ __forceinline__ void seg_rows_body(int block, int nblocks, const uint32_t* __restrict__ val,
+                                              const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
+                                              const int32_t* __restrict__ unique_gid, const int32_t* __restrict__ unique_slot,
+                                              const uint32_t* __restrict__ first_bag, const float* __restrict__ grad,
+                                              const UpdateArgs& A) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = A.meta->num_tables;
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = A.meta->row_base[t];
@@ -276,8 +279,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
     const bool lane_on = c < dq;              // lanes beyond the row stay: they hand out bag ids in sum_grads
     const int cc = min(c, dq - 1);
     const float4* g4 = (const float4*)grad;
-    const int64_t ngroups = (int64_t)gridDim.x * (kBlock / LPG);
-    for (int64_t r = (int64_t)blockIdx.x * (kBlock / LPG) + threadIdx.x / LPG; r < U; r += ngroups) {
+    const int64_t ngroups = (int64_t)nblocks * (kBlock / LPG);
+    for (int64_t r = (int64_t)block * (kBlock / LPG) + threadIdx.x / LPG; r < U; r += ngroups) {
         const int32_t a = seg_start[r], b = seg_start[r + 1];
         const uint32_t gid = (uint32_t)unique_gid[r];
         const int32_t slot = unique_slot[r];
@@ -295,24 +298,33 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict_
     }
 }
 
+template <int DTYPE, int OPT, int LPG>
+__global__ __launch_bounds__(kBlock) void k_seg_rows(const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
+                                                     const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
+                                                     const int32_t* __restrict__ unique_slot, const uint32_t* __restrict__ first_bag,
+                                                     const float* __restrict__ grad, UpdateArgs A) {
+    seg_rows_body<DTYPE, OPT, LPG>((int)blockIdx.x, (int)gridDim.x, val, n_unique, seg_start, unique_gid, unique_slot, first_bag,
+                                   grad, A);
+}
+
 // Runs longer than kLongRun, first half: one lane group per chunk of kLongRun sorted positions.  Such a run
 // overlaps a chunk either by covering its first position ("side 0") or by starting inside it and running past
 // its end ("side 1"); at most one of each per chunk.  The overlap is summed into partial[chunk][side].
 // chunk_run[ch] is the run that holds the chunk's first position.  Independent of k_seg_rows.
-template <int LPG>
-__global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
-                                                     const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
-                                                     const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
-                                                     double* __restrict__ partial, int D, uint32_t Gm1) {
+template <int LPG, int UNROLL>
+__device__ __forceinline__ void seg_long_body(int block, int nblocks, const uint32_t* __restrict__ key,
+                                              const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
+                                              const int32_t* __restrict__ seg_start, const int32_t* __restrict__ chunk_run,
+                                              const float* __restrict__ grad, double* __restrict__ partial, int D, uint32_t Gm1) {
     const int32_t Lv = n_unique[1];
     const int c = threadIdx.x % LPG;
     const bool lane_on = c * 4 < D;
     const int dq = D / 4;
     const float4* g4 = (const float4*)grad;
     constexpr int gpb = kBlock / LPG;
-    const int64_t ngroups = (int64_t)gridDim.x * gpb;
+    const int64_t ngroups = (int64_t)nblocks * gpb;
     const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
-    for (int64_t ch = (int64_t)blockIdx.x * gpb + threadIdx.x / LPG; ch < nchunks; ch += ngroups) {
+    for (int64_t ch = (int64_t)block * gpb + threadIdx.x / LPG; ch < nchunks; ch += ngroups) {
         const int32_t j0 = (int32_t)ch * kLongRun, j1 = min(j0 + kLongRun, Lv);
         const uint32_t k0 = key[j0], k1 = key[j1 - 1];
         const uint32_t kp = j0 > 0 ? key[j0 - 1] : ~k0;
@@ -327,13 +339,43 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
             const int32_t a = seg_start[r], b = seg_start[r + 1];
             if (b - a <= kLongRun) continue;
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            sum_grads<LPG, kTaskUnroll>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
+            sum_grads<LPG, UNROLL>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
             if (lane_on) {
                 double* p = partial + ((int64_t)ch * 2 + side) * D + c * 4;
                 p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
             }
         }
     }
+}
+
+template <int LPG>
+__global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                                     const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
+                                                     const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
+                                                     double* __restrict__ partial, int D, uint32_t Gm1) {
+    seg_long_body<LPG, kTaskUnroll>((int)blockIdx.x, (int)gridDim.x, key, val, n_unique, seg_start, chunk_run, grad, partial, D, Gm1);
+}
+
+// Both of the above in one launch: the first `long_blocks` workgroups take the chunks of long runs, the others the
+// rows.  The two parts touch disjoint rows and share nothing; together the shorter one's chain of dependent memory
+// round trips is hidden behind the other (a whole launch's worth of time for small batches).
+// ULONG: gradient rows in flight in the long-run part.  More of them shorten its chains but cost registers, hence
+// occupancy, for the whole launch: wide for small batches (a few waves per compute unit anyway), narrow for large.
+template <int DTYPE, int OPT, int LPG, int ULONG>
+__global__ __launch_bounds__(kBlock) void k_seg_rows_long(int long_blocks, const uint32_t* __restrict__ key,
+                                                          const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
+                                                          const int32_t* __restrict__ seg_start,
+                                                          const int32_t* __restrict__ unique_gid,
+                                                          const int32_t* __restrict__ unique_slot,
+                                                          const uint32_t* __restrict__ first_bag,
+                                                          const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
+                                                          double* __restrict__ partial, UpdateArgs A) {
+    if ((int)blockIdx.x < long_blocks)
+        seg_long_body<LPG, ULONG>((int)blockIdx.x, long_blocks, key, val, n_unique, seg_start, chunk_run, grad, partial, A.D,
+                                        A.Gm1);
+    else
+        seg_rows_body<DTYPE, OPT, LPG>((int)blockIdx.x - long_blocks, (int)gridDim.x - long_blocks, val, n_unique, seg_start,
+                                       unique_gid, unique_slot, first_bag, grad, A);
 }
 
 // Second half, in a launch of its own so that the partial sums need no fences or atomics: the group of the
@@ -396,6 +438,23 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     const int gpb = kBlock / LPG;
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), 256 * 32));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
+    if (s2 == s && L <= h->fused_long_max_L) {
+        {
+            Timed t(h, s, "seg_rows_long");
+            if (L <= kFusedWideMaxL)
+                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kTaskUnroll>), dim3(chunk_blocks + rows_blocks), dim3(kBlock),
+                                   0, s, chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
+                                   ws.chunk_run, grad, ws.partial, A);
+            else
+                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kGradUnroll>), dim3(chunk_blocks + rows_blocks), dim3(kBlock),
+                                   0, s, chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
+                                   ws.chunk_run, grad, ws.partial, A);
+        }
+        Timed t(h, s, "seg_combine");
+        hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
+                           unique_gid, ws.unique_slot, ws.chunk_run, ws.partial, A);
+        return;
+    }
     {
         Timed t(h, s2, "seg_long");
         hipLaunchKernelGGL((k_seg_long<LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s2, key, val, nu, seg_start, ws.chunk_run,

@@ -146,6 +146,7 @@ int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
     switch (which) {
         case SCARS_TUNE_FUSED_SCAN_MAX_TILES: h->fused_scan_max_tiles = (int)std::min<int64_t>(value, 4096); break;
         case SCARS_TUNE_PRESORT: h->presort_min_L = value; break;
+        case SCARS_TUNE_FUSED_LONG_MAX_L: h->fused_long_max_L = value; break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
     return SCARS_OK;

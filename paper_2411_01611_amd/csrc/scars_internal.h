@@ -109,6 +109,7 @@ struct scars_handle {
     // launch tuning (scars_set_tuning)
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
     int fused_scan_max_tiles = 1024;     // compaction: up to this many tiles the writer sums the tile counts itself
+    int64_t fused_long_max_L = ((int64_t)1 << 31) - 1;   // backward: up to this many lookups long runs and rows share one launch
     // per-kernel timing
     bool profile = false;
     scars::KernelTimer timer;

@@ -46,7 +46,8 @@ def _run_all(c, profile_with_batch=True):
 
 @pytest.mark.parametrize("D,dtype,opt", [(32, "f32", "sgd"), (32, "f32", "adagrad"), (24, "f32", "adagrad"),
                                          (256, "f32", "sgd"), (512, "bf16", "sgd"), (64, "bf16", "adagrad")])
-def test_long_segments(D, dtype, opt):
+@pytest.mark.parametrize("one_launch", [True, False])
+def test_long_segments(D, dtype, opt, one_launch):
     """Rows looked up thousands of times: runs far above the 64-lookup task size, spanning several sort tiles,
     for lane groups narrower than, equal to and wider than a wave, and a row width that is not a power of two."""
     rng = np.random.default_rng(3)
@@ -59,8 +60,10 @@ def test_long_segments(D, dtype, opt):
     idx1[195:259] = 502                                                      # 64 lookups: the longest short run
     idx = np.concatenate([idx0, idx1]).astype(np.int32)
     off = np.arange(2 * B + 1, dtype=np.int32)
-    _say("D", D, dtype, opt)
+    _say("D", D, dtype, opt, "one launch" if one_launch else "two launches")
     c = _custom_case(rows, D, idx, off, B, budget_rows=100, optimizer=opt, dtype=dtype)
+    if not one_launch:      # long runs and the other rows in launches of their own, as large batches do
+        c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
     rm, out, bo, grad = _run_all(c)
     assert c.s.sync_status() == 0
     wl = c.wl
@@ -326,6 +329,8 @@ def test_random_shapes_match_oracle(seed):
     k = int(rng.choice([0, 1, N // 3, N]))
     _say("seed", seed, "T", T, "rows", rows, "D", D, dtype, opt, "B", B, "L", idx.size, "k", k)
     c = _custom_case(rows, D, idx, off, B, budget_rows=k, optimizer=opt, dtype=dtype)
+    if seed % 3 == 0:
+        c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
     rm, out, bo, grad = _run_all(c)
     assert c.s.sync_status() == 0
     wl = c.wl

@@ -37,7 +37,9 @@ def _say(*a):
 # "/scan": the same case with the separate scan kernels of the compactions forced (by default so few tiles add up
 # their counts in the writing kernels)
 # "/presort": remap starts the backward pass's sort on the library's side stream
-VARIANTS = list(CASES) + ["tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan",
+# "/apart": long runs and the other rows updated by two launches (by default small batches share one)
+VARIANTS = list(CASES) + ["tiny/apart", "multi_hot_small/apart", "dlrm_small/apart", "low_skew_bf16/apart",
+                          "tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan",
                           "tiny/presort", "multi_hot_small/presort", "host_spill_small/presort", "low_skew_bf16/presort",
                           "dlrm_small/presort"]
 
@@ -51,6 +53,8 @@ def case(request):
         c.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
     if variant == "presort":
         c.s.set_tuning(binding.TUNE_PRESORT, 1)
+    if variant == "apart":
+        c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
     yield c
     c.close()
 
