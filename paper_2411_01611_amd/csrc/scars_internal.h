@@ -15,7 +15,7 @@ constexpr int kBlock = 256;          // threads per workgroup everywhere: 4 wave
 constexpr int kWave = 64;
 constexpr int kScanTile = 2048;      // items per workgroup in the ordered-compaction kernels
 constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1024 for inputs under 2^21 pairs,
-constexpr int kSortRoundsLarge = 8;   // 2048 above
+constexpr int kSortRoundsLarge = 16;   // 4096 above
 constexpr int kSortMaxBins = 512;     // up to 9 bits per pass
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
 constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
