@@ -73,6 +73,15 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
     const int64_t tile0 = (int64_t)blockIdx.x * kTile;
     const int tile_n = (int)min((int64_t)kTile, n - tile0);
 
+    // the tile's pairs are requested first, so that their round trip overlaps the one of the digit offsets below
+    uint32_t key[ROUNDS], val[ROUNDS], loc[ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+        const int p = w * kPerWave + r * kWave + lane;          // position inside the tile
+        const bool valid = p < tile_n;
+        key[r] = valid ? kin[tile0 + p] : 0xFFFFFFFFu;
+        val[r] = valid ? vin[tile0 + p] : 0u;
+    }
     for (int i = tid; i < kWaves * kMaxBins; i += kBlock) s_wh[i] = 0;
     {   // global base of every digit = scan of the digit totals, plus this tile's offset inside the digit
         uint32_t carry = 0;
@@ -87,15 +96,7 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
     }
     __syncthreads();
 
-    uint32_t key[ROUNDS], val[ROUNDS], loc[ROUNDS];
     volatile uint32_t* wh = s_wh + w * kMaxBins;
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-        const int p = w * kPerWave + r * kWave + lane;          // position inside the tile
-        const bool valid = p < tile_n;
-        key[r] = valid ? kin[tile0 + p] : 0xFFFFFFFFu;
-        val[r] = valid ? vin[tile0 + p] : 0u;
-    }
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
         const int p = w * kPerWave + r * kWave + lane;
