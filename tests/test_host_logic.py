@@ -108,3 +108,14 @@ def test_tuning_counters_and_planning_calls_check_their_arguments():
     assert L.scars_plan_cache(s._h, C.byref(pin), C.byref(po), None) == binding.ERR_WORKSPACE
     assert L.scars_epoch_cost(s._h, C.byref(pin), 0, C.byref(cost), C.byref(b), None) == binding.ERR_WORKSPACE
     assert L.scars_plan_cache(None, C.byref(pin), C.byref(po), None) == binding.ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 (or a multi-rank launch) exits with a message instead of running."""
+    import subprocess
+    import sys
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "2"})):
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *argv], capture_output=True, text=True,
+                           env={**os.environ, **env}, timeout=300)
+        assert r.returncode == 2
+        assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
