@@ -265,6 +265,54 @@ def test_rebuild_after_updates_keeps_updated_rows():
     c.close()
 
 
+def test_binding_new_buffers_starts_over_on_the_same_handle():
+    """scars_bind_buffers on a handle that has already run steps: the old cache is gone (the caller flushed it), a
+    per-batch call before the next build_cache is refused, and with another budget and a larger max_L the path matches
+    the oracle again on the rows the first steps left in host memory."""
+    wl = synth.workload("multi_hot", scale=0.004, batch=200)
+    c = GpuCase(wl)
+    c.build()
+    s = c.s
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps)
+
+    def step(e):
+        idx, off = c.sampler.batch(e)
+        grad = c.sampler.grads(e)
+        d_idx, d_off = idx.to(c.dev), off.to(c.dev)
+        rm = s.remap(d_idx, d_off, wl.batch)
+        out = s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+        rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+        assert rc == 0
+        assert_close(out.cpu().numpy(), want, f"forward of step {e}")
+        s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), float(lr), float(eps))
+        (rc,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1, idx.numpy(), off.numpy(), wl.batch,
+                                                grad.numpy(), lr, eps)
+        assert rc == 0
+
+    step(0)
+    s.flush_cache()
+    assert s.sync_status() == 0
+    torch.cuda.synchronize()
+    old = s.bufs                                              # keep the old buffers alive until the new ones are bound
+    c.budget = wl.budget_bytes * 3
+    s.bind_buffers(c.budget, 2 * s.max_L, wl.num_bags)
+    del old
+    assert s.cache_rows() == -1
+    idx, off = c.batch
+    with pytest.raises(binding.ScarsError):
+        s.remap(idx.to(c.dev), off.to(c.dev), wl.batch)       # nothing selected yet under the new buffers
+    counts, hot, slot_of = c.build()
+    assert np.array_equal(s.hot_gid().cpu().numpy(), hot)
+    assert np.array_equal(s.slot_of().cpu().numpy(), slot_of)
+    step(1)
+    step(2)
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after binding new buffers")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after binding new buffers")
+    c.close()
+
+
 def test_backward_never_reads_stale_staged_rows():
     """The backward pass may take cold rows from the staging area filled by the forward pass of the same batch,
     but not after the arrays were reused for another batch, nor after the rows were already updated once."""
