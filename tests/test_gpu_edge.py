@@ -313,6 +313,56 @@ def test_binding_new_buffers_starts_over_on_the_same_handle():
     c.close()
 
 
+def test_two_handles_on_two_streams_do_not_disturb_each_other():
+    """Two handles (different tables, row widths and optimizers), each driven on a stream of its own with the
+    other's calls issued in between, one of them with its side streams on: each matches the oracle as if alone."""
+    wls = [synth.workload("multi_hot", scale=0.004, batch=333), synth.workload("dlrm_onehot", scale=0.004, batch=1500)]
+    cs = [GpuCase(w, max_L=2 * 333 * 8 * 20 if i == 0 else 0) for i, w in enumerate(wls)]
+    cs[0].s.set_tuning(binding.TUNE_PRESORT, 1)
+    for c in cs:
+        c.build()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    outs = [[], []]
+    for e in range(3):
+        staged = []
+        for i, c in enumerate(cs):                      # remap + forward of both, then the backward passes of both
+            wl = c.wl
+            idx, off = c.sampler.batch(e)
+            grad = c.sampler.grads(e)
+            with torch.cuda.stream(streams[i]):
+                d_idx, d_off, d_grad = idx.to(c.dev), off.to(c.dev), grad.to(c.dev)
+                rm = c.s.remap(d_idx, d_off, wl.batch)
+                out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm).clone()
+            staged.append((idx, off, grad, d_idx, d_off, d_grad, rm, out))
+        for i, c in enumerate(cs):
+            wl = c.wl
+            idx, off, grad, d_idx, d_off, d_grad, rm, out = staged[i]
+            with torch.cuda.stream(streams[i]):
+                c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, d_grad, float(wl.lr), float(wl.eps))
+            rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, idx.numpy(), off.numpy(), wl.batch)
+            assert rc == 0
+            outs[i].append((out, want))
+            (rc,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, 1 if wl.optimizer == "adagrad" else 0,
+                                                    idx.numpy(), off.numpy(), wl.batch, grad.numpy(), np.float32(wl.lr),
+                                                    np.float32(wl.eps))
+            assert rc == 0
+        for st in streams:
+            st.synchronize()                            # the batch tensors above are released only now
+    for i, c in enumerate(cs):
+        with torch.cuda.stream(streams[i]):
+            c.s.flush_cache()
+            assert c.s.sync_status() == 0
+        for e, (out, want) in enumerate(outs[i]):
+            assert_close(out.cpu().numpy(), want, f"handle {i} forward of step {e}")
+    assert cs[0].s.get_counter(binding.COUNTER_PREPARED_USED) == 3
+    assert_close(cs[0].pinned_rows(), np.concatenate(cs[0].ora_tables), "fp32 rows of the first handle")
+    assert_close(cs[0].pinned_state_rows(), np.concatenate(cs[0].ora_state), "accumulators of the first handle")
+    assert_close(cs[1].pinned_rows(), np.concatenate(cs[1].ora_tables), "rows of the second handle")
+    for c in cs:
+        c.close()
+
+
 def test_backward_never_reads_stale_staged_rows():
     """The backward pass may take cold rows from the staging area filled by the forward pass of the same batch,
     but not after the arrays were reused for another batch, nor after the rows were already updated once."""
