@@ -119,3 +119,47 @@ def test_bench_refuses_more_than_one_gpu():
                            env={**os.environ, **env}, timeout=300)
         assert r.returncode == 2
         assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+C_PROGRAM = r"""
+#include <stdio.h>
+#include "scars.h"
+
+int main(void) {
+    int64_t rows[2] = {1000, 50};
+    static char t0[16], t1[16];
+    void* tables[2] = {t0, t1};
+    scars_config cfg;
+    scars_handle* h = NULL;
+    scars_sizes sz;
+    cfg.num_tables = 2; cfg.rows = rows; cfg.dim = 32; cfg.dtype = SCARS_DTYPE_F32;
+    cfg.host_tables = tables; cfg.optimizer = SCARS_OPT_SGD; cfg.host_state = NULL;
+    if (scars_create(&cfg, &h) != SCARS_OK) return 1;
+    if (scars_query_sizes(h, 100 * 128, 4096, 512, &sz) != SCARS_OK) return 2;
+    printf("%lld %lld %lld\n", (long long)sz.k, (long long)sz.cache_bytes, (long long)sz.out_bytes);
+    if (scars_cache_rows(h) != -1) return 3;
+    cfg.dim = 3;                                    /* 12-byte rows: refused */
+    { scars_handle* bad = NULL; if (scars_create(&cfg, &bad) != SCARS_ERR_INVALID_ARG || bad) return 4; }
+    return scars_destroy(h) == SCARS_OK ? 0 : 5;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """include/scars.h compiles as strict C99 with no other include, and a C caller with no Python or torch in the
+    process can create a handle, query sizes and destroy it."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no gcc")
+    src = tmp_path / "caller.c"
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-lscars", "-Wl,-rpath," + libdir,
+                           "-Wl,--allow-shlib-undefined"])
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    k, cache_bytes, out_bytes = (int(x) for x in r.stdout.split())
+    assert k == 100 and cache_bytes >= 100 * 128 and out_bytes >= 512 * 32 * 4
