@@ -190,6 +190,49 @@ __global__ __launch_bounds__(kBlock) void k_pool_short(const int32_t* __restrict
     }
 }
 
+// The bags k_pool_short leaves out under filter 1 (they need a staged row, or hold several lookups), for batches in
+// which such bags are few: one lane per bag reads its offsets and first location, the wave ballots the bags to do
+// and its 64/LPR lane groups take them 64/LPR at a time.  A launch with a lane group per bag would spend its time
+// on the bags it skips.  Same sums as k_pool_short: positions added in order, starting from zero.
+template <int DTYPE, int LPR>
+__global__ __launch_bounds__(kBlock) void k_pool_short_rest(const int32_t* __restrict__ off, int64_t G, int32_t L,
+                                                            const int32_t* __restrict__ loc, const uint4* __restrict__ cache,
+                                                            const uint4* __restrict__ staging, int32_t k, int chunks, int D,
+                                                            float* __restrict__ out) {
+    constexpr int NG = kWave / LPR;
+    const int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    int32_t a = 0, b = 0;
+    if (g < G) {
+        a = min(max(off[g], 0), L);
+        b = min(max(off[g + 1], a), L);
+    }
+    const int32_t l0 = b > a ? loc[a] : -1;
+    const bool take = g < G && !(b - a <= 1 && l0 < k);          // the complement of filter 1
+    uint64_t m = ballot64(take);                                  // the same in every lane
+    const int q = lane_id() / LPR, c = lane_id() % LPR;
+    const bool lane_on = c < chunks;
+    const int64_t g0 = g - lane_id();                             // the wave's first bag
+    while (m) {
+        int src = -1;                                             // the lane that owns this group's bag of the round
+#pragma unroll
+        for (int j = 0; j < NG; ++j) {
+            if (m) {
+                const int l = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                if (q == j) src = l;
+            }
+        }
+        const int sl = max(src, 0);
+        const int32_t aa = __shfl(a, sl, kWave), bb = __shfl(b, sl, kWave);
+        if (src >= 0) {
+            Chunk<DTYPE> acc;
+            acc.zero();
+            pool_range<DTYPE, LPR, kShortTailUnroll>(acc, aa, bb, loc, cache, staging, k, chunks, c, lane_on);
+            if (lane_on) store_chunk<DTYPE>(acc, out, g0 + src, D, c);
+        }
+    }
+}
+
 // one wave per bag; its 64/LPR groups take every (64/LPR)-th lookup and combine by a shuffle tree
 template <int DTYPE, int LPR>
 __global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict__ off, int64_t G, int32_t L,
@@ -239,7 +282,10 @@ __global__ __launch_bounds__(kBlock) void k_pool_wave(const int32_t* __restrict_
 template <int DTYPE, int LPR>
 static void launch_pool_t(hipStream_t s, int mode, const int32_t* off, int64_t G, int64_t L, const int32_t* loc,
                           const void* cache, const void* staging, int64_t k, int chunks, int D, float* out, int filter) {
-    if (mode == 2) {
+    if (mode == 2 && filter == 2) {
+        hipLaunchKernelGGL((k_pool_short_rest<DTYPE, LPR>), dim3((unsigned)div_up(G, kBlock)), dim3(kBlock), 0, s, off, G,
+                           (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out);
+    } else if (mode == 2) {
         const int64_t TG = div_up(G, kShortBags);
         hipLaunchKernelGGL((k_pool_short<DTYPE, LPR>), dim3((unsigned)div_up(TG * LPR, kBlock)), dim3(kBlock), 0, s, off,
                            G, (int32_t)L, loc, (const uint4*)cache, (const uint4*)staging, (int32_t)k, chunks, D, out, filter);
