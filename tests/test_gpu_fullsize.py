@@ -235,3 +235,10 @@ def test_full_size_low_skew_bf16_matches_oracle():
 def test_full_size_dlrm_onehot_matches_oracle():
     """26 fp32 tables of 10 to 10M rows x dim 64, batch 2048, one index per table and sample, Zipf 1.1, 5 % cached."""
     _full_size_sgd_step(synth.workload("dlrm_onehot"), 8)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_low_skew_uniform_bf16_matches_oracle():
+    """The uniform variant of the same configuration: hardly any repeated row, so the cache catches only its own
+    share of the lookups (10 %) and nearly every sorted run has one lookup."""
+    assert _full_size_sgd_step(synth.workload("low_skew_uniform"), 4) > (1 << 21)
