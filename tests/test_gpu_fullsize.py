@@ -297,6 +297,12 @@ def test_row_ids_above_2_to_27_take_a_fourth_sort_pass(rows):
     slot_of = np.full(N, -1, dtype=np.int32)
     slot_of[hot] = np.arange(k, dtype=np.int32)
     assert np.array_equal(sc.slot_of().cpu().numpy(), slot_of)
+    # the cost model reads the whole skew table: eq. (6) with nothing cached, against the same sum over the touched rows
+    M, a, Q = 4000.0, 40.0, 1.0e6
+    cost, b = sc.epoch_cost(M, a, Q, B, 0)
+    pe = np.minimum(1.0, c / B)
+    assert b == M / a
+    np.testing.assert_allclose(cost, 2 * Q + (Q / b) * D * np.sum(1.0 - (1.0 - pe) ** b), rtol=1e-9)
     _say("hot set ok; step")
     ora_tabs = [p.np for p in tabs]
     g = torch.Generator().manual_seed(11)
