@@ -90,6 +90,11 @@ typedef struct {
  * shorter one's chain of dependent memory round trips.  Not used while SCARS_TUNE_PRESORT runs the long runs on the
  * side stream.  0 = never (two launches). */
 #define SCARS_TUNE_FUSED_LONG_MAX_L 3           /* default 2^31 - 1: every batch */
+/* Non-zero: scars_remap also writes the (row, bag) pairs that the backward pass of the same batch sorts, in the
+ * launch that lists hits and misses (8 more bytes written per lookup; a backward pass called with the same remap
+ * outputs, offsets, L and B then starts at its sort).  0: the backward pass builds them itself, as it does anyway
+ * when unique_miss_gid is set or another batch was remapped in between. */
+#define SCARS_TUNE_PAIRS_IN_REMAP 4             /* default 1 */
 
 /* Host-side counters (never reset); -1 for an unknown counter. */
 #define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */

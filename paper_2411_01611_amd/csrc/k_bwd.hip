@@ -12,20 +12,11 @@
 namespace scars {
 
 // ---- (1) pairs ----------------------------------------------------------------------------------------
-// key = gid of the lookup, value = its bag.  A group of LPB lanes walks one bag's positions, so the bag id
-// needs no search; -1 (invalid lookup) becomes the largest key and sorts last.
+// (bag_pairs in scars_dev.h; scars_remap may already have written them in the launch that lists hits and misses)
 __global__ __launch_bounds__(kBlock) void k_bwd_pairs(const int32_t* __restrict__ gid, const int32_t* __restrict__ off,
                                                       int32_t L, int64_t G, int lpb, uint32_t* __restrict__ key,
                                                       uint32_t* __restrict__ val) {
-    const int64_t g = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / lpb;
-    const int c = threadIdx.x % lpb;
-    if (g >= G) return;
-    const int32_t a = min(max(off[g], 0), L);
-    const int32_t b = min(max(off[g + 1], a), L);
-    for (int32_t i = a + c; i < b; i += lpb) {
-        key[i] = (uint32_t)gid[i];
-        val[i] = (uint32_t)g;
-    }
+    bag_pairs((int64_t)blockIdx.x, gid, off, L, G, lpb, key, val);
 }
 
 __global__ void k_bwd_empty(int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start) {
@@ -494,9 +485,12 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
     int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
     const int64_t G = (int64_t)h->T * B;
-    {
+    // the remap of this batch may have left the pairs in the first sort buffer; the sort below uses them up
+    const bool have_pairs = h->pairs_valid && h->pairs_gid == rm->gid && h->pairs_off == off && h->pairs_L == L && h->pairs_B == B;
+    h->pairs_valid = false;
+    if (!have_pairs) {
         Timed t(h, s, "bwd_pairs");
-        const int lpb = std::min(64, next_pow2_host((int)std::max<int64_t>(1, L / std::max<int64_t>(G, 1))));
+        const int lpb = pairs_lanes_per_bag(L, G);
         hipLaunchKernelGGL(k_bwd_pairs, dim3((unsigned)div_up(G * lpb, kBlock)), dim3(kBlock), 0, s, rm->gid, off,
                            (int32_t)L, G, lpb, ws.key_buf[0], ws.val_buf[0]);
     }

@@ -99,14 +99,15 @@ __global__ __launch_bounds__(kBlock) void k_remap_scan(uint32_t* __restrict__ a,
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t* __restrict__ slot,
-                                                        const int32_t* __restrict__ gid, const uint32_t* __restrict__ blk_hit,
-                                                        const uint32_t* __restrict__ blk_miss, int scanned,
-                                                        int32_t* __restrict__ n_hit_miss, int32_t k,
-                                                        int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
-                                                        int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid) {
+// tile `tile` of `ntiles`
+__device__ __forceinline__ void remap_write_body(int tile, int ntiles, int64_t L, const int32_t* __restrict__ slot,
+                                                 const int32_t* __restrict__ gid, const uint32_t* __restrict__ blk_hit,
+                                                 const uint32_t* __restrict__ blk_miss, int scanned,
+                                                 int32_t* __restrict__ n_hit_miss, int32_t k, int32_t* __restrict__ loc,
+                                                 int32_t* __restrict__ hit_pos, int32_t* __restrict__ miss_pos,
+                                                 int32_t* __restrict__ miss_gid) {
     __shared__ uint32_t s_hit[4], s_miss[4], s_red[8];
-    const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWave;
+    const int64_t base = (int64_t)tile * kScanTile + wave_id() * kPerWave;
     int32_t s[kRoundsR], g[kRoundsR];
     uint32_t nh = 0, nm = 0;
 #pragma unroll
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t
     if (lane_id() == 0) { s_hit[wave_id()] = nh; s_miss[wave_id()] = nm; }
     __syncthreads();
     uint32_t hb, mb, th, tm;
-    tile_prefix2(blk_hit, blk_miss, blockIdx.x, gridDim.x, scanned != 0, s_red, n_hit_miss, &hb, &mb, &th, &tm);
+    tile_prefix2(blk_hit, blk_miss, tile, ntiles, scanned != 0, s_red, n_hit_miss, &hb, &mb, &th, &tm);
     for (int w = 0; w < wave_id(); ++w) { hb += s_hit[w]; mb += s_miss[w]; }
 #pragma unroll
     for (int r = 0; r < kRoundsR; ++r) {
@@ -141,6 +142,34 @@ __global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t
         hb += (uint32_t)__popcll(mh);
         mb += (uint32_t)__popcll(mm);
     }
+}
+
+__global__ __launch_bounds__(kBlock) void k_remap_write(int64_t L, const int32_t* __restrict__ slot,
+                                                        const int32_t* __restrict__ gid, const uint32_t* __restrict__ blk_hit,
+                                                        const uint32_t* __restrict__ blk_miss, int scanned,
+                                                        int32_t* __restrict__ n_hit_miss, int32_t k,
+                                                        int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
+                                                        int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid) {
+    remap_write_body((int)blockIdx.x, (int)gridDim.x, L, slot, gid, blk_hit, blk_miss, scanned, n_hit_miss, k, loc, hit_pos,
+                     miss_pos, miss_gid);
+}
+
+// The same, and in the other workgroups of the launch the (gid, bag) pairs the backward pass of this batch will sort:
+// both read what k_remap_probe wrote and nothing of each other, so the pairs cost no launch of their own.
+__global__ __launch_bounds__(kBlock) void k_remap_write_pairs(int ntiles, int64_t L, const int32_t* __restrict__ slot,
+                                                              const int32_t* __restrict__ gid,
+                                                              const uint32_t* __restrict__ blk_hit,
+                                                              const uint32_t* __restrict__ blk_miss, int scanned,
+                                                              int32_t* __restrict__ n_hit_miss, int32_t k,
+                                                              int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
+                                                              int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid,
+                                                              const int32_t* __restrict__ off, int64_t G, int lpb,
+                                                              uint32_t* __restrict__ key, uint32_t* __restrict__ val) {
+    if ((int)blockIdx.x < ntiles)
+        remap_write_body((int)blockIdx.x, ntiles, L, slot, gid, blk_hit, blk_miss, scanned, n_hit_miss, k, loc, hit_pos,
+                         miss_pos, miss_gid);
+    else
+        bag_pairs((int64_t)blockIdx.x - ntiles, gid, off, (int32_t)L, G, lpb, key, val);
 }
 
 __global__ void k_um_empty(int32_t* __restrict__ n_unique_miss) {
@@ -234,7 +263,20 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         Timed t(h, s, "remap_scan");
         hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hit_miss);
     }
-    {
+    // the pairs go into the first sort buffer, which listing each distinct missed row once (below) sorts in as well
+    const bool pairs = h->pairs_in_remap && L > 0 && !out->unique_miss_gid;
+    h->pairs_valid = false;
+    if (pairs) {
+        Timed t(h, s, "remap_write");
+        const int64_t G = (int64_t)h->T * B;
+        const int lpb = pairs_lanes_per_bag(L, G);
+        const int64_t pair_blocks = div_up(G * lpb, kBlock);
+        hipLaunchKernelGGL(k_remap_write_pairs, dim3((unsigned)(nb + pair_blocks)), dim3(kBlock), 0, s, nb, L, out->slot,
+                           out->gid, ws.blk_hit, ws.blk_miss, scan ? 1 : 0, out->n_hit_miss, (int32_t)h->k, out->loc,
+                           out->hit_pos, out->miss_pos, out->miss_gid, off, G, lpb, ws.key_buf[0], ws.val_buf[0]);
+        h->pairs_valid = true;
+        h->pairs_gid = out->gid; h->pairs_off = off; h->pairs_L = L; h->pairs_B = B;
+    } else {
         Timed t(h, s, "remap_write");
         hipLaunchKernelGGL(k_remap_write, dim3(nb), dim3(kBlock), 0, s, L, out->slot, out->gid, ws.blk_hit, ws.blk_miss,
                            scan ? 1 : 0, out->n_hit_miss, (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos,

@@ -147,6 +147,7 @@ int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
         case SCARS_TUNE_FUSED_SCAN_MAX_TILES: h->fused_scan_max_tiles = (int)std::min<int64_t>(value, 4096); break;
         case SCARS_TUNE_PRESORT: h->presort_min_L = value; break;
         case SCARS_TUNE_FUSED_LONG_MAX_L: h->fused_long_max_L = value; break;
+        case SCARS_TUNE_PAIRS_IN_REMAP: h->pairs_in_remap = value != 0; break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
     return SCARS_OK;
@@ -208,6 +209,7 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     if (h->side) (void)hipStreamSynchronize(h->side);   // nothing may still be using the buffers bound before
     h->side_pending = false;
     h->presort_valid = false;
+    h->pairs_valid = false;
     h->buf = *b;
     h->k_cap = k;
     h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);

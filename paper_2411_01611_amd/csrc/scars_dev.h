@@ -110,6 +110,23 @@ __device__ __forceinline__ int upper_table(const int32_t* a, int T, int32_t x) {
     return lo;
 }
 
+// (gid, bag) pairs of a batch in position order: key = gid of the lookup (-1, an invalid lookup, becomes the largest
+// key), value = its bag.  A group of lpb lanes walks one bag's positions, so the bag id needs no search.  `block` of
+// the workgroups that share this job.
+__device__ __forceinline__ void bag_pairs(int64_t block, const int32_t* __restrict__ gid, const int32_t* __restrict__ off,
+                                          int32_t L, int64_t G, int lpb, uint32_t* __restrict__ key,
+                                          uint32_t* __restrict__ val) {
+    const int64_t g = (block * kBlock + threadIdx.x) / lpb;
+    const int c = threadIdx.x % lpb;
+    if (g >= G) return;
+    const int32_t a = min(max(off[g], 0), L);
+    const int32_t b = min(max(off[g + 1], a), L);
+    for (int32_t i = a + c; i < b; i += lpb) {
+        key[i] = (uint32_t)gid[i];
+        val[i] = (uint32_t)g;
+    }
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // fp32 -> bf16, round to nearest even (NaN kept quiet)
@@ -131,5 +148,10 @@ inline int next_pow2_host(int x) {
     int p = 1;
     while (p < x) p <<= 1;
     return p;
+}
+// lanes that walk one bag in bag_pairs: about the mean bag length, a power of two up to a wave
+inline int pairs_lanes_per_bag(int64_t L, int64_t G) {
+    const int64_t mean = L / (G > 1 ? G : 1);
+    return next_pow2_host((int)(mean < 1 ? 1 : (mean > 64 ? 64 : mean)));
 }
 }  // namespace scars

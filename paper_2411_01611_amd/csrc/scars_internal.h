@@ -105,9 +105,15 @@ struct scars_handle {
     int64_t presort_L = 0, presort_B = 0;
     bool presort_staged = false;
     int presort_res = 0;
+    // (gid, bag) pairs of the batch described below are in the first sort buffer (written by scars_remap)
+    bool pairs_valid = false;
+    const int32_t* pairs_gid = nullptr;
+    const int32_t* pairs_off = nullptr;
+    int64_t pairs_L = 0, pairs_B = 0;
     int64_t n_prepared_used = 0;         // bwd_update calls that used segments prepared on the side stream
     // launch tuning (scars_set_tuning)
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
+    bool pairs_in_remap = true;          // scars_remap also writes the backward pass's (gid, bag) pairs
     int fused_scan_max_tiles = 1024;     // compaction: up to this many tiles the writer sums the tile counts itself
     int64_t fused_long_max_L = ((int64_t)1 << 31) - 1;   // backward: up to this many lookups long runs and rows share one launch
     // per-kernel timing

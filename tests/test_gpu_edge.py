@@ -429,6 +429,8 @@ def test_random_shapes_match_oracle(seed):
     c = _custom_case(rows, D, idx, off, B, budget_rows=k, optimizer=opt, dtype=dtype)
     if seed % 3 == 0:
         c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
+    if seed % 4 == 1:
+        c.s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 0)
     rm, out, bo, grad = _run_all(c)
     assert c.s.sync_status() == 0
     wl = c.wl

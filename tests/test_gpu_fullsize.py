@@ -242,97 +242,3 @@ def test_full_size_low_skew_uniform_bf16_matches_oracle():
     """The uniform variant of the same configuration: hardly any repeated row, so the cache catches only its own
     share of the lookups (10 %) and nearly every sorted run has one lookup."""
     assert _full_size_sgd_step(synth.workload("low_skew_uniform"), 4) > (1 << 21)
-
-
-@pytest.mark.timeout(900)
-@pytest.mark.parametrize("rows", [(100_000_000, 45_000_000), (1_500_000_000, 647_483_647)])
-def test_row_ids_above_2_to_27_take_a_fourth_sort_pass(rows):
-    """More than 2^27 rows in all, and the most the interface takes, 2^31 - 1 (16-byte rows, so the tables still fit
-    in pinned memory): the backward pass's keys need 28 and 31 bits, that is four radix passes of 7 and 8 bits instead
-    of three of 9, and the histogram, the slot map and the probes index up to 2^31 - 2.  The batch is made by hand:
-    popular rows at the very end of the id space and at its start, the rest anywhere.  The oracle's ranking sorts
-    every row, so here the hot set is the definition applied with numpy to the rows the profile touched (all others
-    count 0, and k is below the number of touched rows).  At the larger size only the rows the batch touches are
-    given values: no other row is ever read."""
-    dev = torch.device("cuda:0")
-    N, D, B, k = sum(rows), 4, 6000, 1000
-    assert N > (1 << 27) and N < (1 << 31)
-    wl = synth.Workload("custom", rows, D, "f32", B, None, 1.0, k * D * 4, "sgd")
-    rng = np.random.default_rng(7)
-    lens = rng.integers(0, 4, 2 * B)
-    off = np.zeros(2 * B + 1, dtype=np.int32)
-    off[1:] = np.cumsum(lens)
-    n0, n1 = int(off[B]), int(off[2 * B] - off[B])
-    i0 = np.where(rng.random(n0) < 0.3, rng.integers(0, 50, n0), rng.integers(0, rows[0], n0))
-    i1 = np.where(rng.random(n1) < 0.3, rows[1] - 1 - rng.integers(0, 50, n1), rng.integers(0, rows[1], n1))
-    idx = np.concatenate([i0, i1]).astype(np.int32)
-    L = idx.size
-    _say("rows", rows, "lookups", L)
-    tabs = []
-    for t in range(2):
-        p = binding.PinnedArray((rows[t], D), np.float32)
-        if N < 200_000_000:
-            chunk = 1 << 23
-            for r0 in range(0, rows[t], chunk):
-                r1 = min(rows[t], r0 + chunk)
-                p.copy_from_device(synth.row_values(wl, t, r0, r1, dev).contiguous(), r0)
-                torch.cuda.synchronize()
-        else:
-            touched = np.unique(i0 if t == 0 else i1)
-            p.np[touched] = rng.uniform(-0.01, 0.01, (touched.size, D)).astype(np.float32)
-        tabs.append(p)
-    _say("tables filled")
-    sc = binding.Scars(rows, D, binding.DTYPE_F32, [p.ptr for p in tabs], binding.OPT_SGD, None)
-    sc.bind_buffers(wl.budget_bytes, L, 2 * B)
-    d_idx, d_off = torch.from_numpy(idx).to(dev), torch.from_numpy(off).to(dev)
-    sc.build_cache(d_idx, d_off, B, wl.budget_bytes, 0)
-    assert sc.sync_status() == 0 and sc.cache_rows() == k
-    gid = idx.astype(np.int64) + np.where(np.arange(L) < n0, 0, rows[0])
-    u, c = np.unique(gid, return_counts=True)
-    assert u.size > k and u.max() == N - 1
-    got_counts = sc.counts().cpu().numpy().view(np.uint32)
-    assert np.array_equal(got_counts[u], c) and int(got_counts.sum(dtype=np.int64)) == L
-    hot = u[np.lexsort((u, -c))][:k].astype(np.int32)                 # count descending, lower id first
-    assert np.array_equal(sc.hot_gid().cpu().numpy(), hot)
-    slot_of = np.full(N, -1, dtype=np.int32)
-    slot_of[hot] = np.arange(k, dtype=np.int32)
-    assert np.array_equal(sc.slot_of().cpu().numpy(), slot_of)
-    # the cost model reads the whole skew table: eq. (6) with nothing cached, against the same sum over the touched rows
-    M, a, Q = 4000.0, 40.0, 1.0e6
-    cost, b = sc.epoch_cost(M, a, Q, B, 0)
-    pe = np.minimum(1.0, c / B)
-    assert b == M / a
-    np.testing.assert_allclose(cost, 2 * Q + (Q / b) * D * np.sum(1.0 - (1.0 - pe) ** b), rtol=1e-9)
-    _say("hot set ok; step")
-    ora_tabs = [p.np for p in tabs]
-    g = torch.Generator().manual_seed(11)
-    grad = torch.randn(2 * B, D, generator=g)
-    rc, slot, hit, miss, mg = oracle.remap(rows, idx, off, B, slot_of)
-    rc2, want = oracle.embedding_bag_fwd(rows, ora_tabs, idx, off, B)
-    rc3, sg, sb, ss, ug = oracle.bwd_segments(rows, idx, off, B)
-    rc4, nr, ns, gr = oracle.embedding_bag_bwd_update(rows, ora_tabs, None, 0, idx, off, B, grad.numpy(), np.float32(0.01),
-                                                      np.float32(0.0), report=True, n_unique=ug.size)
-    assert rc == rc2 == rc3 == rc4 == 0 and ug.max() == N - 1
-    rm = sc.remap(d_idx, d_off, B)
-    out = sc.embedding_bag_fwd(d_idx, d_off, B, rm)
-    bo = sc.new_bwd_out(L)
-    sc.embedding_bag_bwd_update(d_idx, d_off, B, rm, grad.to(dev), 0.01, 0.0, bo)
-    sc.flush_cache()
-    assert sc.sync_status() == 0
-    assert rm.n_hit_miss.cpu().tolist() == [hit.size, miss.size]
-    assert np.array_equal(rm.slot.cpu().numpy()[:L], slot)
-    assert np.array_equal(rm.miss_gid.cpu().numpy()[: miss.size], mg)
-    assert_close(out.cpu().numpy(), want, "pooled output with row ids above 2^27")
-    U, nv = bo.n_unique.cpu().tolist()
-    assert U == ug.size and nv == sg.size
-    assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
-    assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
-    assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
-    assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
-    t_of = (ug >= rows[0]).astype(np.int64)
-    for t in range(2):
-        sel = t_of == t
-        assert_close(tabs[t].np[ug[sel] - t * rows[0]], nr[sel].astype(np.float32), f"updated rows of table {t}")
-    sc.close()
-    for p in tabs:
-        p.free()

@@ -37,7 +37,8 @@ def _say(*a):
 # "/scan": the same case with the separate scan kernels of the compactions forced (by default so few tiles add up
 # their counts in the writing kernels)
 # "/presort": remap starts the backward pass's sort on the library's side stream
-# "/apart": long runs and the other rows updated by two launches (by default small batches share one)
+# "/apart": long runs and the other rows updated by two launches (by default they share one), and the backward
+#           pass's (row, bag) pairs built by the backward pass (by default remap writes them)
 VARIANTS = list(CASES) + ["tiny/apart", "multi_hot_small/apart", "dlrm_small/apart", "low_skew_bf16/apart",
                           "tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan",
                           "tiny/presort", "multi_hot_small/presort", "host_spill_small/presort", "low_skew_bf16/presort",
@@ -55,6 +56,7 @@ def case(request):
         c.s.set_tuning(binding.TUNE_PRESORT, 1)
     if variant == "apart":
         c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
+        c.s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 0)
     yield c
     c.close()
 
