@@ -320,6 +320,8 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
         whole = alg["pool_short"]
         alg["pool_short"] = whole * n_hit / max(1, n_hit + n_miss)
         alg["pool_short_staged"] = whole - alg["pool_short"]
+    if "bwd_pairs" not in prof:
+        alg["remap_write"] += alg["bwd_pairs"]   # the launch that lists hits and misses also wrote the backward pairs
     kern = {}
     for name, r in prof.items():
         avg_ms = r["total_ms"] / r["launches"]
