@@ -313,7 +313,9 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         Timed t(h, s, "um_empty");   // nothing can miss: the list is empty
         hipLaunchKernelGGL(k_um_empty, dim3(1), dim3(kWave), 0, s, out->n_unique_miss);
     }
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) h->pairs_valid = false;
+    return e;
 }
 
 }  // namespace scars
