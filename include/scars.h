@@ -95,6 +95,11 @@ typedef struct {
  * outputs, offsets, L and B then starts at its sort).  0: the backward pass builds them itself, as it does anyway
  * when unique_miss_gid is set or another batch was remapped in between. */
 #define SCARS_TUNE_PAIRS_IN_REMAP 4             /* default 1 */
+/* Most workgroups the per-row update kernel of the backward pass is launched with (it strides over the rows, so any
+ * value gives the same results).  While it writes cold rows it holds its compute units' memory queues full of host
+ * requests, and kernels of other streams that share those units crawl; a few hundred workgroups still saturate the
+ * host link and leave room for them. */
+#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* default and maximum 8192 */
 
 /* Host-side counters (never reset); -1 for an unknown counter. */
 #define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */

@@ -136,7 +136,7 @@ def _stream() -> int:
 
 
 CALIB_SINK_BYTES = 4 << 20
-TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT, TUNE_FUSED_LONG_MAX_L, TUNE_PAIRS_IN_REMAP = 1, 2, 3, 4
+TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT, TUNE_FUSED_LONG_MAX_L, TUNE_PAIRS_IN_REMAP, TUNE_UPDATE_MAX_BLOCKS = 1, 2, 3, 4, 5
 COUNTER_PREPARED_USED = 1
 
 

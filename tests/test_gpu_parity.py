@@ -57,6 +57,7 @@ def case(request):
     if variant == "apart":
         c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
         c.s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 0)
+        c.s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, 7)      # the update kernel strides over the rows
     yield c
     c.close()
 

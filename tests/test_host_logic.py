@@ -98,6 +98,7 @@ def test_tuning_counters_and_planning_calls_check_their_arguments():
     s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 262144)
     s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 0)
     s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 1)
+    s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, 256)
     for which, value in ((99, 1), (binding.TUNE_PRESORT, -1), (binding.TUNE_PRESORT, 2 ** 31)):
         assert L.scars_set_tuning(s._h, which, value) == binding.ERR_INVALID_ARG
     assert L.scars_set_tuning(None, binding.TUNE_PRESORT, 1) == binding.ERR_INVALID_ARG
