@@ -440,6 +440,8 @@ def main():
     ap.add_argument("--fused-long-max-l", type=int, default=-1,
                     help="largest batch (lookups) whose backward pass updates long runs and the other rows in one "
                          "launch (default: the library's, every batch; 0 = never)")
+    ap.add_argument("--update-max-blocks", type=int, default=0,
+                    help="most workgroups of the per-row update kernel (default: the library's, 8192)")
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
@@ -495,6 +497,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
     if args.fused_long_max_l >= 0:
         b.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, args.fused_long_max_l)
+    if args.update_max_blocks > 0:
+        b.s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, args.update_max_blocks)
     b.prepare(K + W)
     bc = b.build_cache()
     log(name, "build_cache", bc)

@@ -99,7 +99,7 @@ typedef struct {
  * value gives the same results).  While it writes cold rows it holds its compute units' memory queues full of host
  * requests, and kernels of other streams that share those units crawl; a few hundred workgroups still saturate the
  * host link and leave room for them. */
-#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* default and maximum 8192 */
+#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 8192; default 0: 8192 with every row cached, else 1024 */
 
 /* Host-side counters (never reset); -1 for an unknown counter. */
 #define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */

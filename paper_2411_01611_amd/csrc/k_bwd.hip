@@ -427,7 +427,10 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
                             const int32_t* seg_start, const int32_t* unique_gid, const float* grad, int64_t L, UpdateArgs A) {
     Workspace& ws = h->ws;
     const int gpb = kBlock / LPG;
-    const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), h->update_max_blocks));
+    // with cold rows to write the kernel is bound by the host link and a thousand workgroups saturate it; more only
+    // take wave slots and memory queues from the kernels of the library's other streams
+    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->k < h->N ? 1024 : 256 * 32);
+    const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), max_blocks));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
         {
