@@ -25,7 +25,7 @@ EXPORTS = (
     "scars_create", "scars_destroy", "scars_set_tuning", "scars_get_counter", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
     "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_partition_batch", "scars_portion_usage", "scars_epoch_cost",
     "scars_caching_gain",
-    "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update",
+    "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update", "scars_embedding_bag_bwd_update_ahead",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
     "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_profile_enable", "scars_profile_read",
 )
@@ -110,6 +110,8 @@ def lib():
         L.scars_embedding_bag_fwd.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, vp]
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
+        L.scars_embedding_bag_bwd_update_ahead.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
+                                                           C.POINTER(_BwdOut), C.POINTER(_RemapOut), i64, vp]
         L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
         L.scars_partition_batch.argtypes = [vp, vp, vp, i64, i64, vp, vp, C.POINTER(_SubbatchOut), vp]
         L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
@@ -137,7 +139,9 @@ def _stream() -> int:
 
 CALIB_SINK_BYTES = 4 << 20
 TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT, TUNE_FUSED_LONG_MAX_L, TUNE_PAIRS_IN_REMAP, TUNE_UPDATE_MAX_BLOCKS = 1, 2, 3, 4, 5
+TUNE_LOOKAHEAD = 6
 COUNTER_PREPARED_USED = 1
+COUNTER_AHEAD_USED = 2
 
 
 def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:
@@ -384,6 +388,21 @@ class Scars:
         self._check(lib().scars_embedding_bag_bwd_update(self._h, self._i32(indices), self._i32(offsets), L, B,
                                                          C.byref(c), grad_out.data_ptr(), lr, eps,
                                                          C.byref(co) if co is not None else None, _stream()))
+        return out
+
+    def embedding_bag_bwd_update_ahead(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,
+                                       grad_out: torch.Tensor, lr: float, eps: float, next_rm: RemapOut, next_L: int,
+                                       out: Optional[BwdOut] = None) -> Optional[BwdOut]:
+        """The update of this batch, with the next batch's missed rows fetched beside it (TUNE_LOOKAHEAD must be on)."""
+        L = int(indices.numel())
+        assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
+        assert grad_out.numel() == self.T * B * self.D
+        c, cn = rm.c(), next_rm.c()
+        co = out.c() if out is not None else None
+        self._check(lib().scars_embedding_bag_bwd_update_ahead(self._h, self._i32(indices), self._i32(offsets), L, B,
+                                                               C.byref(c), grad_out.data_ptr(), lr, eps,
+                                                               C.byref(co) if co is not None else None, C.byref(cn),
+                                                               next_L, _stream()))
         return out
 
     def classify_samples(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,

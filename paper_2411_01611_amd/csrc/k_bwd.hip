@@ -429,7 +429,8 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     const int gpb = kBlock / LPG;
     // with cold rows to write the kernel is bound by the host link and a thousand workgroups saturate it; more only
     // take wave slots and memory queues from the kernels of the library's other streams
-    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->k < h->N ? 1024 : 256 * 32);
+    // (while rows are fetched ahead beside it, few enough that the fetch and the next remap get their share of every unit)
+    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? 256 : (h->k < h->N ? 1024 : 256 * 32));
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), max_blocks));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
@@ -526,11 +527,14 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
 }
 
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
-                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out) {
+                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out,
+                      const scars_remap_out* next_rm, int64_t next_L) {
     Workspace& ws = h->ws;
-    // rows fetched by this batch's forward pass are still in the staging area: cold rows are read from there
-    const bool use_staged = h->staged_valid && h->staged_loc == rm->loc;
-    h->staged_valid = false;   // this call changes the rows
+    // rows fetched by this batch's forward pass are still in a staging area: cold rows are read from there
+    const int area = h->staged_area(rm->loc);
+    const bool use_staged = area >= 0;
+    h->stg[0].valid = h->stg[1].valid = false;   // this call changes the rows
+    h->ahead.valid = false;                      // ... also rows fetched ahead beside an earlier update
     int32_t* n_unique = out ? out->n_unique : ws.n_unique;
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
     int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
@@ -555,8 +559,17 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const uint32_t* key = ws.key_buf[res];
     const uint32_t* val = ws.val_buf[res];
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
-                 use_staged ? ws.staging : nullptr, (int32_t)h->k, (uint32_t)h->N,
+                 use_staged ? ws.staging[area] : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};
+    // the next batch's missed rows, except those this update writes, are fetched while it runs (its own stream and
+    // staging area); the list of this batch's distinct rows is complete at this point of stream s
+    h->ahead_active = false;
+    if (next_rm && next_L > 0 && h->k < h->N) {
+        hipError_t e = pf_join(h, s);
+        if (e == hipSuccess) e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0);
+        if (e != hipSuccess) return e;
+        h->ahead_active = true;
+    }
     const int lpg = next_pow2_host(h->D / 4);
     // long runs (HBM-bound) beside the per-row kernel (bound by the host link while rows are cold)
     hipStream_t s2 = s;

@@ -17,10 +17,12 @@ constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
+// `fetched` (may be null): rows flagged there are already in the staging area (fetched ahead) and are skipped.
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
                                                          const int32_t* __restrict__ d_count,
                                                          const Meta* __restrict__ meta, u32x4* __restrict__ staging,
-                                                         int chunks, int lpr, int64_t cap_rows) {
+                                                         int chunks, int lpr, int64_t cap_rows,
+                                                         const uint8_t* __restrict__ fetched) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = meta->num_tables;
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
@@ -35,17 +37,74 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restri
         // row numbers are clamped instead of guarded so that the gid loads, then the row loads over the link,
         // are all issued back to back; only rows below n are written
         int32_t gid[kUnroll];
+        bool need[kUnroll];
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t j = min(j0 + u * stride, n - 1);
+            gid[u] = miss_gid[j];
+            need[u] = !fetched || fetched[j] == 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (need[u]) {
+                const int t = upper_table(s_rbase, T, gid[u]);
+                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (need[u] && j0 + u * stride < n) staging[(j0 + u * stride) * chunks + gl] = v[u];
+    }
+}
+
+// The same fetch for the NEXT batch while the current batch's backward pass runs: a missed row is fetched now unless
+// that pass writes it (its distinct rows `excl[0..n_excl)` are sorted, so a binary search tells), and flagged; the next
+// batch's forward pass fetches the others once the update is done.  A row is never read while it may be written.
+__global__ __launch_bounds__(kBlock) void k_fetch_ahead(const int32_t* __restrict__ miss_gid, const int32_t* __restrict__ d_count,
+                                                        const int32_t* __restrict__ excl, const int32_t* __restrict__ d_n_excl,
+                                                        const Meta* __restrict__ meta, u32x4* __restrict__ staging,
+                                                        uint8_t* __restrict__ fetched, int chunks, int lpr, int64_t cap_rows) {
+    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
+    const int T = meta->num_tables;
+    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
+    __syncthreads();
+    const int64_t n = min((int64_t)*d_count, cap_rows);
+    const int32_t ne = max(min(*d_n_excl, (int32_t)cap_rows), 0);
+    const int gpb = kBlock / lpr;
+    const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
+    const int64_t stride = (int64_t)gridDim.x * gpb;
+    if (gl >= chunks || n <= 0) return;
+    for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
+        int32_t gid[kUnroll];
+        bool take[kUnroll];
         u32x4 v[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) gid[u] = miss_gid[min(j0 + u * stride, n - 1)];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int t = upper_table(s_rbase, T, gid[u]);
-            v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
+            int32_t lo = 0, hi = ne;                 // first position with excl[pos] >= gid
+            while (lo < hi) {
+                const int32_t mid = (lo + hi) >> 1;
+                if (excl[mid] < gid[u]) lo = mid + 1; else hi = mid;
+            }
+            take[u] = !(lo < ne && excl[lo] == gid[u]);
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (j0 + u * stride < n) staging[(j0 + u * stride) * chunks + gl] = v[u];
+        for (int u = 0; u < kUnroll; ++u) {
+            if (take[u]) {
+                const int t = upper_table(s_rbase, T, gid[u]);
+                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t j = j0 + u * stride;
+            if (j < n) {
+                if (take[u]) staging[j * chunks + gl] = v[u];
+                if (gl == 0) fetched[j] = take[u] ? 1 : 0;
+            }
+        }
     }
 }
 
@@ -314,17 +373,31 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int64_t G = (int64_t)h->T * B;
-    h->staged_valid = L > 0 && h->k < h->N;
-    h->staged_loc = rm->loc;
+    // rows of this batch that were fetched ahead sit in their own staging area, the others are fetched now
+    hipError_t e0 = pf_join(h, s);
+    if (e0 != hipSuccess) return e0;
+    const bool ahead = h->ahead.valid && h->ahead.loc == rm->loc && !rm->unique_miss_gid && L > 0 && h->k < h->N;
+    const int area = ahead ? h->ahead.area : 0;
+    if (ahead) ++h->n_ahead_used;
+    h->ahead.valid = false;
+    void* const staging = h->ws.staging[area];
+    for (int a = 0; a < 2; ++a)
+        if (a == area || h->stg[a].loc == rm->loc) h->stg[a].valid = false;
+    h->stg[area].valid = L > 0 && h->k < h->N;
+    h->stg[area].loc = rm->loc;
+    // with look-ahead the integer half of this batch's backward pass starts here, beside the fetch and the pooling
+    if (h->lookahead && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {
+        if ((e0 = start_presort(h, s, off, L, B, rm)) != hipSuccess) return e0;   // (the side stream keeps its own order)
+    }
     // 2: bags of one or two lookups, several bags per lane group; 1: long bags, a wave per bag; 0: a group per bag
     const int mode = L < 2 * G ? 2 : ((lpr < 64 && L >= G * 2 * (kWave / lpr)) ? 1 : 0);
     auto pool = [&](hipStream_t st, int filter, const char* name) {
         Timed t(h, st, name);
         if (h->dtype == SCARS_DTYPE_F32)
-            launch_pool_d<SCARS_DTYPE_F32>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k, chunks,
+            launch_pool_d<SCARS_DTYPE_F32>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, staging, h->k, chunks,
                                            h->D, out, filter);
         else
-            launch_pool_d<SCARS_DTYPE_BF16>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, h->ws.staging, h->k, chunks,
+            launch_pool_d<SCARS_DTYPE_BF16>(lpr, st, mode, off, G, L, rm->loc, h->buf.cache, staging, h->k, chunks,
                                             h->D, out, filter);
     };
     // With the side-stream option and short bags, the bags that need no staged row (the hits of a one-index-per-bag
@@ -353,7 +426,7 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         const int32_t* list = rm->unique_miss_gid ? rm->unique_miss_gid : rm->miss_gid;
         const int32_t* count = rm->unique_miss_gid ? rm->n_unique_miss : rm->n_hit_miss + 1;
         hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, list, count, h->ws.meta,
-                           (u32x4*)h->ws.staging, chunks, lpr, h->buf.max_L);
+                           (u32x4*)staging, chunks, lpr, h->buf.max_L, ahead ? h->ws.fetched : (const uint8_t*)nullptr);
     }
     if (G > 0) pool(s, split ? 2 : 0, split ? "pool_short_staged" : (mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group")));
     if (split) {   // the output is complete, in the caller's stream order, when this call returns
@@ -361,6 +434,35 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         if (e != hipSuccess) return e;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
+                              const int32_t* excl, const int32_t* n_excl, int area) {
+    hipError_t e = hipSuccess;
+    if (!h->pf_stream) {
+        if ((e = hipStreamCreateWithFlags(&h->pf_stream, hipStreamNonBlocking)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&h->ev_pf_fork, hipEventDisableTiming)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&h->ev_pf_done, hipEventDisableTiming)) != hipSuccess) return e;
+    }
+    if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(h->pf_stream, h->ev_pf_fork, 0)) != hipSuccess) return e;
+    const int chunks = h->R / 16;
+    const int lpr = std::min(64, next_pow2_host(chunks));
+    const int gpb = kBlock / lpr;
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kUnroll), kStageBlocks));
+    {
+        Timed t(h, h->pf_stream, "fetch_ahead");
+        hipLaunchKernelGGL(k_fetch_ahead, dim3(grid), dim3(kBlock), 0, h->pf_stream, next_rm->miss_gid, next_rm->n_hit_miss + 1,
+                           excl, n_excl, h->ws.meta, (u32x4*)h->ws.staging[area], h->ws.fetched, chunks, lpr, h->buf.max_L);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = hipEventRecord(h->ev_pf_done, h->pf_stream)) != hipSuccess) return e;
+    h->pf_pending = true;
+    h->stg[area].valid = false;
+    h->ahead.valid = true;
+    h->ahead.loc = next_rm->loc;
+    h->ahead.area = area;
+    return hipSuccess;
 }
 
 }  // namespace scars

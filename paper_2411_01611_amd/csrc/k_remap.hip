@@ -264,7 +264,7 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, ws.blk_hit, ws.blk_miss, nb, out->n_hit_miss);
     }
     // the pairs go into the first sort buffer, which listing each distinct missed row once (below) sorts in as well
-    const bool pairs = h->pairs_in_remap && L > 0 && !out->unique_miss_gid;
+    const bool pairs = h->pairs_in_remap && !h->lookahead && L > 0 && !out->unique_miss_gid;
     h->pairs_valid = false;
     if (pairs) {
         Timed t(h, s, "remap_write");

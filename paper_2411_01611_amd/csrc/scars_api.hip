@@ -79,7 +79,9 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.blk_seg_a = (uint32_t*)take((nbLG + 1) * 4);
     w.blk_seg_b = (uint32_t*)take((nbLG + 1) * 4);
     w.plan_cc = (uint32_t*)take((kPlanBins + kPlanBigCap + 4) * 4);
-    w.staging = take(max_L * h->R);
+    w.staging[0] = take(max_L * h->R);
+    w.staging[1] = take(max_L * h->R);
+    w.fetched = (uint8_t*)take(max_L);
     w.total_bytes = off;
     return w;
 }
@@ -101,6 +103,29 @@ hipError_t side_fork(scars_handle* h, hipStream_t s) {
     }
     if ((e = hipEventRecord(h->ev_fork, s)) != hipSuccess) return e;
     return hipStreamWaitEvent(h->side, h->ev_fork, 0);
+}
+
+// Make stream s wait for rows being fetched ahead on the library's third stream, if any are outstanding.
+hipError_t pf_join(scars_handle* h, hipStream_t s) {
+    if (!h->pf_pending) return hipSuccess;
+    h->pf_pending = false;
+    return hipStreamWaitEvent(s, h->ev_pf_done, 0);
+}
+
+// The integer half of the backward pass of a remapped batch (pairs, sort, run starts), started on the side stream
+// behind everything enqueued on s so far; scars_embedding_bag_bwd_update joins it when it is called for that batch.
+hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B, const scars_remap_out* rm) {
+    hipError_t e = side_fork(h, s);
+    if (e != hipSuccess) return e;
+    const bool staged = h->k < h->N;   // misses are possible: the forward pass stages them
+    e = launch_bwd_segments(h, h->side, off, L, B, rm, staged, nullptr, &h->presort_res);
+    if (e == hipSuccess) e = hipEventRecord(h->ev_join, h->side);
+    if (e != hipSuccess) return e;
+    h->side_pending = true;
+    h->presort_valid = true;
+    h->presort_gid = rm->gid; h->presort_loc = rm->loc; h->presort_off = off;
+    h->presort_L = L; h->presort_B = B; h->presort_staged = staged;
+    return hipSuccess;
 }
 
 static int64_t budget_rows(const scars_handle* h, int64_t budget_bytes) {
@@ -148,6 +173,7 @@ int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
         case SCARS_TUNE_PRESORT: h->presort_min_L = value; break;
         case SCARS_TUNE_FUSED_LONG_MAX_L: h->fused_long_max_L = value; break;
         case SCARS_TUNE_PAIRS_IN_REMAP: h->pairs_in_remap = value != 0; break;
+        case SCARS_TUNE_LOOKAHEAD: h->lookahead = value != 0; break;
         case SCARS_TUNE_UPDATE_MAX_BLOCKS: h->update_max_blocks = std::min<int64_t>(value, 256 * 32); break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
@@ -158,6 +184,7 @@ int64_t scars_get_counter(const scars_handle* h, int32_t which) {
     if (!h) return -1;
     switch (which) {
         case SCARS_COUNTER_PREPARED_USED: return h->n_prepared_used;
+        case SCARS_COUNTER_AHEAD_USED: return h->n_ahead_used;
         default: return -1;
     }
 }
@@ -169,6 +196,12 @@ int32_t scars_destroy(scars_handle* h) {
         (void)hipStreamDestroy(h->pool_stream);
         (void)hipEventDestroy(h->ev_pool_fork);
         (void)hipEventDestroy(h->ev_pool_join);
+    }
+    if (h->pf_stream) {
+        (void)hipStreamSynchronize(h->pf_stream);
+        (void)hipStreamDestroy(h->pf_stream);
+        (void)hipEventDestroy(h->ev_pf_fork);
+        (void)hipEventDestroy(h->ev_pf_done);
     }
     if (h->side) {
         (void)hipStreamSynchronize(h->side);
@@ -208,13 +241,16 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     if (k > 0 && (!b->hot_gid || !b->cache || (h->optimizer == SCARS_OPT_ADAGRAD && !b->state_cache)))
         return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: cache buffers missing");
     if (h->side) (void)hipStreamSynchronize(h->side);   // nothing may still be using the buffers bound before
+    if (h->pf_stream) (void)hipStreamSynchronize(h->pf_stream);
+    h->pf_pending = false;
     h->side_pending = false;
     h->presort_valid = false;
     h->pairs_valid = false;
     h->buf = *b;
     h->k_cap = k;
     h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);
-    h->bound = true; h->built = false; h->dirty = false; h->k = -1; h->profiled = 0; h->staged_valid = false;
+    h->bound = true; h->built = false; h->dirty = false; h->k = -1; h->profiled = 0;
+    h->stg[0].valid = h->stg[1].valid = false; h->ahead.valid = false;
     Meta* m = new Meta();
     std::memset(m, 0, sizeof(Meta));
     for (int t = 0; t < h->T; ++t) {
@@ -260,6 +296,7 @@ int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32
         return fail(h, SCARS_ERR_INVALID_ARG, "build_cache: cumulative lookups >= 2^32 would overflow the uint32 counts");
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = side_join(h, s);   // segments being prepared on the side stream read slot_of and the sort buffers
+    if (e == hipSuccess) e = pf_join(h, s);
     if (e != hipSuccess) return hip_fail(h, e, "build_cache(join)");
     h->presort_valid = false;
     if (accumulate != 2 && h->built && h->dirty) {   // keep updated hot rows before they lose their slots
@@ -278,7 +315,8 @@ int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32
     h->profiled = before + (uint64_t)Lp;
     if (accumulate == 2) return SCARS_OK;
     h->built = false;
-    h->staged_valid = false;
+    h->stg[0].valid = h->stg[1].valid = false;
+    h->ahead.valid = false;
     e = launch_select_and_fill(h, s, k);
     if (e != hipSuccess) return hip_fail(h, e, "build_cache(select)");
     h->built = true;
@@ -301,25 +339,25 @@ int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_
     if (rc) return rc;
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "remap: build_cache has not selected a hot set");
     if ((rc = check_remap_out(h, out, L, "remap"))) return rc;
-    if (out->loc == h->staged_loc) h->staged_valid = false;   // these arrays no longer describe the staged batch
+    for (int a = 0; a < 2; ++a)
+        if (out->loc == h->stg[a].loc) h->stg[a].valid = false;   // these arrays no longer describe a staged batch
+    if (out->loc == h->ahead.loc) h->ahead.valid = false;
     hipStream_t s = (hipStream_t)stream;
-    // segments still being prepared on the side stream read the previous batch's arrays and the sort buffers
-    hipError_t e = side_join(h, s);
-    if (e != hipSuccess) return hip_fail(h, e, "remap(join)");
-    h->presort_valid = false;
+    hipError_t e = hipSuccess;
+    // Segments still being prepared on the side stream read the previous batch's arrays and the sort buffers.  With
+    // look-ahead this call may come while the previous batch's backward pass is still to be called: then it touches
+    // nothing that pass uses (no pairs, no preparation: that starts with the forward pass instead), unless it is
+    // given the very arrays the preparation reads or lists each distinct missed row once (that sorts in the same buffers).
+    if (!h->lookahead || out->unique_miss_gid || out->gid == h->presort_gid || out->loc == h->presort_loc) {
+        e = side_join(h, s);
+        if (e != hipSuccess) return hip_fail(h, e, "remap(join)");
+        h->presort_valid = false;
+    }
     e = launch_remap(h, s, d_indices, d_offsets, L, B, out);
     if (e != hipSuccess) return hip_fail(h, e, "remap");
     // worth it only when a link-bound staging kernel will leave the GPU idle (misses are possible)
-    if (h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {
-        if ((e = side_fork(h, s)) != hipSuccess) return hip_fail(h, e, "remap(fork)");
-        const bool staged = h->k < h->N;   // misses are possible: the forward pass will stage them
-        e = launch_bwd_segments(h, h->side, d_offsets, L, B, out, staged, nullptr, &h->presort_res);
-        if (e == hipSuccess) e = hipEventRecord(h->ev_join, h->side);
-        if (e != hipSuccess) return hip_fail(h, e, "remap(backward segments)");
-        h->side_pending = true;
-        h->presort_valid = true;
-        h->presort_gid = out->gid; h->presort_loc = out->loc; h->presort_off = d_offsets;
-        h->presort_L = L; h->presort_B = B; h->presort_staged = staged;
+    if (!h->lookahead && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {
+        if ((e = start_presort(h, s, d_offsets, L, B, out)) != hipSuccess) return hip_fail(h, e, "remap(backward segments)");
     }
     return SCARS_OK;
 }
@@ -336,21 +374,46 @@ int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const
     return SCARS_OK;
 }
 
+static int32_t bwd_update_impl(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                               const scars_remap_out* rm, const float* d_grad_out, float lr, float eps,
+                               const scars_bwd_out* out, const scars_remap_out* next_rm, int64_t next_L, void* stream,
+                               const char* who) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, who);
+    if (rc) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, std::string(who) + ": build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, rm, L, who))) return rc;
+    if (!d_grad_out && L > 0) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": null gradient");
+    if (out && (!out->n_unique || !out->seg_start || (L > 0 && (!out->sorted_gid || !out->sorted_bag || !out->unique_gid))))
+        return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": bwd_out has a null array");
+    if (next_rm) {
+        if (!h->lookahead) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": SCARS_TUNE_LOOKAHEAD is off");
+        if (next_L < 0 || next_L > h->buf.max_L) return fail(h, SCARS_ERR_WORKSPACE, std::string(who) + ": next batch larger than the bound max_L");
+        if ((rc = check_remap_out(h, next_rm, next_L, who))) return rc;
+        if (next_rm->unique_miss_gid) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": the next batch was remapped with unique_miss_gid");
+        if (next_rm->loc == rm->loc || next_rm->miss_gid == rm->miss_gid)
+            return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": the next batch needs remap outputs of its own");
+    }
+    hipError_t e = side_join(h, (hipStream_t)stream);
+    if (e == hipSuccess) e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, next_L);
+    if (e != hipSuccess) return hip_fail(h, e, who);
+    if (L > 0) h->dirty = true;
+    return SCARS_OK;
+}
+
 int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
                                        int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
                                        float lr, float eps, const scars_bwd_out* out, void* stream) {
-    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "embedding_bag_bwd_update");
-    if (rc) return rc;
-    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "embedding_bag_bwd_update: build_cache has not selected a hot set");
-    if ((rc = check_remap_out(h, rm, L, "embedding_bag_bwd_update"))) return rc;
-    if (!d_grad_out && L > 0) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: null gradient");
-    if (out && (!out->n_unique || !out->seg_start || (L > 0 && (!out->sorted_gid || !out->sorted_bag || !out->unique_gid))))
-        return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update: bwd_out has a null array");
-    hipError_t e = side_join(h, (hipStream_t)stream);
-    if (e == hipSuccess) e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out);
-    if (e != hipSuccess) return hip_fail(h, e, "embedding_bag_bwd_update");
-    if (L > 0) h->dirty = true;
-    return SCARS_OK;
+    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, nullptr, 0, stream,
+                           "embedding_bag_bwd_update");
+}
+
+int32_t scars_embedding_bag_bwd_update_ahead(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
+                                             int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
+                                             float lr, float eps, const scars_bwd_out* out,
+                                             const scars_remap_out* next_rm, int64_t next_L, void* stream) {
+    if (h && !next_rm) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update_ahead: null next batch");
+    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, next_L, stream,
+                           "embedding_bag_bwd_update_ahead");
 }
 
 int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
@@ -514,7 +577,8 @@ int32_t scars_flush_cache(scars_handle* h, void* stream) {
     if (!h) return SCARS_ERR_INVALID_ARG;
     if (!h->bound) return fail(h, SCARS_ERR_WORKSPACE, "flush_cache: no buffers bound");
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "flush_cache: nothing cached");
-    hipError_t e = launch_flush(h, (hipStream_t)stream);
+    hipError_t e = pf_join(h, (hipStream_t)stream);
+    if (e == hipSuccess) e = launch_flush(h, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(h, e, "flush_cache");
     h->dirty = false;
     return SCARS_OK;
@@ -526,6 +590,7 @@ int32_t scars_sync_status(scars_handle* h, void* stream) {
     hipStream_t s = (hipStream_t)stream;
     int32_t st[4] = {0, 0, 0, 0};
     hipError_t e = side_join(h, s);   // side-stream kernels latch errors too
+    if (e == hipSuccess) e = pf_join(h, s);
     if (e == hipSuccess) e = hipMemcpyAsync(st, h->ws.status, sizeof(st), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(h, e, "sync_status");
@@ -579,6 +644,7 @@ int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e == hipSuccess && h->side) e = hipStreamSynchronize(h->side);
     if (e == hipSuccess && h->pool_stream) e = hipStreamSynchronize(h->pool_stream);
+    if (e == hipSuccess && h->pf_stream) e = hipStreamSynchronize(h->pf_stream);
     if (e != hipSuccess) return hip_fail(h, e, "profile_read");
     std::vector<scars_kernel_time> acc;
     for (auto& p : h->timer.pending) {

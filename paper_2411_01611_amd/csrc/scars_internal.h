@@ -62,7 +62,8 @@ struct Workspace {
     uint32_t* blk_seg_a;      // [tiles+1] x2: tile counters of the backward pass's run-start compaction (its own pair:
     uint32_t* blk_seg_b;      //   that half of the pass may run on the side stream beside calls that use blk_hit/blk_miss)
     uint32_t* plan_cc;        // [kPlanBins] rows per count value, [kPlanBigCap] counts at or above kPlanBins, [4] their number
-    void* staging;            // [max_L][R] rows fetched over the host link
+    void* staging[2];         // [max_L][R] rows fetched over the host link; the second area is for rows fetched ahead
+    uint8_t* fetched;         // [max_L] 1 = this missed lookup's row was fetched ahead
     int64_t total_bytes;
 };
 
@@ -91,8 +92,19 @@ struct scars_handle {
     bool dirty = false;                  // cache holds rows newer than the host tables
     int64_t k = -1;
     uint64_t profiled = 0;               // cumulative lookups histogrammed
-    bool staged_valid = false;           // the staging area holds the missed rows of the batch whose remap wrote staged_loc
-    const int32_t* staged_loc = nullptr;
+    // staging areas: area a holds the missed rows of the batch whose remap wrote stg[a].loc
+    struct Staged { bool valid = false; const int32_t* loc = nullptr; } stg[2];
+    int staged_area(const int32_t* loc) const {
+        for (int a = 0; a < 2; ++a) if (stg[a].valid && stg[a].loc == loc) return a;
+        return -1;
+    }
+    // look-ahead (SCARS_TUNE_LOOKAHEAD): rows of the next batch fetched while this batch is updated
+    bool lookahead = false;
+    struct { bool valid = false; const int32_t* loc = nullptr; int area = 0; } ahead;   // what was fetched ahead, where
+    hipStream_t pf_stream = nullptr;
+    hipEvent_t ev_pf_fork = nullptr, ev_pf_done = nullptr;
+    bool pf_pending = false;             // work on pf_stream that no other stream has waited for yet
+    bool ahead_active = false;           // the backward pass being enqueued has a fetch running beside it
     std::string err;
     // side stream: the integer half of the backward pass can be started by remap and run beside the forward pass
     hipStream_t side = nullptr;
@@ -110,6 +122,7 @@ struct scars_handle {
     const int32_t* pairs_gid = nullptr;
     const int32_t* pairs_off = nullptr;
     int64_t pairs_L = 0, pairs_B = 0;
+    int64_t n_ahead_used = 0;            // forward passes that used rows fetched ahead
     int64_t n_prepared_used = 0;         // bwd_update calls that used segments prepared on the side stream
     // launch tuning (scars_set_tuning)
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
@@ -175,7 +188,13 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
                       const scars_remap_out* rm, float* out);
 // k_bwd.hip
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
-                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out);
+                      const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out,
+                      const scars_remap_out* next_rm, int64_t next_L);
+// k_fwd.hip: missed rows of a remapped batch that are not in the sorted list `excl` -> staging area `area`
+hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
+                              const int32_t* excl, const int32_t* n_excl, int area);
+hipError_t pf_join(scars_handle* h, hipStream_t s);
+hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B, const scars_remap_out* rm);
 hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                                const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out);
 

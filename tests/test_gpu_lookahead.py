@@ -1,0 +1,185 @@
+"""The look-ahead call order: remap(next) -> bwd_update_ahead(this, next) -> fwd(next).  Rows of the next batch
+are fetched while this batch is updated, except those the update writes; every result must equal that of the calls
+made one batch after the other, which is what the oracle computes."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2411_01611_amd import binding, synth
+from gpu_harness import GpuCase, assert_close
+
+CASES = {
+    "tiny": ("tiny", {}),
+    "dlrm_small": ("dlrm_onehot", {"scale": 0.004, "batch": 1500}),
+    "multi_hot_small": ("multi_hot", {"scale": 0.004, "batch": 333}),
+    "host_spill_small": ("host_spill", {"scale": 0.0005, "batch": 3000}),
+}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _share_rows(wl, prev, cur, frac, rng):
+    """A copy of batch `cur` in which a share of the lookups go to rows batch `prev` looks up in the same table, so
+    that rows updated by one batch are read (and missed) by the next."""
+    pi, po = prev[0].numpy(), prev[1].numpy()
+    ci, co = cur[0].numpy().copy(), cur[1].numpy()
+    B = wl.batch
+    for t in range(wl.num_tables):
+        a0, a1 = int(po[t * B]), int(po[(t + 1) * B])
+        b0, b1 = int(co[t * B]), int(co[(t + 1) * B])
+        n = min(a1 - a0, b1 - b0)
+        m = rng.random(n) < frac
+        ci[b0:b0 + n][m] = pi[a0:a0 + n][m]
+    return torch.from_numpy(ci), cur[1]
+
+
+def _batches(c, n, frac=0.3):
+    rng = np.random.default_rng(5)
+    out = [c.sampler.batch(0)]
+    for e in range(1, n):
+        out.append(_share_rows(c.wl, out[-1], c.sampler.batch(e), frac, rng))
+    return out
+
+
+def _room(wl):
+    return int(wl.num_bags * ((wl.bag_lambda or 0) + 1) * 1.6) + 64
+
+
+def _ora_step(c, batch, grad):
+    wl = c.wl
+    opt = 1 if wl.optimizer == "adagrad" else 0
+    (rc,) = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, opt, batch[0].numpy(), batch[1].numpy(),
+                                            wl.batch, grad.numpy(), np.float32(wl.lr), np.float32(wl.eps if opt else 0.0))
+    assert rc == 0
+
+
+def _ora_fwd(c, batch):
+    rc, want = oracle.embedding_bag_fwd(c.wl.rows, c.ora_tables, batch[0].numpy(), batch[1].numpy(), c.wl.batch)
+    assert rc == 0
+    return want
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("budget", ["own", "none", "all"])
+@pytest.mark.parametrize("presort", [0, 1])
+def test_lookahead_steps_match_the_calls_made_one_after_the_other(name, budget, presort):
+    wname, kw = CASES[name]
+    wl = synth.workload(wname, **kw)
+    bb = {"own": None, "none": 0, "all": wl.total_rows * wl.row_bytes}[budget]
+    _say("lookahead", name, budget, "presort", presort)
+    c = GpuCase(wl, budget_bytes=bb, max_L=_room(wl))
+    s = c.s
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    s.set_tuning(binding.TUNE_PRESORT, presort)
+    c.build()
+    steps = 4
+    bs = _batches(c, steps + 1)
+    dev = [(b[0].to(c.dev), b[1].to(c.dev)) for b in bs]
+    grads = [c.sampler.grads(e) for e in range(steps)]
+    rms = [s.new_remap_out(), s.new_remap_out()]
+    opt = wl.optimizer == "adagrad"
+    lr, eps = float(wl.lr), float(wl.eps if opt else 0.0)
+    s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
+    out = s.embedding_bag_fwd(dev[0][0], dev[0][1], wl.batch, rms[0])
+    assert_close(out.cpu().numpy(), _ora_fwd(c, bs[0]), "first forward pass")
+    for e in range(steps):
+        cur, nxt = rms[e % 2], rms[(e + 1) % 2]
+        s.remap(dev[e + 1][0], dev[e + 1][1], wl.batch, nxt)
+        s.embedding_bag_bwd_update_ahead(dev[e][0], dev[e][1], wl.batch, cur, grads[e].to(c.dev), lr, eps, nxt,
+                                         int(bs[e + 1][0].numel()))
+        _ora_step(c, bs[e], grads[e])
+        out = s.embedding_bag_fwd(dev[e + 1][0], dev[e + 1][1], wl.batch, nxt)
+        assert_close(out.cpu().numpy(), _ora_fwd(c, bs[e + 1]), f"forward pass of batch {e + 1}")
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+    if opt:
+        assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
+    # rows were fetched ahead whenever something can miss
+    assert s.get_counter(binding.COUNTER_AHEAD_USED) == (0 if budget == "all" else steps)
+    c.close()
+
+
+def test_lookahead_rows_updated_by_this_batch_are_left_to_the_forward_pass():
+    """Two batches over the same few cold rows: nearly every missed row of the second is written by the first, so
+    nearly nothing may be fetched ahead, and what is read afterwards is the updated value."""
+    wl = synth.workload("multi_hot", scale=0.004, batch=200)
+    c = GpuCase(wl, budget_bytes=0, max_L=_room(wl))
+    s = c.s
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    c.build()
+    b0 = c.sampler.batch(0)
+    b1 = _share_rows(wl, b0, c.sampler.batch(1), 0.95, np.random.default_rng(1))
+    d0, d1 = [t.to(c.dev) for t in b0], [t.to(c.dev) for t in b1]
+    g = c.sampler.grads(0)
+    r0, r1 = s.new_remap_out(), s.new_remap_out()
+    s.remap(d0[0], d0[1], wl.batch, r0)
+    s.embedding_bag_fwd(d0[0], d0[1], wl.batch, r0)
+    s.remap(d1[0], d1[1], wl.batch, r1)
+    s.embedding_bag_bwd_update_ahead(d0[0], d0[1], wl.batch, r0, g.to(c.dev), float(wl.lr), float(wl.eps), r1, int(b1[0].numel()))
+    _ora_step(c, b0, g)
+    out = s.embedding_bag_fwd(d1[0], d1[1], wl.batch, r1)
+    assert_close(out.cpu().numpy(), _ora_fwd(c, b1), "forward pass over freshly updated rows")
+    assert s.sync_status() == 0
+    c.close()
+
+
+def test_lookahead_calls_that_do_not_line_up():
+    wl = synth.workload("multi_hot", scale=0.004, batch=200)
+    c = GpuCase(wl, max_L=_room(wl))
+    s = c.s
+    c.build()
+    bs = _batches(c, 4)
+    dev = [(b[0].to(c.dev), b[1].to(c.dev)) for b in bs]
+    g = c.sampler.grads(0)
+    dg = g.to(c.dev)
+    lr, eps = float(wl.lr), float(wl.eps)
+    rms = [s.new_remap_out() for _ in range(3)]
+    n = lambda e: int(bs[e][0].numel())
+    s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
+    s.remap(dev[1][0], dev[1][1], wl.batch, rms[1])
+    with pytest.raises(binding.ScarsError):      # the option is off
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], n(1))
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    with pytest.raises(binding.ScarsError):      # the next batch needs arrays of its own
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[0], n(0))
+    rmc = s.new_remap_out(coalesce=True)
+    s.remap(dev[1][0], dev[1][1], wl.batch, rmc, coalesce=True)
+    with pytest.raises(binding.ScarsError):      # not with each distinct missed row listed once
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rmc, n(1))
+    # (1) rows fetched ahead for batch 1, but the forward pass that follows is batch 2's; then batch 1's after all
+    s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
+    s.embedding_bag_fwd(dev[0][0], dev[0][1], wl.batch, rms[0])
+    s.remap(dev[1][0], dev[1][1], wl.batch, rms[1])
+    s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], n(1))
+    _ora_step(c, bs[0], g)
+    s.remap(dev[2][0], dev[2][1], wl.batch, rms[2])
+    out = s.embedding_bag_fwd(dev[2][0], dev[2][1], wl.batch, rms[2])
+    assert_close(out.cpu().numpy(), _ora_fwd(c, bs[2]), "forward pass of another batch than the one fetched ahead")
+    out = s.embedding_bag_fwd(dev[1][0], dev[1][1], wl.batch, rms[1])
+    assert_close(out.cpu().numpy(), _ora_fwd(c, bs[1]), "forward pass of the batch fetched ahead, later")
+    # (2) a plain update in between makes what was fetched ahead stale: it must not be used
+    s.embedding_bag_bwd_update_ahead(dev[1][0], dev[1][1], wl.batch, rms[1], dg, lr, eps, rms[2], n(2))
+    _ora_step(c, bs[1], g)
+    s.embedding_bag_bwd_update(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps)
+    _ora_step(c, bs[0], g)
+    out = s.embedding_bag_fwd(dev[2][0], dev[2][1], wl.batch, rms[2])
+    assert_close(out.cpu().numpy(), _ora_fwd(c, bs[2]), "forward pass after an update that followed the fetch")
+    # (3) a re-selection in between
+    s.remap(dev[3][0], dev[3][1], wl.batch, rms[0])
+    s.embedding_bag_bwd_update_ahead(dev[2][0], dev[2][1], wl.batch, rms[2], dg, lr, eps, rms[0], n(3))
+    _ora_step(c, bs[2], g)
+    s.build_cache(None, None, 0, c.budget // 2, 1)
+    s.remap(dev[3][0], dev[3][1], wl.batch, rms[0])
+    out = s.embedding_bag_fwd(dev[3][0], dev[3][1], wl.batch, rms[0])
+    assert_close(out.cpu().numpy(), _ora_fwd(c, bs[3]), "forward pass after a re-selection")
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
+    c.close()
