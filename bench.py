@@ -361,6 +361,58 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
             "ms_per_step_median": round(per_step[len(per_step) // 2], 5), "ms_per_step_min": round(per_step[0], 5)}
 
 
+def run_lookahead(b: Bench, K: int, W: int) -> dict:
+    """The same K batches in the look-ahead order: remap(e+1), update of batch e with the missed rows of batch e+1
+    fetched beside it, forward pass of batch e+1.  Every batch still goes through remap, forward and update once,
+    and every result is the one of the plain order (tests/test_gpu_lookahead.py)."""
+    wl, s = b.wl, b.s
+    n = len(b.batches)
+    eps = wl.eps if wl.optimizer == "adagrad" else 0.0
+    rms = [b.rm, s.new_remap_out()]
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+
+    def prime(e):
+        idx, off = b.batches[e % n]
+        s.remap(idx, off, wl.batch, rms[e % 2])
+        s.embedding_bag_fwd(idx, off, wl.batch, rms[e % 2], b.out)
+
+    def step(e):
+        idx, off = b.batches[e % n]
+        nidx, noff = b.batches[(e + 1) % n]
+        s.remap(nidx, noff, wl.batch, rms[(e + 1) % 2])
+        s.embedding_bag_bwd_update_ahead(idx, off, wl.batch, rms[e % 2], b.grads[e % len(b.grads)], wl.lr, eps,
+                                         rms[(e + 1) % 2], int(nidx.numel()))
+        s.embedding_bag_fwd(nidx, noff, wl.batch, rms[(e + 1) % 2], b.out)
+        return int(idx.numel())
+
+    prime(0)
+    for e in range(W):
+        step(e)
+    torch.cuda.synchronize()
+    used0 = s.get_counter(binding.COUNTER_AHEAD_USED)
+    lookups = 0
+    t0 = time.perf_counter()
+    for e in range(W, W + K):
+        lookups += step(e)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    used = s.get_counter(binding.COUNTER_AHEAD_USED) - used0
+    assert s.sync_status() == 0
+    s.profile_enable(True)
+    for e in range(W + K, W + 2 * K):
+        step(e)
+    prof = s.profile_read()
+    s.profile_enable(False)
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 0)
+    s.remap(*b.batches[0], wl.batch, b.rm)      # leave no look-ahead state behind for the legs that follow
+    torch.cuda.synchronize()
+    kern = {k: {"launches_per_step": v["launches"] / K, "avg_ms": round(v["total_ms"] / v["launches"], 5)}
+            for k, v in prof.items()}
+    return {"value": lookups / (t1 - t0), "unit": "lookups/s", "ms_per_step": (t1 - t0) * 1e3 / K,
+            "forward_passes_with_rows_fetched_ahead": int(used), "steps": K,
+            "order": "remap(e+1) -> embedding_bag_bwd_update_ahead(e, e+1) -> embedding_bag_fwd(e+1)", "kernels": kern}
+
+
 def pmc_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if any."""
     path = os.path.join(ROOT, "profiles", f"pmc_{workload}.json")
@@ -442,10 +494,12 @@ def main():
                          "launch (default: the library's, every batch; 0 = never)")
     ap.add_argument("--update-max-blocks", type=int, default=0,
                     help="most workgroups of the per-row update kernel (default: the library's, 8192)")
+    ap.add_argument("--no-lookahead", dest="lookahead", action="store_false",
+                    help="skip the extra leg in the look-ahead call order (reported under lookahead)")
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
-    ap.set_defaults(presort=True)
+    ap.set_defaults(presort=True, lookahead=True)
     ap.add_argument("--no-resident", dest="resident", action="store_false",
                     help="skip the second leg in which every row is cached (the paper's 'hot' iteration): same "
                          "kernels, no host-link traffic; reported under cache_resident")
@@ -471,7 +525,8 @@ def main():
         others[name] = {"value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "dtype": r["dtype"],
                         "config": {k: r["config"][k] for k in ("row_scale", "rows", "dim", "batch", "lookups_per_step",
                                                                 "hit_rate", "budget_bytes", "optimizer")},
-                        "roofline": r["roofline"], "host_link": r["host_link"]}
+                        "roofline": r["roofline"], "host_link": r["host_link"],
+                        "lookahead": r["lookahead"] and {k: r["lookahead"][k] for k in ("value", "ms_per_step")}}
     line["other_workloads"] = others
     if args.also != "none" and args.workload != "low_skew_uniform":
         # the gather roofline reference: uniform ids over 6.4 GB of rows, every row cached (no reuse for the caches
@@ -504,6 +559,10 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     log(name, "build_cache", bc)
 
     leg = run_leg(b, K, W, link, args.graph)
+    ahead = None
+    if args.lookahead and not args.coalesce and budget < wl.total_rows * wl.row_bytes:
+        ahead = run_lookahead(b, K, W)
+        log(name, "look-ahead order", {k: ahead[k] for k in ("value", "ms_per_step")})
     resident = None
     if with_resident and budget < wl.total_rows * wl.row_bytes and wl.total_rows * wl.row_bytes * 3 < 150e9:
         # second leg: every row cached (the paper's "hot" iteration): the same kernels, no host-link traffic
@@ -545,7 +604,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         "roofline": leg["roofline"], "host_link": leg["host_link"],
         "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
                      "d2h_GBs": round(link["d2h_GBs"], 2)},
-        "cpu_baseline": cpu, "cache_resident": resident,
+        "cpu_baseline": cpu, "cache_resident": resident, "lookahead": ahead,
         "ms_per_step_median": leg["ms_per_step_median"], "ms_per_step_min": leg["ms_per_step_min"],
         "calls_alone_ms": leg["calls_alone_ms"], "kernels": leg["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
     }

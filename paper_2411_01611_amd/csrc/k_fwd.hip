@@ -17,12 +17,13 @@ constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
-// `fetched` (may be null): rows flagged there are already in the staging area (fetched ahead) and are skipped.
+// `flags` (may be null: every row): only rows whose flag equals `want` are fetched.  flag 1 = the row may be
+// fetched ahead (k_mark_ahead), so want = 1 fetches ahead and want = 0 fetches what was left out.
 __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
                                                          const int32_t* __restrict__ d_count,
                                                          const Meta* __restrict__ meta, u32x4* __restrict__ staging,
                                                          int chunks, int lpr, int64_t cap_rows,
-                                                         const uint8_t* __restrict__ fetched) {
+                                                         const uint8_t* __restrict__ flags, int want) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = meta->num_tables;
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restri
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t j = min(j0 + u * stride, n - 1);
             gid[u] = miss_gid[j];
-            need[u] = !fetched || fetched[j] == 0;
+            need[u] = !flags || flags[j] == want;
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -58,53 +59,24 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restri
     }
 }
 
-// The same fetch for the NEXT batch while the current batch's backward pass runs: a missed row is fetched now unless
-// that pass writes it (its distinct rows `excl[0..n_excl)` are sorted, so a binary search tells), and flagged; the next
-// batch's forward pass fetches the others once the update is done.  A row is never read while it may be written.
-__global__ __launch_bounds__(kBlock) void k_fetch_ahead(const int32_t* __restrict__ miss_gid, const int32_t* __restrict__ d_count,
-                                                        const int32_t* __restrict__ excl, const int32_t* __restrict__ d_n_excl,
-                                                        const Meta* __restrict__ meta, u32x4* __restrict__ staging,
-                                                        uint8_t* __restrict__ fetched, int chunks, int lpr, int64_t cap_rows) {
-    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
-    const int T = meta->num_tables;
-    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
-    __syncthreads();
+// Fetching the NEXT batch's missed rows while the current batch's backward pass runs: a row may be fetched now unless
+// that pass writes it.  Its distinct rows `excl[0..n_excl)` are sorted, so a binary search tells; this kernel only
+// sets the flags (it touches no host memory, so it is not slowed by the link), k_stage_misses then fetches the
+// flagged rows, and the next batch's forward pass the others once the update is done.  A row is never read while
+// it may be written.
+__global__ __launch_bounds__(kBlock) void k_mark_ahead(const int32_t* __restrict__ miss_gid, const int32_t* __restrict__ d_count,
+                                                       const int32_t* __restrict__ excl, const int32_t* __restrict__ d_n_excl,
+                                                       uint8_t* __restrict__ flags, int64_t cap_rows) {
     const int64_t n = min((int64_t)*d_count, cap_rows);
     const int32_t ne = max(min(*d_n_excl, (int32_t)cap_rows), 0);
-    const int gpb = kBlock / lpr;
-    const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
-    const int64_t stride = (int64_t)gridDim.x * gpb;
-    if (gl >= chunks || n <= 0) return;
-    for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
-        int32_t gid[kUnroll];
-        bool take[kUnroll];
-        u32x4 v[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) gid[u] = miss_gid[min(j0 + u * stride, n - 1)];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            int32_t lo = 0, hi = ne;                 // first position with excl[pos] >= gid
-            while (lo < hi) {
-                const int32_t mid = (lo + hi) >> 1;
-                if (excl[mid] < gid[u]) lo = mid + 1; else hi = mid;
-            }
-            take[u] = !(lo < ne && excl[lo] == gid[u]);
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < n; j += (int64_t)gridDim.x * kBlock) {
+        const int32_t gid = miss_gid[j];
+        int32_t lo = 0, hi = ne;                 // first position with excl[pos] >= gid
+        while (lo < hi) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (excl[mid] < gid) lo = mid + 1; else hi = mid;
         }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (take[u]) {
-                const int t = upper_table(s_rbase, T, gid[u]);
-                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t j = j0 + u * stride;
-            if (j < n) {
-                if (take[u]) staging[j * chunks + gl] = v[u];
-                if (gl == 0) fetched[j] = take[u] ? 1 : 0;
-            }
-        }
+        flags[j] = (lo < ne && excl[lo] == gid) ? 0 : 1;
     }
 }
 
@@ -421,12 +393,13 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         // 128 workgroups hold far more than the host link needs in flight (128 x 256 lanes x 4 x 16 bytes = 2 MB) and
         // leave half the compute units, and most wave slots, to work on other streams while this kernel waits on the
         // link (kernels sharing a compute unit with it run several times slower: its host reads fill the memory queues)
-        const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), kStageBlocks));
+        const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), ahead ? 16 * kStageBlocks : kStageBlocks));
+        // (after a fetch ahead only a few rows are left: many workgroups walk the flags quickly)
         // one row per missed lookup, or (after a coalescing remap) one per distinct missed row
         const int32_t* list = rm->unique_miss_gid ? rm->unique_miss_gid : rm->miss_gid;
         const int32_t* count = rm->unique_miss_gid ? rm->n_unique_miss : rm->n_hit_miss + 1;
         hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, list, count, h->ws.meta,
-                           (u32x4*)staging, chunks, lpr, h->buf.max_L, ahead ? h->ws.fetched : (const uint8_t*)nullptr);
+                           (u32x4*)staging, chunks, lpr, h->buf.max_L, ahead ? h->ws.fetched : (const uint8_t*)nullptr, 0);
     }
     if (G > 0) pool(s, split ? 2 : 0, split ? "pool_short_staged" : (mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group")));
     if (split) {   // the output is complete, in the caller's stream order, when this call returns
@@ -444,16 +417,22 @@ hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_
         if ((e = hipEventCreateWithFlags(&h->ev_pf_fork, hipEventDisableTiming)) != hipSuccess) return e;
         if ((e = hipEventCreateWithFlags(&h->ev_pf_done, hipEventDisableTiming)) != hipSuccess) return e;
     }
-    if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(h->pf_stream, h->ev_pf_fork, 0)) != hipSuccess) return e;
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int gpb = kBlock / lpr;
     const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kUnroll), kStageBlocks));
+    {   // on the caller's stream, before the update kernel: beside that kernel it would crawl (see k_stage_misses)
+        Timed t(h, s, "mark_ahead");
+        const int mgrid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, kBlock), 256 * 8));
+        hipLaunchKernelGGL(k_mark_ahead, dim3(mgrid), dim3(kBlock), 0, s, next_rm->miss_gid, next_rm->n_hit_miss + 1,
+                           excl, n_excl, h->ws.fetched, h->buf.max_L);
+    }
+    if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(h->pf_stream, h->ev_pf_fork, 0)) != hipSuccess) return e;
     {
         Timed t(h, h->pf_stream, "fetch_ahead");
-        hipLaunchKernelGGL(k_fetch_ahead, dim3(grid), dim3(kBlock), 0, h->pf_stream, next_rm->miss_gid, next_rm->n_hit_miss + 1,
-                           excl, n_excl, h->ws.meta, (u32x4*)h->ws.staging[area], h->ws.fetched, chunks, lpr, h->buf.max_L);
+        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, h->pf_stream, next_rm->miss_gid, next_rm->n_hit_miss + 1,
+                           h->ws.meta, (u32x4*)h->ws.staging[area], chunks, lpr, h->buf.max_L, h->ws.fetched, 1);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = hipEventRecord(h->ev_pf_done, h->pf_stream)) != hipSuccess) return e;
