@@ -429,8 +429,9 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     const int gpb = kBlock / LPG;
     // with cold rows to write the kernel is bound by the host link and a thousand workgroups saturate it; more only
     // take wave slots and memory queues from the kernels of the library's other streams
-    // (while rows are fetched ahead beside it, few enough that the fetch and the next remap get their share of every unit)
-    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? 256 : (h->k < h->N ? 1024 : 256 * 32));
+    // (while rows are fetched ahead beside it, few enough that the fetch gets its share of every unit's memory queue:
+    // swept 128-8192; 384-512 is best for 512-byte rows, 1024 for 128-byte rows)
+    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? (h->R >= 512 ? 512 : 1024) : (h->k < h->N ? 1024 : 256 * 32));
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), max_blocks));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
