@@ -132,6 +132,62 @@ def test_full_size_path_matches_oracle(full):
         assert np.array_equal(before, after), "rows without a lookup must not change"
 
 
+@pytest.mark.timeout(900)
+def test_full_size_look_ahead_steps_match_oracle(full):
+    """The order bench.py's `lookahead` leg times, at its size: remap(next) -> bwd_update_ahead(this, next) ->
+    fwd(next) over three consecutive batches.  Before each update the oracle computes, in report mode on the same
+    pinned tables, what every touched row and accumulator must become; after it (and a flush) the tables are compared,
+    and the next forward pass, part of whose rows were fetched while the update ran, is compared with the oracle's sums
+    over the updated tables."""
+    wl, dev, tabs, state, sc, smp = full
+    prof = [smp.batch(p, True) for p in range(4)]
+    batches = [smp.batch(e) for e in range(3, 6)]
+    max_L = max(int(b[0].numel()) for b in prof + batches)
+    sc.bind_buffers(wl.budget_bytes, max_L, wl.num_bags)
+    sc.build_cache(None, None, 0, wl.budget_bytes, 0)
+    for n, (idx, off) in enumerate(prof):
+        sc.build_cache(idx, off, wl.batch, wl.budget_bytes, 1 if n == len(prof) - 1 else 2)
+    sc.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    sc.set_tuning(binding.TUNE_PRESORT, 131072)
+    used0 = sc.get_counter(binding.COUNTER_AHEAD_USED)
+    ora_tabs, ora_state = [p.np for p in tabs], [p.np for p in state]
+    lr, eps = np.float32(wl.lr), np.float32(wl.eps)
+    rb = wl.row_base
+    rms = [sc.new_remap_out(max_L), sc.new_remap_out(max_L)]
+    host = [(i.cpu().numpy(), o.cpu().numpy()) for i, o in batches]
+    sc.remap(batches[0][0], batches[0][1], wl.batch, rms[0])
+    out = sc.embedding_bag_fwd(batches[0][0], batches[0][1], wl.batch, rms[0])
+    rc, want = oracle.embedding_bag_fwd(wl.rows, ora_tabs, host[0][0], host[0][1], wl.batch)
+    assert rc == 0
+    assert_close(out.cpu().numpy(), want, "first forward pass")
+    for e in range(2):
+        _say("look-ahead step", e)
+        (idx, off), (nidx, noff) = batches[e], batches[e + 1]
+        grad = smp.grads(e)
+        rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, host[e][0], host[e][1], wl.batch)
+        rc2, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, ora_tabs, ora_state, 1, host[e][0], host[e][1], wl.batch,
+                                                          grad.cpu().numpy(), lr, eps, report=True, n_unique=ug.size)
+        assert rc == rc2 == 0
+        sc.remap(nidx, noff, wl.batch, rms[(e + 1) % 2])
+        sc.embedding_bag_bwd_update_ahead(idx, off, wl.batch, rms[e % 2], grad, float(lr), float(eps), rms[(e + 1) % 2],
+                                          int(nidx.numel()))
+        sc.flush_cache()
+        assert sc.sync_status() == 0
+        ut = np.searchsorted(rb, ug, side="right") - 1
+        for t in range(wl.num_tables):
+            sel = ut == t
+            rows_t = ug[sel] - rb[t]
+            assert_close(tabs[t].np[rows_t], nr[sel].astype(np.float32), f"updated rows of table {t}")
+            assert_close(state[t].np[rows_t], ns[sel].astype(np.float32), f"accumulators of table {t}")
+        rc, want = oracle.embedding_bag_fwd(wl.rows, ora_tabs, host[e + 1][0], host[e + 1][1], wl.batch)
+        assert rc == 0
+        out = sc.embedding_bag_fwd(nidx, noff, wl.batch, rms[(e + 1) % 2])
+        assert_close(out.cpu().numpy(), want, f"forward pass of batch {e + 1} after the update of batch {e}")
+    assert sc.sync_status() == 0
+    assert sc.get_counter(binding.COUNTER_AHEAD_USED) - used0 == 2
+    sc.set_tuning(binding.TUNE_LOOKAHEAD, 0)
+
+
 def _full_size_sgd_step(wl, P):
     """One SGD workload at the size bench.py runs it: build_cache over P profile batches, then one batch through
     remap, forward and backward -- integer outputs bit-exact, pooled sums and every updated row within tolerance --
