@@ -381,7 +381,7 @@ def run_lookahead(b: Bench, K: int, W: int) -> dict:
         nidx, noff = b.batches[(e + 1) % n]
         s.remap(nidx, noff, wl.batch, rms[(e + 1) % 2])
         s.embedding_bag_bwd_update_ahead(idx, off, wl.batch, rms[e % 2], b.grads[e % len(b.grads)], wl.lr, eps,
-                                         rms[(e + 1) % 2], int(nidx.numel()))
+                                         rms[(e + 1) % 2], nidx, noff, wl.batch)
         s.embedding_bag_fwd(nidx, noff, wl.batch, rms[(e + 1) % 2], b.out)
         return int(idx.numel())
 

@@ -101,8 +101,7 @@ typedef struct {
  * host link and leave room for them. */
 #define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 8192; default 0: 8192 with every row cached, else 1024 (512 for rows of 512 bytes or more while rows are fetched ahead) */
 /* Non-zero: scars_remap may be called for the next batch before scars_embedding_bag_bwd_update of the current one (it
- * then leaves alone everything that update uses: it writes no pairs and starts no preparation; under
- * SCARS_TUNE_PRESORT the preparation starts in scars_embedding_bag_fwd instead), and
+ * then leaves alone everything that update uses: it writes no pairs and starts no preparation), and
  * scars_embedding_bag_bwd_update_ahead is allowed.  The two batches need remap outputs of their own. */
 #define SCARS_TUNE_LOOKAHEAD 6                  /* default 0 */
 
@@ -232,16 +231,19 @@ int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices
  * transfer of a batch's embeddings; Section IV attributes the update's time to writes of rows to host memory, which
  * use the link's other direction).  For training loops that know the next batch:
  *     scars_remap(next) -> scars_embedding_bag_bwd_update_ahead(this, next_rm) -> scars_embedding_bag_fwd(next) -> ...
- * `next_rm` / `next_L`: outputs of a scars_remap already enqueued on `stream` for the next batch (arrays of their own,
- * without unique_miss_gid).  A missed row of the next batch is fetched now, into a second staging area and on a
+ * `next_rm`, `d_next_offsets`, `next_L`, `next_B`: the next batch as given to, and the outputs of, a scars_remap
+ * already enqueued on `stream` (arrays of their own, without unique_miss_gid).  A missed row of the next batch is fetched now, into a second staging area and on a
  * stream the library owns, unless this update writes that row (a search in this batch's sorted list of distinct
  * rows); scars_embedding_bag_fwd for `next_rm` then fetches only the rows left out, after the update.  No row is read
- * while it may be written, so every result equals that of the calls made one batch after the other.
+ * while it may be written, so every result equals that of the calls made one batch after the other.  Under
+ * SCARS_TUNE_PRESORT the integer half of the next batch's backward pass is prepared beside this update as well (in a
+ * second set of workspace arrays), so that the next update starts at its reduce kernels.
  * Needs SCARS_TUNE_LOOKAHEAD = 1 (SCARS_ERR_INVALID_ARG otherwise).  Nothing is fetched ahead when L = 0. */
 int32_t scars_embedding_bag_bwd_update_ahead(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
                                              int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
                                              float lr, float eps, const scars_bwd_out* out,
-                                             const scars_remap_out* next_rm, int64_t next_L, void* stream);
+                                             const scars_remap_out* next_rm, const int32_t* d_next_offsets,
+                                             int64_t next_L, int64_t next_B, void* stream);
 
 /* Hot / normal samples (Section III: samples that "only need hot embeddings" versus the rest, so that
  * mini-batches of one kind can be composed).  Sample b is hot when none of its lookups over all T tables is a

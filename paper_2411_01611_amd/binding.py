@@ -111,7 +111,7 @@ def lib():
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
         L.scars_embedding_bag_bwd_update_ahead.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
-                                                           C.POINTER(_BwdOut), C.POINTER(_RemapOut), i64, vp]
+                                                           C.POINTER(_BwdOut), C.POINTER(_RemapOut), vp, i64, i64, vp]
         L.scars_classify_samples.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), C.POINTER(_ClassifyOut), vp]
         L.scars_partition_batch.argtypes = [vp, vp, vp, i64, i64, vp, vp, C.POINTER(_SubbatchOut), vp]
         L.scars_portion_usage.argtypes = [vp, vp, i64, i64, C.POINTER(_RemapOut), i64, i32, vp, vp]
@@ -391,7 +391,8 @@ class Scars:
         return out
 
     def embedding_bag_bwd_update_ahead(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,
-                                       grad_out: torch.Tensor, lr: float, eps: float, next_rm: RemapOut, next_L: int,
+                                       grad_out: torch.Tensor, lr: float, eps: float, next_rm: RemapOut,
+                                       next_indices: torch.Tensor, next_offsets: torch.Tensor, next_B: int,
                                        out: Optional[BwdOut] = None) -> Optional[BwdOut]:
         """The update of this batch, with the next batch's missed rows fetched beside it (TUNE_LOOKAHEAD must be on)."""
         L = int(indices.numel())
@@ -402,7 +403,8 @@ class Scars:
         self._check(lib().scars_embedding_bag_bwd_update_ahead(self._h, self._i32(indices), self._i32(offsets), L, B,
                                                                C.byref(c), grad_out.data_ptr(), lr, eps,
                                                                C.byref(co) if co is not None else None, C.byref(cn),
-                                                               next_L, _stream()))
+                                                               self._i32(next_offsets), int(next_indices.numel()), next_B,
+                                                               _stream()))
         return out
 
     def classify_samples(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,

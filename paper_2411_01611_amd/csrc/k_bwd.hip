@@ -529,7 +529,7 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
 
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out,
-                      const scars_remap_out* next_rm, int64_t next_L) {
+                      const scars_remap_out* next_rm, const int32_t* next_off, int64_t next_L, int64_t next_B) {
     Workspace& ws = h->ws;
     // rows fetched by this batch's forward pass are still in a staging area: cold rows are read from there
     const int area = h->staged_area(rm->loc);
@@ -574,7 +574,17 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int lpg = next_pow2_host(h->D / 4);
     // long runs (HBM-bound) beside the per-row kernel (bound by the host link while rows are cold)
     hipStream_t s2 = s;
-    const bool split = h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
+    // ... and the integer half of the next batch's backward pass is prepared beside this update too, on the side
+    // stream and in the second set of segment arrays (this update still reads the first); it starts now, before the
+    // update kernels are enqueued, and the sets change places when they are
+    const bool prep_next = h->ahead_active && h->presort_min_L > 0 && next_L >= h->presort_min_L;
+    if (prep_next) {
+        swap_segment_sets(h);
+        const hipError_t e = start_presort(h, s, next_off, next_L, next_B, next_rm);
+        swap_segment_sets(h);
+        if (e != hipSuccess) return e;
+    }
+    const bool split = !prep_next && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
     if (split) {
         hipError_t e = side_fork(h, s);
         if (e != hipSuccess) return e;
@@ -592,6 +602,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         if (e == hipSuccess) e = hipStreamWaitEvent(s, h->ev_join, 0);
         if (e != hipSuccess) return e;
     }
+    if (prep_next) swap_segment_sets(h);   // what was prepared is what the next call finds
     return hipGetLastError();
 }
 

@@ -357,10 +357,6 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         if (a == area || h->stg[a].loc == rm->loc) h->stg[a].valid = false;
     h->stg[area].valid = L > 0 && h->k < h->N;
     h->stg[area].loc = rm->loc;
-    // with look-ahead the integer half of this batch's backward pass starts here, beside the fetch and the pooling
-    if (h->lookahead && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {
-        if ((e0 = start_presort(h, s, off, L, B, rm)) != hipSuccess) return e0;   // (the side stream keeps its own order)
-    }
     // 2: bags of one or two lookups, several bags per lane group; 1: long bags, a wave per bag; 0: a group per bag
     const int mode = L < 2 * G ? 2 : ((lpr < 64 && L >= G * 2 * (kWave / lpr)) ? 1 : 0);
     auto pool = [&](hipStream_t st, int filter, const char* name) {

@@ -82,6 +82,16 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
     w.staging[0] = take(max_L * h->R);
     w.staging[1] = take(max_L * h->R);
     w.fetched = (uint8_t*)take(max_L);
+    for (int i = 0; i < 2; ++i) {
+        w.alt.key_buf[i] = (uint32_t*)take(max_L * 4);
+        w.alt.val_buf[i] = (uint32_t*)take(max_L * 4);
+    }
+    w.alt.seg_start = (int32_t*)take((max_L + 1) * 4);
+    w.alt.unique_gid = (int32_t*)take(max_L * 4);
+    w.alt.n_unique = (int32_t*)take(16);
+    w.alt.unique_slot = (int32_t*)take(max_L * 4);
+    w.alt.first_bag = (uint32_t*)take(max_L * 4);
+    w.alt.chunk_run = (int32_t*)take((chunks + 1) * 4);
     w.total_bytes = off;
     return w;
 }
@@ -103,6 +113,20 @@ hipError_t side_fork(scars_handle* h, hipStream_t s) {
     }
     if ((e = hipEventRecord(h->ev_fork, s)) != hipSuccess) return e;
     return hipStreamWaitEvent(h->side, h->ev_fork, 0);
+}
+
+void swap_segment_sets(scars_handle* h) {
+    Workspace& w = h->ws;
+    for (int i = 0; i < 2; ++i) {
+        std::swap(w.key_buf[i], w.alt.key_buf[i]);
+        std::swap(w.val_buf[i], w.alt.val_buf[i]);
+    }
+    std::swap(w.seg_start, w.alt.seg_start);
+    std::swap(w.unique_gid, w.alt.unique_gid);
+    std::swap(w.n_unique, w.alt.n_unique);
+    std::swap(w.unique_slot, w.alt.unique_slot);
+    std::swap(w.first_bag, w.alt.first_bag);
+    std::swap(w.chunk_run, w.alt.chunk_run);
 }
 
 // Make stream s wait for rows being fetched ahead on the library's third stream, if any are outstanding.
@@ -376,8 +400,8 @@ int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const
 
 static int32_t bwd_update_impl(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
                                const scars_remap_out* rm, const float* d_grad_out, float lr, float eps,
-                               const scars_bwd_out* out, const scars_remap_out* next_rm, int64_t next_L, void* stream,
-                               const char* who) {
+                               const scars_bwd_out* out, const scars_remap_out* next_rm, const int32_t* d_next_offsets,
+                               int64_t next_L, int64_t next_B, void* stream, const char* who) {
     int32_t rc = check_batch(h, d_indices, d_offsets, L, B, who);
     if (rc) return rc;
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, std::string(who) + ": build_cache has not selected a hot set");
@@ -387,14 +411,16 @@ static int32_t bwd_update_impl(scars_handle* h, const int32_t* d_indices, const 
         return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": bwd_out has a null array");
     if (next_rm) {
         if (!h->lookahead) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": SCARS_TUNE_LOOKAHEAD is off");
-        if (next_L < 0 || next_L > h->buf.max_L) return fail(h, SCARS_ERR_WORKSPACE, std::string(who) + ": next batch larger than the bound max_L");
+        if (!d_next_offsets || next_L < 0 || next_B < 0) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": null or negative argument for the next batch");
+        if (next_L > h->buf.max_L || (int64_t)h->T * next_B > h->buf.max_G)
+            return fail(h, SCARS_ERR_WORKSPACE, std::string(who) + ": next batch larger than the bound max_L / max_G");
         if ((rc = check_remap_out(h, next_rm, next_L, who))) return rc;
         if (next_rm->unique_miss_gid) return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": the next batch was remapped with unique_miss_gid");
         if (next_rm->loc == rm->loc || next_rm->miss_gid == rm->miss_gid)
             return fail(h, SCARS_ERR_INVALID_ARG, std::string(who) + ": the next batch needs remap outputs of its own");
     }
     hipError_t e = side_join(h, (hipStream_t)stream);
-    if (e == hipSuccess) e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, next_L);
+    if (e == hipSuccess) e = launch_bwd(h, (hipStream_t)stream, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, d_next_offsets, next_L, next_B);
     if (e != hipSuccess) return hip_fail(h, e, who);
     if (L > 0) h->dirty = true;
     return SCARS_OK;
@@ -403,17 +429,18 @@ static int32_t bwd_update_impl(scars_handle* h, const int32_t* d_indices, const 
 int32_t scars_embedding_bag_bwd_update(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
                                        int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
                                        float lr, float eps, const scars_bwd_out* out, void* stream) {
-    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, nullptr, 0, stream,
+    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, nullptr, nullptr, 0, 0, stream,
                            "embedding_bag_bwd_update");
 }
 
 int32_t scars_embedding_bag_bwd_update_ahead(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets,
                                              int64_t L, int64_t B, const scars_remap_out* rm, const float* d_grad_out,
                                              float lr, float eps, const scars_bwd_out* out,
-                                             const scars_remap_out* next_rm, int64_t next_L, void* stream) {
+                                             const scars_remap_out* next_rm, const int32_t* d_next_offsets,
+                                             int64_t next_L, int64_t next_B, void* stream) {
     if (h && !next_rm) return fail(h, SCARS_ERR_INVALID_ARG, "embedding_bag_bwd_update_ahead: null next batch");
-    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, next_L, stream,
-                           "embedding_bag_bwd_update_ahead");
+    return bwd_update_impl(h, d_indices, d_offsets, L, B, rm, d_grad_out, lr, eps, out, next_rm, d_next_offsets, next_L,
+                           next_B, stream, "embedding_bag_bwd_update_ahead");
 }
 
 int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,

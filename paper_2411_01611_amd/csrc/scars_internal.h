@@ -63,6 +63,18 @@ struct Workspace {
     uint32_t* blk_seg_b;      //   that half of the pass may run on the side stream beside calls that use blk_hit/blk_miss)
     uint32_t* plan_cc;        // [kPlanBins] rows per count value, [kPlanBigCap] counts at or above kPlanBins, [4] their number
     void* staging[2];         // [max_L][R] rows fetched over the host link; the second area is for rows fetched ahead
+    // a second set of the arrays that hold a batch's sorted pairs and run starts, so that the next batch's can be
+    // prepared while this batch's are still being read (look-ahead); swap_segment_sets exchanges the two
+    struct SegSet {
+        uint32_t* key_buf[2];
+        uint32_t* val_buf[2];
+        int32_t* seg_start;
+        int32_t* unique_gid;
+        int32_t* n_unique;
+        int32_t* unique_slot;
+        uint32_t* first_bag;
+        int32_t* chunk_run;
+    } alt;
     uint8_t* fetched;         // [max_L] 1 = this missed lookup's row was fetched ahead
     int64_t total_bytes;
 };
@@ -189,11 +201,12 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
 // k_bwd.hip
 hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out,
-                      const scars_remap_out* next_rm, int64_t next_L);
+                      const scars_remap_out* next_rm, const int32_t* next_off, int64_t next_L, int64_t next_B);
 // k_fwd.hip: missed rows of a remapped batch that are not in the sorted list `excl` -> staging area `area`
 hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
                               const int32_t* excl, const int32_t* n_excl, int area);
 hipError_t pf_join(scars_handle* h, hipStream_t s);
+void swap_segment_sets(scars_handle* h);
 hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B, const scars_remap_out* rm);
 hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                                const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out);

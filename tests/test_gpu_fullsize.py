@@ -170,7 +170,7 @@ def test_full_size_look_ahead_steps_match_oracle(full):
         assert rc == rc2 == 0
         sc.remap(nidx, noff, wl.batch, rms[(e + 1) % 2])
         sc.embedding_bag_bwd_update_ahead(idx, off, wl.batch, rms[e % 2], grad, float(lr), float(eps), rms[(e + 1) % 2],
-                                          int(nidx.numel()))
+                                          nidx, noff, wl.batch)
         sc.flush_cache()
         assert sc.sync_status() == 0
         ut = np.searchsorted(rb, ug, side="right") - 1

@@ -123,7 +123,7 @@ def test_graph_replay_of_two_steps_in_the_look_ahead_order_matches_oracle():
                 n = 1 - e
                 s.remap(dev[n][0], dev[n][1], wl.batch, rms[n])
                 s.embedding_bag_bwd_update_ahead(dev[e][0], dev[e][1], wl.batch, rms[e], dgr[e], float(lr), float(eps),
-                                                 rms[n], nL[n])
+                                                 rms[n], dev[n][0], dev[n][1], wl.batch)
                 s.embedding_bag_fwd(dev[n][0], dev[n][1], wl.batch, rms[n], outs[n])
     torch.cuda.current_stream().wait_stream(side)
     for rep in range(3):

@@ -91,7 +91,7 @@ def test_lookahead_steps_match_the_calls_made_one_after_the_other(name, budget, 
         cur, nxt = rms[e % 2], rms[(e + 1) % 2]
         s.remap(dev[e + 1][0], dev[e + 1][1], wl.batch, nxt)
         s.embedding_bag_bwd_update_ahead(dev[e][0], dev[e][1], wl.batch, cur, grads[e].to(c.dev), lr, eps, nxt,
-                                         int(bs[e + 1][0].numel()))
+                                         dev[e + 1][0], dev[e + 1][1], wl.batch)
         _ora_step(c, bs[e], grads[e])
         out = s.embedding_bag_fwd(dev[e + 1][0], dev[e + 1][1], wl.batch, nxt)
         assert_close(out.cpu().numpy(), _ora_fwd(c, bs[e + 1]), f"forward pass of batch {e + 1}")
@@ -102,6 +102,8 @@ def test_lookahead_steps_match_the_calls_made_one_after_the_other(name, budget, 
         assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
     # rows were fetched ahead whenever something can miss
     assert s.get_counter(binding.COUNTER_AHEAD_USED) == (0 if budget == "all" else steps)
+    # ... and with the side-stream option every update but the first found its segments prepared beside the one before
+    assert s.get_counter(binding.COUNTER_PREPARED_USED) == (steps - 1 if presort and budget != "all" else 0)
     c.close()
 
 
@@ -121,7 +123,7 @@ def test_lookahead_rows_updated_by_this_batch_are_left_to_the_forward_pass():
     s.remap(d0[0], d0[1], wl.batch, r0)
     s.embedding_bag_fwd(d0[0], d0[1], wl.batch, r0)
     s.remap(d1[0], d1[1], wl.batch, r1)
-    s.embedding_bag_bwd_update_ahead(d0[0], d0[1], wl.batch, r0, g.to(c.dev), float(wl.lr), float(wl.eps), r1, int(b1[0].numel()))
+    s.embedding_bag_bwd_update_ahead(d0[0], d0[1], wl.batch, r0, g.to(c.dev), float(wl.lr), float(wl.eps), r1, d1[0], d1[1], wl.batch)
     _ora_step(c, b0, g)
     out = s.embedding_bag_fwd(d1[0], d1[1], wl.batch, r1)
     assert_close(out.cpu().numpy(), _ora_fwd(c, b1), "forward pass over freshly updated rows")
@@ -140,23 +142,23 @@ def test_lookahead_calls_that_do_not_line_up():
     dg = g.to(c.dev)
     lr, eps = float(wl.lr), float(wl.eps)
     rms = [s.new_remap_out() for _ in range(3)]
-    n = lambda e: int(bs[e][0].numel())
+    n = lambda e: (dev[e][0], dev[e][1], wl.batch)
     s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
     s.remap(dev[1][0], dev[1][1], wl.batch, rms[1])
     with pytest.raises(binding.ScarsError):      # the option is off
-        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], n(1))
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], *n(1))
     s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
     with pytest.raises(binding.ScarsError):      # the next batch needs arrays of its own
-        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[0], n(0))
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[0], *n(0))
     rmc = s.new_remap_out(coalesce=True)
     s.remap(dev[1][0], dev[1][1], wl.batch, rmc, coalesce=True)
     with pytest.raises(binding.ScarsError):      # not with each distinct missed row listed once
-        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rmc, n(1))
+        s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rmc, *n(1))
     # (1) rows fetched ahead for batch 1, but the forward pass that follows is batch 2's; then batch 1's after all
     s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
     s.embedding_bag_fwd(dev[0][0], dev[0][1], wl.batch, rms[0])
     s.remap(dev[1][0], dev[1][1], wl.batch, rms[1])
-    s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], n(1))
+    s.embedding_bag_bwd_update_ahead(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps, rms[1], *n(1))
     _ora_step(c, bs[0], g)
     s.remap(dev[2][0], dev[2][1], wl.batch, rms[2])
     out = s.embedding_bag_fwd(dev[2][0], dev[2][1], wl.batch, rms[2])
@@ -164,7 +166,7 @@ def test_lookahead_calls_that_do_not_line_up():
     out = s.embedding_bag_fwd(dev[1][0], dev[1][1], wl.batch, rms[1])
     assert_close(out.cpu().numpy(), _ora_fwd(c, bs[1]), "forward pass of the batch fetched ahead, later")
     # (2) a plain update in between makes what was fetched ahead stale: it must not be used
-    s.embedding_bag_bwd_update_ahead(dev[1][0], dev[1][1], wl.batch, rms[1], dg, lr, eps, rms[2], n(2))
+    s.embedding_bag_bwd_update_ahead(dev[1][0], dev[1][1], wl.batch, rms[1], dg, lr, eps, rms[2], *n(2))
     _ora_step(c, bs[1], g)
     s.embedding_bag_bwd_update(dev[0][0], dev[0][1], wl.batch, rms[0], dg, lr, eps)
     _ora_step(c, bs[0], g)
@@ -172,7 +174,7 @@ def test_lookahead_calls_that_do_not_line_up():
     assert_close(out.cpu().numpy(), _ora_fwd(c, bs[2]), "forward pass after an update that followed the fetch")
     # (3) a re-selection in between
     s.remap(dev[3][0], dev[3][1], wl.batch, rms[0])
-    s.embedding_bag_bwd_update_ahead(dev[2][0], dev[2][1], wl.batch, rms[2], dg, lr, eps, rms[0], n(3))
+    s.embedding_bag_bwd_update_ahead(dev[2][0], dev[2][1], wl.batch, rms[2], dg, lr, eps, rms[0], *n(3))
     _ora_step(c, bs[2], g)
     s.build_cache(None, None, 0, c.budget // 2, 1)
     s.remap(dev[3][0], dev[3][1], wl.batch, rms[0])
