@@ -170,7 +170,14 @@ def measure_link(dev) -> dict:
             torch.cuda.synchronize()
             best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
         out[name] = best
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    # two streams of this measurement's own, destroyed afterwards: a process has few hardware queues, and streams left
+    # behind here would push the library's side streams onto the queue of the stream the benchmark runs on
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    raw = [ctypes.c_void_p(), ctypes.c_void_p()]
+    for r in raw:
+        assert hip.hipStreamCreateWithFlags(ctypes.byref(r), 1) == 0
+    s1, s2 = torch.cuda.ExternalStream(raw[0].value), torch.cuda.ExternalStream(raw[1].value)
     best_in = best_out = 0.0
     for _ in range(3):
         torch.cuda.synchronize()
@@ -186,6 +193,10 @@ def measure_link(dev) -> dict:
         torch.cuda.synchronize()
         best_in = max(best_in, n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9)
         best_out = max(best_out, n / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9)
+    del s1, s2, ev
+    torch.cuda.synchronize()
+    for r in raw:
+        assert hip.hipStreamDestroy(r) == 0
     out["h2d_duplex_GBs"], out["d2h_duplex_GBs"] = best_in, best_out
     host.free()
     host2.free()

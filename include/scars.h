@@ -24,6 +24,11 @@
  *    on the caller's stream (a hipStream_t passed as void*; NULL = the default stream) and the
  *    call returns without waiting unless stated.  Calls on one handle must be issued in stream
  *    order; two calls on one handle must not run concurrently.
+ *  - Some options (SCARS_TUNE_PRESORT, SCARS_TUNE_LOOKAHEAD) run part of a call on up to two streams the library
+ *    owns (default priority, non-blocking, created on first use, always joined back into the caller's stream before
+ *    the results are needed).  They only overlap with the caller's stream if they sit on other hardware queues: a
+ *    process has few (4 by default), handed out as streams are created, so create a handle's streams (its first
+ *    calls) before many streams of your own.
  *  - Two errors are detected on the device and latched in the handle's status word, to be read by
  *    scars_sync_status: SCARS_ERR_INDEX_RANGE (an index < 0 or >= rows[t]: that lookup is treated
  *    as absent everywhere -- not counted, neither hit nor miss, adds nothing, updates nothing) and

@@ -562,10 +562,22 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
                  use_staged ? ws.staging[area] : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0)};
-    // the next batch's missed rows, except those this update writes, are fetched while it runs (its own stream and
-    // staging area); the list of this batch's distinct rows is complete at this point of stream s
+    // Look-ahead.  (1) The integer half of the next batch's backward pass is prepared beside this update, on the side
+    // stream and in the second set of segment arrays (this update still reads the first); the sets change places once
+    // the update kernels are enqueued.  It is enqueued before the fetch: should the two library streams share a
+    // hardware queue, a fetch of milliseconds in front of it would push it beside the next forward pass.
+    const bool fetch_next = next_rm && next_L > 0 && h->k < h->N;
+    const bool prep_next = fetch_next && h->presort_min_L > 0 && next_L >= h->presort_min_L;
+    if (prep_next) {
+        swap_segment_sets(h);
+        const hipError_t e = start_presort(h, s, next_off, next_L, next_B, next_rm);
+        swap_segment_sets(h);
+        if (e != hipSuccess) return e;
+    }
+    // (2) The next batch's missed rows, except those this update writes, are fetched while it runs (a stream and a
+    // staging area of their own); the list of this batch's distinct rows is complete at this point of stream s.
     h->ahead_active = false;
-    if (next_rm && next_L > 0 && h->k < h->N) {
+    if (fetch_next) {
         hipError_t e = pf_join(h, s);
         if (e == hipSuccess) e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0);
         if (e != hipSuccess) return e;
@@ -574,16 +586,6 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const int lpg = next_pow2_host(h->D / 4);
     // long runs (HBM-bound) beside the per-row kernel (bound by the host link while rows are cold)
     hipStream_t s2 = s;
-    // ... and the integer half of the next batch's backward pass is prepared beside this update too, on the side
-    // stream and in the second set of segment arrays (this update still reads the first); it starts now, before the
-    // update kernels are enqueued, and the sets change places when they are
-    const bool prep_next = h->ahead_active && h->presort_min_L > 0 && next_L >= h->presort_min_L;
-    if (prep_next) {
-        swap_segment_sets(h);
-        const hipError_t e = start_presort(h, s, next_off, next_L, next_B, next_rm);
-        swap_segment_sets(h);
-        if (e != hipSuccess) return e;
-    }
     const bool split = !prep_next && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
     if (split) {
         hipError_t e = side_fork(h, s);

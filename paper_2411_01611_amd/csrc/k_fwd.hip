@@ -340,6 +340,18 @@ static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, 
     }
 }
 
+// The library's second stream (default priority, created on first use): pooling beside the fetch in the forward pass,
+// and the fetch for the next batch beside the update in the backward pass; the two uses never overlap in time.
+static hipError_t ensure_pool_stream(scars_handle* h) {
+    if (h->pool_stream) return hipSuccess;
+    hipError_t e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pool_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pool_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pf_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pf_done, hipEventDisableTiming);
+    return e;
+}
+
 hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
                       const scars_remap_out* rm, float* out) {
     const int chunks = h->R / 16;
@@ -372,12 +384,8 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     // batch) are pooled on the side stream while the missed rows are still being fetched; the rest follow the fetch.
     const bool split = mode == 2 && G > 0 && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
     if (split) {   // a stream of its own: the side stream may still be busy with the backward pass's sort
-        hipError_t e = hipSuccess;
-        if (!h->pool_stream) {
-            if ((e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking)) != hipSuccess) return e;
-            if ((e = hipEventCreateWithFlags(&h->ev_pool_fork, hipEventDisableTiming)) != hipSuccess) return e;
-            if ((e = hipEventCreateWithFlags(&h->ev_pool_join, hipEventDisableTiming)) != hipSuccess) return e;
-        }
+        hipError_t e = ensure_pool_stream(h);
+        if (e != hipSuccess) return e;
         if ((e = hipEventRecord(h->ev_pool_fork, s)) != hipSuccess) return e;
         if ((e = hipStreamWaitEvent(h->pool_stream, h->ev_pool_fork, 0)) != hipSuccess) return e;
         pool(h->pool_stream, 1, "pool_short");
@@ -407,12 +415,9 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
 
 hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
                               const int32_t* excl, const int32_t* n_excl, int area) {
-    hipError_t e = hipSuccess;
-    if (!h->pf_stream) {
-        if ((e = hipStreamCreateWithFlags(&h->pf_stream, hipStreamNonBlocking)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&h->ev_pf_fork, hipEventDisableTiming)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&h->ev_pf_done, hipEventDisableTiming)) != hipSuccess) return e;
-    }
+    hipError_t e = ensure_pool_stream(h);
+    if (e != hipSuccess) return e;
+    hipStream_t const pf = h->pool_stream;
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int gpb = kBlock / lpr;
@@ -424,14 +429,14 @@ hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_
                            excl, n_excl, h->ws.fetched, h->buf.max_L);
     }
     if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(h->pf_stream, h->ev_pf_fork, 0)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(pf, h->ev_pf_fork, 0)) != hipSuccess) return e;
     {
-        Timed t(h, h->pf_stream, "fetch_ahead");
-        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, h->pf_stream, next_rm->miss_gid, next_rm->n_hit_miss + 1,
+        Timed t(h, pf, "fetch_ahead");
+        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, pf, next_rm->miss_gid, next_rm->n_hit_miss + 1,
                            h->ws.meta, (u32x4*)h->ws.staging[area], chunks, lpr, h->buf.max_L, h->ws.fetched, 1);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = hipEventRecord(h->ev_pf_done, h->pf_stream)) != hipSuccess) return e;
+    if ((e = hipEventRecord(h->ev_pf_done, pf)) != hipSuccess) return e;
     h->pf_pending = true;
     h->stg[area].valid = false;
     h->ahead.valid = true;

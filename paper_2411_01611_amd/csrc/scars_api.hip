@@ -220,10 +220,6 @@ int32_t scars_destroy(scars_handle* h) {
         (void)hipStreamDestroy(h->pool_stream);
         (void)hipEventDestroy(h->ev_pool_fork);
         (void)hipEventDestroy(h->ev_pool_join);
-    }
-    if (h->pf_stream) {
-        (void)hipStreamSynchronize(h->pf_stream);
-        (void)hipStreamDestroy(h->pf_stream);
         (void)hipEventDestroy(h->ev_pf_fork);
         (void)hipEventDestroy(h->ev_pf_done);
     }
@@ -265,7 +261,7 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     if (k > 0 && (!b->hot_gid || !b->cache || (h->optimizer == SCARS_OPT_ADAGRAD && !b->state_cache)))
         return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: cache buffers missing");
     if (h->side) (void)hipStreamSynchronize(h->side);   // nothing may still be using the buffers bound before
-    if (h->pf_stream) (void)hipStreamSynchronize(h->pf_stream);
+    if (h->pool_stream) (void)hipStreamSynchronize(h->pool_stream);
     h->pf_pending = false;
     h->side_pending = false;
     h->presort_valid = false;
@@ -671,7 +667,6 @@ int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e == hipSuccess && h->side) e = hipStreamSynchronize(h->side);
     if (e == hipSuccess && h->pool_stream) e = hipStreamSynchronize(h->pool_stream);
-    if (e == hipSuccess && h->pf_stream) e = hipStreamSynchronize(h->pf_stream);
     if (e != hipSuccess) return hip_fail(h, e, "profile_read");
     std::vector<scars_kernel_time> acc;
     for (auto& p : h->timer.pending) {

@@ -113,9 +113,8 @@ struct scars_handle {
     // look-ahead (SCARS_TUNE_LOOKAHEAD): rows of the next batch fetched while this batch is updated
     bool lookahead = false;
     struct { bool valid = false; const int32_t* loc = nullptr; int area = 0; } ahead;   // what was fetched ahead, where
-    hipStream_t pf_stream = nullptr;
     hipEvent_t ev_pf_fork = nullptr, ev_pf_done = nullptr;
-    bool pf_pending = false;             // work on pf_stream that no other stream has waited for yet
+    bool pf_pending = false;             // a fetch on pool_stream that no other stream has waited for yet
     bool ahead_active = false;           // the backward pass being enqueued has a fetch running beside it
     std::string err;
     // side stream: the integer half of the backward pass can be started by remap and run beside the forward pass
