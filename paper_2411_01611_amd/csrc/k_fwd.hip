@@ -13,6 +13,7 @@ namespace scars {
 
 constexpr int kUnroll = 4;       // rows in flight per lane group when staging misses
 constexpr int kStageBlocks = 128;  // workgroups of the staging kernel
+constexpr int kAheadBlocks = 128;  // ... when it fetches ahead, beside the update kernel (64 and 512 are slower)
 constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
@@ -421,7 +422,7 @@ hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int gpb = kBlock / lpr;
-    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kUnroll), kStageBlocks));
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kUnroll), kAheadBlocks));
     {   // on the caller's stream, before the update kernel: beside that kernel it would crawl (see k_stage_misses)
         Timed t(h, s, "mark_ahead");
         const int mgrid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, kBlock), 256 * 8));
