@@ -274,6 +274,32 @@ def _full_size_sgd_step(wl, P):
             assert_bf16_within(tabs[t].np[ug[sel] - rb[t]], nr[sel], f"updated bf16 rows of table {t}")
         else:
             assert_close(tabs[t].np[ug[sel] - rb[t]], nr[sel].astype(np.float32), f"updated rows of table {t}")
+    # (3) one step in the look-ahead order, as bench.py's second leg runs it: batch 0 once more, batch 1 behind it
+    sc.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    nidx, noff = smp.batch(1)
+    if int(nidx.numel()) <= max_L:
+        rm2 = sc.new_remap_out(max_L)
+        sc.remap(idx, off, wl.batch, rm)
+        sc.embedding_bag_fwd(idx, off, wl.batch, rm, out)
+        rc4, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, ora_tabs, None, 0, hi, ho, wl.batch, grad.cpu().numpy(), lr,
+                                                          np.float32(0.0), report=True, n_unique=ug.size)
+        assert rc4 == 0
+        sc.remap(nidx, noff, wl.batch, rm2)
+        sc.embedding_bag_bwd_update_ahead(idx, off, wl.batch, rm, grad, float(lr), 0.0, rm2, nidx, noff, wl.batch)
+        sc.flush_cache()
+        assert sc.sync_status() == 0
+        for t in range(wl.num_tables):
+            sel = ut == t
+            if bf16:
+                assert_bf16_within(tabs[t].np[ug[sel] - rb[t]], nr[sel], f"look-ahead: updated bf16 rows of table {t}")
+            else:
+                assert_close(tabs[t].np[ug[sel] - rb[t]], nr[sel].astype(np.float32), f"look-ahead: updated rows of table {t}")
+        rc5, want2 = oracle.embedding_bag_fwd(wl.rows, ora_tabs, nidx.cpu().numpy(), noff.cpu().numpy(), wl.batch)
+        assert rc5 == 0
+        out2 = sc.embedding_bag_fwd(nidx, noff, wl.batch, rm2)
+        assert_close(out2.cpu().numpy(), want2, f"look-ahead: pooled output of the next batch, {wl.name} at full size")
+        assert sc.sync_status() == 0
+        assert sc.get_counter(binding.COUNTER_AHEAD_USED) == (1 if k < wl.total_rows else 0)
     sc.close()
     for p in tabs:
         p.free()
