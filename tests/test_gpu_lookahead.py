@@ -185,3 +185,42 @@ def test_lookahead_calls_that_do_not_line_up():
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
     c.close()
+
+
+def test_lookahead_with_segment_outputs():
+    """With the sorted segments requested, the update sorts for itself and writes the caller's arrays; the rows it
+    leaves to the forward pass are then looked up in those arrays."""
+    wl = synth.workload("multi_hot", scale=0.004, batch=333)
+    c = GpuCase(wl, max_L=_room(wl))
+    s = c.s
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    s.set_tuning(binding.TUNE_PRESORT, 1)
+    c.build()
+    bs = _batches(c, 3, frac=0.5)
+    dev = [(b[0].to(c.dev), b[1].to(c.dev)) for b in bs]
+    rms = [s.new_remap_out(), s.new_remap_out()]
+    lr, eps = float(wl.lr), float(wl.eps)
+    s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
+    s.embedding_bag_fwd(dev[0][0], dev[0][1], wl.batch, rms[0])
+    for e in range(2):
+        g = c.sampler.grads(e)
+        bo = s.new_bwd_out(int(bs[e][0].numel()))
+        s.remap(dev[e + 1][0], dev[e + 1][1], wl.batch, rms[(e + 1) % 2])
+        s.embedding_bag_bwd_update_ahead(dev[e][0], dev[e][1], wl.batch, rms[e % 2], g.to(c.dev), lr, eps, rms[(e + 1) % 2],
+                                         dev[e + 1][0], dev[e + 1][1], wl.batch, bo)
+        rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, bs[e][0].numpy(), bs[e][1].numpy(), wl.batch)
+        U, nv = bo.n_unique.cpu().tolist()
+        assert rc == 0 and U == ug.size and nv == sg.size
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+        assert np.array_equal(bo.unique_gid.cpu().numpy()[:U], ug)
+        _ora_step(c, bs[e], g)
+        out = s.embedding_bag_fwd(dev[e + 1][0], dev[e + 1][1], wl.batch, rms[(e + 1) % 2])
+        assert_close(out.cpu().numpy(), _ora_fwd(c, bs[e + 1]), f"forward pass of batch {e + 1}")
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert s.get_counter(binding.COUNTER_AHEAD_USED) == 2
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+    assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
+    c.close()
