@@ -224,3 +224,44 @@ def test_lookahead_with_segment_outputs():
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
     assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
     c.close()
+
+
+@pytest.mark.parametrize("name", ["multi_hot_small", "host_spill_small"])
+def test_twenty_lookahead_steps_match_oracle(name):
+    """A long run of the look-ahead order with every side-stream path on: both staging areas, both sets of segment
+    arrays and all three streams change roles every step."""
+    wname, kw = CASES[name]
+    wl = synth.workload(wname, **kw)
+    c = GpuCase(wl, max_L=_room(wl))
+    s = c.s
+    s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    s.set_tuning(binding.TUNE_PRESORT, 1)
+    c.build()
+    steps = 20
+    bs = _batches(c, steps + 1, frac=0.2)
+    opt = wl.optimizer == "adagrad"
+    lr, eps = float(wl.lr), float(wl.eps if opt else 0.0)
+    rms = [s.new_remap_out(), s.new_remap_out()]
+    d = lambda e: (bs[e][0].to(c.dev), bs[e][1].to(c.dev))
+    cur = d(0)
+    s.remap(cur[0], cur[1], wl.batch, rms[0])
+    s.embedding_bag_fwd(cur[0], cur[1], wl.batch, rms[0])
+    for e in range(steps):
+        nxt = d(e + 1)
+        g = c.sampler.grads(e % 4)
+        s.remap(nxt[0], nxt[1], wl.batch, rms[(e + 1) % 2])
+        s.embedding_bag_bwd_update_ahead(cur[0], cur[1], wl.batch, rms[e % 2], g.to(c.dev), lr, eps, rms[(e + 1) % 2],
+                                         nxt[0], nxt[1], wl.batch)
+        _ora_step(c, bs[e], g)
+        out = s.embedding_bag_fwd(nxt[0], nxt[1], wl.batch, rms[(e + 1) % 2])
+        if e % 5 == 4:
+            assert_close(out.cpu().numpy(), _ora_fwd(c, bs[e + 1]), f"forward pass of batch {e + 1}")
+        cur = nxt
+    s.flush_cache()
+    assert s.sync_status() == 0
+    assert s.get_counter(binding.COUNTER_AHEAD_USED) == steps
+    assert s.get_counter(binding.COUNTER_PREPARED_USED) == steps - 1
+    assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after twenty steps")
+    if opt:
+        assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after twenty steps")
+    c.close()
