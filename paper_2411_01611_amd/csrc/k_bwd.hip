@@ -540,8 +540,9 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
     int32_t* unique_gid = out ? out->unique_gid : ws.unique_gid;
     const int64_t G = (int64_t)h->T * B;
-    // segments prepared on the side stream by the remap of this very batch (the caller's stream has already been
-    // made to wait for them); they are in the workspace arrays, built for staged cold rows when misses are possible
+    // segments prepared on the side stream for this very batch, by its remap or (look-ahead) beside the previous
+    // batch's update (the caller's stream has already been made to wait for them); they are in the workspace arrays,
+    // built for staged cold rows when misses are possible
     const bool prepared = h->presort_valid && h->presort_gid == rm->gid && h->presort_loc == rm->loc &&
                           h->presort_off == off && h->presort_L == L && h->presort_B == B && !out &&
                           h->presort_staged == use_staged;
