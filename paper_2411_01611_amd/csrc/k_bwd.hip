@@ -578,9 +578,12 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     // (2) The next batch's missed rows, except those this update writes, are fetched while it runs (a stream and a
     // staging area of their own); the list of this batch's distinct rows is complete at this point of stream s.
     h->ahead_active = false;
+    {   // a fetch still running beside an earlier update reads host rows: it must be over before this update writes any
+        const hipError_t e = pf_join(h, s);
+        if (e != hipSuccess) return e;
+    }
     if (fetch_next) {
-        hipError_t e = pf_join(h, s);
-        if (e == hipSuccess) e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0);
+        hipError_t e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0);
         if (e != hipSuccess) return e;
         h->ahead_active = true;
     }

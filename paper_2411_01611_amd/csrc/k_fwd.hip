@@ -442,6 +442,7 @@ hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_
     h->stg[area].valid = false;
     h->ahead.valid = true;
     h->ahead.loc = next_rm->loc;
+    h->ahead.miss_gid = next_rm->miss_gid;
     h->ahead.area = area;
     return hipSuccess;
 }

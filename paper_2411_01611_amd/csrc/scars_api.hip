@@ -353,17 +353,22 @@ static int32_t check_remap_out(scars_handle* h, const scars_remap_out* o, int64_
     return SCARS_OK;
 }
 
-int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
-                    const scars_remap_out* out, void* stream) {
-    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "remap");
+// What every remap does before its kernels: argument checks, and the look-ahead / preparation bookkeeping for the
+// arrays it is about to overwrite.
+static int32_t remap_prologue(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                              const scars_remap_out* out, hipStream_t s, const char* who) {
+    int32_t rc = check_batch(h, d_indices, d_offsets, L, B, who);
     if (rc) return rc;
-    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, "remap: build_cache has not selected a hot set");
-    if ((rc = check_remap_out(h, out, L, "remap"))) return rc;
+    if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, std::string(who) + ": build_cache has not selected a hot set");
+    if ((rc = check_remap_out(h, out, L, who))) return rc;
     for (int a = 0; a < 2; ++a)
         if (out->loc == h->stg[a].loc) h->stg[a].valid = false;   // these arrays no longer describe a staged batch
-    if (out->loc == h->ahead.loc) h->ahead.valid = false;
-    hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
+    if (out->loc == h->ahead.loc || out->miss_gid == h->ahead.miss_gid) {
+        // the fetch ahead may still be reading these arrays on the library's stream: wait for it, then drop its rows
+        if ((e = pf_join(h, s)) != hipSuccess) return hip_fail(h, e, "remap(join fetch)");
+        h->ahead.valid = false;
+    }
     // Segments still being prepared on the side stream read the previous batch's arrays and the sort buffers.  With
     // look-ahead this call may come while the previous batch's backward pass is still to be called: then it touches
     // nothing that pass uses (no pairs, no preparation: that starts with the forward pass instead), unless it is
@@ -373,7 +378,15 @@ int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_
         if (e != hipSuccess) return hip_fail(h, e, "remap(join)");
         h->presort_valid = false;
     }
-    e = launch_remap(h, s, d_indices, d_offsets, L, B, out);
+    return SCARS_OK;
+}
+
+int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                    const scars_remap_out* out, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    int32_t rc = remap_prologue(h, d_indices, d_offsets, L, B, out, s, "remap");
+    if (rc) return rc;
+    hipError_t e = launch_remap(h, s, d_indices, d_offsets, L, B, out);
     if (e != hipSuccess) return hip_fail(h, e, "remap");
     // worth it only when a link-bound staging kernel will leave the GPU idle (misses are possible)
     if (!h->lookahead && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N) {

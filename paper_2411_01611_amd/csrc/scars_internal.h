@@ -112,7 +112,7 @@ struct scars_handle {
     }
     // look-ahead (SCARS_TUNE_LOOKAHEAD): rows of the next batch fetched while this batch is updated
     bool lookahead = false;
-    struct { bool valid = false; const int32_t* loc = nullptr; int area = 0; } ahead;   // what was fetched ahead, where
+    struct { bool valid = false; const int32_t* loc = nullptr; const int32_t* miss_gid = nullptr; int area = 0; } ahead;   // what was fetched ahead, where
     hipEvent_t ev_pf_fork = nullptr, ev_pf_done = nullptr;
     bool pf_pending = false;             // a fetch on pool_stream that no other stream has waited for yet
     bool ahead_active = false;           // the backward pass being enqueued has a fetch running beside it
