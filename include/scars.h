@@ -214,6 +214,20 @@ int64_t scars_cache_rows(const scars_handle* h);
 int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
                     const scars_remap_out* out, void* stream);
 
+/* scars_remap for callers that cannot allocate device memory or hand over a workspace for this step (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same outputs from the same kernels, but
+ * the scratch this step needs (table descriptor, status word, per-tile hit and miss counts) lives in a 64 KiB static
+ * device array inside the library, one copy per GPU, held until the process ends.  The call allocates nothing.
+ * Limits: L <= SCARS_REMAP_STATIC_MAX_L (SCARS_ERR_WORKSPACE beyond), no unique_miss_gid (SCARS_ERR_INVALID_ARG).
+ * It does not write the backward pass's pairs and starts no preparation (SCARS_TUNE_PAIRS_IN_REMAP / _PRESORT do
+ * not apply).  Device-detected errors of this call are latched in the array's own status word, which
+ * scars_sync_status reads and clears as well.  Every call on a GPU, from any handle, shares that GPU's array: calls
+ * that overlap in time on one GPU (two streams, two handles) race on it and give unspecified hit/miss lists; calls in
+ * stream order are safe, nothing in the array has to survive from one call to the next. */
+#define SCARS_REMAP_STATIC_MAX_L (1 << 23)
+int32_t scars_remap_static(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                           const scars_remap_out* out, void* stream);
+
 /* Pooled gather-sum (Fig. 1 step 2 with sum pooling; Section II-B for the cached rows):
  * d_out[g][:] = sum over the bag's lookups of the row, fp32, empty bag -> 0.  Hits are read from the HBM
  * cache; misses are first fetched from the pinned host tables into the workspace's staging area (the

@@ -23,7 +23,7 @@ OPT_SGD, OPT_ADAGRAD = 0, 1
 
 EXPORTS = (
     "scars_create", "scars_destroy", "scars_set_tuning", "scars_get_counter", "scars_query_sizes", "scars_bind_buffers", "scars_build_cache",
-    "scars_cache_rows", "scars_remap", "scars_classify_samples", "scars_partition_batch", "scars_portion_usage", "scars_epoch_cost",
+    "scars_cache_rows", "scars_remap", "scars_remap_static", "scars_classify_samples", "scars_partition_batch", "scars_portion_usage", "scars_epoch_cost",
     "scars_caching_gain",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update", "scars_embedding_bag_bwd_update_ahead",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
@@ -107,6 +107,7 @@ def lib():
         L.scars_cache_rows.argtypes = [vp]
         L.scars_cache_rows.restype = i64
         L.scars_remap.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp]
+        L.scars_remap_static.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp]
         L.scars_embedding_bag_fwd.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, vp]
         L.scars_embedding_bag_bwd_update.argtypes = [vp, vp, vp, i64, i64, C.POINTER(_RemapOut), vp, f32, f32,
                                                      C.POINTER(_BwdOut), vp]
@@ -364,6 +365,14 @@ class Scars:
         out = out or self.new_remap_out(L, coalesce)
         c = out.c()
         self._check(lib().scars_remap(self._h, self._i32(indices), self._i32(offsets), L, B, C.byref(c), _stream()))
+        return out
+
+    def remap_static(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, out: RemapOut) -> RemapOut:
+        """scars_remap_static: the remap whose scratch is the library's static device array (allocates nothing, so the
+        output arrays must be passed in)."""
+        c = out.c()
+        self._check(lib().scars_remap_static(self._h, self._i32(indices), self._i32(offsets), int(indices.numel()), B,
+                                             C.byref(c), _stream()))
         return out
 
     def embedding_bag_fwd(self, indices: torch.Tensor, offsets: torch.Tensor, B: int, rm: RemapOut,

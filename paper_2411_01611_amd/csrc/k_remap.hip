@@ -6,6 +6,8 @@
 // (per-tile counts -> scan -> write) lists hits and misses in ascending position, so that the lists are
 // unique and comparable bit for bit.  loc[i] tells the forward kernel where to read the row: the cache slot
 // for a hit, k + rank-in-miss-list (a row of the staging area) for a miss.
+#include <mutex>
+
 #include "scars_dev.h"
 
 namespace scars {
@@ -316,6 +318,97 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) h->pairs_valid = false;
     return e;
+}
+
+// ---- remap with the scratch in the library's own static device array ---------------------------------------
+// For callers that cannot hand over (or allocate) a workspace: everything scars_remap keeps in the bound workspace
+// for this step -- the table descriptor, the status word, the per-tile hit and miss counts -- lives in one file-scope
+// device array instead.  Each GPU holds its own copy of that array at its own address; the address is looked up once
+// per device with hipGetSymbolAddress and only that pointer is ever handed to kernels or copies.
+constexpr int64_t kStaticMaxTiles = kStaticRemapMaxL / kScanTile;                       // 4096
+constexpr int64_t kStaticMetaOff = 0;
+constexpr int64_t kStaticStatusOff = (sizeof(Meta) + 255) / 256 * 256;
+constexpr int64_t kStaticHitOff = kStaticStatusOff + 256;
+constexpr int64_t kStaticTileBytes = ((kStaticMaxTiles + 1) * 4 + 255) / 256 * 256;
+constexpr int64_t kStaticMissOff = kStaticHitOff + kStaticTileBytes;
+constexpr int64_t kStaticBytes = kStaticMissOff + kStaticTileBytes;
+static_assert(kStaticBytes <= 64 * 1024, "the static scratch is meant to stay modest");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];   // zero when the code object is loaded
+
+constexpr int kStaticMaxDevices = 64;
+static std::mutex g_static_mu;
+static void* g_static_ptr[kStaticMaxDevices];      // per device: address of that device's copy of `scratch`
+
+// Address of the current device's copy of the array (looked up on the first call on that device).
+static hipError_t static_scratch(unsigned char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kStaticMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_static_ptr[dev] = p;
+    }
+    *out = (unsigned char*)g_static_ptr[dev];
+    return hipSuccess;
+}
+
+int32_t* static_status_if_used() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    return g_static_ptr[dev] ? (int32_t*)((unsigned char*)g_static_ptr[dev] + kStaticStatusOff) : nullptr;
+}
+
+// The part of the descriptor the remap kernels read (row_base, num_tables), handed over as kernel arguments: a copy
+// from ordinary host memory could make the runtime allocate a staging buffer.
+constexpr int kMetaPack = 512;
+struct MetaPack { int32_t v[kMetaPack]; };
+
+__global__ void k_static_meta(Meta* __restrict__ meta, int first, int n, int num_tables, MetaPack pack) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) meta->row_base[first + i] = pack.v[i];
+    if (threadIdx.x == 0) meta->num_tables = num_tables;
+}
+
+hipError_t launch_remap_static(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
+                               const scars_remap_out* out) {
+    unsigned char* base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return e;
+    Meta* meta = (Meta*)(base + kStaticMetaOff);
+    int32_t* status = (int32_t*)(base + kStaticStatusOff);
+    uint32_t* blk_hit = (uint32_t*)(base + kStaticHitOff);
+    uint32_t* blk_miss = (uint32_t*)(base + kStaticMissOff);
+    // another handle may have used the array last: the descriptor is written again on every call (stream order)
+    for (int first = 0; first <= h->T; first += kMetaPack) {
+        MetaPack pack;
+        const int n = std::min(kMetaPack, h->T + 1 - first);
+        for (int i = 0; i < n; ++i) pack.v[i] = (int32_t)h->row_base[first + i];
+        Timed t(h, s, "static_meta");
+        hipLaunchKernelGGL(k_static_meta, dim3(1), dim3(kBlock), 0, s, meta, first, n, h->T, pack);
+    }
+    const int nb = (int)std::max<int64_t>(1, div_up(L, kScanTile));     // <= kStaticMaxTiles: the caller checked L
+    {
+        Timed t(h, s, "remap_probe");
+        hipLaunchKernelGGL(k_remap_probe, dim3(nb), dim3(kBlock), 0, s, idx, off, L, B, meta, h->buf.slot_of, out->slot,
+                           out->gid, blk_hit, blk_miss, status);
+    }
+    const bool scan = nb > h->fused_scan_max_tiles;
+    if (scan) {
+        Timed t(h, s, "remap_scan");
+        hipLaunchKernelGGL(k_remap_scan, dim3(1), dim3(kBlock), 0, s, blk_hit, blk_miss, nb, out->n_hit_miss);
+    }
+    {
+        Timed t(h, s, "remap_write");
+        hipLaunchKernelGGL(k_remap_write, dim3(nb), dim3(kBlock), 0, s, L, out->slot, out->gid, blk_hit, blk_miss,
+                           scan ? 1 : 0, out->n_hit_miss, (int32_t)h->k, out->loc, out->hit_pos, out->miss_pos, out->miss_gid);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace scars

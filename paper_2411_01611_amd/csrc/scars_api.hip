@@ -395,6 +395,21 @@ int32_t scars_remap(scars_handle* h, const int32_t* d_indices, const int32_t* d_
     return SCARS_OK;
 }
 
+int32_t scars_remap_static(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L, int64_t B,
+                           const scars_remap_out* out, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    int32_t rc = remap_prologue(h, d_indices, d_offsets, L, B, out, s, "remap_static");
+    if (rc) return rc;
+    if (L > SCARS_REMAP_STATIC_MAX_L)
+        return fail(h, SCARS_ERR_WORKSPACE, "remap_static: more than SCARS_REMAP_STATIC_MAX_L lookups; use scars_remap");
+    if (out->unique_miss_gid)
+        return fail(h, SCARS_ERR_INVALID_ARG, "remap_static: unique_miss_gid needs the workspace's sort buffers; use scars_remap");
+    h->pairs_valid = false;   // (the pairs of an earlier scars_remap describe another batch once `out` is rewritten)
+    hipError_t e = launch_remap_static(h, s, d_indices, d_offsets, L, B, out);
+    if (e != hipSuccess) return hip_fail(h, e, "remap_static");
+    return SCARS_OK;
+}
+
 int32_t scars_embedding_bag_fwd(scars_handle* h, const int32_t* d_indices, const int32_t* d_offsets, int64_t L,
                                 int64_t B, const scars_remap_out* rm, float* d_out, void* stream) {
     int32_t rc = check_batch(h, d_indices, d_offsets, L, B, "embedding_bag_fwd");
@@ -627,14 +642,20 @@ int32_t scars_sync_status(scars_handle* h, void* stream) {
     int32_t st[4] = {0, 0, 0, 0};
     hipError_t e = side_join(h, s);   // side-stream kernels latch errors too
     if (e == hipSuccess) e = pf_join(h, s);
+    // scars_remap_static latches into the status word of the library's static array (shared by every handle on this GPU)
+    int32_t* const st2_dev = static_status_if_used();
+    int32_t st2[4] = {0, 0, 0, 0};
     if (e == hipSuccess) e = hipMemcpyAsync(st, h->ws.status, sizeof(st), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess && st2_dev) e = hipMemcpyAsync(st2, st2_dev, sizeof(st2), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(h, e, "sync_status");
-    if (st[0] != 0) {
-        e = launch_fill_u32(h, s, (uint32_t*)h->ws.status, 4, 0u);
+    if (st[0] != 0 || st2[0] != 0) {
+        if (st[0] != 0) e = launch_fill_u32(h, s, (uint32_t*)h->ws.status, 4, 0u);
+        if (e == hipSuccess && st2[0] != 0) e = launch_fill_u32(h, s, (uint32_t*)st2_dev, 4, 0u);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) return hip_fail(h, e, "sync_status(clear)");
-        return fail(h, st[0], st[0] == SCARS_ERR_INDEX_RANGE ? "device: index out of range" : "device: bad offsets");
+        const int32_t code = st[0] != 0 ? st[0] : st2[0];
+        return fail(h, code, code == SCARS_ERR_INDEX_RANGE ? "device: index out of range" : "device: bad offsets");
     }
     return SCARS_OK;
 }

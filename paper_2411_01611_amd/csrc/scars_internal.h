@@ -21,6 +21,7 @@ constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10
 constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
 constexpr int kPlanBigCap = 4096;
 constexpr int kLongRunMin = 64;      // runs longer than this are cut into tasks of this many lookups
+constexpr int64_t kStaticRemapMaxL = SCARS_REMAP_STATIC_MAX_L;   // largest batch of scars_remap_static
 
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline int64_t div_up(int64_t x, int64_t a) { return (x + a - 1) / a; }
@@ -181,6 +182,11 @@ hipError_t launch_calib_read(hipStream_t s, const void* src, int64_t bytes, void
 // k_remap.hip
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out);
+// k_remap.hip: the same three launches with the library's static device array in place of the workspace
+hipError_t launch_remap_static(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
+                               const scars_remap_out* out);
+// k_remap.hip: the status word inside that array on the current device, or null if nothing has used the array there
+int32_t* static_status_if_used();
 // k_remap.hip (also used by k_classify.hip): exclusive scan of two per-tile count arrays, totals to out2[0..1]
 __global__ void k_remap_scan(uint32_t* a, uint32_t* b, int n, int32_t* out2);
 // k_classify.hip
