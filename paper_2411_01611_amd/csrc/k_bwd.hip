@@ -14,9 +14,9 @@ namespace scars {
 // ---- (1) pairs ----------------------------------------------------------------------------------------
 // (bag_pairs in scars_dev.h; scars_remap may already have written them in the launch that lists hits and misses)
 __global__ __launch_bounds__(kBlock) void k_bwd_pairs(const int32_t* __restrict__ gid, const int32_t* __restrict__ off,
-                                                      int32_t L, int64_t G, int lpb, uint32_t* __restrict__ key,
-                                                      uint32_t* __restrict__ val) {
-    bag_pairs((int64_t)blockIdx.x, gid, off, L, G, lpb, key, val);
+                                                      int32_t L, int64_t G, int lpb, int shift,
+                                                      uint32_t* __restrict__ key, uint32_t* __restrict__ val) {
+    bag_pairs((int64_t)blockIdx.x, gid, off, L, G, lpb, shift, key, val);
 }
 
 __global__ void k_bwd_empty(int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start) {
@@ -69,6 +69,10 @@ __global__ __launch_bounds__(kBlock) void k_seg_scan(uint32_t* __restrict__ a, u
     if (threadIdx.x == 0) { n_unique[0] = (int32_t)ca; n_unique[1] = (int32_t)cb; }
 }
 
+// Run starts by ordered compaction; per run also where the update kernel finds the row and its first gradient row.
+// A pair's value holds the bag and the lookup's place inside it (bag_pairs), so the first lookup of a run of a cold
+// row is at position off[bag] + place, and loc[] there names the copy its forward pass staged: two dependent loads,
+// no search.  (When the place saturated, or the offsets were bad, the row is simply read from host memory.)
 __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                       int64_t L, const uint32_t* __restrict__ blk_head,
                                                       const uint32_t* __restrict__ blk_valid, int scanned,
@@ -78,17 +82,43 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
                                                       const int32_t* __restrict__ slot_of, uint32_t N,
                                                       int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag,
                                                       const int32_t* __restrict__ off, int64_t G, const int32_t* __restrict__ gid_of,
-                                                      const int32_t* __restrict__ loc_of, int32_t k, int staged) {
+                                                      const int32_t* __restrict__ loc_of, int32_t k, int staged, int shift) {
     __shared__ uint32_t s_a[4], s_red[8];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
+    const uint32_t sat = (1u << shift) - 1u;
     bool hd[kRoundsS];
+    uint32_t kk[kRoundsS], vv[kRoundsS];
     uint32_t nh = 0;
+    // stage 1: keys (and their left neighbours) and values of all rounds
 #pragma unroll
     for (int r = 0; r < kRoundsS; ++r) {
-        hd[r] = is_head(key, base + r * kWave + lane_id(), L);
+        const int64_t j = base + r * kWave + lane_id();
+        hd[r] = is_head(key, j, L);
+        kk[r] = j < L ? key[j] : 0xFFFFFFFFu;
+        vv[r] = j < L ? val[j] : 0u;
         nh += (uint32_t)__popcll(ballot64(hd[r]));
     }
     if (lane_id() == 0) s_a[wave_id()] = nh;
+    // stage 2: per run start, the cache slot of the row and the start of its first bag, requested together
+    int32_t src[kRoundsS], p0[kRoundsS];
+#pragma unroll
+    for (int r = 0; r < kRoundsS; ++r) {
+        const bool h = hd[r] && kk[r] < N;
+        const uint32_t bag = vv[r] >> shift;
+        src[r] = h ? slot_of[kk[r]] : -1;
+        p0[r] = (h && staged && (int64_t)bag < G && (vv[r] & sat) < sat) ? off[bag] : -1;
+    }
+    // stage 3: a cold row's first lookup: its location (the staged copy) and, as a check, its row id
+#pragma unroll
+    for (int r = 0; r < kRoundsS; ++r) {
+        if (hd[r] && src[r] < 0 && p0[r] >= 0) {
+            const int64_t p = (int64_t)p0[r] + (vv[r] & sat);
+            if (p < L) {
+                const int32_t l = loc_of[p];
+                if ((uint32_t)gid_of[p] == kk[r] && l >= k) src[r] = l;
+            }
+        }
+    }
     __syncthreads();
     uint32_t before, bv, n_runs, n_valid;
     const bool last = tile_prefix2(blk_head, blk_valid, blockIdx.x, gridDim.x, scanned != 0, s_red, n_unique, &before, &bv,
@@ -103,30 +133,19 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
         const uint64_t m = ballot64(hd[r]);
         if (hd[r]) {
             const uint32_t u = before + (uint32_t)rank_below(m);
-            const uint32_t gk = key[j];
             seg_start[u] = (int32_t)j;
-            unique_gid[u] = (int32_t)gk;
+            unique_gid[u] = (int32_t)kk[r];
             // for the update kernel: where the row lives and which gradient row comes first, so that it can
             // issue the row fetch and the first gradient fetch at once
-            int32_t src = gk < N ? slot_of[gk] : -1;
-            const uint32_t bag = val[j];
-            if (src < 0 && staged && gk < N && (int64_t)bag < G) {
-                // a cold row: the forward pass of this batch left its value in the staging area, at the location
-                // of any of its lookups; the first lookup of the run is in bag `bag`, so search that bag
-                const int32_t a = min(max(off[bag], 0), (int32_t)L);
-                const int32_t b = min(max(off[bag + 1], a), (int32_t)L);
-                for (int32_t i = a; i < b; ++i)
-                    if ((uint32_t)gid_of[i] == gk) { src = loc_of[i] >= k ? loc_of[i] : -1; break; }
-            }
-            unique_slot[u] = src;
-            first_bag[u] = bag;
+            unique_slot[u] = src[r];
+            first_bag[u] = vv[r] >> shift;
         }
         // each round is one chunk of kLongRunMin (= 64) positions: remember which run its first position is in
         if (lane_id() == 0 && j < L) chunk_run[j / kLongRunMin] = (int32_t)(before + (hd[r] ? 1u : 0u)) - 1;
         before += (uint32_t)__popcll(m);
         if (sorted_gid && j < L) {   // caller asked for the sorted pairs as well
-            sorted_gid[j] = (int32_t)key[j];
-            sorted_bag[j] = (int32_t)val[j];
+            sorted_gid[j] = (int32_t)kk[r];
+            sorted_bag[j] = (int32_t)(vv[r] >> shift);
         }
     }
 }
@@ -143,6 +162,7 @@ struct UpdateArgs {
     int32_t k;       // cached rows: a source index >= k is row (index - k) of the staging area
     uint32_t N;      // rows in all tables: a key at or above it is never dereferenced
     uint32_t Gm1;    // last bag: bag ids are clamped to it (both only matter after an offsets error)
+    int shift;       // a pair's value is (bag << shift) | place inside the bag
 };
 
 // Where a row lives: cache slot (HBM) or pinned host table; the Adagrad accumulator beside it.
@@ -226,14 +246,14 @@ constexpr int64_t kFusedWideMaxL = 1 << 17;   // shared launch: batches up to th
 // never stored).  Indices are clamped instead of guarded so that the loads are issued back to back.
 template <int LPG, int UNROLL>
 __device__ __forceinline__ void sum_grads(const uint32_t* __restrict__ val, const float4* __restrict__ g4, int dq, int c,
-                                          int32_t p0, int32_t p1, uint32_t Gm1, double (&acc)[4]) {
+                                          int32_t p0, int32_t p1, uint32_t Gm1, int shift, double (&acc)[4]) {
     constexpr int W = LPG < kWave ? LPG : kWave;                 // positions one load of the group covers
     const int wl = LPG < kWave ? c : lane_id();                  // this lane's place in the window
     const int gl0 = LPG < kWave ? (lane_id() / LPG) * LPG : 0;   // first lane of the group inside the wave
     const int cc = min(c, dq - 1);
     for (int32_t w0 = p0; w0 < p1; w0 += W) {
         const int32_t n = min((int32_t)W, p1 - w0);
-        const uint32_t bv = min(val[min(w0 + wl, p1 - 1)], Gm1);
+        const uint32_t bv = min(val[min(w0 + wl, p1 - 1)] >> shift, Gm1);
         for (int base = 0; base < n; base += UNROLL) {
             float4 gv[UNROLL];
 #pragma unroll
@@ -284,7 +304,7 @@ __device__ __forceinline__ void seg_rows_body(int block, int nblocks, const uint
         ref.load(cc, wv, sv);
         const float4 g0 = g4[(int64_t)bag0 * dq + cc];
         double acc[4] = {(double)g0.x, (double)g0.y, (double)g0.z, (double)g0.w};
-        if (b - a > 1) sum_grads<LPG, kGradUnroll>(val, g4, dq, c, a + 1, b, A.Gm1, acc);
+        if (b - a > 1) sum_grads<LPG, kGradUnroll>(val, g4, dq, c, a + 1, b, A.Gm1, A.shift, acc);
         if (lane_on) ref.step_and_store(A, c, wv, sv, acc);
     }
 }
@@ -306,7 +326,7 @@ template <int LPG, int UNROLL>
 __device__ __forceinline__ void seg_long_body(int block, int nblocks, const uint32_t* __restrict__ key,
                                               const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                               const int32_t* __restrict__ seg_start, const int32_t* __restrict__ chunk_run,
-                                              const float* __restrict__ grad, double* __restrict__ partial, int D, uint32_t Gm1) {
+                                              const float* __restrict__ grad, double* __restrict__ partial, int D, uint32_t Gm1, int shift) {
     const int32_t Lv = n_unique[1];
     const int c = threadIdx.x % LPG;
     const bool lane_on = c * 4 < D;
@@ -330,7 +350,7 @@ __device__ __forceinline__ void seg_long_body(int block, int nblocks, const uint
             const int32_t a = seg_start[r], b = seg_start[r + 1];
             if (b - a <= kLongRun) continue;
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            sum_grads<LPG, UNROLL>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, acc);
+            sum_grads<LPG, UNROLL>(val, g4, dq, c, max(a, j0), min(b, j1), Gm1, shift, acc);
             if (lane_on) {
                 double* p = partial + ((int64_t)ch * 2 + side) * D + c * 4;
                 p[0] = acc[0]; p[1] = acc[1]; p[2] = acc[2]; p[3] = acc[3];
@@ -343,8 +363,8 @@ template <int LPG>
 __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                      const int32_t* __restrict__ n_unique, const int32_t* __restrict__ seg_start,
                                                      const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
-                                                     double* __restrict__ partial, int D, uint32_t Gm1) {
-    seg_long_body<LPG, kTaskUnroll>((int)blockIdx.x, (int)gridDim.x, key, val, n_unique, seg_start, chunk_run, grad, partial, D, Gm1);
+                                                     double* __restrict__ partial, int D, uint32_t Gm1, int shift) {
+    seg_long_body<LPG, kTaskUnroll>((int)blockIdx.x, (int)gridDim.x, key, val, n_unique, seg_start, chunk_run, grad, partial, D, Gm1, shift);
 }
 
 // Both of the above in one launch: the first `long_blocks` workgroups take the chunks of long runs, the others the
@@ -363,7 +383,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows_long(int long_blocks, const
                                                           double* __restrict__ partial, UpdateArgs A) {
     if ((int)blockIdx.x < long_blocks)
         seg_long_body<LPG, ULONG>((int)blockIdx.x, long_blocks, key, val, n_unique, seg_start, chunk_run, grad, partial, A.D,
-                                        A.Gm1);
+                                        A.Gm1, A.shift);
     else
         seg_rows_body<DTYPE, OPT, LPG>((int)blockIdx.x - long_blocks, (int)gridDim.x - long_blocks, val, n_unique, seg_start,
                                        unique_gid, unique_slot, first_bag, grad, A);
@@ -454,7 +474,7 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     {
         Timed t(h, s2, "seg_long");
         hipLaunchKernelGGL((k_seg_long<LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s2, key, val, nu, seg_start, ws.chunk_run,
-                           grad, ws.partial, A.D, A.Gm1);
+                           grad, ws.partial, A.D, A.Gm1, A.shift);
     }
     {
         Timed t(h, s2, "seg_combine");
@@ -497,7 +517,7 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
         Timed t(h, s, "bwd_pairs");
         const int lpb = pairs_lanes_per_bag(L, G);
         hipLaunchKernelGGL(k_bwd_pairs, dim3((unsigned)div_up(G * lpb, kBlock)), dim3(kBlock), 0, s, rm->gid, off,
-                           (int32_t)L, G, lpb, ws.key_buf[0], ws.val_buf[0]);
+                           (int32_t)L, G, lpb, bag_shift_host(G), ws.key_buf[0], ws.val_buf[0]);
     }
     int bits = 1;
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
@@ -522,7 +542,7 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
         hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_seg_a, ws.blk_seg_b, scan ? 1 : 0,
                            n_unique, seg_start, unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr,
                            ws.chunk_run, h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid,
-                           rm->loc, (int32_t)h->k, staged ? 1 : 0);
+                           rm->loc, (int32_t)h->k, staged ? 1 : 0, bag_shift_host(G));
     }
     return hipGetLastError();
 }
@@ -562,7 +582,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     const uint32_t* val = ws.val_buf[res];
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
                  use_staged ? ws.staging[area] : nullptr, (int32_t)h->k, (uint32_t)h->N,
-                 (uint32_t)std::max<int64_t>(G - 1, 0)};
+                 (uint32_t)std::max<int64_t>(G - 1, 0), bag_shift_host(G)};
     // Look-ahead.  (1) The integer half of the next batch's backward pass is prepared beside this update, on the side
     // stream and in the second set of segment arrays (this update still reads the first); the sets change places once
     // the update kernels are enqueued.  It is enqueued before the fetch: should the two library streams share a

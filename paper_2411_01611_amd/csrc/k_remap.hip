@@ -166,12 +166,13 @@ __global__ __launch_bounds__(kBlock) void k_remap_write_pairs(int ntiles, int64_
                                                               int32_t* __restrict__ loc, int32_t* __restrict__ hit_pos,
                                                               int32_t* __restrict__ miss_pos, int32_t* __restrict__ miss_gid,
                                                               const int32_t* __restrict__ off, int64_t G, int lpb,
-                                                              uint32_t* __restrict__ key, uint32_t* __restrict__ val) {
+                                                              int shift, uint32_t* __restrict__ key,
+                                                              uint32_t* __restrict__ val) {
     if ((int)blockIdx.x < ntiles)
         remap_write_body((int)blockIdx.x, ntiles, L, slot, gid, blk_hit, blk_miss, scanned, n_hit_miss, k, loc, hit_pos,
                          miss_pos, miss_gid);
     else
-        bag_pairs((int64_t)blockIdx.x - ntiles, gid, off, (int32_t)L, G, lpb, key, val);
+        bag_pairs((int64_t)blockIdx.x - ntiles, gid, off, (int32_t)L, G, lpb, shift, key, val);
 }
 
 __global__ void k_um_empty(int32_t* __restrict__ n_unique_miss) {
@@ -275,7 +276,7 @@ hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, cons
         const int64_t pair_blocks = div_up(G * lpb, kBlock);
         hipLaunchKernelGGL(k_remap_write_pairs, dim3((unsigned)(nb + pair_blocks)), dim3(kBlock), 0, s, nb, L, out->slot,
                            out->gid, ws.blk_hit, ws.blk_miss, scan ? 1 : 0, out->n_hit_miss, (int32_t)h->k, out->loc,
-                           out->hit_pos, out->miss_pos, out->miss_gid, off, G, lpb, ws.key_buf[0], ws.val_buf[0]);
+                           out->hit_pos, out->miss_pos, out->miss_gid, off, G, lpb, bag_shift_host(G), ws.key_buf[0], ws.val_buf[0]);
         h->pairs_valid = true;
         h->pairs_gid = out->gid; h->pairs_off = off; h->pairs_L = L; h->pairs_B = B;
     } else {

@@ -14,24 +14,59 @@ namespace scars {
 constexpr int kMaxBins = kSortMaxBins;
 constexpr int kWaves = kBlock / kWave;
 
-// hist is digit-major: hist[d * nb + tile]
+// Lanes of the wave that hold the same digit as this lane (valid lanes only): one ballot per digit bit.
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid, int dbits) {
+    uint64_t m = ballot64(valid);
+    for (int b = 0; b < dbits; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bal = ballot64(bit);
+        m &= bit ? bal : ~bal;
+    }
+    return m;
+}
+
+// hist is digit-major: hist[d * nb + tile].  Each wave counts into a histogram of its own; lanes holding the same
+// digit are matched by ballots and only the first of them adds their number (equal keys, which skewed row ids have
+// many of, then cost one LDS operation instead of one each).  Keys are read 16 bytes per lane.
 template <int ROUNDS>
 __global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict__ keys, int64_t n, const int32_t* __restrict__ d_n,
                                                       int shift, int dbits, uint32_t* __restrict__ hist, int nb) {
-    __shared__ uint32_t s_hist[kMaxBins];
+    __shared__ uint32_t s_hist[kWaves * kMaxBins];
+    static_assert(ROUNDS % 4 == 0, "a lane takes four consecutive keys per load");
     if (d_n) n = min(n, (int64_t)max(*d_n, 0));    // the pair count may live on the device (n is then its bound)
     const int bins = 1 << dbits;
     const uint32_t mask = (uint32_t)bins - 1u;
-    for (int d = threadIdx.x; d < bins; d += kBlock) s_hist[d] = 0;
+    for (int i = threadIdx.x; i < kWaves * kMaxBins; i += kBlock) s_hist[i] = 0;
     __syncthreads();
+    uint32_t* wh = s_hist + wave_id() * kMaxBins;
     const int64_t tile0 = (int64_t)blockIdx.x * (kBlock * ROUNDS);
+    uint32_t kk[ROUNDS];
+#pragma unroll
+    for (int q = 0; q < ROUNDS / 4; ++q) {
+        const int64_t i = tile0 + ((int64_t)q * kBlock + threadIdx.x) * 4;
+        if (i + 3 < n) {
+            const uint4 v = *(const uint4*)(keys + i);           // tile0 and i are multiples of 4: 16-byte aligned
+            kk[4 * q] = v.x; kk[4 * q + 1] = v.y; kk[4 * q + 2] = v.z; kk[4 * q + 3] = v.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) kk[4 * q + e] = i + e < n ? keys[i + e] : 0u;
+        }
+    }
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-        const int64_t i = tile0 + (int64_t)r * kBlock + threadIdx.x;
-        if (i < n) atomicAdd(&s_hist[(keys[i] >> shift) & mask], 1u);
+        const int64_t i = tile0 + ((int64_t)(r / 4) * kBlock + threadIdx.x) * 4 + (r % 4);
+        const bool valid = i < n;
+        const uint32_t d = (kk[r] >> shift) & mask;
+        const uint64_t m = match_digit(d, valid, dbits);
+        if (valid && rank_below(m) == 0) atomicAdd(&wh[d], (uint32_t)__popcll(m));   // distinct digits: distinct words
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < bins; d += kBlock) hist[(int64_t)d * nb + blockIdx.x] = s_hist[d];
+    for (int d = threadIdx.x; d < bins; d += kBlock) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) c += s_hist[w * kMaxBins + d];
+        hist[(int64_t)d * nb + blockIdx.x] = c;
+    }
 }
 
 // One workgroup per digit: exclusive scan of that digit's per-tile counts, digit total to tot[digit].
@@ -96,25 +131,28 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
     }
     __syncthreads();
 
-    volatile uint32_t* wh = s_wh + w * kMaxBins;
+    // Stable rank of every pair among its wave's pairs of the same digit.  First the lanes of each round that share a
+    // digit are matched (ballots only); then the first lane of each such set adds the set's size to the wave's counter
+    // of the digit and gets back what was there -- the sets of a round have distinct digits, and a wave's LDS
+    // operations are carried out in order, so the rounds' additions are issued back to back and need no barrier;
+    // finally every lane takes that number from its set's first lane.
+    uint32_t* wh = s_wh + w * kMaxBins;
+    uint32_t old[ROUNDS];
+    int lead[ROUNDS];
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
         const int p = w * kPerWave + r * kWave + lane;
         const bool valid = p < tile_n;
         const uint32_t d = (key[r] >> shift) & mask;
-        uint64_t m = ballot64(valid);                            // lanes holding the same digit
-        for (int b = 0; b < dbits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t bal = ballot64(bit);
-            m &= bit ? bal : ~bal;
-        }
-        const uint32_t before = valid ? wh[d] : 0u;
-        __builtin_amdgcn_wave_barrier();
+        const uint64_t m = match_digit(d, valid, dbits);
         const int rk = rank_below(m);
-        if (valid && rk == 0) wh[d] = before + (uint32_t)__popcll(m);
-        __builtin_amdgcn_wave_barrier();
-        loc[r] = before + (uint32_t)rk;                          // stable rank among this wave's pairs of digit d
+        lead[r] = valid ? __ffsll((unsigned long long)m) - 1 : lane;
+        loc[r] = (uint32_t)rk;
+        old[r] = 0u;
+        if (valid && rk == 0) old[r] = atomicAdd(&wh[d], (uint32_t)__popcll(m));
     }
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) loc[r] += __shfl(old[r], lead[r], kWave);   // stable rank among this wave's pairs of digit d
     __syncthreads();
     {   // per digit: wave counts -> exclusive wave bases; tile count of the digit -> LDS start of the digit
         uint32_t carry = 0;

@@ -111,19 +111,22 @@ __device__ __forceinline__ int upper_table(const int32_t* a, int T, int32_t x) {
 }
 
 // (gid, bag) pairs of a batch in position order: key = gid of the lookup (-1, an invalid lookup, becomes the largest
-// key), value = its bag.  A group of lpb lanes walks one bag's positions, so the bag id needs no search.  `block` of
-// the workgroups that share this job.
+// key), value = (bag << shift) | (place of the lookup inside its bag, saturating at 2^shift - 1).  The place costs
+// nothing to carry through the sort and lets the backward pass find a run's first lookup, hence the staged copy of a
+// cold row, without searching the bag; `shift` = 32 - (bits of the largest bag id), see bag_shift_host.  A group of
+// lpb lanes walks one bag's positions, so the bag id needs no search.  `block` of the workgroups that share this job.
 __device__ __forceinline__ void bag_pairs(int64_t block, const int32_t* __restrict__ gid, const int32_t* __restrict__ off,
-                                          int32_t L, int64_t G, int lpb, uint32_t* __restrict__ key,
+                                          int32_t L, int64_t G, int lpb, int shift, uint32_t* __restrict__ key,
                                           uint32_t* __restrict__ val) {
     const int64_t g = (block * kBlock + threadIdx.x) / lpb;
     const int c = threadIdx.x % lpb;
     if (g >= G) return;
     const int32_t a = min(max(off[g], 0), L);
     const int32_t b = min(max(off[g + 1], a), L);
+    const uint32_t sat = (1u << shift) - 1u;
     for (int32_t i = a + c; i < b; i += lpb) {
         key[i] = (uint32_t)gid[i];
-        val[i] = (uint32_t)g;
+        val[i] = ((uint32_t)g << shift) | min((uint32_t)(i - a), sat);
     }
 }
 
@@ -148,6 +151,12 @@ inline int next_pow2_host(int x) {
     int p = 1;
     while (p < x) p <<= 1;
     return p;
+}
+// how far the bag id is shifted up in a pair's value: the bits left over hold the lookup's place inside its bag
+inline int bag_shift_host(int64_t G) {
+    int bits = 1;
+    while (bits < 31 && ((int64_t)1 << bits) < G) ++bits;
+    return 32 - bits;
 }
 // lanes that walk one bag in bag_pairs: about the mean bag length, a power of two up to a wave
 inline int pairs_lanes_per_bag(int64_t L, int64_t G) {
