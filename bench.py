@@ -7,6 +7,13 @@ memory).  build_cache runs once before the timed region (it is amortised over ma
 separately.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scale S] [--no-resident] [--no-cpu-baseline]
+
+What the line's `roofline` object is: the kernel that takes the largest share of the reported step, priced against
+the resource that bounds it -- the host link (its measured one-way copy rate) for the kernels that move cold rows,
+HBM (8 TB/s, published) for the others -- with `frac` = the bytes the method cannot avoid moving / launch time / that
+rate, never above 1.  The pooled-sum (gather) kernel, the HBM-bound core of the forward pass, is reported beside it
+under `gather` with three figures: compulsory bytes, effective bytes (every lookup's row counted, so repeats served
+by the caches push it past the peak) and counter bytes.
 """
 from __future__ import annotations
 
@@ -26,32 +33,49 @@ from paper_2411_01611_amd import binding, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 PRESORT_MIN_L = 1 << 17  # batches this large start the backward sort in remap, on the library's side stream
+POOL_KERNELS = ("pool_wave", "pool_group", "pool_short")
+UPDATE_KERNELS = ("seg_rows_long+fetch_ahead", "seg_rows_long", "seg_rows")
 
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+def pin_tables(wl: synth.Workload, with_state: bool):
+    """Pinned host arrays for every table (and accumulator) of the workload, or (None, what failed)."""
+    npdt = np.float32 if wl.dtype == "f32" else np.uint16
+    tables, state, done = [], [], 0
+    try:
+        for t in range(wl.num_tables):
+            tables.append(binding.PinnedArray((wl.rows[t], wl.dim), npdt))
+            done += tables[-1].nbytes
+            if with_state:
+                state.append(binding.PinnedArray((wl.rows[t], wl.dim), np.float32))
+                done += state[-1].nbytes
+    except binding.ScarsError as e:
+        for p in tables + state:
+            p.free()
+        need = wl.total_rows * (wl.row_bytes + (wl.dim * 4 if with_state else 0))
+        return None, {"pinned_bytes_wanted": int(need), "pinned_bytes_before_failure": int(done),
+                      "failing_table": len(tables), "error": f"hipHostMalloc: {e}"}
+    return (tables, state), None
+
+
 class Bench:
-    def __init__(self, wl: synth.Workload, budget_bytes: int, coalesce: bool = False):
+    def __init__(self, wl: synth.Workload, budget_bytes: int, pinned, coalesce: bool = False):
         self.wl = wl
         self.coalesce = coalesce
         self.dev = torch.device("cuda:0")
         self.budget = budget_bytes
         t0 = time.time()
-        npdt = np.float32 if wl.dtype == "f32" else np.uint16
-        self.tables, self.state = [], []
+        self.tables, self.state = pinned
         for t in range(wl.num_tables):
-            p = binding.PinnedArray((wl.rows[t], wl.dim), npdt)
-            self._fill(p, t)
-            self.tables.append(p)
-            if wl.optimizer == "adagrad":
-                s = binding.PinnedArray((wl.rows[t], wl.dim), np.float32)
-                self._zero(s)
-                self.state.append(s)
+            self._fill(self.tables[t], t)
+            if self.state:
+                self._zero(self.state[t])
         torch.cuda.synchronize()
         log(f"tables: {wl.total_rows} rows x {wl.row_bytes} B = {wl.total_rows * wl.row_bytes / 1e9:.2f} GB pinned "
-            f"(+{len(self.state) and wl.total_rows * wl.dim * 4 / 1e9:.2f} GB state) in {time.time() - t0:.1f}s")
+            f"(+{len(self.state) and wl.total_rows * wl.dim * 4 / 1e9:.2f} GB state) filled in {time.time() - t0:.1f}s")
         self.sampler = synth.Sampler(wl, self.dev)
         self.s = binding.Scars(wl.rows, wl.dim, binding.DTYPE_F32 if wl.dtype == "f32" else binding.DTYPE_BF16,
                                [p.ptr for p in self.tables],
@@ -87,27 +111,28 @@ class Bench:
         self.rm = self.s.new_remap_out(coalesce=self.coalesce)
         self.out = torch.empty(wl.num_bags, wl.dim, dtype=torch.float32, device=self.dev)
 
-    def build_cache(self) -> dict:
+    def build_cache(self, link: dict) -> dict:
+        """The three parts of build_cache apart, each against the bytes it has to move."""
         wl = self.wl
         P = wl.profile_batches
+        R, N = wl.row_bytes, wl.total_rows
         torch.cuda.synchronize()
-        t0 = time.time()
-        gen = 0.0
         Lp = 0
         self.s.build_cache(None, None, 0, self.budget, 0)
         t_hist = 0.0
+        self.s.profile_enable(True)
         for p in range(P):
-            g0 = time.time()
             idx, off = self.sampler.batch(p, True)
             if idx.numel() > self.max_L:
                 continue
             torch.cuda.synchronize()
-            gen += time.time() - g0
             h0 = time.time()
             self.s.build_cache(idx, off, wl.batch, self.budget, 2)
             torch.cuda.synchronize()
             t_hist += time.time() - h0
             Lp += int(idx.numel())
+        hist_prof = self.s.profile_read()
+        self.s.profile_enable(False)
         s0 = time.time()
         self.s.build_cache(None, None, 0, self.budget, 1)
         torch.cuda.synchronize()
@@ -118,18 +143,41 @@ class Bench:
         prof = self.s.profile_read()
         self.s.profile_enable(False)
         ms = lambda *names: sum(v["total_ms"] for n, v in prof.items() if n.startswith(names))
-        t_select = ms("sel_", "win_", "scan_two", "fill") * 1e-3
+        t_select = ms("sel_", "win_", "scan_two") * 1e-3
         t_rank = ms("sort_", "slot_scatter") * 1e-3
         t_fill = ms("cache_fill") * 1e-3
         st = self.s.sync_status()
         assert st == 0, f"device error {st} during build_cache"
         k = self.s.cache_rows()
+        state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
+        hk = hist_prof.get("histogram", {"launches": 1, "total_ms": 0.0})
+        hist_launch_s = hk["total_ms"] / max(1, hk["launches"]) * 1e-3
+        Lp_launch = Lp / max(1, hk["launches"])
+        # bytes each part has to move: 12 per profiled lookup (index + counter read-modify-write); one read of the
+        # counts per select pass (three) and per winner pass (two) plus the slot map written once; k rows over the link
+        sel_bytes = 5 * 4 * N + 4 * N + 8 * k
+        fill_bytes = k * (R + state_b)
+        fill_rate = fill_bytes / max(t_fill, 1e-9) / 1e9
+        parts = {
+            "a1_histogram": {"kernel": "histogram", "bound": "hbm", "lookups_per_launch": Lp_launch,
+                             "avg_launch_ms": round(hist_launch_s * 1e3, 5), "alg_bytes_per_launch": int(12 * Lp_launch),
+                             "achieved": round(12 * Lp_launch / max(hist_launch_s, 1e-12) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(12 * Lp_launch / max(hist_launch_s, 1e-12) / 1e9 / HBM_PEAK_GBS, 4),
+                             "Mlookups_per_s": round(Lp_launch / max(hist_launch_s, 1e-12) / 1e6, 1)},
+            "a2_select": {"kernels": "sel_hist x3, sel_pick x3, win_count, scan_two, win_write", "bound": "hbm",
+                          "ms": round(t_select * 1e3, 4), "alg_bytes": int(sel_bytes),
+                          "achieved": round(sel_bytes / max(t_select, 1e-12) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": round(sel_bytes / max(t_select, 1e-12) / 1e9 / HBM_PEAK_GBS, 4),
+                          "Mrows_per_s": round(N / max(t_select, 1e-12) / 1e6, 1),
+                          "rank_sort_of_the_k_winners_ms": round(t_rank * 1e3, 4)},
+            "a3_fill": {"kernel": "cache_fill", "bound": "host_link", "ms": round(t_fill * 1e3, 3),
+                        "link_read_bytes": int(fill_bytes), "achieved": round(fill_rate, 2), "peak": round(link["h2d_GBs"], 2),
+                        "peak_source": "hipMemcpyAsync of 1 GiB pinned -> device, this run", "unit": "GB/s",
+                        "frac": round(min(1.0, fill_rate / link["h2d_GBs"]), 4)},
+        }
         return {"profile_lookups": Lp, "histogram_s": t_hist, "select_and_fill_s": t_sel, "k": k,
-                "histogram_Mlookups_per_s": Lp / max(t_hist, 1e-9) / 1e6,
-                "fill_host_link_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_sel, 1e-9) / 1e9,
-                "select_s": t_select, "select_Mrows_per_s": wl.total_rows / max(t_select, 1e-9) / 1e6, "rank_sort_s": t_rank,
-                "fill_s": t_fill, "fill_kernel_GBs": k * (wl.row_bytes + (wl.dim * 4 if wl.optimizer == "adagrad" else 0)) / max(t_fill, 1e-9) / 1e9,
-                "kernels_ms": {n: round(v["total_ms"], 4) for n, v in prof.items()}, "total_s": t_hist + t_sel}
+                "roofline": parts, "kernels_ms": {n: round(v["total_ms"], 4) for n, v in prof.items()},
+                "total_s": t_hist + t_sel}
 
     def step(self, e: int):
         wl = self.wl
@@ -151,53 +199,77 @@ class Bench:
             p.free()
 
 
+def _timed(fn, reps=3):
+    best = float("inf")
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b) * 1e-3)
+    return best
+
+
 def measure_link(dev) -> dict:
-    """Pinned <-> device hipMemcpyAsync of 1 GiB: each way alone, and both ways at once on two streams (the rate each
-    direction keeps while the other is busy): the host-link denominators."""
+    """The host-link denominators, all measured in this run: hipMemcpyAsync of 1 GiB each way, alone and both ways at
+    once; and the library's calibration kernel moving scattered pieces of 64 .. 512 bytes the way the fetch of missed
+    rows (reads) and the update of cold rows (writes) do, alone and both at once."""
     n = 1 << 30
     host = binding.PinnedArray((n,), np.uint8)
     host2 = binding.PinnedArray((n,), np.uint8)
     d = torch.empty(n, dtype=torch.uint8, device=dev)
     d2 = torch.empty(n, dtype=torch.uint8, device=dev)
     out = {}
-    for name, kind, dst, src in (("h2d_GBs", 1, d.data_ptr(), host.ptr), ("d2h_GBs", 2, host.ptr, d.data_ptr())):
-        best = 0.0
-        for _ in range(3):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            binding.memcpy(dst, src, n, kind)
-            b.record()
-            torch.cuda.synchronize()
-            best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
-        out[name] = best
+    out["h2d_GBs"] = n / _timed(lambda: binding.memcpy(d.data_ptr(), host.ptr, n, 1)) / 1e9
+    out["d2h_GBs"] = n / _timed(lambda: binding.memcpy(host.ptr, d.data_ptr(), n, 2)) / 1e9
+    # scattered pieces over the whole 1 GiB of host memory, 256 MiB moved per launch
+    moved = 1 << 28
+    rd, wr = {}, {}
+    for g in (64, 128, 256, 512):
+        rd[str(g)] = round(moved / _timed(lambda: binding.calibration_link(host, d, moved // g, g, True, False, 128)) / 1e9, 2)
+        wr[str(g)] = round(moved / _timed(lambda: binding.calibration_link(host2, d2, moved // g, g, True, True, 512)) / 1e9, 2)
+    out["link_random_read_GBs"] = rd
+    out["link_random_write_GBs"] = wr
+    out["link_sequential_read_512B_GBs"] = round(
+        moved / _timed(lambda: binding.calibration_link(host, d, moved // 512, 512, False, False, 128)) / 1e9, 2)
     # two streams of this measurement's own, destroyed afterwards: a process has few hardware queues, and streams left
-    # behind here would push the library's side streams onto the queue of the stream the benchmark runs on
+    # behind here could push the library's side streams onto the queue of the stream the benchmark runs on
     import ctypes
     hip = ctypes.CDLL("libamdhip64.so")
     raw = [ctypes.c_void_p(), ctypes.c_void_p()]
     for r in raw:
         assert hip.hipStreamCreateWithFlags(ctypes.byref(r), 1) == 0
     s1, s2 = torch.cuda.ExternalStream(raw[0].value), torch.cuda.ExternalStream(raw[1].value)
-    best_in = best_out = 0.0
-    for _ in range(3):
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        with torch.cuda.stream(s1):
-            ev[0].record()
-            binding.memcpy(d.data_ptr(), host.ptr, n, 1)
-            ev[1].record()
-        with torch.cuda.stream(s2):
-            ev[2].record()
-            binding.memcpy(host2.ptr, d2.data_ptr(), n, 2)
-            ev[3].record()
-        torch.cuda.synchronize()
-        best_in = max(best_in, n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9)
-        best_out = max(best_out, n / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9)
-    del s1, s2, ev
+
+    def both(fn_in, fn_out, nbytes):
+        best_in = best_out = 0.0
+        for _ in range(3):
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            with torch.cuda.stream(s1):
+                ev[0].record()
+                fn_in()
+                ev[1].record()
+            with torch.cuda.stream(s2):
+                ev[2].record()
+                fn_out()
+                ev[3].record()
+            torch.cuda.synchronize()
+            best_in = max(best_in, nbytes / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9)
+            best_out = max(best_out, nbytes / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9)
+            del ev
+        return best_in, best_out
+
+    out["h2d_duplex_GBs"], out["d2h_duplex_GBs"] = both(lambda: binding.memcpy(d.data_ptr(), host.ptr, n, 1),
+                                                          lambda: binding.memcpy(host2.ptr, d2.data_ptr(), n, 2), n)
+    kin, kout = both(lambda: binding.calibration_link(host, d, moved // 512, 512, True, False, 128),
+                     lambda: binding.calibration_link(host2, d2, moved // 512, 512, True, True, 512), moved)
+    out["link_kernel_duplex_512B_GBs"] = {"read": round(kin, 2), "write": round(kout, 2)}
+    del s1, s2
     torch.cuda.synchronize()
     for r in raw:
         assert hip.hipStreamDestroy(r) == 0
-    out["h2d_duplex_GBs"], out["d2h_duplex_GBs"] = best_in, best_out
     host.free()
     host2.free()
     return out
@@ -209,43 +281,116 @@ def calibration(dev) -> dict:
     n = 1 << 30
     a = torch.empty(n, dtype=torch.uint8, device=dev)
     b = torch.zeros(n, dtype=torch.uint8, device=dev)
-    best = 0.0
-    for _ in range(3):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        binding.calibration_copy(a, b)
-        e1.record()
-        torch.cuda.synchronize()
-        best = max(best, 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    t_copy = _timed(lambda: binding.calibration_copy(a, b))
     sink = torch.empty(binding.CALIB_SINK_BYTES, dtype=torch.uint8, device=dev)
-    best_r = 0.0
-    for _ in range(3):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        binding.calibration_read(a, sink)
-        e1.record()
-        torch.cuda.synchronize()
-        best_r = max(best_r, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    return {"copy_bytes_each_way": n, "copy_GBs": best, "read_GBs": best_r}
+    t_read = _timed(lambda: binding.calibration_read(a, sink))
+    return {"copy_bytes_each_way": n, "copy_GBs": 2 * n / t_copy / 1e9, "read_GBs": n / t_read / 1e9}
 
 
-def algorithmic_bytes(wl: synth.Workload, L: float, U: float, n_miss: float) -> dict:
-    """Bytes the method itself must move per launch of each kernel (per-lookup figures times the batch)."""
+def bytes_model(wl: synth.Workload, L: float, U: float, U_cold: float, n_miss: float, n_staged: float) -> dict:
+    """Bytes per launch of each kernel: `alg` = what the kernel's own definition moves (every lookup's row counted),
+    `min` = what no implementation could avoid (a row that several lookups of the batch share is counted once)."""
     R, D, G = wl.row_bytes, wl.dim, wl.num_bags
     st = 8 * D if wl.optimizer == "adagrad" else 0
-    return {
-        "pool_wave": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
-        "pool_group": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
-        "pool_short": L * R + G * D * 4 + 4 * L + 4 * (G + 1),
-        "stage_misses": 2 * n_miss * R + 4 * n_miss,          # link read + HBM write
-        "seg_rows": L * D * 4 + 8 * L + U * (2 * R + st + 12),   # with seg_long: gradient rows + row read-modify-write
-        "seg_rows_long": L * D * 4 + 8 * L + U * (2 * R + st + 12),   # small batches: both in one launch
-        "remap_probe": 16 * L,
-        "remap_write": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss),
-        "sort_scatter": 16 * L,
-        "sort_hist": 4 * L,
-        "bwd_pairs": 12 * L,
-    }
+    pool_alg = L * R + G * D * 4 + 4 * L + 4 * (G + 1)
+    pool_min = (U - U_cold + n_staged) * R + G * D * 4 + 4 * L + 4 * (G + 1)
+    upd_alg = L * D * 4 + 8 * L + U * (2 * R + st + 12)
+    upd_min = min(L, G) * D * 4 + 8 * L + U * (2 * R + st + 12)
+    m = {n: {"alg": pool_alg, "min": pool_min} for n in POOL_KERNELS}
+    m.update({n: {"alg": upd_alg, "min": upd_min} for n in UPDATE_KERNELS})
+    m.update({
+        "stage_misses": {"alg": 2 * n_staged * R + 4 * n_staged, "min": 2 * n_staged * R + 4 * n_staged},   # link read + HBM write
+        "remap_probe": {"alg": 16 * L, "min": 16 * L},
+        "remap_write": {"alg": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss), "min": 8 * L + 4 * L + 4 * n_miss * 2 + 4 * (L - n_miss)},
+        "sort_scatter": {"alg": 16 * L, "min": 16 * L},
+        "sort_hist": {"alg": 4 * L, "min": 4 * L},
+        "bwd_pairs": {"alg": 12 * L, "min": 12 * L},
+        "seg_count": {"alg": 4 * L, "min": 4 * L},
+        "seg_write": {"alg": 12 * L + 20 * U, "min": 12 * L + 20 * U},
+    })
+    return m
+
+
+def pmc_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload (a separate run of
+    the same command: the counters cannot be read from inside this process), or None."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.json")
+    try:
+        rec = json.load(open(path))
+        return rec[kernel]["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
+def avg_s(prof: dict, name: str) -> float:
+    return prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
+
+
+def hbm_roofline(name: str, t_s: float, model: dict, traffic, ms_per_step: float, launches_per_step: float) -> dict:
+    b = model[name]
+    r = {"kernel": name, "bound": "hbm", "achieved": round(b["min"] / t_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(min(1.0, b["min"] / t_s / 1e9 / HBM_PEAK_GBS), 4),
+         "bytes_counted": "compulsory: a row shared by several lookups of the batch counted once",
+         "compulsory_bytes_per_launch": int(b["min"]), "alg_bytes_per_launch": int(b["alg"]),
+         "effective_GBs": round(b["alg"] / t_s / 1e9, 1), "effective_vs_peak": round(b["alg"] / t_s / 1e9 / HBM_PEAK_GBS, 4),
+         "traffic": traffic, "avg_launch_ms": round(t_s * 1e3, 5),
+         "share_of_step": round(t_s * 1e3 * launches_per_step / ms_per_step, 4)}
+    if traffic:
+        r["counter_GBs"] = round(traffic / t_s / 1e9, 1)
+        r["frac_counter"] = round(traffic / t_s / 1e9 / HBM_PEAK_GBS, 4)
+        r["traffic_source"] = "profiles/pmc_<workload>.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run of this command, scaled by the 1 GiB copy kernel; not measured in this process"
+    return r
+
+
+def link_roofline(name: str, t_s: float, rd: float, wr: float, link: dict, traffic, ms_per_step: float,
+                  granule: int) -> dict:
+    """A kernel bound by the host link: both directions against the measured one-way copy rates; beside them the
+    rates the link gives a kernel moving scattered pieces of this row size, measured in the same run."""
+    t_min = max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9))
+    lead_rd = rd / link["h2d_GBs"] >= wr / link["d2h_GBs"]
+    g = str(min(512, max(64, granule)))
+    r = {"kernel": name, "bound": "host_link", "achieved": round((rd if lead_rd else wr) / t_s / 1e9, 2),
+         "peak": round(link["h2d_GBs"] if lead_rd else link["d2h_GBs"], 2),
+         "peak_source": "hipMemcpyAsync of 1 GiB, one way, measured in this run", "unit": "GB/s",
+         "frac": round(min(1.0, t_min / t_s), 4), "direction_priced": "host to device" if lead_rd else "device to host",
+         "link_read_bytes": int(rd), "link_write_bytes": int(wr), "read_GBs": round(rd / t_s / 1e9, 2),
+         "write_GBs": round(wr / t_s / 1e9, 2), "avg_launch_ms": round(t_s * 1e3, 5),
+         "share_of_step": round(t_s * 1e3 / ms_per_step, 4), "traffic": traffic,
+         "row_bytes": granule,
+         "measured_ceiling_for_scattered_rows_of_this_size_GBs": {"read": link["link_random_read_GBs"][g],
+                                                                  "write": link["link_random_write_GBs"][g]},
+         "frac_of_that_ceiling": round(min(1.0, max(rd / (link["link_random_read_GBs"][g] * 1e9),
+                                                    wr / (link["link_random_write_GBs"][g] * 1e9)) / t_s), 4)}
+    if rd > 0 and wr > 0:
+        r["frac_of_duplex_copy"] = round(min(1.0, max(rd / (link["h2d_duplex_GBs"] * 1e9), wr / (link["d2h_duplex_GBs"] * 1e9)) / t_s), 4)
+        r["request_bound"] = False
+    if granule < 256:
+        r["request_bound"] = True      # below 256 bytes per piece the link gives requests per second, not bytes
+    return r
+
+
+def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None):
+    """(dominant-kernel roofline, gather roofline, host_link list) of one leg from its per-kernel times."""
+    per_step = {n: r["total_ms"] / K for n, r in prof.items()}
+    dominant = max(per_step, key=per_step.get)
+    pool = which_pool or [n for n in POOL_KERNELS if n in prof][0]
+    gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc_traffic(wl.name, pool), ms_per_step, prof[pool]["launches"] / K)
+    host_link = []
+    for name in ("stage_misses",) + UPDATE_KERNELS:
+        if name not in prof:
+            continue
+        rd, wr = link_bytes(name)
+        if rd + wr > 0:
+            host_link.append(link_roofline(name, avg_s(prof, name), rd, wr, link, pmc_traffic(wl.name, name), ms_per_step, wl.row_bytes))
+    by_name = {r["kernel"]: r for r in host_link}
+    if dominant in by_name:
+        top = by_name[dominant]
+    elif dominant in model:
+        top = hbm_roofline(dominant, avg_s(prof, dominant), model, pmc_traffic(wl.name, dominant), ms_per_step,
+                           prof[dominant]["launches"] / K)
+    else:
+        top = dict(gather, note=f"the largest share of the step is {dominant}, for which no byte model is kept")
+    return top, gather, host_link
 
 
 def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> dict:
@@ -279,6 +424,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     assert b.s.sync_status() == 0
+    ms_per_step = (t1 - t0) * 1e3 / K
     n_hit, n_miss = b.rm.n_hit_miss.cpu().tolist()
     n_staged = b.rm.n_unique_miss.cpu().tolist()[0] if b.coalesce else n_miss   # rows fetched over the link
 
@@ -345,54 +491,43 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     per_step = sorted(a.elapsed_time(c) for a, c in evs)
 
     L_avg = lookups / K
-    alg = algorithmic_bytes(wl, L_avg, U, n_miss)
+    model = bytes_model(wl, L_avg, U, U_cold, n_miss, n_staged)
     if "pool_short_staged" in prof:
         # one index per bag, side-stream option: bags whose row is cached are pooled by one launch while the missed
         # rows are fetched, the others by a second launch after the fetch; the bytes split with the bags
-        whole = alg["pool_short"]
-        alg["pool_short"] = whole * n_hit / max(1, n_hit + n_miss)
-        alg["pool_short_staged"] = whole - alg["pool_short"]
-    if "bwd_pairs" not in prof:
-        alg["remap_write"] += alg["bwd_pairs"]   # the launch that lists hits and misses also wrote the backward pairs
+        share = n_hit / max(1, n_hit + n_miss)
+        whole = model["pool_short"]
+        model["pool_short_staged"] = {k: v * (1 - share) for k, v in whole.items()}
+        model["pool_short"] = {k: v * share for k, v in whole.items()}
+    if "bwd_pairs" not in prof:    # the launch that lists hits and misses also wrote the backward pairs
+        model["remap_write"] = {k: v + model["bwd_pairs"][k] for k, v in model["remap_write"].items()}
     kern = {}
     for name, r in prof.items():
-        avg_ms = r["total_ms"] / r["launches"]
-        kern[name] = {"launches_per_step": r["launches"] / K, "avg_ms": round(avg_ms, 5),
-                      "ms_per_step": round(r["total_ms"] / K, 5)}
-        if name in alg:
-            kern[name]["alg_GBs"] = round(alg[name] / (avg_ms * 1e-3) / 1e9, 1)
-    pool = [n for n in ("pool_wave", "pool_group", "pool_short") if n in prof][0]
-    pool_avg_s = prof[pool]["total_ms"] / prof[pool]["launches"] * 1e-3
-    achieved = alg[pool] / pool_avg_s / 1e9
-    roofline = {"kernel": pool, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": pmc_traffic(wl.name, pool),
-                "alg_bytes_per_launch": int(alg[pool]), "avg_launch_ms": round(pool_avg_s * 1e3, 5)}
-    alone_s = prof_fwd[pool]["total_ms"] / prof_fwd[pool]["launches"] * 1e-3
-    roofline["forward_alone"] = {"avg_launch_ms": round(alone_s * 1e3, 5), "achieved": round(alg[pool] / alone_s / 1e9, 1),
-                                 "frac": round(alg[pool] / alone_s / 1e9 / HBM_PEAK_GBS, 4)}
-    cold_s = prof_cold[pool]["total_ms"] / prof_cold[pool]["launches"] * 1e-3
-    roofline["forward_cold_caches"] = {"avg_launch_ms": round(cold_s * 1e3, 5), "achieved": round(alg[pool] / cold_s / 1e9, 1),
-                                       "frac": round(alg[pool] / cold_s / 1e9 / HBM_PEAK_GBS, 4)}
-    calls = {c: round(v, 5) for c, v in alone.items()}
-    host_link = []
+        a_ms = r["total_ms"] / r["launches"]
+        kern[name] = {"launches_per_step": r["launches"] / K, "avg_ms": round(a_ms, 5), "ms_per_step": round(r["total_ms"] / K, 5)}
+        if name in model:
+            kern[name]["alg_GBs"] = round(model[name]["alg"] / (a_ms * 1e-3) / 1e9, 1)
     state_b = wl.dim * 4 if wl.optimizer == "adagrad" else 0
     # forward: every missed lookup's row is read over the link.  backward: a cold row's value comes from the copy
     # the forward pass staged, so only its accumulator is read over the link; row and accumulator are written back
-    for name, rd, wr in (("stage_misses", n_staged * wl.row_bytes, 0),
-                         ("seg_rows", U_cold * state_b, U_cold * (wl.row_bytes + state_b)),
-                         ("seg_rows_long", U_cold * state_b, U_cold * (wl.row_bytes + state_b))):
-        if name in prof and rd + wr > 0:
-            t_s = prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
-            t_min = max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9))
-            host_link.append({"kernel": name, "link_read_bytes": int(rd), "link_write_bytes": int(wr),
-                              "avg_launch_ms": round(t_s * 1e3, 5), "read_GBs": round(rd / t_s / 1e9, 2),
-                              "write_GBs": round(wr / t_s / 1e9, 2), "frac_of_measured_link": round(t_min / t_s, 4)})
-    return {"value": lookups / (t1 - t0), "ms_per_step": (t1 - t0) * 1e3 / K, "lookups_per_step": L_avg,
-            "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "n_miss": n_miss, "n_staged": n_staged, "roofline": roofline,
-            "host_link": host_link, "kernels": kern, "calls_alone_ms": calls,
+    lb = {"fetch": n_staged * wl.row_bytes, "acc": U_cold * state_b, "write": U_cold * (wl.row_bytes + state_b)}
+    link_bytes = lambda name: (lb["fetch"], 0) if name == "stage_misses" else (lb["acc"], lb["write"])
+    top, gather, host_link = rooflines(wl, prof, K, ms_per_step, model, link, link_bytes)
+    pool = gather["kernel"]
+    for tag, p in (("forward_alone", prof_fwd), ("forward_cold_caches", prof_cold)):
+        t = avg_s(p, pool)
+        gather[tag] = {"avg_launch_ms": round(t * 1e3, 5), "achieved": round(model[pool]["min"] / t / 1e9, 1),
+                       "frac": round(min(1.0, model[pool]["min"] / t / 1e9 / HBM_PEAK_GBS), 4),
+                       "effective_GBs": round(model[pool]["alg"] / t / 1e9, 1),
+                       "effective_vs_peak": round(model[pool]["alg"] / t / 1e9 / HBM_PEAK_GBS, 4)}
+        if gather.get("traffic"):
+            gather[tag]["frac_counter"] = round(gather["traffic"] / t / 1e9 / HBM_PEAK_GBS, 4)
+    return {"value": lookups / (t1 - t0), "ms_per_step": ms_per_step, "lookups_per_step": L_avg,
+            "hit_rate": n_hit / max(1, n_hit + n_miss), "U": U, "U_cold": U_cold, "n_miss": n_miss, "n_staged": n_staged,
+            "roofline": top, "gather": gather, "host_link": host_link, "kernels": kern,
+            "calls_alone_ms": {c: round(v, 5) for c, v in alone.items()},
             "ms_per_step_median": round(per_step[len(per_step) // 2], 5), "ms_per_step_min": round(per_step[0], 5),
-            "_alg": alg, "_pool": pool, "_link_bytes": {"fetch": n_staged * wl.row_bytes, "acc": U_cold * state_b,
-                                                        "write": U_cold * (wl.row_bytes + state_b)}}
+            "_model": model, "_pool": pool, "_link_bytes": lb}
 
 
 def run_lookahead(b: Bench, K: int, W: int, leg: dict, link: dict) -> dict:
@@ -404,6 +539,7 @@ def run_lookahead(b: Bench, K: int, W: int, leg: dict, link: dict) -> dict:
     eps = wl.eps if wl.optimizer == "adagrad" else 0.0
     rms = [b.rm, s.new_remap_out()]
     s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    s.set_tuning(binding.TUNE_FUSED_FETCH, 1 if b.fused_fetch else 0)
 
     def prime(e):
         idx, off = b.batches[e % n]
@@ -432,55 +568,44 @@ def run_lookahead(b: Bench, K: int, W: int, leg: dict, link: dict) -> dict:
     t1 = time.perf_counter()
     used = s.get_counter(binding.COUNTER_AHEAD_USED) - used0
     assert s.sync_status() == 0
+    ms_per_step = (t1 - t0) * 1e3 / K
+    timed0, serial0 = s.get_counter(binding.COUNTER_AHEAD_TIMED), s.get_counter(binding.COUNTER_AHEAD_NOT_OVERLAPPED)
     s.profile_enable(True)
     for e in range(W + K, W + 2 * K):
         step(e)
     prof = s.profile_read()
     s.profile_enable(False)
+    timed = s.get_counter(binding.COUNTER_AHEAD_TIMED) - timed0
+    serial = s.get_counter(binding.COUNTER_AHEAD_NOT_OVERLAPPED) - serial0
     s.set_tuning(binding.TUNE_LOOKAHEAD, 0)
     s.remap(*b.batches[0], wl.batch, b.rm)      # leave no look-ahead state behind for the legs that follow
     torch.cuda.synchronize()
-    kern = {k: {"launches_per_step": v["launches"] / K, "avg_ms": round(v["total_ms"] / v["launches"], 5)}
-            for k, v in prof.items()}
-    # the gather kernel inside this order, against the same algorithmic bytes as in the plain order
-    alg, pool = leg["_alg"], leg["_pool"]
-    pool_s = prof[pool]["total_ms"] / prof[pool]["launches"] * 1e-3
-    roofline = {"kernel": pool, "bound": "hbm", "achieved": round(alg[pool] / pool_s / 1e9, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(alg[pool] / pool_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": pmc_traffic(wl.name, pool),
-                "alg_bytes_per_launch": int(alg[pool]), "avg_launch_ms": round(pool_s * 1e3, 5)}
+    kern = {k: {"launches_per_step": v["launches"] / K, "avg_ms": round(v["total_ms"] / v["launches"], 5),
+                "ms_per_step": round(v["total_ms"] / K, 5)} for k, v in prof.items()}
     # the link while the update runs: the fetch for the next batch and the accumulators come in, rows and
-    # accumulators go out, at the same time
+    # accumulators go out, at the same time (the few rows left to the forward pass's own fetch are not counted)
     lb = leg["_link_bytes"]
-    upd = "seg_rows_long" if "seg_rows_long" in prof else "seg_rows"
-    t_upd = max(prof[upd]["total_ms"] / prof[upd]["launches"],
-                prof["fetch_ahead"]["total_ms"] / prof["fetch_ahead"]["launches"] if "fetch_ahead" in prof else 0.0) * 1e-3
-    rd, wr = lb["fetch"] + lb["acc"], lb["write"]
-    host_link = [{"kernel": upd + " beside fetch_ahead", "link_read_bytes": int(rd), "link_write_bytes": int(wr),
-                  "avg_launch_ms": round(t_upd * 1e3, 5), "read_GBs": round(rd / t_upd / 1e9, 2),
-                  "write_GBs": round(wr / t_upd / 1e9, 2),
-                  "frac_of_measured_link": round(max(rd / (link["h2d_GBs"] * 1e9), wr / (link["d2h_GBs"] * 1e9)) / t_upd, 4),
-                  "frac_of_measured_duplex_link": round(max(rd / (link["h2d_duplex_GBs"] * 1e9),
-                                                            wr / (link["d2h_duplex_GBs"] * 1e9)) / t_upd, 4)}]
-    return {"value": lookups / (t1 - t0), "unit": "lookups/s", "ms_per_step": (t1 - t0) * 1e3 / K,
+    fused = "seg_rows_long+fetch_ahead" in prof
+
+    def link_bytes(name):
+        if name == "stage_misses":
+            return (0, 0)
+        return (lb["acc"] + (lb["fetch"] if fused or "fetch_ahead" in prof else 0), lb["write"])
+
+    top, gather, host_link = rooflines(wl, prof, K, ms_per_step, leg["_model"], link, link_bytes, leg["_pool"])
+    return {"value": lookups / (t1 - t0), "unit": "lookups/s", "ms_per_step": ms_per_step,
             "forward_passes_with_rows_fetched_ahead": int(used), "steps": K,
+            "fetch": "in the first workgroups of the update's own launch" if fused else "a launch of its own on the library's second stream",
+            "updates_timed_beside_a_fetch_on_the_library_stream": int(timed), "of_which_not_overlapped": int(serial),
             "order": "remap(e+1) -> embedding_bag_bwd_update_ahead(e, e+1) -> embedding_bag_fwd(e+1)",
-            "roofline": roofline, "host_link": host_link, "kernels": kern}
-
-
-def pmc_traffic(workload: str, kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if any."""
-    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.json")
-    try:
-        return json.load(open(path))[kernel]["hbm_bytes_per_launch"]
-    except Exception:
-        return None
+            "roofline": top, "gather": gather, "host_link": host_link, "kernels": kern}
 
 
 def cpu_baseline(b: Bench, seconds_target: float = 12.0) -> dict:
     """The CPU oracle, as it stands, on the machine's host cores, on a bounded sample of the same workload."""
     import oracle
     wl = b.wl
-    cores = min(16, os.cpu_count() or 1)
+    cores = min(16, os.cpu_count() or 1)     # a one-GPU box's CPU share is 16 cores, whatever os.cpu_count() shows
     used = oracle.set_threads(cores)
     tabs = [p.np for p in b.tables]
     st = [p.np for p in b.state] if b.state else None
@@ -519,9 +644,18 @@ def cpu_baseline(b: Bench, seconds_target: float = 12.0) -> dict:
         pass
     return {"value": done_L / t_total, "unit": "lookups/s", "cores": used, "kind": "oracle",
             "sample": f"{nb} batch(es) of the same workload ({done_L} lookups): oracle remap + fwd + bwd_update "
-                      f"(report mode, nothing mutated) in {t_total:.1f}s",
+                      f"(report mode, nothing mutated) in {t_total:.1f}s.  A stated baseline, not a target: the oracle is "
+                      f"the plain definition (fp64 sums, one qsort of the (row, position) pairs on a single thread, "
+                      f"OpenMP only over bags and rows), so {used} threads gain little over one",
             "value_1_thread": one_L / one_t, "sample_1_thread": f"{one_nb} batch(es) in {one_t:.1f}s",
             "cpu_model": model, "host_cpus_visible": os.cpu_count()}
+
+
+def measured_block(cal: dict, link: dict) -> dict:
+    m = {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1)}
+    for k, v in link.items():
+        m[k] = round(v, 2) if isinstance(v, float) else v
+    return m
 
 
 def main():
@@ -532,8 +666,8 @@ def main():
     ap.add_argument("--workload", default="multi_hot", choices=synth.WORKLOAD_NAMES)
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--row-scale", type=float, default=None,
-                    help="shrink table rows and budget only (default 1.0; 0.5 for host_spill, whose 102 GB of "
-                         "tables exceed what one box lets a process pin, about 64 GB)")
+                    help="shrink table rows and budget only (default: 1.0, and for host_spill, whose 102 GB of tables "
+                         "may exceed what the box lets one process pin, the largest multiple of 0.05 that can be pinned)")
     ap.add_argument("--budget-bytes", type=int, default=-1, help="override the workload's cache budget")
     ap.add_argument("--also", default="dlrm_onehot,low_skew,host_spill",
                     help="comma-separated other workloads to run briefly afterwards and report under other_workloads "
@@ -543,6 +677,8 @@ def main():
     ap.add_argument("--coalesce", action="store_true",
                     help="remap lists each distinct missed row once (Section II-A): one link read per unique cold row")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-calibration", action="store_true",
+                    help="measure the HBM and host-link ceilings (copy kernels, copies, scattered-piece kernels), print them and stop")
     ap.add_argument("--fused-long-max-l", type=int, default=-1,
                     help="largest batch (lookups) whose backward pass updates long runs and the other rows in one "
                          "launch (default: the library's, every batch; 0 = never)")
@@ -550,10 +686,13 @@ def main():
                     help="most workgroups of the per-row update kernel (default: the library's, 8192)")
     ap.add_argument("--no-lookahead", dest="lookahead", action="store_false",
                     help="skip the extra leg in the look-ahead call order (reported under lookahead)")
+    ap.add_argument("--fetch-on-own-stream", dest="fused_fetch", action="store_false",
+                    help="look-ahead order: fetch the next batch's rows in a launch of its own on the library's second "
+                         "stream instead of inside the update's launch")
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
-    ap.set_defaults(presort=True, lookahead=True)
+    ap.set_defaults(presort=True, lookahead=True, fused_fetch=True)
     ap.add_argument("--no-resident", dest="resident", action="store_false",
                     help="skip the second leg in which every row is cached (the paper's 'hot' iteration): same "
                          "kernels, no host-link traffic; reported under cache_resident")
@@ -570,6 +709,9 @@ def main():
     cal = calibration(dev)
     link = measure_link(dev)
     log("calibration", cal, "link", link)
+    if args.only_calibration:
+        print(json.dumps({"measured": measured_block(cal, link)}), flush=True)
+        return
     line = run_workload(args.workload, args, args.steps, args.warmup, cal, link, not args.no_cpu_baseline, args.resident)
     others = {}
     for name in [w for w in args.also.split(",") if w and w != "none" and w != args.workload]:
@@ -577,11 +719,13 @@ def main():
         torch.cuda.empty_cache()
         r = run_workload(name, args, min(args.steps, 10), min(args.warmup, 3), cal, link, False, False)
         others[name] = {"value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "dtype": r["dtype"],
-                        "config": {k: r["config"][k] for k in ("row_scale", "rows", "dim", "batch", "lookups_per_step",
-                                                                "hit_rate", "budget_bytes", "optimizer")},
-                        "roofline": r["roofline"], "host_link": r["host_link"], "call_order": r["config"]["step"].split("call order: ")[1],
+                        "config": {k: r["config"][k] for k in ("row_scale", "scaled", "pinning", "rows", "dim", "batch", "lookups_per_step",
+                                                                "hit_rate", "budget_bytes", "optimizer") if k in r["config"]},
+                        "roofline": r["roofline"], "gather": r["gather"], "host_link": r["host_link"],
+                        "call_order": r["config"]["step"].split("call order: ")[1],
                         "plain_order": {k: r["plain_order"][k] for k in ("value", "ms_per_step")},
-                        "lookahead": r["lookahead"] and {k: r["lookahead"][k] for k in ("value", "ms_per_step")}}
+                        "lookahead": r["lookahead"] and {k: r["lookahead"][k] for k in ("value", "ms_per_step")},
+                        "build_cache_roofline": r["build_cache"]["roofline"]}
     line["other_workloads"] = others
     if args.also != "none" and args.workload != "low_skew_uniform":
         # the gather roofline reference: uniform ids over 6.4 GB of rows, every row cached (no reuse for the caches
@@ -589,28 +733,41 @@ def main():
         torch.cuda.empty_cache()
         r = run_workload("low_skew_uniform", args, min(args.steps, 10), min(args.warmup, 3), cal, link, False, False, True)
         line["gather_reference"] = {"workload": "low_skew_uniform, every row cached", "value": r["value"], "unit": r["unit"],
-                                    "ms_per_step": r["ms_per_step"], "roofline": r["roofline"]}
+                                    "ms_per_step": r["ms_per_step"], "roofline": r["roofline"], "gather": r["gather"]}
     print(json.dumps(line), flush=True)
 
 
 def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cpu: bool, with_resident: bool,
                  all_cached: bool = False) -> dict:
-    dev = torch.device("cuda:0")
-    row_scale = args.row_scale if args.row_scale is not None else (0.5 if name == "host_spill" else 1.0)
-    wl = synth.workload(name, scale=args.scale, row_scale=row_scale)
+    # host_spill asks for 102.4 GB of pinned tables: try that first, record what the box refuses, and step down
+    forced = args.row_scale is not None
+    row_scale = args.row_scale if forced else 1.0
+    attempts = []
+    while True:
+        wl = synth.workload(name, scale=args.scale, row_scale=row_scale)
+        pinned, failure = pin_tables(wl, wl.optimizer == "adagrad")
+        if pinned is not None:
+            break
+        failure["row_scale"] = round(row_scale, 2)
+        attempts.append(failure)
+        log(name, "cannot pin its tables at row_scale", round(row_scale, 2), failure)
+        if forced or row_scale <= 0.05 + 1e-9:
+            raise SystemExit(f"bench.py: cannot pin the tables of {name}: {failure}")
+        row_scale = round(row_scale - 0.05, 2)
     budget = wl.budget_bytes if (args.budget_bytes < 0 or name != args.workload) else args.budget_bytes
     if all_cached:
         budget = wl.total_rows * wl.row_bytes
 
-    b = Bench(wl, budget, args.coalesce)
+    b = Bench(wl, budget, pinned, args.coalesce)
     b.presort = bool(args.presort)
+    b.fused_fetch = bool(args.fused_fetch)
     b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
     if args.fused_long_max_l >= 0:
         b.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, args.fused_long_max_l)
     if args.update_max_blocks > 0:
         b.s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, args.update_max_blocks)
     b.prepare(K + W)
-    bc = b.build_cache()
+    bc = b.build_cache(link)
     log(name, "build_cache", bc)
 
     leg = run_leg(b, K, W, link, args.graph)
@@ -630,8 +787,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         r = run_leg(b, K, W, link, args.graph)
         resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
                     "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
-                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "calls_alone_ms": r["calls_alone_ms"],
-                    "kernels": r["kernels"]}
+                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "gather": r["gather"],
+                    "calls_alone_ms": r["calls_alone_ms"], "kernels": r["kernels"]}
         log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
 
     cpu = None
@@ -645,16 +802,26 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     plain = {"value": leg["value"], "unit": "lookups/s", "ms_per_step": leg["ms_per_step"],
              "ms_per_step_median": leg["ms_per_step_median"], "ms_per_step_min": leg["ms_per_step_min"],
              "order": "remap(e) -> embedding_bag_fwd(e) -> embedding_bag_bwd_update(e)",
-             "roofline": leg["roofline"], "host_link": leg["host_link"], "calls_alone_ms": leg["calls_alone_ms"],
-             "kernels": leg["kernels"]}
+             "roofline": leg["roofline"], "gather": leg["gather"], "host_link": leg["host_link"],
+             "calls_alone_ms": leg["calls_alone_ms"], "kernels": leg["kernels"]}
     # the headline is the faster of the two call orders; both are reported in full (same batches, same results)
     best = ahead if (ahead is not None and ahead["value"] > leg["value"]) else plain
+    gather = dict(best["gather"])
+    if best is ahead:      # the gather kernel alone and with cold caches do not depend on the call order
+        gather["forward_alone"] = leg["gather"]["forward_alone"]
+        gather["forward_cold_caches"] = leg["gather"]["forward_cold_caches"]
+    full_rows = synth.workload(name, scale=args.scale).total_rows
     line = {
         "metric": "pooled embedding lookups/sec (fwd+bwd) + achieved HBM GB/s, 1 GPU",
         "value": best["value"], "unit": "lookups/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 sums", "data": "synthetic",
-        "config": {"workload": wl.name, "scale": args.scale, "row_scale": row_scale, "tables": wl.num_tables, "rows": wl.total_rows,
+        "config": {"workload": wl.name, "scale": args.scale, "row_scale": row_scale, "scaled": wl.total_rows != full_rows,
+                   "pinning": {"rows_of_the_full_workload": full_rows, "rows_run": wl.total_rows,
+                               "refused_attempts": attempts,
+                               "note": "full size" if wl.total_rows == full_rows else
+                                       "the box refused to pin the full tables; this is the largest multiple of 0.05 of the rows it pins"},
+                   "tables": wl.num_tables, "rows": wl.total_rows,
                    "dim": wl.dim, "batch": wl.batch, "lookups_per_step": leg["lookups_per_step"], "zipf_s": wl.zipf_s,
                    "budget_bytes": budget, "cached_rows": bc["k"], "optimizer": wl.optimizer,
                    "hit_rate": leg["hit_rate"], "unique_rows_per_step": leg["U"],
@@ -663,16 +830,11 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
                    "launch": ("hip graph of the K steps" if args.graph else "eager") +
                              (", backward sort prepared on the library's side stream" if args.presort else ""),
                    "step": "every batch goes through remap, embedding_bag_fwd and embedding_bag_bwd_update once; call order: " + best["order"]},
-        "roofline": best["roofline"], "host_link": best["host_link"],
-        "measured": {"hbm_copy_GBs": round(cal["copy_GBs"], 1), "hbm_read_GBs": round(cal["read_GBs"], 1), "h2d_GBs": round(link["h2d_GBs"], 2),
-                     "d2h_GBs": round(link["d2h_GBs"], 2), "h2d_duplex_GBs": round(link["h2d_duplex_GBs"], 2),
-                     "d2h_duplex_GBs": round(link["d2h_duplex_GBs"], 2)},
+        "roofline": best["roofline"], "gather": gather, "host_link": best["host_link"],
+        "measured": measured_block(cal, link),
         "cpu_baseline": cpu, "cache_resident": resident, "plain_order": plain, "lookahead": ahead,
         "kernels": best["kernels"], "build_cache": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in bc.items()},
     }
-    if best is ahead:      # the gather kernel alone and with cold caches do not depend on the call order
-        line["roofline"] = dict(ahead["roofline"], forward_alone=leg["roofline"]["forward_alone"],
-                                forward_cold_caches=leg["roofline"]["forward_cold_caches"])
     b.close()
     del b
     return line

@@ -25,10 +25,11 @@
  *    call returns without waiting unless stated.  Calls on one handle must be issued in stream
  *    order; two calls on one handle must not run concurrently.
  *  - Some options (SCARS_TUNE_PRESORT, SCARS_TUNE_LOOKAHEAD) run part of a call on up to two streams the library
- *    owns (default priority, non-blocking, created on first use, always joined back into the caller's stream before
- *    the results are needed).  They only overlap with the caller's stream if they sit on other hardware queues: a
- *    process has few (4 by default), handed out as streams are created, so create a handle's streams (its first
- *    calls) before many streams of your own.
+ *    owns (default priority, non-blocking, created by the first scars_bind_buffers on a handle, always joined back
+ *    into the caller's stream before the results are needed).  They only overlap with the caller's stream if they sit
+ *    on other hardware queues: a process has few (4 by default), handed out as streams are created, so bind a
+ *    handle's buffers before creating many streams of your own.  SCARS_COUNTER_AHEAD_NOT_OVERLAPPED tells, in profile
+ *    mode, when such an overlap did not happen.
  *  - Two errors are detected on the device and latched in the handle's status word, to be read by
  *    scars_sync_status: SCARS_ERR_INDEX_RANGE (an index < 0 or >= rows[t]: that lookup is treated
  *    as absent everywhere -- not counted, neither hit nor miss, adds nothing, updates nothing) and
@@ -109,10 +110,21 @@ typedef struct {
  * then leaves alone everything that update uses: it writes no pairs and starts no preparation), and
  * scars_embedding_bag_bwd_update_ahead is allowed.  The two batches need remap outputs of their own. */
 #define SCARS_TUNE_LOOKAHEAD 6                  /* default 0 */
+/* Non-zero: scars_embedding_bag_bwd_update_ahead carries the fetch of the next batch's rows in the first workgroups
+ * of its own update launch, on the caller's stream, whenever the update is one launch (see
+ * SCARS_TUNE_FUSED_LONG_MAX_L); the two directions of the host link then overlap without a second hardware queue.
+ * 0: the fetch is a launch of its own on the library's second stream. */
+#define SCARS_TUNE_FUSED_FETCH 7                /* default 1 */
 
 /* Host-side counters (never reset); -1 for an unknown counter. */
 #define SCARS_COUNTER_PREPARED_USED 1  /* bwd_update calls that used the segments prepared under SCARS_TUNE_PRESORT */
 #define SCARS_COUNTER_AHEAD_USED 2     /* forward passes that found their missed rows fetched ahead */
+/* Self-check of the overlap the library's own streams are for (only counted while scars_profile_enable is on, at
+ * scars_profile_read): updates that had the next batch's fetch enqueued beside them on the library's second stream,
+ * and how many of those fetches did NOT run at the same time as the update (less than a quarter of the shorter one
+ * overlapped): a sign that the library's stream shares a hardware queue with the caller's. */
+#define SCARS_COUNTER_AHEAD_TIMED 3
+#define SCARS_COUNTER_AHEAD_NOT_OVERLAPPED 4
 int64_t scars_get_counter(const scars_handle* h, int32_t which);
 int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value);
 
@@ -142,6 +154,9 @@ typedef struct {
     int64_t budget_bytes; /* the three arguments scars_query_sizes was called with */
     int64_t max_L;
     int64_t max_G;
+    /* how many bytes each buffer above really has; scars_bind_buffers returns SCARS_ERR_WORKSPACE when one is
+     * smaller than scars_query_sizes asks for with these three arguments (a buffer that may be NULL may say 0) */
+    int64_t counts_bytes, slot_of_bytes, hot_gid_bytes, cache_bytes, state_cache_bytes, workspace_bytes;
 } scars_buffers;
 
 /* Outputs of scars_remap, all DEVICE, each int32 [L] unless noted. */
@@ -192,8 +207,8 @@ int32_t scars_query_sizes(const scars_handle* h, int64_t budget_bytes, int64_t m
  * the status word on `stream`; waits for that copy.  Forgets any previously built hot set. */
 int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* bufs, void* stream);
 
-/* Skew table + top-k + cache fill (Section III: "ranked skew table for all embeddings, selecting the top
- * few embeddings for caching"; Section IV: fixed byte budget).
+/* Skew table + top-k + cache fill (Section III: a frequency ranking over all rows, the hottest of which are kept on
+ * the device; Section IV: fixed byte budget).
  *   counts[gid] += 1 for each of the Lp lookups of the profile batch (d_indices/d_offsets DEVICE,
  *   offsets has T*bags_per_table+1 entries);  then, unless accumulate == 2:
  *   k = min(N, floor(budget_bytes / R)); the hot set is the first k rows in the order (count descending,
@@ -264,8 +279,8 @@ int32_t scars_embedding_bag_bwd_update_ahead(scars_handle* h, const int32_t* d_i
                                              const scars_remap_out* next_rm, const int32_t* d_next_offsets,
                                              int64_t next_L, int64_t next_B, void* stream);
 
-/* Hot / normal samples (Section III: samples that "only need hot embeddings" versus the rest, so that
- * mini-batches of one kind can be composed).  Sample b is hot when none of its lookups over all T tables is a
+/* Hot / normal samples (Section III: samples whose lookups are all cached versus the rest, so that mini-batches of
+ * one kind can be composed).  Sample b is hot when none of its lookups over all T tables is a
  * miss; invalid lookups are ignored.  `rm` must come from scars_remap on this batch. */
 int32_t scars_classify_samples(scars_handle* h, const int32_t* d_offsets, int64_t L, int64_t B, const scars_remap_out* rm,
                                const scars_classify_out* out, void* stream);
@@ -339,8 +354,9 @@ int32_t scars_host_free(void* p);
 int32_t scars_memcpy(void* dst, const void* src, int64_t bytes, int32_t kind /* 1 = H2D, 2 = D2H, 3 = D2D */,
                      void* stream);
 
-/* Measurement aid: a plain grid-stride copy kernel (k_calib_copy) of `bytes` (multiple of 16) between two DEVICE
- * buffers, used to scale hardware byte counters against a transfer of known size. */
+/* Measurement aid: a plain streaming copy kernel (k_calib_copy; four 16-byte loads in flight per lane) of `bytes`
+ * (multiple of 16) between two DEVICE buffers, used to scale hardware byte counters against a transfer of known size
+ * and as the box's own copy rate. */
 int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
 
 /* Measurement aid: a plain grid-stride read-only kernel over `bytes` (multiple of 16) of a DEVICE buffer; each
@@ -348,6 +364,16 @@ int32_t scars_calibration_copy(void* d_dst, const void* d_src, int64_t bytes, vo
  * box's streaming read rate, the practical ceiling of a gather. */
 #define SCARS_CALIB_SINK_BYTES (4 << 20)
 int32_t scars_calibration_read(const void* d_src, int64_t bytes, void* d_sink, void* stream);
+
+/* Measurement aid for the host link: n_granules pieces of granule_bytes (16 .. 1024, a power of two) move between
+ * h_pinned (PINNED, host_bytes long) and d_buf (DEVICE, at least n_granules * granule_bytes), 16 bytes per lane and
+ * granule_bytes / 16 lanes per piece, four pieces in flight per lane group, `workgroups` workgroups of 256 lanes.
+ * Piece j of d_buf pairs with a piece of the host buffer picked by a hash of j (scattered != 0: the pattern in which
+ * the rows of a batch lie in their tables) or with piece j modulo the host buffer (sequential).  to_host 0 reads the
+ * host (the missed-row fetch of Fig. 1), 1 writes it (the cold-row update of Section IV).  Timed by the caller; gives
+ * the link's ceiling for this access pattern, which below 256 bytes per piece is a request rate, not a byte rate. */
+int32_t scars_calibration_link(void* h_pinned, int64_t host_bytes, void* d_buf, int64_t n_granules, int32_t granule_bytes,
+                               int32_t scattered, int32_t to_host, int32_t workgroups, void* stream);
 
 /* Per-kernel timing for measurement: when enabled, every kernel launch is bracketed by HIP events on the
  * caller's stream.  scars_profile_read waits for the stream, then returns up to `cap` records

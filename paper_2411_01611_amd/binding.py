@@ -27,7 +27,7 @@ EXPORTS = (
     "scars_caching_gain",
     "scars_plan_cache", "scars_embedding_bag_fwd", "scars_embedding_bag_bwd_update", "scars_embedding_bag_bwd_update_ahead",
     "scars_flush_cache", "scars_sync_status", "scars_last_error", "scars_host_alloc", "scars_host_free",
-    "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_profile_enable", "scars_profile_read",
+    "scars_memcpy", "scars_calibration_copy", "scars_calibration_read", "scars_calibration_link", "scars_profile_enable", "scars_profile_read",
 )
 
 
@@ -51,7 +51,9 @@ class _Sizes(C.Structure):
 class _Buffers(C.Structure):
     _fields_ = [("counts", C.c_void_p), ("slot_of", C.c_void_p), ("hot_gid", C.c_void_p), ("cache", C.c_void_p),
                 ("state_cache", C.c_void_p), ("workspace", C.c_void_p), ("budget_bytes", C.c_int64),
-                ("max_L", C.c_int64), ("max_G", C.c_int64)]
+                ("max_L", C.c_int64), ("max_G", C.c_int64), ("counts_bytes", C.c_int64), ("slot_of_bytes", C.c_int64),
+                ("hot_gid_bytes", C.c_int64), ("cache_bytes", C.c_int64), ("state_cache_bytes", C.c_int64),
+                ("workspace_bytes", C.c_int64)]
 
 
 class _RemapOut(C.Structure):
@@ -128,6 +130,7 @@ def lib():
         L.scars_memcpy.argtypes = [vp, vp, i64, i32, vp]
         L.scars_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.scars_calibration_read.argtypes = [vp, i64, vp, vp]
+        L.scars_calibration_link.argtypes = [vp, i64, vp, i64, i32, i32, i32, i32, vp]
         L.scars_profile_enable.argtypes = [vp, i32]
         L.scars_profile_read.argtypes = [vp, vp, C.POINTER(_KernelTime), i32, C.POINTER(i32)]
         _lib = L
@@ -141,8 +144,11 @@ def _stream() -> int:
 CALIB_SINK_BYTES = 4 << 20
 TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT, TUNE_FUSED_LONG_MAX_L, TUNE_PAIRS_IN_REMAP, TUNE_UPDATE_MAX_BLOCKS = 1, 2, 3, 4, 5
 TUNE_LOOKAHEAD = 6
+TUNE_FUSED_FETCH = 7
 COUNTER_PREPARED_USED = 1
 COUNTER_AHEAD_USED = 2
+COUNTER_AHEAD_TIMED = 3
+COUNTER_AHEAD_NOT_OVERLAPPED = 4
 
 
 def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:
@@ -152,6 +158,16 @@ def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:
     rc = lib().scars_calibration_read(src.data_ptr(), n, sink.data_ptr(), _stream())
     if rc != OK:
         raise ScarsError(rc, "calibration read failed")
+
+
+def calibration_link(host: "PinnedArray", dev: torch.Tensor, n_granules: int, granule_bytes: int, scattered: bool,
+                     to_host: bool, workgroups: int = 128) -> None:
+    """Launch the host-link calibration kernel on the current stream (see scars_calibration_link)."""
+    assert dev.is_cuda and dev.numel() * dev.element_size() >= n_granules * granule_bytes
+    rc = lib().scars_calibration_link(host.ptr, host.nbytes, dev.data_ptr(), n_granules, granule_bytes, int(scattered),
+                                      int(to_host), workgroups, _stream())
+    if rc != OK:
+        raise ScarsError(rc, "link calibration failed")
 
 
 def calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
@@ -306,7 +322,9 @@ class Scars:
         b = _Buffers(self.bufs["counts"].data_ptr(), self.bufs["slot_of"].data_ptr(), self.bufs["hot_gid"].data_ptr(),
                      self.bufs["cache"].data_ptr(),
                      self.bufs["state_cache"].data_ptr() if self.bufs["state_cache"] is not None else None,
-                     self.bufs["workspace"].data_ptr(), budget_bytes, max_L, max_G)
+                     self.bufs["workspace"].data_ptr(), budget_bytes, max_L, max_G,
+                     *[self.bufs[n].numel() if self.bufs[n] is not None else 0
+                       for n in ("counts", "slot_of", "hot_gid", "cache", "state_cache", "workspace")])
         self._check(lib().scars_bind_buffers(self._h, C.byref(b), _stream()))
         self.max_L, self.max_G, self.budget_bytes, self.device = max_L, max_G, budget_bytes, dev
         return sz

@@ -23,13 +23,72 @@ hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t 
     return hipGetLastError();
 }
 
-// Plain streaming copy of 16-byte words: the known-size kernel against which HBM byte counters are scaled.
-__global__ __launch_bounds__(kBlock) void k_calib_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, int64_t n16) {
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kBlock) dst[i] = src[i];
+// Plain streaming copy of 16-byte words: the known-size kernel against which HBM byte counters are scaled, and the
+// box's own copy rate.  Four independent 16-byte loads per lane are in flight before the first store.
+__global__ __launch_bounds__(kBlock) void k_calib_copy(u32x4* __restrict__ dst, const u32x4* __restrict__ src, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(a, dst + i);
+        __builtin_nontemporal_store(b, dst + i + stride);
+        __builtin_nontemporal_store(c, dst + i + 2 * stride);
+        __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t bytes) {
-    hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(kBlock), 0, s, (uint4*)dst, (const uint4*)src, bytes / 16);
+    hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(kBlock), 0, s, (u32x4*)dst, (const u32x4*)src, bytes / 16);
+    return hipGetLastError();
+}
+
+// Host-link calibration: `n` granules of `lpr` 16-byte pieces each move between pinned host memory and a device buffer.
+// Granule j of the device buffer pairs with granule pick(j) of the host buffer, pick = a 64-bit mixer of j modulo the
+// host buffer's granules (scattered like the rows of a batch) or j itself (sequential).  to_host 0: host -> device,
+// the access pattern of the missed-row fetch; 1: device -> host, that of the cold-row write-back.
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+__global__ __launch_bounds__(kBlock) void k_calib_link(u32x4* __restrict__ host, int64_t host_granules, u32x4* __restrict__ dev,
+                                                       int64_t n, int lpr, int scattered, int to_host) {
+    const int gpb = kBlock / lpr;
+    const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
+    const int64_t stride = (int64_t)gridDim.x * gpb;
+    constexpr int U = 4;
+    for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * U) {
+        int64_t hj[U];
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = min(j0 + u * stride, n - 1);
+            hj[u] = scattered ? (int64_t)(mix64((uint64_t)j) % (uint64_t)host_granules) : j % host_granules;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = min(j0 + u * stride, n - 1);
+            v[u] = to_host ? dev[j * lpr + gl] : __builtin_nontemporal_load(host + hj[u] * lpr + gl);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = j0 + u * stride;
+            if (j < n) {
+                if (to_host) host[hj[u] * lpr + gl] = v[u]; else dev[j * lpr + gl] = v[u];
+            }
+        }
+    }
+}
+
+hipError_t launch_calib_link(hipStream_t s, void* host, int64_t host_bytes, void* dev, int64_t n, int granule_bytes,
+                             int scattered, int to_host, int blocks) {
+    const int lpr = granule_bytes / 16;
+    hipLaunchKernelGGL(k_calib_link, dim3(blocks), dim3(kBlock), 0, s, (u32x4*)host, host_bytes / granule_bytes, (u32x4*)dev, n,
+                       lpr, scattered, to_host);
     return hipGetLastError();
 }
 

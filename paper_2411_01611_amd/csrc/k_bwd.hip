@@ -372,21 +372,29 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
 // round trips is hidden behind the other (a whole launch's worth of time for small batches).
 // ULONG: gradient rows in flight in the long-run part.  More of them shorten its chains but cost registers, hence
 // occupancy, for the whole launch: wide for small batches (a few waves per compute unit anyway), narrow for large.
+// With fetch_blocks > 0 the launch carries a third, independent job in its first workgroups: the NEXT batch's missed
+// rows are copied from host memory into a staging area (rows this update writes are flagged out beforehand), so that
+// the host link's two directions work at once without depending on a second hardware queue.
 template <int DTYPE, int OPT, int LPG, int ULONG>
-__global__ __launch_bounds__(kBlock) void k_seg_rows_long(int long_blocks, const uint32_t* __restrict__ key,
+__global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int long_blocks, const uint32_t* __restrict__ key,
                                                           const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                                           const int32_t* __restrict__ seg_start,
                                                           const int32_t* __restrict__ unique_gid,
                                                           const int32_t* __restrict__ unique_slot,
                                                           const uint32_t* __restrict__ first_bag,
                                                           const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
-                                                          double* __restrict__ partial, UpdateArgs A) {
-    if ((int)blockIdx.x < long_blocks)
-        seg_long_body<LPG, ULONG>((int)blockIdx.x, long_blocks, key, val, n_unique, seg_start, chunk_run, grad, partial, A.D,
-                                        A.Gm1, A.shift);
-    else
-        seg_rows_body<DTYPE, OPT, LPG>((int)blockIdx.x - long_blocks, (int)gridDim.x - long_blocks, val, n_unique, seg_start,
-                                       unique_gid, unique_slot, first_bag, grad, A);
+                                                          double* __restrict__ partial, UpdateArgs A, StageArgs F) {
+    const int b = (int)blockIdx.x;
+    if (b < fetch_blocks) {
+        __shared__ int32_t s_rbase_f[SCARS_MAX_TABLES + 1];
+        stage_rows_body(b, fetch_blocks, A.meta, s_rbase_f, F);
+    } else if (b - fetch_blocks < long_blocks) {
+        seg_long_body<LPG, ULONG>(b - fetch_blocks, long_blocks, key, val, n_unique, seg_start, chunk_run, grad, partial, A.D,
+                                  A.Gm1, A.shift);
+    } else {
+        seg_rows_body<DTYPE, OPT, LPG>(b - fetch_blocks - long_blocks, (int)gridDim.x - fetch_blocks - long_blocks, val, n_unique,
+                                       seg_start, unique_gid, unique_slot, first_bag, grad, A);
+    }
 }
 
 // Second half, in a launch of its own so that the partial sums need no fences or atomics: the group of the
@@ -444,7 +452,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_combine(const uint32_t* __restri
 
 template <int DTYPE, int OPT, int LPG>
 static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, const uint32_t* key, const uint32_t* val, const int32_t* nu,
-                            const int32_t* seg_start, const int32_t* unique_gid, const float* grad, int64_t L, UpdateArgs A) {
+                            const int32_t* seg_start, const int32_t* unique_gid, const float* grad, int64_t L, UpdateArgs A,
+                            int fetch_blocks, StageArgs F) {
     Workspace& ws = h->ws;
     const int gpb = kBlock / LPG;
     // with cold rows to write the kernel is bound by the host link and a thousand workgroups saturate it; more only
@@ -456,15 +465,16 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
         {
-            Timed t(h, s, "seg_rows_long");
+            Timed t(h, s, fetch_blocks > 0 ? "seg_rows_long+fetch_ahead" : "seg_rows_long");
+            const dim3 grid(fetch_blocks + chunk_blocks + rows_blocks);
             if (L <= kFusedWideMaxL)
-                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kTaskUnroll>), dim3(chunk_blocks + rows_blocks), dim3(kBlock),
-                                   0, s, chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
-                                   ws.chunk_run, grad, ws.partial, A);
+                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kTaskUnroll>), grid, dim3(kBlock), 0, s, fetch_blocks,
+                                   chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
+                                   ws.chunk_run, grad, ws.partial, A, F);
             else
-                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kGradUnroll>), dim3(chunk_blocks + rows_blocks), dim3(kBlock),
-                                   0, s, chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
-                                   ws.chunk_run, grad, ws.partial, A);
+                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kGradUnroll>), grid, dim3(kBlock), 0, s, fetch_blocks,
+                                   chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
+                                   ws.chunk_run, grad, ws.partial, A, F);
         }
         Timed t(h, s, "seg_combine");
         hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
@@ -491,9 +501,9 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
 template <int DTYPE, int OPT>
 static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, hipStream_t s2, const uint32_t* key, const uint32_t* val,
                             const int32_t* nu, const int32_t* seg_start, const int32_t* unique_gid, const float* grad,
-                            int64_t L, UpdateArgs A) {
+                            int64_t L, UpdateArgs A, int fetch_blocks, StageArgs F) {
     switch (lpg) {
-#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, s2, key, val, nu, seg_start, unique_gid, grad, L, A); break;
+#define SCARS_CASE(N) case N: launch_reduce_t<DTYPE, OPT, N>(h, s, s2, key, val, nu, seg_start, unique_gid, grad, L, A, fetch_blocks, F); break;
         SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
         SCARS_CASE(128)
 #undef SCARS_CASE
@@ -602,32 +612,41 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         const hipError_t e = pf_join(h, s);
         if (e != hipSuccess) return e;
     }
-    if (fetch_next) {
-        hipError_t e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0);
-        if (e != hipSuccess) return e;
-        h->ahead_active = true;
-    }
     const int lpg = next_pow2_host(h->D / 4);
     // long runs (HBM-bound) beside the per-row kernel (bound by the host link while rows are cold)
     hipStream_t s2 = s;
     const bool split = !prep_next && h->presort_min_L > 0 && L >= h->presort_min_L && h->k < h->N;
+    // the fetch rides in the update's own launch whenever long runs and rows share one (no second hardware queue
+    // needed for the two directions of the link to overlap); otherwise it goes to the library's second stream
+    const bool fuse_fetch = fetch_next && h->fused_fetch && !split && L <= h->fused_long_max_L;
+    StageArgs F{};
+    int fetch_blocks = 0;
+    h->timer_tag = (fetch_next && !fuse_fetch) ? ++h->timer_serial : 0;
+    if (fetch_next) {
+        hipError_t e = launch_fetch_ahead(h, s, next_rm, next_L, unique_gid, n_unique, use_staged ? 1 - area : 0,
+                                          fuse_fetch ? &F : nullptr, &fetch_blocks);
+        if (e != hipSuccess) return e;
+        if (!fuse_fetch) fetch_blocks = 0;
+        h->ahead_active = true;
+    }
     if (split) {
         hipError_t e = side_fork(h, s);
         if (e != hipSuccess) return e;
         s2 = h->side;
     }
     if (h->dtype == SCARS_DTYPE_F32) {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A, fetch_blocks, F);
+        else launch_reduce_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A, fetch_blocks, F);
     } else {
-        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
-        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A);
+        if (h->optimizer == SCARS_OPT_SGD) launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A, fetch_blocks, F);
+        else launch_reduce_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, s2, key, val, n_unique, seg_start, unique_gid, grad, L, A, fetch_blocks, F);
     }
     if (split) {
         hipError_t e = hipEventRecord(h->ev_join, h->side);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, h->ev_join, 0);
         if (e != hipSuccess) return e;
     }
+    h->timer_tag = 0;
     if (prep_next) swap_segment_sets(h);   // what was prepared is what the next call finds
     return hipGetLastError();
 }

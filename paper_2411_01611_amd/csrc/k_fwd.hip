@@ -11,53 +11,17 @@
 
 namespace scars {
 
-constexpr int kUnroll = 4;       // rows in flight per lane group when staging misses
 constexpr int kStageBlocks = 128;  // workgroups of the staging kernel
 constexpr int kAheadBlocks = 128;  // ... when it fetches ahead, beside the update kernel (64 and 512 are slower)
 constexpr int kPoolUnroll = 8;   // rows in flight per lane group when pooling
 constexpr int kShortTailUnroll = 2;   // the same for lookups after the first of a short bag: few registers, more waves
 
 // ---- staging of missed rows ---------------------------------------------------------------------------
-// `flags` (may be null: every row): only rows whose flag equals `want` are fetched.  flag 1 = the row may be
-// fetched ahead (k_mark_ahead), so want = 1 fetches ahead and want = 0 fetches what was left out.
-__global__ __launch_bounds__(kBlock) void k_stage_misses(const int32_t* __restrict__ miss_gid,
-                                                         const int32_t* __restrict__ d_count,
-                                                         const Meta* __restrict__ meta, u32x4* __restrict__ staging,
-                                                         int chunks, int lpr, int64_t cap_rows,
-                                                         const uint8_t* __restrict__ flags, int want) {
+// (stage_rows_body in scars_dev.h; the backward pass can carry the same job in its update launch)
+// flag 1 = the row may be fetched ahead (k_mark_ahead), so want = 1 fetches ahead and want = 0 fetches what was left out.
+__global__ __launch_bounds__(kBlock) void k_stage_misses(const Meta* __restrict__ meta, StageArgs S) {
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
-    const int T = meta->num_tables;
-    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
-    __syncthreads();
-    const int64_t n = min((int64_t)*d_count, cap_rows);
-    const int gpb = kBlock / lpr;
-    const int grp = threadIdx.x / lpr, gl = threadIdx.x % lpr;
-    const int64_t stride = (int64_t)gridDim.x * gpb;
-    const bool lane_on = gl < chunks;      // lpr >= chunks: one 16-byte piece per lane
-    if (!lane_on || n <= 0) return;
-    for (int64_t j0 = (int64_t)blockIdx.x * gpb + grp; j0 < n; j0 += stride * kUnroll) {
-        // row numbers are clamped instead of guarded so that the gid loads, then the row loads over the link,
-        // are all issued back to back; only rows below n are written
-        int32_t gid[kUnroll];
-        bool need[kUnroll];
-        u32x4 v[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t j = min(j0 + u * stride, n - 1);
-            gid[u] = miss_gid[j];
-            need[u] = !flags || flags[j] == want;
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (need[u]) {
-                const int t = upper_table(s_rbase, T, gid[u]);
-                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * chunks + gl);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (need[u] && j0 + u * stride < n) staging[(j0 + u * stride) * chunks + gl] = v[u];
-    }
+    stage_rows_body((int)blockIdx.x, (int)gridDim.x, meta, s_rbase, S);
 }
 
 // Fetching the NEXT batch's missed rows while the current batch's backward pass runs: a row may be fetched now unless
@@ -343,7 +307,7 @@ static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, 
 
 // The library's second stream (default priority, created on first use): pooling beside the fetch in the forward pass,
 // and the fetch for the next batch beside the update in the backward pass; the two uses never overlap in time.
-static hipError_t ensure_pool_stream(scars_handle* h) {
+hipError_t ensure_pool_stream(scars_handle* h) {
     if (h->pool_stream) return hipSuccess;
     hipError_t e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pool_fork, hipEventDisableTiming);
@@ -398,13 +362,14 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         // 128 workgroups hold far more than the host link needs in flight (128 x 256 lanes x 4 x 16 bytes = 2 MB) and
         // leave half the compute units, and most wave slots, to work on other streams while this kernel waits on the
         // link (kernels sharing a compute unit with it run several times slower: its host reads fill the memory queues)
-        const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kUnroll), ahead ? 16 * kStageBlocks : kStageBlocks));
+        const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, (int64_t)gpb * kStageUnroll), ahead ? 16 * kStageBlocks : kStageBlocks));
         // (after a fetch ahead only a few rows are left: many workgroups walk the flags quickly)
         // one row per missed lookup, or (after a coalescing remap) one per distinct missed row
         const int32_t* list = rm->unique_miss_gid ? rm->unique_miss_gid : rm->miss_gid;
         const int32_t* count = rm->unique_miss_gid ? rm->n_unique_miss : rm->n_hit_miss + 1;
-        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, list, count, h->ws.meta,
-                           (u32x4*)staging, chunks, lpr, h->buf.max_L, ahead ? h->ws.fetched : (const uint8_t*)nullptr, 0);
+        const StageArgs S{list, count, (u32x4*)staging, chunks, lpr, h->buf.max_L,
+                          ahead ? h->ws.fetched : (const uint8_t*)nullptr, 0};
+        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, h->ws.meta, S);
     }
     if (G > 0) pool(s, split ? 2 : 0, split ? "pool_short_staged" : (mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group")));
     if (split) {   // the output is complete, in the caller's stream order, when this call returns
@@ -414,37 +379,45 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     return hipGetLastError();
 }
 
+// `fused` set: nothing is launched for the fetch itself; *fused receives the job (and *fused_blocks its workgroups)
+// for the caller to carry in its own launch on stream s.  Otherwise the fetch runs on the library's second stream.
 hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
-                              const int32_t* excl, const int32_t* n_excl, int area) {
-    hipError_t e = ensure_pool_stream(h);
-    if (e != hipSuccess) return e;
-    hipStream_t const pf = h->pool_stream;
+                              const int32_t* excl, const int32_t* n_excl, int area, StageArgs* fused, int* fused_blocks) {
+    hipError_t e = hipSuccess;
     const int chunks = h->R / 16;
     const int lpr = std::min(64, next_pow2_host(chunks));
     const int gpb = kBlock / lpr;
-    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kUnroll), kAheadBlocks));
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kStageUnroll), kAheadBlocks));
     {   // on the caller's stream, before the update kernel: beside that kernel it would crawl (see k_stage_misses)
         Timed t(h, s, "mark_ahead");
         const int mgrid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, kBlock), 256 * 8));
         hipLaunchKernelGGL(k_mark_ahead, dim3(mgrid), dim3(kBlock), 0, s, next_rm->miss_gid, next_rm->n_hit_miss + 1,
                            excl, n_excl, h->ws.fetched, h->buf.max_L);
     }
-    if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(pf, h->ev_pf_fork, 0)) != hipSuccess) return e;
-    {
-        Timed t(h, pf, "fetch_ahead");
-        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, pf, next_rm->miss_gid, next_rm->n_hit_miss + 1,
-                           h->ws.meta, (u32x4*)h->ws.staging[area], chunks, lpr, h->buf.max_L, h->ws.fetched, 1);
+    const StageArgs S{next_rm->miss_gid, next_rm->n_hit_miss + 1, (u32x4*)h->ws.staging[area], chunks, lpr, h->buf.max_L,
+                      h->ws.fetched, 1};
+    if (fused) {
+        *fused = S;
+        *fused_blocks = grid;
+    } else {
+        if ((e = ensure_pool_stream(h)) != hipSuccess) return e;
+        hipStream_t const pf = h->pool_stream;
+        if ((e = hipEventRecord(h->ev_pf_fork, s)) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(pf, h->ev_pf_fork, 0)) != hipSuccess) return e;
+        {
+            Timed t(h, pf, "fetch_ahead");
+            hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, pf, h->ws.meta, S);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = hipEventRecord(h->ev_pf_done, pf)) != hipSuccess) return e;
+        h->pf_pending = true;
     }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = hipEventRecord(h->ev_pf_done, pf)) != hipSuccess) return e;
-    h->pf_pending = true;
     h->stg[area].valid = false;
     h->ahead.valid = true;
     h->ahead.loc = next_rm->loc;
     h->ahead.miss_gid = next_rm->miss_gid;
     h->ahead.area = area;
-    return hipSuccess;
+    return hipGetLastError();
 }
 
 }  // namespace scars

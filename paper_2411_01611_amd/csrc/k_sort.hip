@@ -3,7 +3,8 @@
 // Used for (a) ordering the selected hot rows by descending count (key = ~count, value = gid; the input is
 // in ascending gid order, so stability gives "lower id first among equal counts"), and (b) ordering a
 // batch's lookups by (gid, position) for the backward pass (key = gid, value = bag; the input is in
-// position order).  Per pass: per-tile digit histogram -> per-digit exclusive scan over tiles -> scatter
+// position order).  Per pass: per-tile digit histogram (one row of `bins` counts per tile) -> per-digit exclusive scan
+// down the tiles (a few digit columns per workgroup, so that a row of lanes touches one contiguous piece of a tile's row) -> scatter
 // in which each tile is first ordered in LDS (wave-level multi-split by ballot matching) and then written
 // out as contiguous runs per digit.  The number of passes is ceil(bits / 9) and the digit width is
 // ceil(bits / passes), so 26-bit row ids take three 9-bit passes instead of four 8-bit ones.
@@ -14,20 +15,9 @@ namespace scars {
 constexpr int kMaxBins = kSortMaxBins;
 constexpr int kWaves = kBlock / kWave;
 
-// Lanes of the wave that hold the same digit as this lane (valid lanes only): one ballot per digit bit.
-__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid, int dbits) {
-    uint64_t m = ballot64(valid);
-    for (int b = 0; b < dbits; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const uint64_t bal = ballot64(bit);
-        m &= bit ? bal : ~bal;
-    }
-    return m;
-}
-
-// hist is digit-major: hist[d * nb + tile].  Each wave counts into a histogram of its own; lanes holding the same
-// digit are matched by ballots and only the first of them adds their number (equal keys, which skewed row ids have
-// many of, then cost one LDS operation instead of one each).  Keys are read 16 bytes per lane.
+// hist is tile-major: hist[tile * bins + d].  Each wave counts into a histogram of its own in LDS (one atomic per key;
+// matching the lanes that hold equal digits first, as the scatter kernel does for its ranks, cost twice the time it
+// saved: nine ballots per key against a conflict now and then).  Keys are read 16 bytes per lane.
 template <int ROUNDS>
 __global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict__ keys, int64_t n, const int32_t* __restrict__ d_n,
                                                       int shift, int dbits, uint32_t* __restrict__ hist, int nb) {
@@ -57,32 +47,66 @@ __global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict
         const int64_t i = tile0 + ((int64_t)(r / 4) * kBlock + threadIdx.x) * 4 + (r % 4);
         const bool valid = i < n;
         const uint32_t d = (kk[r] >> shift) & mask;
-        const uint64_t m = match_digit(d, valid, dbits);
-        if (valid && rank_below(m) == 0) atomicAdd(&wh[d], (uint32_t)__popcll(m));   // distinct digits: distinct words
+        if (valid) atomicAdd(&wh[d], 1u);
     }
     __syncthreads();
     for (int d = threadIdx.x; d < bins; d += kBlock) {
         uint32_t c = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) c += s_hist[w * kMaxBins + d];
-        hist[(int64_t)d * nb + blockIdx.x] = c;
+        hist[(int64_t)blockIdx.x * bins + d] = c;
     }
 }
 
-// One workgroup per digit: exclusive scan of that digit's per-tile counts, digit total to tot[digit].
-__global__ __launch_bounds__(kBlock) void k_sort_scan(uint32_t* __restrict__ hist, int nb, uint32_t* __restrict__ tot) {
-    __shared__ uint32_t s_scan[8];
-    uint32_t* row = hist + (int64_t)blockIdx.x * nb;
-    uint32_t carry = 0;
-    for (int base = 0; base < nb; base += kBlock) {
-        const int i = base + threadIdx.x;
-        const uint32_t v = i < nb ? row[i] : 0u;
-        uint32_t total;
-        const uint32_t ex = block_exclusive_scan(v, s_scan, &total);
-        if (i < nb) row[i] = carry + ex;
-        carry += total;
+// Exclusive scan of every digit's counts down the tiles, in place; digit totals to tot[digit].  A workgroup takes a
+// group of g = min(kScanDigits, bins) neighbouring digits; lane (row, dg) = (tid / g, tid % g) owns the digit's counts
+// of `per` consecutive tiles.  Three steps whatever the number of tiles: every lane adds up its tiles (independent
+// loads), one scan of those sums across the rows of lanes, then every lane writes the running sums of its tiles.
+constexpr int kScanDigits = 2;  // digits per workgroup (fewer when a pass has fewer bins)
+constexpr int kScanUnroll = 16;  // loads in flight per lane: the kernel is a chain of round trips, not of bytes
+__global__ __launch_bounds__(kBlock) void k_sort_scan(uint32_t* __restrict__ hist, int nb, int bins, int g,
+                                                      uint32_t* __restrict__ tot) {
+    __shared__ uint32_t s_w[kWaves][kScanDigits];
+    const int dg = threadIdx.x % g, row = threadIdx.x / g;
+    const int rows = kBlock / g;                 // rows of lanes in the workgroup
+    const int d = blockIdx.x * g + dg;
+    const int per = (nb + rows - 1) / rows;
+    const int t0 = min(row * per, nb), t1 = min(t0 + per, nb);
+    uint32_t* const col = hist + d;
+    uint32_t sum = 0;
+    for (int t = t0; t < t1; t += kScanUnroll) {
+        uint32_t v[kScanUnroll];
+#pragma unroll
+        for (int i = 0; i < kScanUnroll; ++i) v[i] = t + i < t1 ? col[(int64_t)(t + i) * bins] : 0u;
+#pragma unroll
+        for (int i = 0; i < kScanUnroll; ++i) sum += v[i];
     }
-    if (threadIdx.x == 0) tot[blockIdx.x] = carry;
+    // inclusive scan of `sum` over the rows of this wave (lanes of one digit are g apart), then over the waves
+    uint32_t inc = sum;
+    for (int st = g; st < kWave; st <<= 1) {
+        const uint32_t o = __shfl_up(inc, st, kWave);
+        if (lane_id() >= st) inc += o;
+    }
+    if (lane_id() >= kWave - g) s_w[wave_id()][dg] = inc;    // the wave's last row holds the wave's total
+    __syncthreads();
+    uint32_t run = inc - sum, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = s_w[w][dg];
+        if (w < wave_id()) run += t;
+        all += t;
+    }
+    for (int t = t0; t < t1; t += kScanUnroll) {
+        uint32_t v[kScanUnroll];
+#pragma unroll
+        for (int i = 0; i < kScanUnroll; ++i) v[i] = t + i < t1 ? col[(int64_t)(t + i) * bins] : 0u;
+#pragma unroll
+        for (int i = 0; i < kScanUnroll; ++i) {
+            if (t + i < t1) col[(int64_t)(t + i) * bins] = run;
+            run += v[i];
+        }
+    }
+    if (row == 0) tot[d] = all;
 }
 
 // Tile = 256 * ROUNDS pairs; wave w owns the contiguous quarter [w * 64 * ROUNDS, ...) in ROUNDS rounds of 64.
@@ -93,10 +117,18 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
                                                          const uint32_t* __restrict__ hist, const uint32_t* __restrict__ tot, int nb) {
     constexpr int kTile = kBlock * ROUNDS;
     if (d_n) n = min(n, (int64_t)max(*d_n, 0));
-    if ((int64_t)blockIdx.x * kTile >= n) return;   // whole workgroup: nothing of this tile is in use
+    // Workgroups are handed to the chip's eight dies (each with an L2 of its own) in turn; tiles next to each other
+    // write next to each other (the runs of one digit from consecutive tiles are adjacent in the output), so each
+    // die takes a contiguous eighth of the tiles and its L2 can put the pieces of a line together before writing it.
+    const int per_die = (nb + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * per_die + (int)(blockIdx.x / 8);
+    if (tile >= nb || (int64_t)tile * kTile >= n) return;   // whole workgroup: nothing of this tile is in use
     constexpr int kPerWave = kWave * ROUNDS;
-    __shared__ uint32_t s_key[kTile];
-    __shared__ uint32_t s_val[kTile];
+    // the ordered tile; before that the same memory holds, per wave and digit, the lanes of the round in hand
+    constexpr int kPairWords = 2 * kTile > 2 * kWaves * kMaxBins ? 2 * kTile : 2 * kWaves * kMaxBins;
+    __shared__ __align__(8) uint32_t s_pairs[kPairWords];
+    uint32_t* const s_key = s_pairs;
+    uint32_t* const s_val = s_pairs + kTile;
     __shared__ uint32_t s_wh[kWaves * kMaxBins];   // per-wave digit counters, then exclusive wave bases
     __shared__ uint32_t s_dstart[kMaxBins];         // first LDS position of each digit in this tile
     __shared__ uint32_t s_goff[kMaxBins];           // global position of this tile's first pair of each digit
@@ -105,7 +137,7 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int bins = 1 << dbits;
     const uint32_t mask = (uint32_t)bins - 1u;
-    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+    const int64_t tile0 = (int64_t)tile * kTile;
     const int tile_n = (int)min((int64_t)kTile, n - tile0);
 
     // the tile's pairs are requested first, so that their round trip overlaps the one of the digit offsets below
@@ -118,6 +150,7 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
         val[r] = valid ? vin[tile0 + p] : 0u;
     }
     for (int i = tid; i < kWaves * kMaxBins; i += kBlock) s_wh[i] = 0;
+    for (int i = tid; i < 2 * kWaves * kMaxBins; i += kBlock) s_pairs[i] = 0;
     {   // global base of every digit = scan of the digit totals, plus this tile's offset inside the digit
         uint32_t carry = 0;
         for (int base = 0; base < bins; base += kBlock) {
@@ -125,31 +158,41 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
             const uint32_t v = d < bins ? tot[d] : 0u;
             uint32_t total;
             const uint32_t ex = block_exclusive_scan(v, s_scan, &total);
-            if (d < bins) s_goff[d] = carry + ex + hist[(int64_t)d * nb + blockIdx.x];
+            if (d < bins) s_goff[d] = carry + ex + hist[(int64_t)tile * bins + d];
             carry += total;
         }
     }
     __syncthreads();
 
-    // Stable rank of every pair among its wave's pairs of the same digit.  First the lanes of each round that share a
-    // digit are matched (ballots only); then the first lane of each such set adds the set's size to the wave's counter
-    // of the digit and gets back what was there -- the sets of a round have distinct digits, and a wave's LDS
-    // operations are carried out in order, so the rounds' additions are issued back to back and need no barrier;
-    // finally every lane takes that number from its set's first lane.
+    // Stable rank of every pair among its wave's pairs of the same digit.  The lanes of a round that share a digit are
+    // matched; the first lane of each such set adds the set's size to the wave's counter of the digit and gets back
+    // what was there (the sets of a round have distinct digits); every lane then takes that number from its set's
+    // first lane and adds its own place in the set.
     uint32_t* wh = s_wh + w * kMaxBins;
     uint32_t old[ROUNDS];
     int lead[ROUNDS];
+    // the lanes sharing a digit are found through LDS instead of nine ballots: every lane sets its bit in the
+    // wave's 64-bit word of its digit, then reads the word back (one wave's LDS operations are carried out in
+    // order, and all lanes of an instruction before the next); the set's first lane clears the word again
+    unsigned long long* const mk = (unsigned long long*)s_pairs + w * kMaxBins;
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
         const int p = w * kPerWave + r * kWave + lane;
         const bool valid = p < tile_n;
         const uint32_t d = (key[r] >> shift) & mask;
-        const uint64_t m = match_digit(d, valid, dbits);
+        if (valid) atomicOr(&mk[d], 1ull << lane);
+        __builtin_amdgcn_wave_barrier();
+        const uint64_t m = valid ? *(volatile unsigned long long*)&mk[d] : (1ull << lane);
+        __builtin_amdgcn_wave_barrier();
         const int rk = rank_below(m);
-        lead[r] = valid ? __ffsll((unsigned long long)m) - 1 : lane;
+        lead[r] = __ffsll((unsigned long long)m) - 1;
         loc[r] = (uint32_t)rk;
         old[r] = 0u;
-        if (valid && rk == 0) old[r] = atomicAdd(&wh[d], (uint32_t)__popcll(m));
+        if (valid && rk == 0) {
+            *(volatile unsigned long long*)&mk[d] = 0ull;
+            old[r] = atomicAdd(&wh[d], (uint32_t)__popcll(m));
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) loc[r] += __shfl(old[r], lead[r], kWave);   // stable rank among this wave's pairs of digit d
@@ -209,11 +252,12 @@ static void sort_passes(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32
         }
         {
             Timed t(h, s, "sort_scan");
-            hipLaunchKernelGGL(k_sort_scan, dim3(1 << dbits), dim3(kBlock), 0, s, h->ws.sort_hist, nb, h->ws.sort_tot);
+            const int bins = 1 << dbits, g = std::min(kScanDigits, bins);
+            hipLaunchKernelGGL(k_sort_scan, dim3(bins / g), dim3(kBlock), 0, s, h->ws.sort_hist, nb, bins, g, h->ws.sort_tot);
         }
         {
             Timed t(h, s, "sort_scatter");
-            hipLaunchKernelGGL((k_sort_scatter<ROUNDS>), dim3(nb), dim3(kBlock), 0, s, key[*cur], val[*cur], key[*cur ^ 1],
+            hipLaunchKernelGGL((k_sort_scatter<ROUNDS>), dim3((nb + 7) / 8 * 8), dim3(kBlock), 0, s, key[*cur], val[*cur], key[*cur ^ 1],
                                val[*cur ^ 1], n, d_n, shift, dbits, h->ws.sort_hist, h->ws.sort_tot, nb);
         }
         *cur ^= 1;
@@ -224,8 +268,10 @@ hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key
                                    const int32_t* d_n, int bits, int* result_buffer) {
     int cur = 0;
     if (n > 0) {
-        // small inputs: small tiles, so that there are enough workgroups to fill the chip
-        if (n < ((int64_t)1 << 21)) sort_passes<kSortRoundsSmall>(h, s, key, val, n, d_n, bits, &cur);
+        // small inputs: small tiles, so that there are enough workgroups to fill the chip (measured: 655 k pairs are
+        // fastest with tiles of 2048, 4.3 M pairs with tiles of 4096)
+        if (n <= ((int64_t)1 << 18)) sort_passes<kSortRoundsSmall>(h, s, key, val, n, d_n, bits, &cur);
+        else if (n < ((int64_t)1 << 22)) sort_passes<kSortRoundsMid>(h, s, key, val, n, d_n, bits, &cur);
         else sort_passes<kSortRoundsLarge>(h, s, key, val, n, d_n, bits, &cur);
     }
     *result_buffer = cur;

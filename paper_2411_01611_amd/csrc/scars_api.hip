@@ -23,6 +23,7 @@ int32_t hip_fail(scars_handle* h, hipError_t e, const char* what) {
 
 Timed::Timed(scars_handle* h_, hipStream_t s_, const char* n) : h(h_), s(s_), name(n) {
     if (h && h->profile) {
+        tag = h->timer_tag;
         if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
             (void)hipEventRecord(a, s);
         } else {
@@ -34,7 +35,7 @@ Timed::Timed(scars_handle* h_, hipStream_t s_, const char* n) : h(h_), s(s_), na
 Timed::~Timed() {
     if (a && b) {
         (void)hipEventRecord(b, s);
-        h->timer.pending.push_back({name, {a, b}});
+        h->timer.pending.push_back({name, a, b, tag});
     }
 }
 
@@ -103,14 +104,20 @@ static hipError_t side_join(scars_handle* h, hipStream_t s) {
     return hipStreamWaitEvent(s, h->ev_join, 0);
 }
 
-// Make the side stream (created on first use, default priority) wait for everything enqueued on s so far.
-hipError_t side_fork(scars_handle* h, hipStream_t s) {
+static hipError_t ensure_side_stream(scars_handle* h) {
     hipError_t e = hipSuccess;
     if (!h->side) {
         if ((e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking)) != hipSuccess) return e;
         if ((e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming)) != hipSuccess) return e;
         if ((e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming)) != hipSuccess) return e;
     }
+    return e;
+}
+
+// Make the side stream (default priority; created when buffers are first bound) wait for everything enqueued on s so far.
+hipError_t side_fork(scars_handle* h, hipStream_t s) {
+    hipError_t e = ensure_side_stream(h);
+    if (e != hipSuccess) return e;
     if ((e = hipEventRecord(h->ev_fork, s)) != hipSuccess) return e;
     return hipStreamWaitEvent(h->side, h->ev_fork, 0);
 }
@@ -199,6 +206,7 @@ int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
         case SCARS_TUNE_PAIRS_IN_REMAP: h->pairs_in_remap = value != 0; break;
         case SCARS_TUNE_LOOKAHEAD: h->lookahead = value != 0; break;
         case SCARS_TUNE_UPDATE_MAX_BLOCKS: h->update_max_blocks = std::min<int64_t>(value, 256 * 32); break;
+        case SCARS_TUNE_FUSED_FETCH: h->fused_fetch = value != 0; break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
     return SCARS_OK;
@@ -209,6 +217,8 @@ int64_t scars_get_counter(const scars_handle* h, int32_t which) {
     switch (which) {
         case SCARS_COUNTER_PREPARED_USED: return h->n_prepared_used;
         case SCARS_COUNTER_AHEAD_USED: return h->n_ahead_used;
+        case SCARS_COUNTER_AHEAD_TIMED: return h->n_ahead_timed;
+        case SCARS_COUNTER_AHEAD_NOT_OVERLAPPED: return h->n_ahead_serial;
         default: return -1;
     }
 }
@@ -229,7 +239,7 @@ int32_t scars_destroy(scars_handle* h) {
         (void)hipEventDestroy(h->ev_fork);
         (void)hipEventDestroy(h->ev_join);
     }
-    for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.second.first); (void)hipEventDestroy(p.second.second); }
+    for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     delete h;
     return SCARS_OK;
 }
@@ -260,6 +270,24 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     if (k + b->max_L >= ((int64_t)1 << 31)) return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: k + max_L >= 2^31");
     if (k > 0 && (!b->hot_gid || !b->cache || (h->optimizer == SCARS_OPT_ADAGRAD && !b->state_cache)))
         return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: cache buffers missing");
+    {   // every buffer at least as large as scars_query_sizes says for these arguments
+        scars_sizes need;
+        if (scars_query_sizes(h, b->budget_bytes, b->max_L, b->max_G, &need) != SCARS_OK)
+            return fail(h, SCARS_ERR_INVALID_ARG, "bind_buffers: sizes out of range");
+        const bool adagrad = h->optimizer == SCARS_OPT_ADAGRAD;
+        if (b->counts_bytes < need.counts_bytes || b->slot_of_bytes < need.slot_of_bytes ||
+            b->workspace_bytes < need.workspace_bytes ||
+            (k > 0 && (b->hot_gid_bytes < need.hot_gid_bytes || b->cache_bytes < need.cache_bytes ||
+                       (adagrad && b->state_cache_bytes < need.state_cache_bytes))))
+            return fail(h, SCARS_ERR_WORKSPACE, "bind_buffers: a buffer is smaller than scars_query_sizes asks for");
+    }
+    // The library's two streams are created here, not on first use: a process has few hardware queues, handed out as
+    // streams are created, and a caller who binds before creating streams of its own keeps these two off its queue.
+    {
+        hipError_t es = ensure_side_stream(h);
+        if (es == hipSuccess) es = ensure_pool_stream(h);
+        if (es != hipSuccess) return hip_fail(h, es, "bind_buffers(streams)");
+    }
     if (h->side) (void)hipStreamSynchronize(h->side);   // nothing may still be using the buffers bound before
     if (h->pool_stream) (void)hipStreamSynchronize(h->pool_stream);
     h->pf_pending = false;
@@ -666,7 +694,12 @@ int32_t scars_host_alloc(int64_t bytes, void** out) {
     if (!out || bytes <= 0) return SCARS_ERR_INVALID_ARG;
     *out = nullptr;
     hipError_t e = hipHostMalloc(out, (size_t)bytes, hipHostMallocDefault);
-    return e == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+    if (e != hipSuccess) {
+        (void)hipGetLastError();   // a refused allocation must not be reported again by the next launch's error check
+        *out = nullptr;
+        return SCARS_ERR_HIP;
+    }
+    return SCARS_OK;
 }
 
 int32_t scars_host_free(void* p) {
@@ -690,6 +723,18 @@ int32_t scars_calibration_read(const void* d_src, int64_t bytes, void* d_sink, v
     return launch_calib_read((hipStream_t)stream, d_src, bytes, d_sink) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
 }
 
+int32_t scars_calibration_link(void* h_pinned, int64_t host_bytes, void* d_buf, int64_t n_granules, int32_t granule_bytes,
+                               int32_t scattered, int32_t to_host, int32_t workgroups, void* stream) {
+    if (!h_pinned || !d_buf || n_granules < 0 || workgroups < 1 || workgroups > 65536) return SCARS_ERR_INVALID_ARG;
+    if (granule_bytes != 16 && granule_bytes != 32 && granule_bytes != 64 && granule_bytes != 128 && granule_bytes != 256 &&
+        granule_bytes != 512 && granule_bytes != 1024)
+        return SCARS_ERR_INVALID_ARG;
+    if (host_bytes < granule_bytes) return SCARS_ERR_INVALID_ARG;
+    if (n_granules == 0) return SCARS_OK;
+    return launch_calib_link((hipStream_t)stream, h_pinned, host_bytes, d_buf, n_granules, granule_bytes, scattered != 0,
+                             to_host != 0, workgroups) == hipSuccess ? SCARS_OK : SCARS_ERR_HIP;
+}
+
 int32_t scars_profile_enable(scars_handle* h, int32_t on) {
     if (!h) return SCARS_ERR_INVALID_ARG;
     h->profile = on != 0;
@@ -703,15 +748,34 @@ int32_t scars_profile_read(scars_handle* h, void* stream, scars_kernel_time* out
     if (e == hipSuccess && h->pool_stream) e = hipStreamSynchronize(h->pool_stream);
     if (e != hipSuccess) return hip_fail(h, e, "profile_read");
     std::vector<scars_kernel_time> acc;
+    // an update and the fetch enqueued beside it on the library's stream carry the same tag: did they run together?
+    struct Pair { hipEvent_t ua = nullptr, ub = nullptr, fa = nullptr, fb = nullptr; };
+    std::map<int64_t, Pair> pairs;
+    for (auto& p : h->timer.pending) {
+        if (p.tag <= 0) continue;
+        if (std::strcmp(p.name, "fetch_ahead") == 0) { pairs[p.tag].fa = p.a; pairs[p.tag].fb = p.b; }
+        else if (std::strncmp(p.name, "seg_rows", 8) == 0) { pairs[p.tag].ua = p.a; pairs[p.tag].ub = p.b; }
+    }
+    for (auto& kv : pairs) {
+        const Pair& q = kv.second;
+        if (!q.ua || !q.fa) continue;
+        float u = 0.f, f = 0.f, d = 0.f;     // update and fetch durations, fetch start relative to update start (ms)
+        if (hipEventElapsedTime(&u, q.ua, q.ub) != hipSuccess || hipEventElapsedTime(&f, q.fa, q.fb) != hipSuccess ||
+            hipEventElapsedTime(&d, q.ua, q.fa) != hipSuccess)
+            continue;
+        const float overlap = std::min(d + f, u) - std::max(d, 0.f);
+        ++h->n_ahead_timed;
+        if (overlap < 0.25f * std::min(u, f)) ++h->n_ahead_serial;
+    }
     for (auto& p : h->timer.pending) {
         float ms = 0.f;
-        (void)hipEventElapsedTime(&ms, p.second.first, p.second.second);
-        (void)hipEventDestroy(p.second.first);
-        (void)hipEventDestroy(p.second.second);
+        (void)hipEventElapsedTime(&ms, p.a, p.b);
+        (void)hipEventDestroy(p.a);
+        (void)hipEventDestroy(p.b);
         bool found = false;
         for (auto& r : acc)
-            if (std::strcmp(r.name, p.first) == 0) { r.launches += 1; r.total_ms += ms; found = true; break; }
-        if (!found) acc.push_back({p.first, 1, (double)ms});
+            if (std::strcmp(r.name, p.name) == 0) { r.launches += 1; r.total_ms += ms; found = true; break; }
+        if (!found) acc.push_back({p.name, 1, (double)ms});
     }
     h->timer.pending.clear();
     const int32_t n = (int32_t)std::min<size_t>(acc.size(), (size_t)cap);

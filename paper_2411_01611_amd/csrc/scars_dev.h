@@ -130,6 +130,56 @@ __device__ __forceinline__ void bag_pairs(int64_t block, const int32_t* __restri
     }
 }
 
+// Rows of the pinned host tables -> a staging area in HBM, `lpr` lanes per row (lane gl holds 16-byte piece gl of the
+// `chunks` pieces of a row), kStageUnroll rows in flight per lane group.  list[0 .. min(*d_count, cap_rows)) names the
+// rows (global row ids); row j goes to staging row j.  `flags` (may be null: every row): only rows whose flag equals
+// `want` are copied.  `block` of `nblocks` workgroups share the job; s_rbase is LDS [num_tables + 1], filled here.
+constexpr int kStageUnroll = 4;
+struct StageArgs {
+    const int32_t* list;
+    const int32_t* d_count;
+    u32x4* staging;
+    int chunks, lpr;
+    int64_t cap_rows;
+    const uint8_t* flags;
+    int want;
+};
+__device__ __forceinline__ void stage_rows_body(int block, int nblocks, const Meta* __restrict__ meta, int32_t* s_rbase,
+                                                const StageArgs& S) {
+    const int T = meta->num_tables;
+    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = meta->row_base[t];
+    __syncthreads();
+    const int64_t n = min((int64_t)*S.d_count, S.cap_rows);
+    const int gpb = kBlock / S.lpr;
+    const int grp = threadIdx.x / S.lpr, gl = threadIdx.x % S.lpr;
+    const int64_t stride = (int64_t)nblocks * gpb;
+    const bool lane_on = gl < S.chunks;      // lpr >= chunks: one 16-byte piece per lane
+    if (!lane_on || n <= 0) return;
+    for (int64_t j0 = (int64_t)block * gpb + grp; j0 < n; j0 += stride * kStageUnroll) {
+        // row numbers are clamped instead of guarded so that the id loads, then the row loads over the link,
+        // are all issued back to back; only rows below n are written
+        int32_t gid[kStageUnroll];
+        bool need[kStageUnroll];
+        u32x4 v[kStageUnroll];
+#pragma unroll
+        for (int u = 0; u < kStageUnroll; ++u) {
+            const int64_t j = min(j0 + u * stride, n - 1);
+            gid[u] = S.list[j];
+            need[u] = !S.flags || S.flags[j] == S.want;
+        }
+#pragma unroll
+        for (int u = 0; u < kStageUnroll; ++u) {
+            if (need[u]) {
+                const int t = upper_table(s_rbase, T, gid[u]);
+                v[u] = __builtin_nontemporal_load((const u32x4*)meta->table[t] + (int64_t)(gid[u] - s_rbase[t]) * S.chunks + gl);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kStageUnroll; ++u)
+            if (need[u] && j0 + u * stride < n) S.staging[(j0 + u * stride) * S.chunks + gl] = v[u];
+    }
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // fp32 -> bf16, round to nearest even (NaN kept quiet)

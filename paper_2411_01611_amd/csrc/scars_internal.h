@@ -14,8 +14,9 @@ namespace scars {
 constexpr int kBlock = 256;          // threads per workgroup everywhere: 4 wave64
 constexpr int kWave = 64;
 constexpr int kScanTile = 2048;      // items per workgroup in the ordered-compaction kernels
-constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1024 for inputs under 2^21 pairs,
-constexpr int kSortRoundsLarge = 16;   // 4096 above
+constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1024 for inputs up to 2^18 pairs,
+constexpr int kSortRoundsMid = 8;     // 2048 below 2^22,
+constexpr int kSortRoundsLarge = 16;   // 4096 from there on
 constexpr int kSortMaxBins = 512;     // up to 9 bits per pass
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
 constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
@@ -49,7 +50,7 @@ struct Workspace {
     // per batch
     uint32_t* blk_hit;        // [tiles of max(max_L, max_G) + 1] per-tile counts of the ordered compactions
     uint32_t* blk_miss;       // same
-    uint32_t* sort_hist;      // [kSortMaxBins * nbS] digit-major per-tile histogram, nbS tiles for max(max_L, k) pairs
+    uint32_t* sort_hist;      // [nbS * bins] per-tile digit histogram (a row per tile), nbS tiles for max(max_L, k) pairs
     uint32_t* sort_tot;       // [kSortMaxBins]
     uint32_t* key_buf[2];     // [max_L]
     uint32_t* val_buf[2];     // [max_L]
@@ -81,7 +82,8 @@ struct Workspace {
 };
 
 struct KernelTimer {
-    std::vector<std::pair<const char*, std::pair<hipEvent_t, hipEvent_t>>> pending;
+    struct Rec { const char* name; hipEvent_t a, b; int64_t tag; };
+    std::vector<Rec> pending;
 };
 
 }  // namespace scars
@@ -135,6 +137,11 @@ struct scars_handle {
     const int32_t* pairs_off = nullptr;
     int64_t pairs_L = 0, pairs_B = 0;
     int64_t n_ahead_used = 0;            // forward passes that used rows fetched ahead
+    int64_t n_ahead_timed = 0;           // updates with a fetch on the library's stream beside them, timed in profile mode
+    int64_t n_ahead_serial = 0;          // ... of which the fetch and the update did not run at the same time
+    int64_t timer_tag = 0;               // > 0: launches being enqueued belong to the update/fetch pair with this number
+    int64_t timer_serial = 0;
+    bool fused_fetch = true;             // the fetch ahead rides in the update's launch when it can
     int64_t n_prepared_used = 0;         // bwd_update calls that used segments prepared on the side stream
     // launch tuning (scars_set_tuning)
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
@@ -160,6 +167,7 @@ struct Timed {
     hipStream_t s;
     const char* name;
     hipEvent_t a = nullptr, b = nullptr;
+    int64_t tag = 0;
     Timed(scars_handle* h_, hipStream_t s_, const char* n);
     ~Timed();
 };
@@ -179,6 +187,8 @@ hipError_t launch_select_and_fill(scars_handle* h, hipStream_t s, int64_t k);
 hipError_t launch_flush(scars_handle* h, hipStream_t s);
 hipError_t launch_calib_copy(hipStream_t s, void* dst, const void* src, int64_t bytes);
 hipError_t launch_calib_read(hipStream_t s, const void* src, int64_t bytes, void* sink);
+hipError_t launch_calib_link(hipStream_t s, void* host, int64_t host_bytes, void* dev, int64_t n, int granule_bytes,
+                             int scattered, int to_host, int blocks);
 // k_remap.hip
 hipError_t launch_remap(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L, int64_t B,
                         const scars_remap_out* out);
@@ -208,8 +218,11 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
                       const scars_remap_out* rm, const float* grad, float lr, float eps, const scars_bwd_out* out,
                       const scars_remap_out* next_rm, const int32_t* next_off, int64_t next_L, int64_t next_B);
 // k_fwd.hip: missed rows of a remapped batch that are not in the sorted list `excl` -> staging area `area`
+// (`fused` set: only flags the rows and describes the job in *fused / *fused_blocks, for the caller's own launch)
+struct StageArgs;
 hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_out* next_rm, int64_t next_L,
-                              const int32_t* excl, const int32_t* n_excl, int area);
+                              const int32_t* excl, const int32_t* n_excl, int area, StageArgs* fused, int* fused_blocks);
+hipError_t ensure_pool_stream(scars_handle* h);
 hipError_t pf_join(scars_handle* h, hipStream_t s);
 void swap_segment_sets(scars_handle* h);
 hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B, const scars_remap_out* rm);

@@ -188,23 +188,23 @@ def test_full_size_look_ahead_steps_match_oracle(full):
     sc.set_tuning(binding.TUNE_LOOKAHEAD, 0)
 
 
-def _full_size_sgd_step(wl, P):
+def _full_size_sgd_step(wl, P, tabs=None):
     """One SGD workload at the size bench.py runs it: build_cache over P profile batches, then one batch through
     remap, forward and backward -- integer outputs bit-exact, pooled sums and every updated row within tolerance --
     the backward pass a second time in bench.py's launch configuration (sort started by remap on the side stream)."""
     from gpu_harness import assert_bf16_within
     dev = torch.device("cuda:0")
     bf16 = wl.dtype == "bf16"
-    tabs = []
+    tabs = tabs if tabs is not None else [binding.PinnedArray((wl.rows[t], wl.dim), np.uint16 if bf16 else np.float32)
+                                          for t in range(wl.num_tables)]
     for t in range(wl.num_tables):
-        p = binding.PinnedArray((wl.rows[t], wl.dim), np.uint16 if bf16 else np.float32)
+        p = tabs[t]
         chunk = max(1, (1 << 27) // wl.dim)
         for r0 in range(0, wl.rows[t], chunk):
             r1 = min(wl.rows[t], r0 + chunk)
             v = synth.row_values(wl, t, r0, r1, dev).contiguous()
             p.copy_from_device(v.view(torch.int16) if bf16 else v, r0)
             torch.cuda.synchronize()
-        tabs.append(p)
     sc = binding.Scars(wl.rows, wl.dim, binding.DTYPE_BF16 if bf16 else binding.DTYPE_F32, [p.ptr for p in tabs],
                        binding.OPT_SGD, None)
     smp = synth.Sampler(wl, dev)

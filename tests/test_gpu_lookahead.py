@@ -66,16 +66,21 @@ def _ora_fwd(c, batch):
 
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("budget", ["own", "none", "all"])
-@pytest.mark.parametrize("presort", [0, 1])
+@pytest.mark.parametrize("presort", [0, 1, 2])
 def test_lookahead_steps_match_the_calls_made_one_after_the_other(name, budget, presort):
+    # presort 2: as 1, but with the fetch on the library's second stream instead of inside the update's launch
+    own_stream = presort == 2
+    presort = min(presort, 1)
     wname, kw = CASES[name]
     wl = synth.workload(wname, **kw)
     bb = {"own": None, "none": 0, "all": wl.total_rows * wl.row_bytes}[budget]
-    _say("lookahead", name, budget, "presort", presort)
+    _say("lookahead", name, budget, "presort", presort, "fetch on its own stream" if own_stream else "fetch inside the update launch")
     c = GpuCase(wl, budget_bytes=bb, max_L=_room(wl))
     s = c.s
     s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
     s.set_tuning(binding.TUNE_PRESORT, presort)
+    if own_stream:
+        s.set_tuning(binding.TUNE_FUSED_FETCH, 0)
     c.build()
     steps = 4
     bs = _batches(c, steps + 1)
@@ -265,3 +270,49 @@ def test_twenty_lookahead_steps_match_oracle(name):
     if opt:
         assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators after twenty steps")
     c.close()
+
+
+def test_overlap_self_check_with_caller_streams_created_first():
+    """The library's streams only overlap with the caller's when they sit on hardware queues of their own, and a process
+    has few.  With two caller streams created before the handle, the fetch on the library's stream may or may not run
+    beside the update; profile mode must time every such pair and say how many did not overlap.  With the fetch
+    carried inside the update's launch (the default) nothing depends on a second queue and nothing is timed."""
+    mine = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st in mine:                                   # make sure both really exist on the device
+        with torch.cuda.stream(st):
+            torch.zeros(16, device="cuda:0").add_(1)
+    torch.cuda.synchronize()
+    wl = synth.workload("multi_hot", scale=0.05, batch=1024)
+    for fused in (0, 1):
+        _say("overlap self-check, fetch", "inside the update launch" if fused else "on the library's stream")
+        c = GpuCase(wl, max_L=_room(wl))
+        s = c.s
+        s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+        s.set_tuning(binding.TUNE_FUSED_FETCH, fused)
+        c.build()
+        steps = 4
+        bs = [c.sampler.batch(e) for e in range(steps + 1)]
+        dev = [(b[0].to(c.dev), b[1].to(c.dev)) for b in bs]
+        g = c.sampler.grads(0).to(c.dev)
+        rms = [s.new_remap_out(), s.new_remap_out()]
+        s.remap(dev[0][0], dev[0][1], wl.batch, rms[0])
+        s.embedding_bag_fwd(dev[0][0], dev[0][1], wl.batch, rms[0])
+        s.profile_enable(True)
+        for e in range(steps):
+            s.remap(dev[e + 1][0], dev[e + 1][1], wl.batch, rms[(e + 1) % 2])
+            s.embedding_bag_bwd_update_ahead(dev[e][0], dev[e][1], wl.batch, rms[e % 2], g, float(wl.lr), float(wl.eps),
+                                             rms[(e + 1) % 2], dev[e + 1][0], dev[e + 1][1], wl.batch)
+            s.embedding_bag_fwd(dev[e + 1][0], dev[e + 1][1], wl.batch, rms[(e + 1) % 2])
+        prof = s.profile_read()
+        s.profile_enable(False)
+        assert s.sync_status() == 0
+        timed = s.get_counter(binding.COUNTER_AHEAD_TIMED)
+        serial = s.get_counter(binding.COUNTER_AHEAD_NOT_OVERLAPPED)
+        _say("  kernels", sorted(prof), "timed", timed, "not overlapped", serial)
+        assert s.get_counter(binding.COUNTER_AHEAD_USED) == steps
+        if fused:
+            assert timed == 0 and serial == 0 and "seg_rows_long+fetch_ahead" in prof and "fetch_ahead" not in prof
+        else:
+            assert timed == steps and 0 <= serial <= timed and "fetch_ahead" in prof
+        c.close()
+    del mine

@@ -60,3 +60,45 @@ def test_calibration_kernels_and_copy_helper():
     L = binding.lib()
     assert L.scars_calibration_copy(dst.data_ptr(), src.data_ptr(), 24, None) == binding.ERR_INVALID_ARG   # not 16-byte units
     assert L.scars_memcpy(None, src.data_ptr(), 16, 1, None) == binding.ERR_INVALID_ARG
+
+
+def test_link_calibration_moves_the_granules_it_says():
+    """The host-link calibration kernel: sequential reads copy the host buffer, scattered reads fetch whole granules
+    of it, writes land whole granules; the arguments are checked."""
+    dev = torch.device("cuda:0")
+    n_words = 1 << 18                                             # 1 MiB of host memory
+    host = binding.PinnedArray((n_words,), np.int32)
+    host.np[...] = np.arange(n_words, dtype=np.int32)
+    for granule in (64, 128, 512):
+        gw = granule // 4
+        n_gran = n_words // gw
+        d = torch.full((n_words + 7 * gw,), -1, dtype=torch.int32, device=dev)
+        binding.calibration_link(host, d, n_gran, granule, scattered=False, to_host=False)
+        torch.cuda.synchronize()
+        assert np.array_equal(d.cpu().numpy()[:n_words], host.np) and int(d[n_words]) == -1
+        # scattered: more granules than the host holds; every fetched granule is a whole, aligned host granule
+        n2 = n_gran + 7
+        d.fill_(-1)
+        binding.calibration_link(host, d, n2, granule, scattered=True, to_host=False, workgroups=7)
+        torch.cuda.synchronize()
+        got = d.cpu().numpy()[: n2 * gw].reshape(n2, gw)
+        assert (got[:, 0] % gw == 0).all() and (np.diff(got, axis=1) == 1).all()
+        assert np.unique(got[:, 0]).size > n_gran // 4               # spread over the buffer, not one granule
+        # scattered writes: the host buffer ends up holding whole granules of the device buffer
+        src = torch.arange(n_gran * gw, dtype=torch.int32, device=dev) + (1 << 24)
+        binding.calibration_link(host, src, n_gran, granule, scattered=True, to_host=True)
+        torch.cuda.synchronize()
+        # (two device granules may land on one host granule, each 16-byte piece then comes from either of them)
+        h = host.np.reshape(-1, 4)
+        written = h[:, 0] >= (1 << 24)
+        assert written.sum() > n_gran // 4 and ((h[written, 0] - (1 << 24)) % 4 == 0).all()
+        assert (np.diff(h[written], axis=1) == 1).all()
+        piece = np.arange(h.shape[0]) % (gw // 4)                      # a piece keeps its place inside the granule
+        assert (((h[written, 0] - (1 << 24)) // 4) % (gw // 4) == piece[written]).all()
+        host.np[...] = np.arange(n_words, dtype=np.int32)
+    L = binding.lib()
+    d = torch.zeros(1024, dtype=torch.int32, device=dev)
+    assert L.scars_calibration_link(host.ptr, host.nbytes, d.data_ptr(), 4, 48, 1, 0, 16, None) == binding.ERR_INVALID_ARG
+    assert L.scars_calibration_link(None, host.nbytes, d.data_ptr(), 4, 64, 1, 0, 16, None) == binding.ERR_INVALID_ARG
+    assert L.scars_calibration_link(host.ptr, host.nbytes, d.data_ptr(), 4, 64, 1, 0, 0, None) == binding.ERR_INVALID_ARG
+    host.free()

@@ -113,6 +113,31 @@ def test_tuning_counters_and_planning_calls_check_their_arguments():
     assert L.scars_plan_cache(None, C.byref(pin), C.byref(po), None) == binding.ERR_INVALID_ARG
 
 
+def test_bind_buffers_refuses_buffers_smaller_than_query_sizes_asks_for():
+    """Every buffer handed to scars_bind_buffers carries its size; one byte short of what scars_query_sizes asks for
+    with the same three arguments is refused before anything touches the device."""
+    L = binding.lib()
+    for opt, state in ((binding.OPT_SGD, None), (binding.OPT_ADAGRAD, [0x3000, 0x4000])):
+        s = binding.Scars([1000, 3000], 64, binding.DTYPE_F32, [0x1000, 0x2000], opt, state)
+        budget, max_L, max_G = 256 * 500, 4096, 512
+        z = s.query_sizes(budget, max_L, max_G)
+        names = ["counts", "slot_of", "hot_gid", "cache", "state_cache", "workspace"]
+        full = [z[n + "_bytes"] for n in names]
+        ptr = lambda n: None if (n == "state_cache" and opt == binding.OPT_SGD) else 0x10000
+        for short in names:
+            if short == "state_cache" and opt == binding.OPT_SGD:
+                continue
+            sizes = [v - 1 if n == short else v for n, v in zip(names, full)]
+            b = binding._Buffers(*[ptr(n) for n in names], budget, max_L, max_G, *sizes)
+            assert L.scars_bind_buffers(s._h, C.byref(b), None) == binding.ERR_WORKSPACE, short
+            assert b"smaller" in L.scars_last_error(s._h)
+        # binding a larger budget or batch than the buffers were sized for is the same mistake
+        for bud, ml, mg in ((budget * 2, max_L, max_G), (budget, max_L * 2, max_G), (budget, max_L, max_G * 4096)):
+            b = binding._Buffers(*[ptr(n) for n in names], bud, ml, mg, *full)
+            assert L.scars_bind_buffers(s._h, C.byref(b), None) == binding.ERR_WORKSPACE
+        s.close()
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N with N > 1 (or a multi-rank launch) exits with a message instead of running."""
     import subprocess
