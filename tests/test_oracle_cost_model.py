@@ -136,3 +136,55 @@ def test_caching_one_more_row_criterion_agrees_with_the_cost_difference(ora):
     # refused: nothing left to cache, or no room for a batch of one after caching one more
     assert ora.caching_gain(skewed, 8 * wl.batch, 3000, 1e6, 10.0, d)[0] != 0
     assert ora.caching_gain(skewed, 8 * wl.batch, 10, 10 * d + 20.0, 10.0, d)[0] != 0
+
+
+def _cost_numpy(T, counts, S, k, M, a, d, Q):
+    """Eq. (6) with eq. (7)'s batch size, restated with numpy: the first k rows by (count descending, row ascending)
+    are cached; None when no batch of one sample fits."""
+    b = (M - k * d) / a
+    if not b >= 1.0:
+        return None
+    order = np.lexsort((np.arange(counts.size), -counts.astype(np.int64)))
+    p = np.minimum(1.0, counts[order][k:].astype(np.float64) / S)
+    return T * Q + (Q / b) * d * float(np.sum(1.0 - (1.0 - p) ** b))
+
+
+def test_plan_brute_is_the_first_minimum_of_the_cost_over_every_feasible_k(ora):
+    """ora_plan_brute against an argmin written with numpy over a numpy restatement of the cost: an interior optimum,
+    an optimum at k_max (a > d: caching always pays), an optimum at the last feasible k before k_max (the rest leaves
+    no room for a sample), and a tie (rows never seen add nothing: the smallest such k wins)."""
+    rng = np.random.default_rng(11)
+    T, d, Q = 3, 16.0, 1.0e5
+
+    def check(counts, S, k_max, M, a):
+        costs = [_cost_numpy(T, counts, S, k, M, a, d, Q) for k in range(k_max + 1)]
+        feas = [(c, k) for k, c in enumerate(costs) if c is not None]
+        want_c, want_k = min(feas, key=lambda ck: (ck[0], ck[1]))
+        rc, bk, bc = ora.plan_brute(T, counts, S, k_max, M, a, d, Q)
+        assert rc == 0
+        # equal to rounding: the two sums add the same terms in different orders
+        near = [k for c, k in feas if abs(c - want_c) <= 1e-9 * want_c]
+        assert bk in near and abs(bc - want_c) <= 1e-9 * want_c
+        return bk, want_k, len(feas)
+
+    zipf = np.round(2000.0 / np.arange(1, 401) ** 1.1).astype(np.uint32)
+    rng.shuffle(zipf)
+    S = 4000
+    # interior optimum: a tight device (M), cheap samples
+    bk, wk, nf = check(zipf, S, 400, 400 * d * 0.6, 20.0)
+    assert bk == wk and 0 < bk < 400 and nf < 401
+    # a > d and plenty of room: every cached row lowers the cost, the optimum is k_max itself
+    bk, wk, nf = check(zipf, S, 150, 1.0e7, 64.0)
+    assert bk == wk == 150 and nf == 151
+    # k_max beyond what leaves room for one sample: the optimum is the last feasible k, not k_max
+    M = 100 * d + 64.0                                   # b(k) = (M - k d) / a >= 1  <=>  k <= 100
+    bk, wk, nf = check(zipf, S, 150, M, 64.0)
+    assert nf == 101 and bk == wk <= 100
+    # a tie: beyond the 5 rows that were ever seen nothing is left to send, and with a = d * 1e9 the batch size does
+    # not move: the cost is the same for every k >= 5 and the smallest of them is reported
+    seen = np.zeros(60, dtype=np.uint32)
+    seen[[3, 17, 18, 40, 59]] = [9, 2, 2, 7, 1]
+    rc, bk, bc = ora.plan_brute(T, seen, 100, 60, 1.0e15, d * 1.0e9, d, Q)
+    assert rc == 0 and bk == 5 and bc == T * Q
+    # nothing feasible at all
+    assert ora.plan_brute(T, seen, 100, 60, 10.0, 64.0, d, Q)[0] != 0
