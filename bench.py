@@ -311,15 +311,21 @@ def bytes_model(wl: synth.Workload, L: float, U: float, U_cold: float, n_miss: f
     return m
 
 
-def pmc_traffic(workload: str, kernel: str):
+def pmc_traffic(wl: synth.Workload, kernel: str, every_row_cached: bool = False):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload (a separate run of
-    the same command: the counters cannot be read from inside this process), or None."""
-    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.json")
-    try:
-        rec = json.load(open(path))
-        return rec[kernel]["hbm_bytes_per_launch"]
-    except Exception:
+    the same command: the counters cannot be read from inside this process), or None.  The counters belong to the
+    full-size workload with its own budget, or with every row cached: anything else gets None."""
+    if wl.total_rows != synth.workload(wl.name).total_rows:
         return None
+    names = [f"pmc_{wl.name}_every_row_cached.json", f"pmc_{wl.name}.json"] if every_row_cached else [f"pmc_{wl.name}.json"]
+    if wl.name == "low_skew_uniform" and not every_row_cached:
+        return None          # only its every-row-cached leg was profiled (profiles/pmc_low_skew_uniform.json)
+    for n in names:
+        try:
+            return json.load(open(os.path.join(ROOT, "profiles", n)))[kernel]["hbm_bytes_per_launch"]
+        except Exception:
+            continue
+    return None
 
 
 def avg_s(prof: dict, name: str) -> float:
@@ -338,7 +344,7 @@ def hbm_roofline(name: str, t_s: float, model: dict, traffic, ms_per_step: float
     if traffic:
         r["counter_GBs"] = round(traffic / t_s / 1e9, 1)
         r["frac_counter"] = round(traffic / t_s / 1e9 / HBM_PEAK_GBS, 4)
-        r["traffic_source"] = "profiles/pmc_<workload>.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run of this command, scaled by the 1 GiB copy kernel; not measured in this process"
+        r["traffic_source"] = "profiles/pmc_<workload>[_every_row_cached].json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run of this workload (command in the file), scaled by the 1 GiB copy kernel; not measured in this process"
     return r
 
 
@@ -369,24 +375,25 @@ def link_roofline(name: str, t_s: float, rd: float, wr: float, link: dict, traff
     return r
 
 
-def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None):
+def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None, cached=False):
     """(dominant-kernel roofline, gather roofline, host_link list) of one leg from its per-kernel times."""
+    pmc = lambda kernel: pmc_traffic(wl, kernel, cached)
     per_step = {n: r["total_ms"] / K for n, r in prof.items()}
     dominant = max(per_step, key=per_step.get)
     pool = which_pool or [n for n in POOL_KERNELS if n in prof][0]
-    gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc_traffic(wl.name, pool), ms_per_step, prof[pool]["launches"] / K)
+    gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc(pool), ms_per_step, prof[pool]["launches"] / K)
     host_link = []
     for name in ("stage_misses",) + UPDATE_KERNELS:
         if name not in prof:
             continue
         rd, wr = link_bytes(name)
         if rd + wr > 0:
-            host_link.append(link_roofline(name, avg_s(prof, name), rd, wr, link, pmc_traffic(wl.name, name), ms_per_step, wl.row_bytes))
+            host_link.append(link_roofline(name, avg_s(prof, name), rd, wr, link, pmc(name), ms_per_step, wl.row_bytes))
     by_name = {r["kernel"]: r for r in host_link}
     if dominant in by_name:
         top = by_name[dominant]
     elif dominant in model:
-        top = hbm_roofline(dominant, avg_s(prof, dominant), model, pmc_traffic(wl.name, dominant), ms_per_step,
+        top = hbm_roofline(dominant, avg_s(prof, dominant), model, pmc(dominant), ms_per_step,
                            prof[dominant]["launches"] / K)
     else:
         top = dict(gather, note=f"the largest share of the step is {dominant}, for which no byte model is kept")
@@ -512,7 +519,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     # the forward pass staged, so only its accumulator is read over the link; row and accumulator are written back
     lb = {"fetch": n_staged * wl.row_bytes, "acc": U_cold * state_b, "write": U_cold * (wl.row_bytes + state_b)}
     link_bytes = lambda name: (lb["fetch"], 0) if name == "stage_misses" else (lb["acc"], lb["write"])
-    top, gather, host_link = rooflines(wl, prof, K, ms_per_step, model, link, link_bytes)
+    top, gather, host_link = rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, None, b.budget >= wl.total_rows * wl.row_bytes)
     pool = gather["kernel"]
     for tag, p in (("forward_alone", prof_fwd), ("forward_cold_caches", prof_cold)):
         t = avg_s(p, pool)

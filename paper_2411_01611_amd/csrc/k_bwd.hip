@@ -24,6 +24,7 @@ __global__ void k_bwd_empty(int32_t* __restrict__ n_unique, int32_t* __restrict_
 }
 
 // ---- (3) segment heads ----------------------------------------------------------------------------------
+constexpr int64_t kSegViaLocMaxL = 1 << 20;   // up to this many lookups a run's slot is taken from remap's per-lookup arrays
 constexpr int kPerWaveS = kScanTile / (kBlock / kWave);
 constexpr int kRoundsS = kPerWaveS / kWave;
 
@@ -70,9 +71,10 @@ __global__ __launch_bounds__(kBlock) void k_seg_scan(uint32_t* __restrict__ a, u
 }
 
 // Run starts by ordered compaction; per run also where the update kernel finds the row and its first gradient row.
-// A pair's value holds the bag and the lookup's place inside it (bag_pairs), so the first lookup of a run of a cold
-// row is at position off[bag] + place, and loc[] there names the copy its forward pass staged: two dependent loads,
-// no search.  (When the place saturated, or the offsets were bad, the row is simply read from host memory.)
+// A pair's value holds the bag and the lookup's place inside it (bag_pairs), so the first lookup of a run is at
+// position off[bag] + place, and loc[] there is what remap found for it: the cache slot, or the copy of a cold row its
+// forward pass staged.  Two dependent loads from arrays the size of the batch, no search and no probe of the dense
+// row map.  (When the place saturated, or the offsets were bad, the map is probed and a cold row read from host memory.)
 __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
                                                       int64_t L, const uint32_t* __restrict__ blk_head,
                                                       const uint32_t* __restrict__ blk_valid, int scanned,
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
                                                       const int32_t* __restrict__ slot_of, uint32_t N,
                                                       int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag,
                                                       const int32_t* __restrict__ off, int64_t G, const int32_t* __restrict__ gid_of,
-                                                      const int32_t* __restrict__ loc_of, int32_t k, int staged, int shift) {
+                                                      const int32_t* __restrict__ loc_of, int32_t k, int staged, int shift, int via_loc) {
     __shared__ uint32_t s_a[4], s_red[8];
     const int64_t base = (int64_t)blockIdx.x * kScanTile + wave_id() * kPerWaveS;
     const uint32_t sat = (1u << shift) - 1u;
@@ -99,24 +101,35 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
         nh += (uint32_t)__popcll(ballot64(hd[r]));
     }
     if (lane_id() == 0) s_a[wave_id()] = nh;
-    // stage 2: per run start, the cache slot of the row and the start of its first bag, requested together
+    // stage 2: per run start, the start of its first bag and/or the row's slot in the dense map.  via_loc: the slot is
+    // not probed (a random access into an array of N entries) unless the place inside the bag is unknown (it saturated);
+    // stage 3 takes it from what remap found for the run's first lookup.  That pays while the batch's own arrays stay in
+    // the caches (655 k lookups, rows partly cold: 27 -> 20 us); for a batch of 4.3 M lookups it is three scattered
+    // reads instead of one (50 -> 92 us), so there only the cold rows go through stage 3.
     int32_t src[kRoundsS], p0[kRoundsS];
 #pragma unroll
     for (int r = 0; r < kRoundsS; ++r) {
         const bool h = hd[r] && kk[r] < N;
         const uint32_t bag = vv[r] >> shift;
-        src[r] = h ? slot_of[kk[r]] : -1;
-        p0[r] = (h && staged && (int64_t)bag < G && (vv[r] & sat) < sat) ? off[bag] : -1;
+        const bool placed = h && (int64_t)bag < G && (vv[r] & sat) < sat && (via_loc || staged);
+        p0[r] = placed ? off[bag] : -1;
+        src[r] = (h && !(placed && via_loc)) ? slot_of[kk[r]] : -1;
     }
-    // stage 3: a cold row's first lookup: its location (the staged copy) and, as a check, its row id
+    // stage 3: the run's first lookup: its location (cache slot, or the staged copy of a cold row) and, as a check,
+    // its row id
 #pragma unroll
     for (int r = 0; r < kRoundsS; ++r) {
-        if (hd[r] && src[r] < 0 && p0[r] >= 0) {
+        if (hd[r] && p0[r] >= 0 && (via_loc || src[r] < 0)) {
             const int64_t p = (int64_t)p0[r] + (vv[r] & sat);
+            bool found = false;
             if (p < L) {
                 const int32_t l = loc_of[p];
-                if ((uint32_t)gid_of[p] == kk[r] && l >= k) src[r] = l;
+                if ((uint32_t)gid_of[p] == kk[r]) {
+                    found = true;
+                    src[r] = (l < k || staged) ? l : -1;      // without a staged copy a cold row is read from host memory
+                }
             }
+            if (!found && via_loc) src[r] = kk[r] < N ? slot_of[kk[r]] : -1;   // offsets that do not describe the batch
         }
     }
     __syncthreads();
@@ -375,7 +388,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
 // With fetch_blocks > 0 the launch carries a third, independent job in its first workgroups: the NEXT batch's missed
 // rows are copied from host memory into a staging area (rows this update writes are flagged out beforehand), so that
 // the host link's two directions work at once without depending on a second hardware queue.
-template <int DTYPE, int OPT, int LPG, int ULONG>
+template <int DTYPE, int OPT, int LPG, int ULONG, bool FETCH>
 __global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int long_blocks, const uint32_t* __restrict__ key,
                                                           const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                                           const int32_t* __restrict__ seg_start,
@@ -385,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int 
                                                           const int32_t* __restrict__ chunk_run, const float* __restrict__ grad,
                                                           double* __restrict__ partial, UpdateArgs A, StageArgs F) {
     const int b = (int)blockIdx.x;
-    if (b < fetch_blocks) {
+    if (FETCH && b < fetch_blocks) {   // (an instantiation of its own, so that profiles tell the two launches apart)
         __shared__ int32_t s_rbase_f[SCARS_MAX_TABLES + 1];
         stage_rows_body(b, fetch_blocks, A.meta, s_rbase_f, F);
     } else if (b - fetch_blocks < long_blocks) {
@@ -459,22 +472,21 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     // with cold rows to write the kernel is bound by the host link and a thousand workgroups saturate it; more only
     // take wave slots and memory queues from the kernels of the library's other streams
     // (while rows are fetched ahead beside it, few enough that the fetch gets its share of every unit's memory queue:
-    // swept 128-8192; 384-512 is best for 512-byte rows, 1024 for 128-byte rows)
-    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? (h->R >= 512 ? 512 : 1024) : (h->k < h->N ? 1024 : 256 * 32));
+    // swept 128-8192 against 64-1024 workgroups of the fetch: what matters is their ratio; 128 : 384-512 and 256 : 768-1024
+    // are equally good for 512-byte rows, 256 : 2048 and more for 128-byte rows)
+    const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? (h->R >= 512 ? 512 : (h->R <= 128 ? 4096 : 1024)) : (h->k < h->N ? 1024 : 256 * 32));
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), max_blocks));
     const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
         {
             Timed t(h, s, fetch_blocks > 0 ? "seg_rows_long+fetch_ahead" : "seg_rows_long");
             const dim3 grid(fetch_blocks + chunk_blocks + rows_blocks);
-            if (L <= kFusedWideMaxL)
-                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kTaskUnroll>), grid, dim3(kBlock), 0, s, fetch_blocks,
-                                   chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
-                                   ws.chunk_run, grad, ws.partial, A, F);
-            else
-                hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, kGradUnroll>), grid, dim3(kBlock), 0, s, fetch_blocks,
-                                   chunk_blocks, key, val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag,
-                                   ws.chunk_run, grad, ws.partial, A, F);
+#define SCARS_RL(UL, FE)                                                                                                  \
+    hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, UL, FE>), grid, dim3(kBlock), 0, s, fetch_blocks, chunk_blocks, key, \
+                       val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag, ws.chunk_run, grad, ws.partial, A, F)
+            if (L <= kFusedWideMaxL) { if (fetch_blocks > 0) SCARS_RL(kTaskUnroll, true); else SCARS_RL(kTaskUnroll, false); }
+            else { if (fetch_blocks > 0) SCARS_RL(kGradUnroll, true); else SCARS_RL(kGradUnroll, false); }
+#undef SCARS_RL
         }
         Timed t(h, s, "seg_combine");
         hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
@@ -552,7 +564,7 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
         hipLaunchKernelGGL(k_seg_write, dim3(nb), dim3(kBlock), 0, s, key, val, L, ws.blk_seg_a, ws.blk_seg_b, scan ? 1 : 0,
                            n_unique, seg_start, unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr,
                            ws.chunk_run, h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, off, G, rm->gid,
-                           rm->loc, (int32_t)h->k, staged ? 1 : 0, bag_shift_host(G));
+                           rm->loc, (int32_t)h->k, staged ? 1 : 0, bag_shift_host(G), L <= kSegViaLocMaxL ? 1 : 0);
     }
     return hipGetLastError();
 }
