@@ -4,7 +4,7 @@
 // in ascending gid order, so stability gives "lower id first among equal counts"), and (b) ordering a
 // batch's lookups by (gid, position) for the backward pass (key = gid, value = bag; the input is in
 // position order).  Per pass: per-tile digit histogram (one row of `bins` counts per tile) -> per-digit exclusive scan
-// down the tiles (a few digit columns per workgroup, so that a row of lanes touches one contiguous piece of a tile's row) -> scatter
+// down the tiles (eight digit columns per workgroup, so that a row of lanes touches one 32-byte piece of a tile's row) -> scatter
 // in which each tile is first ordered in LDS (wave-level multi-split by ballot matching) and then written
 // out as contiguous runs per digit.  The number of passes is ceil(bits / 9) and the digit width is
 // ceil(bits / passes), so 26-bit row ids take three 9-bit passes instead of four 8-bit ones.
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kBlock) void k_sort_hist(const uint32_t* __restrict
 // group of g = min(kScanDigits, bins) neighbouring digits; lane (row, dg) = (tid / g, tid % g) owns the digit's counts
 // of `per` consecutive tiles.  Three steps whatever the number of tiles: every lane adds up its tiles (independent
 // loads), one scan of those sums across the rows of lanes, then every lane writes the running sums of its tiles.
-constexpr int kScanDigits = 2;  // digits per workgroup (fewer when a pass has fewer bins)
+constexpr int kScanDigits = 8;  // digits per workgroup (fewer when a pass has fewer bins): 32-byte pieces of a tile's row; swept 1/2/4/8
 constexpr int kScanUnroll = 16;  // loads in flight per lane: the kernel is a chain of round trips, not of bytes
 __global__ __launch_bounds__(kBlock) void k_sort_scan(uint32_t* __restrict__ hist, int nb, int bins, int g,
                                                       uint32_t* __restrict__ tot) {
