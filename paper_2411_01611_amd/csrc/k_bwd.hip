@@ -115,21 +115,24 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
         p0[r] = placed ? off[bag] : -1;
         src[r] = (h && !(placed && via_loc)) ? slot_of[kk[r]] : -1;
     }
-    // stage 3: the run's first lookup: its location (cache slot, or the staged copy of a cold row) and, as a check,
-    // its row id
+    // stage 3: the run's first lookup: its location (cache slot, or the staged copy of a cold row).  The pairs were
+    // built from these very offsets, so the position is the lookup's own; should the offsets not describe the batch
+    // (a latched error, outputs unspecified) the location read is still one remap wrote for this batch, hence a valid
+    // cache slot or staging row.  In the cold-rows-only form the row id at that position is checked as well.
 #pragma unroll
     for (int r = 0; r < kRoundsS; ++r) {
         if (hd[r] && p0[r] >= 0 && (via_loc || src[r] < 0)) {
             const int64_t p = (int64_t)p0[r] + (vv[r] & sat);
-            bool found = false;
             if (p < L) {
                 const int32_t l = loc_of[p];
-                if ((uint32_t)gid_of[p] == kk[r]) {
-                    found = true;
+                if (via_loc) {
                     src[r] = (l < k || staged) ? l : -1;      // without a staged copy a cold row is read from host memory
+                } else if ((uint32_t)gid_of[p] == kk[r] && l >= k) {
+                    src[r] = l;
                 }
+            } else if (via_loc) {
+                src[r] = slot_of[kk[r]];
             }
-            if (!found && via_loc) src[r] = kk[r] < N ? slot_of[kk[r]] : -1;   // offsets that do not describe the batch
         }
     }
     __syncthreads();
