@@ -311,6 +311,32 @@ def bytes_model(wl: synth.Workload, L: float, U: float, U_cold: float, n_miss: f
     return m
 
 
+def sources_sha1() -> str:
+    """One hash over the library's kernel sources: the committed counter summaries record the hash they were taken
+    with, so that a bench line can say when its `traffic` figures belong to other kernels than the ones it timed."""
+    import hashlib
+    h = hashlib.sha1()
+    d = os.path.join(ROOT, "paper_2411_01611_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def pmc_sources_match(wl: synth.Workload, every_row_cached: bool = False):
+    """True / False when the counter summary of this workload records the kernel sources it was taken with; else None."""
+    name = f"pmc_{wl.name}_every_row_cached.json" if every_row_cached else f"pmc_{wl.name}.json"
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", name)))
+    except Exception:
+        try:
+            rec = json.load(open(os.path.join(ROOT, "profiles", f"pmc_{wl.name}.json")))
+        except Exception:
+            return None
+    return (rec["_sources_sha1"] == sources_sha1()) if "_sources_sha1" in rec else None
+
+
 def pmc_traffic(wl: synth.Workload, kernel: str, every_row_cached: bool = False):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload (a separate run of
     the same command: the counters cannot be read from inside this process), or None.  The counters belong to the
@@ -332,7 +358,8 @@ def avg_s(prof: dict, name: str) -> float:
     return prof[name]["total_ms"] / prof[name]["launches"] * 1e-3
 
 
-def hbm_roofline(name: str, t_s: float, model: dict, traffic, ms_per_step: float, launches_per_step: float) -> dict:
+def hbm_roofline(name: str, t_s: float, model: dict, traffic, ms_per_step: float, launches_per_step: float,
+                 sources_match=None) -> dict:
     b = model[name]
     r = {"kernel": name, "bound": "hbm", "achieved": round(b["min"] / t_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": round(min(1.0, b["min"] / t_s / 1e9 / HBM_PEAK_GBS), 4),
@@ -342,6 +369,7 @@ def hbm_roofline(name: str, t_s: float, model: dict, traffic, ms_per_step: float
          "traffic": traffic, "avg_launch_ms": round(t_s * 1e3, 5),
          "share_of_step": round(t_s * 1e3 * launches_per_step / ms_per_step, 4)}
     if traffic:
+        r["traffic_taken_with_these_kernel_sources"] = sources_match
         r["counter_GBs"] = round(traffic / t_s / 1e9, 1)
         r["frac_counter"] = round(traffic / t_s / 1e9 / HBM_PEAK_GBS, 4)
         r["traffic_source"] = "profiles/pmc_<workload>[_every_row_cached].json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a separate run of this workload (command in the file), scaled by the 1 GiB copy kernel; not measured in this process"
@@ -378,10 +406,11 @@ def link_roofline(name: str, t_s: float, rd: float, wr: float, link: dict, traff
 def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None, cached=False):
     """(dominant-kernel roofline, gather roofline, host_link list) of one leg from its per-kernel times."""
     pmc = lambda kernel: pmc_traffic(wl, kernel, cached)
+    match = pmc_sources_match(wl, cached)
     per_step = {n: r["total_ms"] / K for n, r in prof.items()}
     dominant = max(per_step, key=per_step.get)
     pool = which_pool or [n for n in POOL_KERNELS if n in prof][0]
-    gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc(pool), ms_per_step, prof[pool]["launches"] / K)
+    gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc(pool), ms_per_step, prof[pool]["launches"] / K, match)
     host_link = []
     for name in ("stage_misses",) + UPDATE_KERNELS:
         if name not in prof:
@@ -389,12 +418,14 @@ def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None
         rd, wr = link_bytes(name)
         if rd + wr > 0:
             host_link.append(link_roofline(name, avg_s(prof, name), rd, wr, link, pmc(name), ms_per_step, wl.row_bytes))
+            if host_link[-1]["traffic"]:
+                host_link[-1]["traffic_taken_with_these_kernel_sources"] = match
     by_name = {r["kernel"]: r for r in host_link}
     if dominant in by_name:
         top = by_name[dominant]
     elif dominant in model:
         top = hbm_roofline(dominant, avg_s(prof, dominant), model, pmc(dominant), ms_per_step,
-                           prof[dominant]["launches"] / K)
+                           prof[dominant]["launches"] / K, match)
     else:
         top = dict(gather, note=f"the largest share of the step is {dominant}, for which no byte model is kept")
     return top, gather, host_link

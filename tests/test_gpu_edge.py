@@ -560,3 +560,70 @@ def test_call_order_and_size_errors_leave_outputs_alone():
     rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
     assert_close(out.cpu().numpy(), want, "forward after the refused calls")
     c.close()
+
+
+@pytest.mark.parametrize("n_rows", [1, 2, 5])
+def test_tables_of_a_few_rows_sort_with_a_handful_of_bins(n_rows):
+    """One table of 1, 2 or 5 rows looked up thousands of times: the radix sort of the backward pass then runs a
+    single pass of 1 to 3 bits (2 to 8 bins, fewer than its scan kernel's digit group), over several tiles."""
+    rng = np.random.default_rng(n_rows)
+    B, per = 700, 5
+    L = B * per
+    idx = rng.integers(0, n_rows, L).astype(np.int32)
+    off = (np.arange(B + 1) * per).astype(np.int32)
+    for k in (0, n_rows):
+        _say("rows", n_rows, "cached", k)
+        c = _custom_case([n_rows], 16, idx, off, B, budget_rows=k, optimizer="adagrad")
+        rm, out, bo, grad = _run_all(c)
+        assert c.s.sync_status() == 0
+        rc, sg, sb, ss, ug = oracle.bwd_segments(c.wl.rows, idx, off, B)
+        U, nv = bo.n_unique.cpu().tolist()
+        assert rc == 0 and U == ug.size and nv == sg.size == L
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[:nv], sg)
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+        (rc,) = oracle.embedding_bag_bwd_update(c.wl.rows, c.ora_tables, c.ora_state, 1, idx, off, B, grad.numpy(),
+                                                np.float32(0.01), np.float32(1e-8))
+        assert rc == 0
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+        assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "accumulators")
+        c.close()
+
+
+def test_a_bag_longer_than_the_place_field_of_a_pair_can_count():
+    """A pair's value holds the bag and the lookup's place inside it; with 2^17 bags the place saturates at 32767.
+    One bag of 40000 lookups over cold rows, some of them first seen beyond that place: their runs must still find
+    the rows (from host memory instead of the staged copy) and every row must end up as the oracle's."""
+    rng = np.random.default_rng(3)
+    B, long_bag, n_long = 1 << 17, 77, 40000
+    lens = (rng.random(B) < 0.5).astype(np.int64)
+    lens[long_bag] = n_long
+    off = np.zeros(B + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    L = int(off[-1])
+    n_rows = 60000
+    idx = rng.integers(0, 30000, L).astype(np.int32)
+    a = int(off[long_bag])
+    # the tail of the long bag looks up rows no other lookup touches: their runs start beyond the saturated place
+    idx[a + 33000:a + n_long] = 30000 + rng.integers(0, 30000, n_long - 33000)
+    for k in (0, 2000):
+        _say("long bag, cached rows", k)
+        c = _custom_case([n_rows], 8, idx, off, B, budget_rows=k)
+        rm, out, bo, grad = _run_all(c)
+        assert c.s.sync_status() == 0
+        rc, want = oracle.embedding_bag_fwd(c.wl.rows, c.ora_tables, idx, off, B)
+        got = out.cpu().numpy()
+        others = np.arange(B) != long_bag
+        assert_close(got[others], want[others], "forward, the ordinary bags")
+        # 40000 terms added in fp32 against an fp64 sum: the 1e-5 bar is for bags of the workloads' lengths
+        assert np.allclose(got[long_bag], want[long_bag], rtol=1e-3, atol=1e-4)
+        rc, sg, sb, ss, ug = oracle.bwd_segments(c.wl.rows, idx, off, B)
+        U, nv = bo.n_unique.cpu().tolist()
+        assert U == ug.size and nv == L
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[:nv], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: U + 1], ss)
+        (rc,) = oracle.embedding_bag_bwd_update(c.wl.rows, c.ora_tables, None, 0, idx, off, B, grad.numpy(),
+                                                np.float32(0.01), np.float32(0.0))
+        assert rc == 0
+        assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows")
+        c.close()
