@@ -703,6 +703,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="multi_hot", choices=synth.WORKLOAD_NAMES)
     ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--batch", type=int, default=0,
+                    help="samples per table in a batch, for --workload only (default: the workload's own); the axis of the "
+                         "paper's batch-size tables")
     ap.add_argument("--row-scale", type=float, default=None,
                     help="shrink table rows and budget only (default: 1.0, and for host_spill, whose 102 GB of tables "
                          "may exceed what the box lets one process pin, the largest multiple of 0.05 that can be pinned)")
@@ -782,7 +785,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
     row_scale = args.row_scale if forced else 1.0
     attempts = []
     while True:
-        wl = synth.workload(name, scale=args.scale, row_scale=row_scale)
+        over = {"batch": args.batch} if (args.batch > 0 and name == args.workload) else {}
+        wl = synth.workload(name, scale=args.scale, row_scale=row_scale, **over)
         pinned, failure = pin_tables(wl, wl.optimizer == "adagrad")
         if pinned is not None:
             break
