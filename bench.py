@@ -412,15 +412,24 @@ def rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, which_pool=None
     pool = which_pool or [n for n in POOL_KERNELS if n in prof][0]
     gather = hbm_roofline(pool, avg_s(prof, pool), model, pmc(pool), ms_per_step, prof[pool]["launches"] / K, match)
     host_link = []
+    beside = None
     for name in ("stage_misses",) + UPDATE_KERNELS:
         if name not in prof:
             continue
         rd, wr = link_bytes(name)
         if rd + wr > 0:
-            host_link.append(link_roofline(name, avg_s(prof, name), rd, wr, link, pmc(name), ms_per_step, wl.row_bytes))
+            t, label = avg_s(prof, name), name
+            if name != "stage_misses" and "fetch_ahead" in prof:
+                # the fetch for the next batch is a launch of its own on the library's stream, beside this update:
+                # the pair is priced as one, over the longer of the two
+                t, label = max(t, avg_s(prof, "fetch_ahead")), name + " beside fetch_ahead"
+                beside = label
+            host_link.append(link_roofline(label, t, rd, wr, link, pmc(name), ms_per_step, wl.row_bytes))
             if host_link[-1]["traffic"]:
                 host_link[-1]["traffic_taken_with_these_kernel_sources"] = match
     by_name = {r["kernel"]: r for r in host_link}
+    if beside and (dominant == "fetch_ahead" or dominant + " beside fetch_ahead" == beside):
+        dominant = beside
     if dominant in by_name:
         top = by_name[dominant]
     elif dominant in model:
