@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libscars.so")
+# SCARS_LIB_PATH: load another build of the same sources instead (the test suite's host-sanitizer run sets it)
+LIB_PATH = os.environ.get("SCARS_LIB_PATH") or os.path.join(_HERE, "libscars.so")
 
 OK, ERR_INVALID_ARG, ERR_NOT_BUILT, ERR_WORKSPACE, ERR_HIP, ERR_INDEX_RANGE, ERR_OFFSETS = 0, -1, -2, -3, -4, -5, -6
 DTYPE_F32, DTYPE_BF16 = 0, 1
