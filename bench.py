@@ -459,6 +459,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
                     lookups += b.step(e)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
+        enqueue_ms = None
         t0 = time.perf_counter()
         g.replay()
         torch.cuda.synchronize()
@@ -468,8 +469,10 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
         t0 = time.perf_counter()
         for e in range(W, W + K):
             lookups += b.step(e)
+        t_enq = time.perf_counter()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        enqueue_ms = (t_enq - t0) * 1e3 / K
     assert b.s.sync_status() == 0
     ms_per_step = (t1 - t0) * 1e3 / K
     n_hit, n_miss = b.rm.n_hit_miss.cpu().tolist()
@@ -574,6 +577,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
             "roofline": top, "gather": gather, "host_link": host_link, "kernels": kern,
             "calls_alone_ms": {c: round(v, 5) for c, v in alone.items()},
             "ms_per_step_median": round(per_step[len(per_step) // 2], 5), "ms_per_step_min": round(per_step[0], 5),
+            "host_enqueue_ms_per_step": None if enqueue_ms is None else round(enqueue_ms, 5),
             "_model": model, "_pool": pool, "_link_bytes": lb}
 
 
@@ -890,7 +894,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         r = run_leg(b, K, W, link, args.graph)
         resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
                     "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
-                    "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "gather": r["gather"],
+                    "host_enqueue_ms_per_step": r["host_enqueue_ms_per_step"], "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "gather": r["gather"],
                     "calls_alone_ms": r["calls_alone_ms"], "kernels": r["kernels"]}
         log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
 
@@ -904,6 +908,7 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
 
     plain = {"value": leg["value"], "unit": "lookups/s", "ms_per_step": leg["ms_per_step"],
              "ms_per_step_median": leg["ms_per_step_median"], "ms_per_step_min": leg["ms_per_step_min"],
+             "host_enqueue_ms_per_step": leg["host_enqueue_ms_per_step"],
              "order": "remap(e) -> embedding_bag_fwd(e) -> embedding_bag_bwd_update(e)",
              "roofline": leg["roofline"], "gather": leg["gather"], "host_link": leg["host_link"],
              "calls_alone_ms": leg["calls_alone_ms"], "kernels": leg["kernels"]}
