@@ -181,6 +181,9 @@ struct UpdateArgs {
     int shift;       // a pair's value is (bag << shift) | place inside the bag
 };
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 // Where a row lives: cache slot (HBM) or pinned host table; the Adagrad accumulator beside it.
 template <int DTYPE, int OPT>
 struct RowRef {
@@ -204,18 +207,20 @@ struct RowRef {
             if (OPT == SCARS_OPT_ADAGRAD) s = A.meta->state[t] + row * A.D;
         }
     }
-    // lane owns columns [4c, 4c+4)
+    // lane owns columns [4c, 4c+4).  A row and its accumulator are read once per launch, the gradient rows beside them
+    // about once per lookup of their bag: streaming loads keep the former from pushing the latter out of the caches
+    // (every row cached, 20 lookups a bag: step 0.387 -> 0.360 ms; one index per bag: unchanged).
     __device__ __forceinline__ void load(int c, float (&wv)[4], float (&sv)[4]) const {
         if (DTYPE == SCARS_DTYPE_F32) {
-            const float4 v = ((const float4*)wr)[c];
+            const f32x4 v = __builtin_nontemporal_load((const f32x4*)wr + c);
             wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
         } else {
-            const uint2 v = ((const uint2*)wr)[c];
+            const u32x2 v = __builtin_nontemporal_load((const u32x2*)wr + c);
             wv[0] = __uint_as_float(v.x << 16); wv[1] = __uint_as_float(v.x & 0xFFFF0000u);
             wv[2] = __uint_as_float(v.y << 16); wv[3] = __uint_as_float(v.y & 0xFFFF0000u);
         }
         if (OPT == SCARS_OPT_ADAGRAD) {
-            const float4 v = ((const float4*)s)[c];
+            const f32x4 v = __builtin_nontemporal_load((const f32x4*)s + c);
             sv[0] = v.x; sv[1] = v.y; sv[2] = v.z; sv[3] = v.w;
         }
     }
@@ -236,15 +241,18 @@ struct RowRef {
                 st[i] = (double)sv[i] + g[i] * g[i];
                 wn[i] = (double)wv[i] - lr * g[i] / (sqrt(st[i]) + eps);
             }
-            ((float4*)s)[c] = make_float4((float)st[0], (float)st[1], (float)st[2], (float)st[3]);
+            const f32x4 o = {(float)st[0], (float)st[1], (float)st[2], (float)st[3]};
+            __builtin_nontemporal_store(o, (f32x4*)s + c);
         }
+        // A row is written once per launch and not read again by it: streaming stores (measured against ordinary
+        // ones: steps with cold rows 1-2 % shorter, the 53 k-lookup batch 6 %, nothing slower).
         if (DTYPE == SCARS_DTYPE_F32) {
-            ((float4*)w)[c] = make_float4((float)wn[0], (float)wn[1], (float)wn[2], (float)wn[3]);
+            const f32x4 o = {(float)wn[0], (float)wn[1], (float)wn[2], (float)wn[3]};
+            __builtin_nontemporal_store(o, (f32x4*)w + c);
         } else {
-            uint2 o;
-            o.x = (uint32_t)f32_to_bf16((float)wn[0]) | ((uint32_t)f32_to_bf16((float)wn[1]) << 16);
-            o.y = (uint32_t)f32_to_bf16((float)wn[2]) | ((uint32_t)f32_to_bf16((float)wn[3]) << 16);
-            ((uint2*)w)[c] = o;
+            const u32x2 o = {(uint32_t)f32_to_bf16((float)wn[0]) | ((uint32_t)f32_to_bf16((float)wn[1]) << 16),
+                             (uint32_t)f32_to_bf16((float)wn[2]) | ((uint32_t)f32_to_bf16((float)wn[3]) << 16)};
+            __builtin_nontemporal_store(o, (u32x2*)w + c);
         }
     }
 };
