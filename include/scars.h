@@ -204,7 +204,8 @@ int32_t scars_query_sizes(const scars_handle* h, int64_t budget_bytes, int64_t m
                           scars_sizes* out);
 
 /* Hand the allocated buffers to the handle.  Copies the table descriptors into the workspace and clears
- * the status word on `stream`; waits for that copy.  Forgets any previously built hot set. */
+ * the status word on `stream`; waits for that copy.  Forgets any previously built hot set: updated rows that are
+ * only in the cache bound before are lost unless scars_flush_cache has written them back first. */
 int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* bufs, void* stream);
 
 /* Skew table + top-k + cache fill (Section III: a frequency ranking over all rows, the hottest of which are kept on

@@ -320,12 +320,10 @@ static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, 
 // The library's second stream (default priority, created on first use): pooling beside the fetch in the forward pass,
 // and the fetch for the next batch beside the update in the backward pass; the two uses never overlap in time.
 hipError_t ensure_pool_stream(scars_handle* h) {
-    if (h->pool_stream) return hipSuccess;
-    hipError_t e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pool_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pool_join, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pf_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_pf_done, hipEventDisableTiming);
+    hipError_t e = hipSuccess;   // (a call that failed half way is completed by the next one)
+    if (!h->pool_stream) e = hipStreamCreateWithFlags(&h->pool_stream, hipStreamNonBlocking);
+    for (hipEvent_t* ev : {&h->ev_pool_fork, &h->ev_pool_join, &h->ev_pf_fork, &h->ev_pf_done})
+        if (e == hipSuccess && !*ev) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
     return e;
 }
 

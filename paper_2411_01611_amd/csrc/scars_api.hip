@@ -106,11 +106,9 @@ static hipError_t side_join(scars_handle* h, hipStream_t s) {
 
 static hipError_t ensure_side_stream(scars_handle* h) {
     hipError_t e = hipSuccess;
-    if (!h->side) {
-        if ((e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming)) != hipSuccess) return e;
-    }
+    if (!h->side && (e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking)) != hipSuccess) return e;
+    if (!h->ev_fork && (e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming)) != hipSuccess) return e;
+    if (!h->ev_join && (e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming)) != hipSuccess) return e;
     return e;
 }
 
@@ -228,17 +226,15 @@ int32_t scars_destroy(scars_handle* h) {
     if (h->pool_stream) {
         (void)hipStreamSynchronize(h->pool_stream);
         (void)hipStreamDestroy(h->pool_stream);
-        (void)hipEventDestroy(h->ev_pool_fork);
-        (void)hipEventDestroy(h->ev_pool_join);
-        (void)hipEventDestroy(h->ev_pf_fork);
-        (void)hipEventDestroy(h->ev_pf_done);
     }
+    for (hipEvent_t ev : {h->ev_pool_fork, h->ev_pool_join, h->ev_pf_fork, h->ev_pf_done})
+        if (ev) (void)hipEventDestroy(ev);
     if (h->side) {
         (void)hipStreamSynchronize(h->side);
         (void)hipStreamDestroy(h->side);
-        (void)hipEventDestroy(h->ev_fork);
-        (void)hipEventDestroy(h->ev_join);
     }
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
     for (auto& p : h->timer.pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     delete h;
     return SCARS_OK;
