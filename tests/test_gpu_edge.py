@@ -11,7 +11,6 @@ pytestmark = pytest.mark.gpu
 import oracle
 from paper_2411_01611_amd import binding, synth
 from gpu_harness import GpuCase, assert_close
-from util import gids_of
 
 
 def _say(*a):

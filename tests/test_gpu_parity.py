@@ -12,8 +12,8 @@ pytestmark = pytest.mark.gpu
 
 import oracle
 from paper_2411_01611_amd import binding, synth
-from gpu_harness import ATOL, RTOL, GpuCase, assert_bf16_within, assert_close
-from util import bag_of, gids_of
+from gpu_harness import GpuCase, assert_bf16_within, assert_close
+from util import gids_of
 
 CASES = {
     "tiny": ("tiny", {}),

@@ -9,7 +9,7 @@ import torch
 import torch.nn.functional as F
 
 from paper_2411_01611_amd import synth
-from util import bag_of, bf16_bits_to_f32, gids_of, np_tables
+from util import bag_of, gids_of, np_tables
 
 CASES = (("tiny", {}), ("multi_hot", {"scale": 0.004}), ("dlrm_onehot", {"scale": 0.002}))
 

@@ -6,8 +6,6 @@ a brute-force loop, a closed form from the paper, or an invariant that any corre
 import math
 
 import numpy as np
-import pytest
-import torch
 
 from paper_2411_01611_amd import synth
 from util import bag_of, gids_of
