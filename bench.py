@@ -786,6 +786,9 @@ def main():
                          "launch (default: the library's, every batch; 0 = never)")
     ap.add_argument("--update-max-blocks", type=int, default=0,
                     help="most workgroups of the per-row update kernel (default: the library's, 8192)")
+    ap.add_argument("--fused-scan-max-tiles", type=int, default=-1,
+                    help="ordered compactions of up to this many 2048-item tiles add up the tile counts inside the "
+                         "writing kernel instead of running a scan kernel between counting and writing (default: the library's)")
     ap.add_argument("--no-lookahead", dest="lookahead", action="store_false",
                     help="skip the extra leg in the look-ahead call order (reported under lookahead)")
     ap.add_argument("--fetch-on-own-stream", dest="fused_fetch", action="store_false",
@@ -869,6 +872,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         b.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, args.fused_long_max_l)
     if args.update_max_blocks > 0:
         b.s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, args.update_max_blocks)
+    if args.fused_scan_max_tiles >= 0:
+        b.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, args.fused_scan_max_tiles)
     b.prepare(K + W)
     bc = b.build_cache(link)
     log(name, "build_cache", bc)

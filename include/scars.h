@@ -76,7 +76,7 @@ typedef struct {
 /* Launch tuning; results never depend on it.  The ordered compactions (hit/miss lists, run starts, sample lists)
  * count per tile of 2048 items, then need each tile's start: with few tiles the writing kernel adds up the counts
  * of the tiles before its own, beyond the limit a separate scan kernel runs first.  A limit of 0 always scans. */
-#define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 1024, at most 4096 */
+#define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 4096, which is also the most */
 /* Value n > 0: for batches of at least n lookups, when the cache is smaller than the tables, scars_remap also starts
  * the integer half of the backward pass of the same batch (pairs, sort, run starts; it needs the remap outputs only)
  * on a stream the library owns (default priority, created on first use), so that it runs while

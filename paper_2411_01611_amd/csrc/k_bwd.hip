@@ -58,15 +58,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_count(const uint32_t* __restrict
 __global__ __launch_bounds__(kBlock) void k_seg_scan(uint32_t* __restrict__ a, uint32_t* __restrict__ b, int n,
                                                      int32_t* __restrict__ n_unique) {
     __shared__ uint32_t s_scan[8];
-    uint32_t ca = 0, cb = 0;
-    for (int base = 0; base < n; base += kBlock) {
-        const int i = base + threadIdx.x;
-        uint32_t va = i < n ? a[i] : 0u, vb = i < n ? b[i] : 0u, ta, tb;
-        const uint32_t ea = block_exclusive_scan(va, s_scan, &ta);
-        const uint32_t eb = block_exclusive_scan(vb, s_scan, &tb);
-        if (i < n) { a[i] = ca + ea; b[i] = cb + eb; }
-        ca += ta; cb += tb;
-    }
+    uint32_t ca, cb;
+    scan_two_counts(a, b, n, s_scan, &ca, &cb);
     if (threadIdx.x == 0) { n_unique[0] = (int32_t)ca; n_unique[1] = (int32_t)cb; }
 }
 

@@ -48,6 +48,49 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
     return base + inc - v;
 }
 
+// One workgroup: exclusive scan of a[0..n) and b[0..n) in place; the two sums to *ta, *tb.  Thread t owns the items
+// [t * per, (t + 1) * per): it adds them up (loads eight at a time), one scan across the threads gives its start, then
+// it writes the running sums.  Three steps whatever n is.  s_scan is LDS scratch [8]; every thread must call.
+__device__ __forceinline__ void scan_two_counts(uint32_t* __restrict__ a, uint32_t* __restrict__ b, int n, uint32_t* s_scan,
+                                                uint32_t* ta, uint32_t* tb) {
+    constexpr int kU = 8;
+    const int per = (n + kBlock - 1) / kBlock;
+    const int i0 = min((int)threadIdx.x * per, n), i1 = min(i0 + per, n);
+    uint32_t sa = 0, sb = 0;
+    for (int i = i0; i < i1; i += kU) {
+        uint32_t va[kU], vb[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int j = min(i + u, i1 - 1);
+            va[u] = a[j];
+            vb[u] = b[j];
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u)
+            if (i + u < i1) { sa += va[u]; sb += vb[u]; }
+    }
+    uint32_t ea = block_exclusive_scan(sa, s_scan, ta);
+    uint32_t eb = block_exclusive_scan(sb, s_scan, tb);
+    for (int i = i0; i < i1; i += kU) {
+        uint32_t va[kU], vb[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int j = min(i + u, i1 - 1);
+            va[u] = a[j];
+            vb[u] = b[j];
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if (i + u < i1) {
+                a[i + u] = ea;
+                b[i + u] = eb;
+                ea += va[u];
+                eb += vb[u];
+            }
+        }
+    }
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);

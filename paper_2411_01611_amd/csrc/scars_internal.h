@@ -148,7 +148,7 @@ struct scars_handle {
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
     int64_t update_max_blocks = 0;       // workgroups of the per-row update kernel (it strides over the rows); 0 = by case
     bool pairs_in_remap = true;          // scars_remap also writes the backward pass's (gid, bag) pairs
-    int fused_scan_max_tiles = 1024;     // compaction: up to this many tiles the writer sums the tile counts itself
+    int fused_scan_max_tiles = 4096;     // compaction: up to this many tiles the writer sums the tile counts itself
     int64_t fused_long_max_L = ((int64_t)1 << 31) - 1;   // backward: up to this many lookups long runs and rows share one launch
     // per-kernel timing
     bool profile = false;
