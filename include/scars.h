@@ -79,7 +79,7 @@ typedef struct {
 #define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 4096, which is also the most */
 /* Value n > 0: for batches of at least n lookups, when the cache is smaller than the tables, scars_remap also starts
  * the integer half of the backward pass of the same batch (pairs, sort, run starts; it needs the remap outputs only)
- * on a stream the library owns (default priority, created on first use), so that it runs while
+ * on a stream the library owns (default priority, created by scars_bind_buffers), so that it runs while
  * scars_embedding_bag_fwd waits on the host link for the missed rows.  scars_embedding_bag_bwd_update makes the
  * caller's stream wait for it and uses it when it is called for that batch (same remap_out arrays, offsets, L and
  * B), after that batch's forward pass, and without a scars_bwd_out; otherwise it sorts again itself.  The next call

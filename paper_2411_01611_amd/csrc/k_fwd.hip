@@ -317,7 +317,7 @@ static void launch_pool_d(int lpr, hipStream_t s, int mode, const int32_t* off, 
     }
 }
 
-// The library's second stream (default priority, created on first use): pooling beside the fetch in the forward pass,
+// The library's second stream (default priority, created when buffers are first bound): pooling beside the fetch in the forward pass,
 // and the fetch for the next batch beside the update in the backward pass; the two uses never overlap in time.
 hipError_t ensure_pool_stream(scars_handle* h) {
     hipError_t e = hipSuccess;   // (a call that failed half way is completed by the next one)

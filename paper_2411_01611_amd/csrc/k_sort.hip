@@ -5,7 +5,7 @@
 // batch's lookups by (gid, position) for the backward pass (key = gid, value = bag; the input is in
 // position order).  Per pass: per-tile digit histogram (one row of `bins` counts per tile) -> per-digit exclusive scan
 // down the tiles (eight digit columns per workgroup, so that a row of lanes touches one 32-byte piece of a tile's row) -> scatter
-// in which each tile is first ordered in LDS (wave-level multi-split by ballot matching) and then written
+// in which each tile is first ordered in LDS (wave-level multi-split; equal digits are matched through LDS) and then written
 // out as contiguous runs per digit.  The number of passes is ceil(bits / 9) and the digit width is
 // ceil(bits / passes), so 26-bit row ids take three 9-bit passes instead of four 8-bit ones.
 #include "scars_dev.h"
