@@ -789,6 +789,8 @@ def main():
     ap.add_argument("--fused-scan-max-tiles", type=int, default=-1,
                     help="ordered compactions of up to this many 2048-item tiles add up the tile counts inside the "
                          "writing kernel instead of running a scan kernel between counting and writing (default: the library's)")
+    ap.add_argument("--no-table-limit", dest="table_limit", action="store_false",
+                    help="one-index-per-bag workloads: do not tell the library that a table gets at most `batch` lookups")
     ap.add_argument("--no-lookahead", dest="lookahead", action="store_false",
                     help="skip the extra leg in the look-ahead call order (reported under lookahead)")
     ap.add_argument("--fetch-on-own-stream", dest="fused_fetch", action="store_false",
@@ -797,7 +799,7 @@ def main():
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
-    ap.set_defaults(presort=True, lookahead=True, fused_fetch=True)
+    ap.set_defaults(presort=True, lookahead=True, fused_fetch=True, table_limit=True)
     ap.add_argument("--no-resident", dest="resident", action="store_false",
                     help="skip the second leg in which every row is cached (the paper's 'hot' iteration): same "
                          "kernels, no host-link traffic; reported under cache_resident")
@@ -874,6 +876,10 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         b.s.set_tuning(binding.TUNE_UPDATE_MAX_BLOCKS, args.update_max_blocks)
     if args.fused_scan_max_tiles >= 0:
         b.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, args.fused_scan_max_tiles)
+    # one index per sample and table: a table gets exactly `batch` lookups, which the caller may state; up to 4096 the
+    # backward pass then sorts each table's pairs in LDS (two launches instead of three per radix pass)
+    table_limit = wl.batch if (wl.bag_lambda is None and args.table_limit) else 0
+    b.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, table_limit)
     b.prepare(K + W)
     bc = b.build_cache(link)
     log(name, "build_cache", bc)
@@ -941,7 +947,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
                    "unique_cold_rows_per_step": leg["U_cold"], "missed_lookups_per_step": leg["n_miss"],
                    "rows_fetched_over_link_per_step": leg["n_staged"], "coalesce": args.coalesce,
                    "launch": ("hip graph of the K steps" if args.graph else "eager") +
-                             (", backward sort prepared on the library's side stream" if args.presort else ""),
+                             (", backward sort prepared on the library's side stream" if args.presort else "") +
+                             (f", at most {table_limit} lookups per table stated (per-table sort in LDS)" if 0 < table_limit <= 4096 else ""),
                    "step": "every batch goes through remap, embedding_bag_fwd and embedding_bag_bwd_update once; call order: " + best["order"]},
         "roofline": best["roofline"], "gather": gather, "host_link": best["host_link"],
         "measured": measured_block(cal, link),

@@ -146,6 +146,7 @@ CALIB_SINK_BYTES = 4 << 20
 TUNE_FUSED_SCAN_MAX_TILES, TUNE_PRESORT, TUNE_FUSED_LONG_MAX_L, TUNE_PAIRS_IN_REMAP, TUNE_UPDATE_MAX_BLOCKS = 1, 2, 3, 4, 5
 TUNE_LOOKAHEAD = 6
 TUNE_FUSED_FETCH = 7
+TUNE_MAX_TABLE_LOOKUPS = 8
 COUNTER_PREPARED_USED = 1
 COUNTER_AHEAD_USED = 2
 COUNTER_AHEAD_TIMED = 3

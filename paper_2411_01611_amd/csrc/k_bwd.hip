@@ -548,7 +548,10 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     int bits = 1;
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
     int res = 0;
-    hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
+    // the caller has stated that no table gets more than a few thousand lookups: each table's piece is sorted in LDS
+    const bool small = h->table_lookups_limit > 0 && h->table_lookups_limit <= kSmallSortCap;
+    hipError_t e = small ? launch_small_sort_pairs(h, s, ws.key_buf, ws.val_buf, off, L, B, (int)h->table_lookups_limit)
+                         : launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
     if (e != hipSuccess) return e;
     *res_out = res;
     const uint32_t* key = ws.key_buf[res];

@@ -205,6 +205,7 @@ int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value) {
         case SCARS_TUNE_LOOKAHEAD: h->lookahead = value != 0; break;
         case SCARS_TUNE_UPDATE_MAX_BLOCKS: h->update_max_blocks = std::min<int64_t>(value, 1 << 16); break;
         case SCARS_TUNE_FUSED_FETCH: h->fused_fetch = value != 0; break;
+        case SCARS_TUNE_MAX_TABLE_LOOKUPS: h->table_lookups_limit = value; break;
         default: return fail(h, SCARS_ERR_INVALID_ARG, "set_tuning: unknown parameter");
     }
     return SCARS_OK;

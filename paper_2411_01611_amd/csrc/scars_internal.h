@@ -19,6 +19,7 @@ constexpr int kSortRoundsSmall = 4;   // radix-sort tile = 256 * rounds pairs: 1
 constexpr int kSortRoundsMid = 8;     // 2048 below 2^22,
 constexpr int kSortRoundsLarge = 16;   // 4096 from there on
 constexpr int kSortMaxBins = 512;     // up to 9 bits per pass
+constexpr int kSmallSortCap = 4096;   // pairs per table the one-workgroup-per-table sort takes
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
 constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
 constexpr int kPlanBigCap = 4096;
@@ -148,6 +149,7 @@ struct scars_handle {
     int64_t presort_min_L = 0;           // > 0: remap starts the backward pass's sort on the side stream for batches this large
     int64_t update_max_blocks = 0;       // workgroups of the per-row update kernel (it strides over the rows); 0 = by case
     bool pairs_in_remap = true;          // scars_remap also writes the backward pass's (gid, bag) pairs
+    int64_t table_lookups_limit = 0;     // > 0: the caller states that no table gets more lookups than this in a batch
     int fused_scan_max_tiles = 4096;     // compaction: up to this many tiles the writer sums the tile counts itself
     int64_t fused_long_max_L = ((int64_t)1 << 31) - 1;   // backward: up to this many lookups long runs and rows share one launch
     // per-kernel timing
@@ -180,6 +182,10 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
 hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n,
                                    const int32_t* d_n /*device-side pair count bounded by n, or null*/, int bits,
                                    int* result_buffer /*0 or 1: which buffer holds the result*/);
+// k_sort.hip: the same result for a batch whose tables each hold at most `limit` (<= kSmallSortCap) of the L pairs
+// (positions [off[t*B], off[(t+1)*B]) belong to table t): one workgroup per table sorts in LDS, two launches in all
+hipError_t launch_small_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
+                                   int64_t L, int64_t B, int limit);
 // k_build_cache.hip
 hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
 hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,

@@ -178,7 +178,8 @@ def test_large_counts_use_all_select_passes():
     c.close()
 
 
-def test_out_of_range_index_is_latched_and_treated_as_absent():
+@pytest.mark.parametrize("small_sort", [False, True])
+def test_out_of_range_index_is_latched_and_treated_as_absent(small_sort):
     rows = [40, 30]
     B = 64
     rng = np.random.default_rng(4)
@@ -188,6 +189,8 @@ def test_out_of_range_index_is_latched_and_treated_as_absent():
     idx[127] = 1000
     off = np.arange(2 * B + 1, dtype=np.int32)
     c = _custom_case(rows, 4, idx, off, B, budget_rows=20)
+    if small_sort:     # each table's pairs sorted by a workgroup of their own: invalid lookups still end up last of all
+        c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, B)
     c.profile = []
     c.build()
     d_idx, d_off = c.dev_batch()
@@ -220,6 +223,30 @@ def test_out_of_range_index_is_latched_and_treated_as_absent():
     assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
     oracle.embedding_bag_bwd_update(rows, c.ora_tables, None, 0, idx, off, B, grad.numpy(), np.float32(0.5), np.float32(0))
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after update with invalid lookups")
+    c.close()
+
+
+def test_more_lookups_in_a_table_than_stated_is_latched_and_stays_in_bounds():
+    """SCARS_TUNE_MAX_TABLE_LOOKUPS is a statement of the caller's; a batch that breaks it is reported, not trusted."""
+    wl = synth.workload("tiny")                                    # 256 lookups per table
+    c = GpuCase(wl)
+    c.build()
+    d_idx, d_off = c.dev_batch()
+    grad = c.sampler.grads(0).to(c.dev)
+    c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 100)
+    rm = c.s.remap(d_idx, d_off, wl.batch)
+    c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    assert c.s.sync_status() == 0                                   # remap and the forward pass do not depend on it
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
+    assert c.s.sync_status() == binding.ERR_OFFSETS
+    assert c.s.sync_status() == 0
+    c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 10 ** 6)         # beyond what the per-table sort takes: the general sort
+    bo = c.s.new_bwd_out()
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0, bo)
+    assert c.s.sync_status() == 0
+    rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
+    assert bo.n_unique.cpu().tolist() == [ug.size, sg.size]
+    assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
     c.close()
 
 

@@ -212,6 +212,8 @@ def _full_size_sgd_step(wl, P, tabs=None):
     idx, off = smp.batch(0)
     max_L = max(int(b[0].numel()) for b in prof + [(idx, off)])
     sc.bind_buffers(wl.budget_bytes, max_L, wl.num_bags)
+    if wl.bag_lambda is None:      # as bench.py does: one index per bag, so a table gets `batch` lookups (up to 4096
+        sc.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, wl.batch)   # the backward pass then sorts per table in LDS)
     counts = np.zeros(wl.total_rows, dtype=np.uint32)
     sc.build_cache(None, None, 0, wl.budget_bytes, 0)
     for n, (pi, po) in enumerate(prof):

@@ -37,12 +37,15 @@ def _say(*a):
 # "/scan": the same case with the separate scan kernels of the compactions forced (by default so few tiles add up
 # their counts in the writing kernels)
 # "/presort": remap starts the backward pass's sort on the library's side stream
+# "/small": the caller states that no table gets more than 4096 lookups per batch, so the backward pass sorts each
+#           table's pairs in LDS (one workgroup per table)
 # "/apart": long runs and the other rows updated by two launches (by default they share one), and the backward
 #           pass's (row, bag) pairs built by the backward pass (by default remap writes them)
 VARIANTS = list(CASES) + ["tiny/apart", "multi_hot_small/apart", "dlrm_small/apart", "low_skew_bf16/apart",
                           "tiny/scan", "multi_hot_small/scan", "host_spill_small/scan", "low_skew_bf16/scan",
                           "tiny/presort", "multi_hot_small/presort", "host_spill_small/presort", "low_skew_bf16/presort",
-                          "dlrm_small/presort"]
+                          "dlrm_small/presort",
+                          "tiny/small", "dlrm_small/small", "host_spill_small/small", "low_skew_uniform_bf16/small"]
 
 
 @pytest.fixture(params=VARIANTS)
@@ -54,6 +57,11 @@ def case(request):
         c.s.set_tuning(binding.TUNE_FUSED_SCAN_MAX_TILES, 0)
     if variant == "presort":
         c.s.set_tuning(binding.TUNE_PRESORT, 1)
+    if variant == "small":
+        off = c.batch[1].numpy()
+        per_table = np.diff(off[:: c.wl.batch])
+        assert per_table.size == c.wl.num_tables and 0 < per_table.max() <= 4096
+        c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 4096)
     if variant == "apart":
         c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
         c.s.set_tuning(binding.TUNE_PAIRS_IN_REMAP, 0)

@@ -39,6 +39,26 @@ def test_kernel_timers_count_every_launch_of_a_step():
     c.close()
 
 
+def test_per_table_sort_replaces_the_radix_passes_when_the_caller_states_the_limit():
+    wl = synth.workload("dlrm_onehot", scale=0.004, batch=1500)
+    c = GpuCase(wl)
+    c.build()
+    s = c.s
+    d_idx, d_off = c.dev_batch()
+    grad = c.sampler.grads(0).to(c.dev)
+    s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, wl.batch)
+    s.profile_enable(True)
+    rm = s.remap(d_idx, d_off, wl.batch)
+    s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
+    prof = s.profile_read()
+    s.profile_enable(False)
+    assert prof["small_sort"]["launches"] == 1 and prof["small_place"]["launches"] == 1
+    assert not any(k.startswith("sort_") for k in prof), prof
+    assert s.sync_status() == 0
+    c.close()
+
+
 def test_calibration_kernels_and_copy_helper():
     dev = torch.device("cuda:0")
     src = torch.randint(0, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=dev)
