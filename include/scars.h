@@ -116,9 +116,10 @@ typedef struct {
  * 0: the fetch is a launch of its own on the library's second stream. */
 #define SCARS_TUNE_FUSED_FETCH 7                /* default 1 */
 /* Value n > 0: the caller states that in every batch each table gets at most n lookups (offsets[(t+1)*B] -
- * offsets[t*B] <= n; one index per sample and table with B <= n is the usual case).  For n <= 4096 the backward pass
- * then sorts each table's (row, bag) pairs by itself, one workgroup per table in LDS, in two launches instead of
- * three per radix pass; the results are the same.  A batch that breaks the statement latches SCARS_ERR_OFFSETS
+ * offsets[t*B] <= n; one index per sample and table with B <= n is the usual case).  For n <= 4096 (and up to 256
+ * tables) the backward pass then sorts each table's (row, bag) pairs by itself, one workgroup per table in LDS, and
+ * lists the run starts in a second launch: two launches instead of three per radix pass and two more; the results
+ * are the same.  A batch that breaks the statement latches SCARS_ERR_OFFSETS
  * (reported by scars_sync_status) and its backward results are unspecified (all accesses stay in bounds).
  * 0 (default): nothing is assumed. */
 #define SCARS_TUNE_MAX_TABLE_LOOKUPS 8

@@ -159,6 +159,137 @@ __global__ __launch_bounds__(kBlock) void k_seg_write(const uint32_t* __restrict
     }
 }
 
+// The same outputs for a batch whose tables were each sorted by a workgroup of their own (k_small_sort): table t's
+// sorted piece lies at the piece's own place in kin / vin, and the tables' numbers of valid pairs and of distinct rows
+// are known, so one workgroup per table can place its piece in the final order (valid pairs of all tables first, in
+// table order; invalid ones behind them) and list its run starts at once: no counting launch, no tile prefix.
+__global__ __launch_bounds__(kBlock) void k_small_segments(const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin,
+                                                           const int32_t* __restrict__ off, int64_t B, int32_t L, int T, int limit,
+                                                           const uint32_t* __restrict__ tab_valid,
+                                                           const uint32_t* __restrict__ tab_heads,
+                                                           uint32_t* __restrict__ kout, uint32_t* __restrict__ vout,
+                                                           int32_t* __restrict__ n_unique, int32_t* __restrict__ seg_start,
+                                                           int32_t* __restrict__ unique_gid, int32_t* __restrict__ sorted_gid,
+                                                           int32_t* __restrict__ sorted_bag, int32_t* __restrict__ chunk_run,
+                                                           const int32_t* __restrict__ slot_of, uint32_t N,
+                                                           int32_t* __restrict__ unique_slot, uint32_t* __restrict__ first_bag,
+                                                           int64_t G, const int32_t* __restrict__ gid_of,
+                                                           const int32_t* __restrict__ loc_of, int32_t k, int staged, int shift,
+                                                           int via_loc) {
+    constexpr int R = kSmallSortCap / kBlock;
+    constexpr int kW = kBlock / kWave;
+    __shared__ uint32_t s_red[kW][5];
+    __shared__ uint32_t s_a[kW];
+    const int t = blockIdx.x, w = wave_id(), lane = lane_id();
+    // over the tables: valid pairs and distinct rows before this table and in all, invalid pairs before this table
+    uint32_t acc[5] = {0u, 0u, 0u, 0u, 0u};
+    for (int i = threadIdx.x; i < T; i += kBlock) {
+        int32_t ai, ni;
+        bool oi;
+        small_piece(off, B, L, i, limit, &ai, &ni, &oi);
+        const uint32_t vi = min(tab_valid[i], (uint32_t)ni), hi = min(tab_heads[i], vi);
+        acc[1] += vi;
+        acc[4] += hi;
+        if (i < t) { acc[0] += vi; acc[2] += (uint32_t)ni - vi; acc[3] += hi; }
+    }
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        acc[j] = wave_sum(acc[j]);
+        if (lane == 0) s_red[w][j] = acc[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        acc[j] = 0;
+#pragma unroll
+        for (int ww = 0; ww < kW; ++ww) acc[j] += s_red[ww][j];
+    }
+    const uint32_t base = acc[0], valid_all = acc[1], tail = acc[1] + acc[2], heads_before = acc[3], heads_all = acc[4];
+    int32_t a, n;
+    bool over;
+    small_piece(off, B, L, t, limit, &a, &n, &over);
+    const uint32_t nv = min(tab_valid[t], (uint32_t)n);
+    const uint32_t sat = (1u << shift) - 1u;
+    const int rounds = (n + kBlock - 1) / kBlock;           // the piece dealt out as in k_small_sort
+    const int per_wave = rounds * kWave;
+    bool hd[R];
+    uint32_t kk[R], vv[R];
+    uint32_t nh = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int q = w * per_wave + r * kWave + lane;
+        const bool in = r < rounds && q < n;
+        kk[r] = in ? kin[a + q] : 0xFFFFFFFFu;
+        vv[r] = in ? vin[a + q] : 0u;
+        hd[r] = in && (uint32_t)q < nv && kk[r] != 0xFFFFFFFFu && (q == 0 || kin[a + q - 1] != kk[r]);
+        nh += (uint32_t)__popcll(ballot64(hd[r]));
+    }
+    if (lane == 0) s_a[w] = nh;
+    // where the update finds each run's row: the two stages of k_seg_write
+    int32_t src[R], p0[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool h = hd[r] && kk[r] < N;
+        const uint32_t bag = vv[r] >> shift;
+        const bool placed = h && (int64_t)bag < G && (vv[r] & sat) < sat && (via_loc || staged);
+        p0[r] = placed ? off[bag] : -1;
+        src[r] = (h && !(placed && via_loc)) ? slot_of[kk[r]] : -1;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (hd[r] && p0[r] >= 0 && (via_loc || src[r] < 0)) {
+            const int64_t p = (int64_t)p0[r] + (vv[r] & sat);
+            if (p < L) {
+                const int32_t l = loc_of[p];
+                if (via_loc) {
+                    src[r] = (l < k || staged) ? l : -1;
+                } else if ((uint32_t)gid_of[p] == kk[r] && l >= k) {
+                    src[r] = l;
+                }
+            } else if (via_loc) {
+                src[r] = slot_of[kk[r]];
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t before = heads_before;
+    for (int ww = 0; ww < w; ++ww) before += s_a[ww];
+    const uint64_t le = lane == 63 ? ~0ull : ((1ull << (lane + 1)) - 1ull);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r >= rounds) continue;                            // (the same for every lane of the workgroup)
+        const int q = w * per_wave + r * kWave + lane;
+        const bool in = q < n;
+        const uint64_t m = ballot64(hd[r]);
+        const uint32_t j = (uint32_t)q < nv ? base + (uint32_t)q : tail + ((uint32_t)q - nv);   // final position
+        if (in) {
+            kout[j] = kk[r];
+            vout[j] = vv[r];
+            if (sorted_gid) {
+                sorted_gid[j] = (int32_t)kk[r];
+                sorted_bag[j] = (int32_t)(vv[r] >> shift);
+            }
+            // a chunk of kLongRunMin positions remembers which run its first position is in
+            if (j % kLongRunMin == 0)
+                chunk_run[j / kLongRunMin] = (uint32_t)q < nv ? (int32_t)(before + (uint32_t)__popcll(m & le)) - 1
+                                                              : (int32_t)heads_all - 1;
+        }
+        if (hd[r]) {
+            const uint32_t u = before + (uint32_t)rank_below(m);
+            seg_start[u] = (int32_t)j;
+            unique_gid[u] = (int32_t)kk[r];
+            unique_slot[u] = src[r];
+            first_bag[u] = vv[r] >> shift;
+        }
+        before += (uint32_t)__popcll(m);
+    }
+    if (t == T - 1 && threadIdx.x == 0) {
+        seg_start[heads_all] = (int32_t)valid_all;
+        n_unique[0] = (int32_t)heads_all;
+        n_unique[1] = (int32_t)valid_all;
+    }
+}
+
 // ---- (4)/(5) segment reduce and update --------------------------------------------------------------------
 struct UpdateArgs {
     const Meta* meta;
@@ -549,9 +680,22 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
     int res = 0;
     // the caller has stated that no table gets more than a few thousand lookups: each table's piece is sorted in LDS
-    const bool small = h->table_lookups_limit > 0 && h->table_lookups_limit <= kSmallSortCap;
-    hipError_t e = small ? launch_small_sort_pairs(h, s, ws.key_buf, ws.val_buf, off, L, B, (int)h->table_lookups_limit)
-                         : launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
+    // (the tables' counts take 2 T words of the sort's count matrix, which has kSortMaxBins at least)
+    const bool small = h->table_lookups_limit > 0 && h->table_lookups_limit <= kSmallSortCap && 2 * h->T <= kSortMaxBins;
+    if (small) {
+        const int limit = (int)h->table_lookups_limit;
+        hipError_t e = launch_small_sort(h, s, ws.key_buf, ws.val_buf, off, L, B, limit);
+        if (e != hipSuccess) return e;
+        *res_out = 0;
+        Timed t(h, s, "small_segments");
+        hipLaunchKernelGGL(k_small_segments, dim3(h->T), dim3(kBlock), 0, s, ws.key_buf[1], ws.val_buf[1], off, B, (int32_t)L,
+                           h->T, limit, ws.sort_hist, ws.sort_hist + h->T, ws.key_buf[0], ws.val_buf[0], n_unique, seg_start,
+                           unique_gid, out ? out->sorted_gid : nullptr, out ? out->sorted_bag : nullptr, ws.chunk_run,
+                           h->buf.slot_of, (uint32_t)h->N, ws.unique_slot, ws.first_bag, G, rm->gid, rm->loc, (int32_t)h->k,
+                           staged ? 1 : 0, bag_shift_host(G), L <= kSegViaLocMaxL ? 1 : 0);
+        return hipGetLastError();
+    }
+    hipError_t e = launch_radix_sort_pairs(h, s, ws.key_buf, ws.val_buf, L, nullptr, bits, &res);
     if (e != hipSuccess) return e;
     *res_out = res;
     const uint32_t* key = ws.key_buf[res];

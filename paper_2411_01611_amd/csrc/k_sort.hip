@@ -285,26 +285,19 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
 // a few thousand samples is the case), a workgroup per table does all the passes of its piece in LDS, on keys made
 // table-local (a table of a thousand rows takes two passes, not three), in one launch instead of three per pass.
 // Invalid lookups (key 0xFFFFFFFF) come last in the whole array, as in the general sort: the workgroups write their
-// sorted pieces in place and the number of valid pairs of each; a second launch moves the pieces to where the counts
-// of the tables before them put them (every piece stays where it is when no lookup is invalid).
+// sorted pieces in place and each piece's numbers of valid pairs and of distinct rows; the launch that lists the run
+// starts (k_small_segments) moves the pieces to where the counts of the tables before them put them (every piece
+// stays where it is when no lookup is invalid).
 constexpr int kSmallRounds = 16;
 constexpr int kSmallCap = kBlock * kSmallRounds;   // 4096 pairs per table
 static_assert(kSmallCap == kSmallSortCap, "the host picks the path by kSmallSortCap");
-
-__device__ __forceinline__ void small_piece(const int32_t* __restrict__ off, int64_t B, int32_t L, int t, int limit,
-                                            int32_t* a_out, int32_t* n_out, bool* over) {
-    const int32_t a = min(max(off[(int64_t)t * B], 0), L);
-    const int32_t b = min(max(off[(int64_t)(t + 1) * B], a), L);
-    *over = b - a > limit;
-    *a_out = a;
-    *n_out = min(b - a, min(limit, kSmallCap));
-}
 
 __global__ __launch_bounds__(kBlock) void k_small_sort(const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin,
                                                        const int32_t* __restrict__ off, int64_t B, int32_t L,
                                                        const Meta* __restrict__ meta, int limit,
                                                        uint32_t* __restrict__ kout, uint32_t* __restrict__ vout,
-                                                       uint32_t* __restrict__ tab_valid, int32_t* __restrict__ status) {
+                                                       uint32_t* __restrict__ tab_valid, uint32_t* __restrict__ tab_heads,
+                                                       int32_t* __restrict__ status) {
     constexpr int R = kSmallRounds, kTile = kSmallCap;
     __shared__ __align__(8) uint32_t s_pairs[2 * kTile];   // the ordered piece; during ranking, the lane sets per wave and digit
     uint32_t* const s_key = s_pairs;
@@ -413,70 +406,32 @@ __global__ __launch_bounds__(kBlock) void k_small_sort(const uint32_t* __restric
             __syncthreads();
         }
     }
-    uint32_t nv = 0;
+    uint32_t nv = 0, nh = 0;     // valid pairs; distinct rows among them
     for (int q = tid; q < n; q += kBlock) {
         const uint32_t k = s_key[q];
         const bool ok = k != 0xFFFFFFFFu;
         kout[a + q] = ok ? k + rbase : k;
         vout[a + q] = s_val[q];
         nv += ok ? 1u : 0u;
+        nh += (ok && (q == 0 || s_key[q - 1] != k)) ? 1u : 0u;
     }
     nv = wave_sum(nv);
-    if (lane == 0) s_scan[w] = nv;
+    nh = wave_sum(nh);
+    if (lane == 0) { s_scan[w] = nv; s_scan[4 + w] = nh; }
     __syncthreads();
-    if (tid == 0) tab_valid[t] = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
-}
-
-// Second launch: table t's sorted piece goes from its own place to the place the valid counts of the tables before it
-// give it; its invalid pairs go behind all valid pairs, tables in order.
-__global__ __launch_bounds__(kBlock) void k_small_place(const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin,
-                                                        const int32_t* __restrict__ off, int64_t B, int32_t L, int T, int limit,
-                                                        const uint32_t* __restrict__ tab_valid,
-                                                        uint32_t* __restrict__ kout, uint32_t* __restrict__ vout) {
-    __shared__ uint32_t s_red[kWaves][3];
-    const int t = blockIdx.x;
-    uint32_t valid_before = 0, valid_all = 0, invalid_before = 0;
-    for (int i = threadIdx.x; i < T; i += kBlock) {
-        int32_t ai, ni;
-        bool oi;
-        small_piece(off, B, L, i, limit, &ai, &ni, &oi);
-        const uint32_t vi = min(tab_valid[i], (uint32_t)ni);
-        valid_all += vi;
-        if (i < t) { valid_before += vi; invalid_before += (uint32_t)ni - vi; }
-    }
-    valid_before = wave_sum(valid_before);
-    valid_all = wave_sum(valid_all);
-    invalid_before = wave_sum(invalid_before);
-    if (lane_id() == 0) { s_red[wave_id()][0] = valid_before; s_red[wave_id()][1] = valid_all; s_red[wave_id()][2] = invalid_before; }
-    __syncthreads();
-    uint32_t s_base[3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) s_base[j] = s_red[0][j] + s_red[1][j] + s_red[2][j] + s_red[3][j];
-    int32_t a, n;
-    bool over;
-    small_piece(off, B, L, t, limit, &a, &n, &over);
-    const uint32_t nv = min(tab_valid[t], (uint32_t)n);
-    const uint32_t base = s_base[0], tail = s_base[1] + s_base[2];
-    for (int q = threadIdx.x; q < n; q += kBlock) {
-        const uint32_t dst = (uint32_t)q < nv ? base + (uint32_t)q : tail + ((uint32_t)q - nv);
-        kout[dst] = kin[a + q];
-        vout[dst] = vin[a + q];
+    if (tid == 0) {
+        tab_valid[t] = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
+        tab_heads[t] = s_scan[4] + s_scan[5] + s_scan[6] + s_scan[7];
     }
 }
 
-// The pairs are in key[0] / val[0] (position order) and end up sorted there; key[1] / val[1] are used in between.
-hipError_t launch_small_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                                   int64_t L, int64_t B, int limit) {
-    {
-        Timed t(h, s, "small_sort");
-        hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, key[0], val[0], off, B, (int32_t)L, h->ws.meta, limit,
-                           key[1], val[1], h->ws.sort_hist, h->ws.status);
-    }
-    {
-        Timed t(h, s, "small_place");
-        hipLaunchKernelGGL(k_small_place, dim3(h->T), dim3(kBlock), 0, s, key[1], val[1], off, B, (int32_t)L, h->T, limit,
-                           h->ws.sort_hist, key[0], val[0]);
-    }
+// The pairs are in key[0] / val[0] (position order); each table's sorted piece is left at the piece's own place in
+// key[1] / val[1], the tables' counts of valid pairs and of distinct rows in the first 2 T words of the sort's count matrix.
+hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
+                             int64_t L, int64_t B, int limit) {
+    Timed t(h, s, "small_sort");
+    hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, key[0], val[0], off, B, (int32_t)L, h->ws.meta, limit,
+                       key[1], val[1], h->ws.sort_hist, h->ws.sort_hist + h->T, h->ws.status);
     return hipGetLastError();
 }
 

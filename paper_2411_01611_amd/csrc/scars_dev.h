@@ -173,6 +173,17 @@ __device__ __forceinline__ void bag_pairs(int64_t block, const int32_t* __restri
     }
 }
 
+// The piece of a table-major batch that belongs to table t: positions [*a_out, *a_out + *n_out), clamped so that it
+// stays inside the batch and within what the per-table sort takes; *over: more lookups than the caller stated.
+__device__ __forceinline__ void small_piece(const int32_t* __restrict__ off, int64_t B, int32_t L, int t, int limit,
+                                            int32_t* a_out, int32_t* n_out, bool* over) {
+    const int32_t a = min(max(off[(int64_t)t * B], 0), L);
+    const int32_t b = min(max(off[(int64_t)(t + 1) * B], a), L);
+    *over = b - a > limit;
+    *a_out = a;
+    *n_out = min(b - a, min(limit, kSmallSortCap));
+}
+
 // Rows of the pinned host tables -> a staging area in HBM, `lpr` lanes per row (lane gl holds 16-byte piece gl of the
 // `chunks` pieces of a row), kStageUnroll rows in flight per lane group.  list[0 .. min(*d_count, cap_rows)) names the
 // rows (global row ids); row j goes to staging row j.  `flags` (may be null: every row): only rows whose flag equals

@@ -182,10 +182,11 @@ Workspace carve(const scars_handle* h, void* base, int64_t k_cap, int64_t max_L,
 hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], int64_t n,
                                    const int32_t* d_n /*device-side pair count bounded by n, or null*/, int bits,
                                    int* result_buffer /*0 or 1: which buffer holds the result*/);
-// k_sort.hip: the same result for a batch whose tables each hold at most `limit` (<= kSmallSortCap) of the L pairs
-// (positions [off[t*B], off[(t+1)*B]) belong to table t): one workgroup per table sorts in LDS, two launches in all
-hipError_t launch_small_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                                   int64_t L, int64_t B, int limit);
+// k_sort.hip: for a batch whose tables each hold at most `limit` (<= kSmallSortCap) of the L pairs (positions
+// [off[t*B], off[(t+1)*B]) belong to table t): one workgroup per table sorts its piece in LDS, from key[0] / val[0]
+// into the same positions of key[1] / val[1]; per-table counts go to ws.sort_hist (valid pairs [T], distinct rows [T])
+hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
+                             int64_t L, int64_t B, int limit);
 // k_build_cache.hip
 hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
 hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,

@@ -53,8 +53,8 @@ def test_per_table_sort_replaces_the_radix_passes_when_the_caller_states_the_lim
     s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
     prof = s.profile_read()
     s.profile_enable(False)
-    assert prof["small_sort"]["launches"] == 1 and prof["small_place"]["launches"] == 1
-    assert not any(k.startswith("sort_") for k in prof), prof
+    assert prof["small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1
+    assert not any(k.startswith("sort_") or k in ("seg_count", "seg_scan", "seg_write") for k in prof), prof
     assert s.sync_status() == 0
     c.close()
 
