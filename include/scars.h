@@ -119,7 +119,9 @@ typedef struct {
  * offsets[t*B] <= n; one index per sample and table with B <= n is the usual case).  For n <= 4096 (and up to 256
  * tables) the backward pass then sorts each table's (row, bag) pairs by itself, one workgroup per table in LDS, and
  * lists the run starts in a second launch: two launches instead of three per radix pass and two more; the results
- * are the same.  A batch that breaks the statement latches SCARS_ERR_OFFSETS
+ * are the same.  When scars_remap has left the batch's pairs for the backward pass (SCARS_TUNE_PAIRS_IN_REMAP) and
+ * rows can be cold, scars_embedding_bag_fwd of the same batch carries the sort in the first workgroups of the launch
+ * that fetches the missed rows, and scars_embedding_bag_bwd_update finds it done if it is the next call that sorts.  A batch that breaks the statement latches SCARS_ERR_OFFSETS
  * (reported by scars_sync_status) and its backward results are unspecified (all accesses stay in bounds).
  * 0 (default): nothing is assumed. */
 #define SCARS_TUNE_MAX_TABLE_LOOKUPS 8
@@ -133,6 +135,7 @@ typedef struct {
  * overlapped): a sign that the library's stream shares a hardware queue with the caller's. */
 #define SCARS_COUNTER_AHEAD_TIMED 3
 #define SCARS_COUNTER_AHEAD_NOT_OVERLAPPED 4
+#define SCARS_COUNTER_SORTED_IN_FWD_USED 5 /* bwd_update calls whose per-table sort (SCARS_TUNE_MAX_TABLE_LOOKUPS) the forward pass had done */
 int64_t scars_get_counter(const scars_handle* h, int32_t which);
 int32_t scars_set_tuning(scars_handle* h, int32_t which, int64_t value);
 

@@ -151,6 +151,7 @@ COUNTER_PREPARED_USED = 1
 COUNTER_AHEAD_USED = 2
 COUNTER_AHEAD_TIMED = 3
 COUNTER_AHEAD_NOT_OVERLAPPED = 4
+COUNTER_SORTED_IN_FWD_USED = 5
 
 
 def calibration_read(src: torch.Tensor, sink: torch.Tensor) -> None:

@@ -670,7 +670,12 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     // the remap of this batch may have left the pairs in the first sort buffer; the sort below uses them up
     const bool have_pairs = h->pairs_valid && h->pairs_gid == rm->gid && h->pairs_off == off && h->pairs_L == L && h->pairs_B == B;
     h->pairs_valid = false;
-    if (!have_pairs) {
+    // ... and its forward pass may already have sorted each table's piece (beside the fetch of the missed rows)
+    const bool small = h->small_sort_applies();
+    const bool pieces_sorted = small && h->small_sorted && h->small_gid == rm->gid && h->small_off == off &&
+                               h->small_L == L && h->small_B == B;
+    h->small_sorted = false;
+    if (!have_pairs && !pieces_sorted) {
         Timed t(h, s, "bwd_pairs");
         const int lpb = pairs_lanes_per_bag(L, G);
         hipLaunchKernelGGL(k_bwd_pairs, dim3((unsigned)div_up(G * lpb, kBlock)), dim3(kBlock), 0, s, rm->gid, off,
@@ -680,12 +685,14 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     while (bits < 32 && ((int64_t)1 << bits) <= h->N) ++bits;   // 2^bits - 1 >= N: the sentinel stays the largest key
     int res = 0;
     // the caller has stated that no table gets more than a few thousand lookups: each table's piece is sorted in LDS
-    // (the tables' counts take 2 T words of the sort's count matrix, which has kSortMaxBins at least)
-    const bool small = h->table_lookups_limit > 0 && h->table_lookups_limit <= kSmallSortCap && 2 * h->T <= kSortMaxBins;
     if (small) {
         const int limit = (int)h->table_lookups_limit;
-        hipError_t e = launch_small_sort(h, s, ws.key_buf, ws.val_buf, off, L, B, limit);
-        if (e != hipSuccess) return e;
+        if (!pieces_sorted) {
+            hipError_t e = launch_small_sort(h, s, ws.key_buf, ws.val_buf, off, L, B);
+            if (e != hipSuccess) return e;
+        } else {
+            ++h->n_small_sorted_used;
+        }
         *res_out = 0;
         Timed t(h, s, "small_segments");
         hipLaunchKernelGGL(k_small_segments, dim3(h->T), dim3(kBlock), 0, s, ws.key_buf[1], ws.val_buf[1], off, B, (int32_t)L,
@@ -740,6 +747,7 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
                           h->presort_off == off && h->presort_L == L && h->presort_B == B && !out &&
                           h->presort_staged == use_staged;
     h->presort_valid = false;
+    if (prepared || L == 0) h->small_sorted = false;   // (otherwise launch_bwd_segments below takes it or drops it)
     if (L == 0) {
         Timed t(h, s, "bwd_empty");
         hipLaunchKernelGGL(k_bwd_empty, dim3(1), dim3(kWave), 0, s, n_unique, seg_start);

@@ -24,6 +24,18 @@ __global__ __launch_bounds__(kBlock) void k_stage_misses(const Meta* __restrict_
     stage_rows_body((int)blockIdx.x, (int)gridDim.x, meta, s_rbase, S);
 }
 
+// The same launch with, in its first T workgroups, the per-table sort of the batch's (row, bag) pairs that its backward
+// pass will need (small batches of a caller who has stated the lookups per table): the sort reads what remap wrote and
+// nothing of the fetch, and takes about as long as the fetch of a small batch's missed rows takes on the host link.
+__global__ __launch_bounds__(kBlock) void k_stage_misses_sort(const Meta* __restrict__ meta, StageArgs S, int T, SmallSortArgs Q) {
+    if ((int)blockIdx.x < T) {
+        small_sort_body((int)blockIdx.x, meta, Q);
+    } else {
+        __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
+        stage_rows_body((int)blockIdx.x - T, (int)gridDim.x - T, meta, s_rbase, S);
+    }
+}
+
 // Fetching the NEXT batch's missed rows while the current batch's backward pass runs: a row may be fetched now unless
 // that pass writes it.  Its distinct rows `excl[0..n_excl)` are sorted, so a binary search tells; this kernel only
 // sets the flags (it touches no host memory, so it is not slowed by the link), k_stage_misses then fetches the
@@ -366,8 +378,13 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         pool(h->pool_stream, 1, "pool_short");
         if ((e = hipEventRecord(h->ev_pool_join, h->pool_stream)) != hipSuccess) return e;
     }
+    // remap left this batch's (row, bag) pairs for the backward pass, and the caller has stated how many lookups a
+    // table gets at most: each table's piece is sorted in the first workgroups of the fetch's launch
+    const bool sort_here = L > 0 && h->k < h->N && h->small_sort_applies() && h->pairs_valid && h->pairs_gid == rm->gid &&
+                           h->pairs_off == off && h->pairs_L == L && h->pairs_B == B;
+    h->small_sorted = false;
     if (L > 0 && h->k < h->N) {   // with every row cached there can be no miss
-        Timed t(h, s, "stage_misses");
+        Timed t(h, s, sort_here ? "stage_misses+small_sort" : "stage_misses");
         const int gpb = kBlock / lpr;
         // 128 workgroups hold far more than the host link needs in flight (128 x 256 lanes x 4 x 16 bytes = 2 MB) and
         // leave half the compute units, and most wave slots, to work on other streams while this kernel waits on the
@@ -379,7 +396,14 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         const int32_t* count = rm->unique_miss_gid ? rm->n_unique_miss : rm->n_hit_miss + 1;
         const StageArgs S{list, count, (u32x4*)staging, chunks, lpr, h->buf.max_L,
                           ahead ? h->ws.fetched : (const uint8_t*)nullptr, 0};
-        hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, h->ws.meta, S);
+        if (sort_here) {
+            hipLaunchKernelGGL(k_stage_misses_sort, dim3(grid + h->T), dim3(kBlock), 0, s, h->ws.meta, S, h->T,
+                               small_sort_args(h, h->ws.key_buf, h->ws.val_buf, off, L, B));
+            h->small_sorted = true;
+            h->small_gid = rm->gid; h->small_off = off; h->small_L = L; h->small_B = B;
+        } else {
+            hipLaunchKernelGGL(k_stage_misses, dim3(grid), dim3(kBlock), 0, s, h->ws.meta, S);
+        }
     }
     if (G > 0) pool(s, split ? 2 : 0, split ? "pool_short_staged" : (mode == 2 ? "pool_short" : (mode == 1 ? "pool_wave" : "pool_group")));
     if (split) {   // the output is complete, in the caller's stream order, when this call returns

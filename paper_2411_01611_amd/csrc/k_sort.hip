@@ -281,157 +281,25 @@ __global__ __launch_bounds__(kBlock) void k_sort_scatter(const uint32_t* __restr
 // ---- small batches: one workgroup sorts one table's pairs entirely in LDS ------------------------------------------
 // A batch is table-major, so the pairs of table t sit at positions [offsets[t*B], offsets[(t+1)*B]) and their keys lie
 // in the table's own range of row ids: sorting each table's piece by itself sorts the whole array.  When the caller
-// has stated that no table gets more than kSmallCap lookups per batch (one index per sample and table with a batch of
+// has stated that no table gets more than kSmallSortCap lookups per batch (one index per sample and table with a batch of
 // a few thousand samples is the case), a workgroup per table does all the passes of its piece in LDS, on keys made
 // table-local (a table of a thousand rows takes two passes, not three), in one launch instead of three per pass.
 // Invalid lookups (key 0xFFFFFFFF) come last in the whole array, as in the general sort: the workgroups write their
 // sorted pieces in place and each piece's numbers of valid pairs and of distinct rows; the launch that lists the run
 // starts (k_small_segments) moves the pieces to where the counts of the tables before them put them (every piece
 // stays where it is when no lookup is invalid).
-constexpr int kSmallRounds = 16;
-constexpr int kSmallCap = kBlock * kSmallRounds;   // 4096 pairs per table
-static_assert(kSmallCap == kSmallSortCap, "the host picks the path by kSmallSortCap");
+static_assert(kSmallSortCap % kBlock == 0, "a table's piece is dealt out in whole rounds of the workgroup");
 
-__global__ __launch_bounds__(kBlock) void k_small_sort(const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin,
-                                                       const int32_t* __restrict__ off, int64_t B, int32_t L,
-                                                       const Meta* __restrict__ meta, int limit,
-                                                       uint32_t* __restrict__ kout, uint32_t* __restrict__ vout,
-                                                       uint32_t* __restrict__ tab_valid, uint32_t* __restrict__ tab_heads,
-                                                       int32_t* __restrict__ status) {
-    constexpr int R = kSmallRounds, kTile = kSmallCap;
-    __shared__ __align__(8) uint32_t s_pairs[2 * kTile];   // the ordered piece; during ranking, the lane sets per wave and digit
-    uint32_t* const s_key = s_pairs;
-    uint32_t* const s_val = s_pairs + kTile;
-    __shared__ uint32_t s_wh[kWaves * kMaxBins];
-    __shared__ uint32_t s_dstart[kMaxBins];
-    __shared__ uint32_t s_scan[8];
-    const int t = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    int32_t a, n;
-    bool over;
-    small_piece(off, B, L, t, limit, &a, &n, &over);
-    if (over && tid == 0) latch_error(status, SCARS_ERR_OFFSETS);   // more lookups in a table than the caller stated
-    // the piece is dealt out evenly: wave w owns positions [w * per_wave, (w + 1) * per_wave) in `rounds` rounds of 64
-    const int rounds = (n + kBlock - 1) / kBlock;            // <= R
-    const int per_wave = rounds * kWave;
-    const uint32_t rbase = (uint32_t)meta->row_base[t];
-    const uint32_t rows = (uint32_t)meta->row_base[t + 1] - rbase;
-    int bits = 1;
-    while (bits < 32 && (1u << bits) <= rows) ++bits;      // 2^bits - 1 >= rows: the key of an invalid lookup stays the largest
-    const int passes = (bits + 8) / 9;
-    const int dbits = (bits + passes - 1) / passes;
-    const int bins = 1 << dbits;
-    const uint32_t mask = (uint32_t)bins - 1u;
-
-    uint32_t key[R], val[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int p = w * per_wave + r * kWave + lane;
-        const bool valid = r < rounds && p < n;
-        const uint32_t k = valid ? kin[a + p] : 0xFFFFFFFFu;
-        key[r] = k == 0xFFFFFFFFu ? k : k - rbase;
-        val[r] = valid ? vin[a + p] : 0u;
-    }
-    uint32_t* wh = s_wh + w * kMaxBins;
-    unsigned long long* const mk = (unsigned long long*)s_pairs + w * kMaxBins;
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = pass * dbits;
-        for (int i = tid; i < kWaves * kMaxBins; i += kBlock) s_wh[i] = 0;
-        for (int i = tid; i < 2 * kWaves * kMaxBins; i += kBlock) s_pairs[i] = 0;
-        __syncthreads();
-        // stable rank of every pair among its wave's pairs of the same digit (as in k_sort_scatter)
-        uint32_t loc[R], old[R];
-        int lead[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            loc[r] = old[r] = 0u;
-            lead[r] = 0;
-            if (r >= rounds) continue;                       // (the same for every lane of the workgroup)
-            const int p = w * per_wave + r * kWave + lane;
-            const bool valid = p < n;
-            const uint32_t d = (key[r] >> shift) & mask;
-            if (valid) atomicOr(&mk[d], 1ull << lane);
-            __builtin_amdgcn_wave_barrier();
-            const uint64_t m = valid ? *(volatile unsigned long long*)&mk[d] : (1ull << lane);
-            __builtin_amdgcn_wave_barrier();
-            const int rk = rank_below(m);
-            lead[r] = __ffsll((unsigned long long)m) - 1;
-            loc[r] = (uint32_t)rk;
-            old[r] = 0u;
-            if (valid && rk == 0) {
-                *(volatile unsigned long long*)&mk[d] = 0ull;
-                old[r] = atomicAdd(&wh[d], (uint32_t)__popcll(m));
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) loc[r] += __shfl(old[r], lead[r], kWave);
-        __syncthreads();
-        {   // per digit: wave counts -> exclusive wave bases; the piece's count of the digit -> its first position
-            uint32_t carry = 0;
-            for (int base = 0; base < bins; base += kBlock) {
-                const int d = base + tid;
-                uint32_t run = 0;
-                if (d < bins) {
-#pragma unroll
-                    for (int ww = 0; ww < kWaves; ++ww) {
-                        const uint32_t c = s_wh[ww * kMaxBins + d];
-                        s_wh[ww * kMaxBins + d] = run;
-                        run += c;
-                    }
-                }
-                uint32_t total;
-                const uint32_t ex = block_exclusive_scan(run, s_scan, &total);
-                if (d < bins) s_dstart[d] = carry + ex;
-                carry += total;
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int p = w * per_wave + r * kWave + lane;
-            if (r < rounds && p < n) {
-                const uint32_t d = (key[r] >> shift) & mask;
-                const uint32_t q = s_dstart[d] + s_wh[w * kMaxBins + d] + loc[r];
-                s_key[q] = key[r];
-                s_val[q] = val[r];
-            }
-        }
-        __syncthreads();
-        if (pass + 1 < passes) {   // the ordered piece back into registers, in position order, for the next digit
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int p = w * per_wave + r * kWave + lane;
-                if (r < rounds && p < n) { key[r] = s_key[p]; val[r] = s_val[p]; }
-            }
-            __syncthreads();
-        }
-    }
-    uint32_t nv = 0, nh = 0;     // valid pairs; distinct rows among them
-    for (int q = tid; q < n; q += kBlock) {
-        const uint32_t k = s_key[q];
-        const bool ok = k != 0xFFFFFFFFu;
-        kout[a + q] = ok ? k + rbase : k;
-        vout[a + q] = s_val[q];
-        nv += ok ? 1u : 0u;
-        nh += (ok && (q == 0 || s_key[q - 1] != k)) ? 1u : 0u;
-    }
-    nv = wave_sum(nv);
-    nh = wave_sum(nh);
-    if (lane == 0) { s_scan[w] = nv; s_scan[4 + w] = nh; }
-    __syncthreads();
-    if (tid == 0) {
-        tab_valid[t] = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
-        tab_heads[t] = s_scan[4] + s_scan[5] + s_scan[6] + s_scan[7];
-    }
+__global__ __launch_bounds__(kBlock) void k_small_sort(const Meta* __restrict__ meta, SmallSortArgs S) {
+    small_sort_body((int)blockIdx.x, meta, S);
 }
 
 // The pairs are in key[0] / val[0] (position order); each table's sorted piece is left at the piece's own place in
 // key[1] / val[1], the tables' counts of valid pairs and of distinct rows in the first 2 T words of the sort's count matrix.
 hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                             int64_t L, int64_t B, int limit) {
+                             int64_t L, int64_t B) {
     Timed t(h, s, "small_sort");
-    hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, key[0], val[0], off, B, (int32_t)L, h->ws.meta, limit,
-                       key[1], val[1], h->ws.sort_hist, h->ws.sort_hist + h->T, h->ws.status);
+    hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, h->ws.meta, small_sort_args(h, key, val, off, L, B));
     return hipGetLastError();
 }
 

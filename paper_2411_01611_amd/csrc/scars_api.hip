@@ -218,6 +218,7 @@ int64_t scars_get_counter(const scars_handle* h, int32_t which) {
         case SCARS_COUNTER_AHEAD_USED: return h->n_ahead_used;
         case SCARS_COUNTER_AHEAD_TIMED: return h->n_ahead_timed;
         case SCARS_COUNTER_AHEAD_NOT_OVERLAPPED: return h->n_ahead_serial;
+        case SCARS_COUNTER_SORTED_IN_FWD_USED: return h->n_small_sorted_used;
         default: return -1;
     }
 }
@@ -291,6 +292,7 @@ int32_t scars_bind_buffers(scars_handle* h, const scars_buffers* b, void* stream
     h->side_pending = false;
     h->presort_valid = false;
     h->pairs_valid = false;
+    h->small_sorted = false;
     h->buf = *b;
     h->k_cap = k;
     h->ws = carve(h, b->workspace, k, b->max_L, b->max_G);
@@ -344,6 +346,7 @@ int32_t scars_build_cache(scars_handle* h, const int32_t* d_indices, const int32
     if (e == hipSuccess) e = pf_join(h, s);
     if (e != hipSuccess) return hip_fail(h, e, "build_cache(join)");
     h->presort_valid = false;
+    h->small_sorted = false;    // (the selection sorts in the same buffers)
     if (accumulate != 2 && h->built && h->dirty) {   // keep updated hot rows before they lose their slots
         e = launch_flush(h, s);
         if (e != hipSuccess) return hip_fail(h, e, "build_cache(flush)");
@@ -386,6 +389,7 @@ static int32_t remap_prologue(scars_handle* h, const int32_t* d_indices, const i
     if (rc) return rc;
     if (!h->built) return fail(h, SCARS_ERR_NOT_BUILT, std::string(who) + ": build_cache has not selected a hot set");
     if ((rc = check_remap_out(h, out, L, who))) return rc;
+    h->small_sorted = false;   // pieces a forward pass sorted belong to an earlier remap
     for (int a = 0; a < 2; ++a)
         if (out->loc == h->stg[a].loc) h->stg[a].valid = false;   // these arrays no longer describe a staged batch
     hipError_t e = hipSuccess;

@@ -184,6 +184,166 @@ __device__ __forceinline__ void small_piece(const int32_t* __restrict__ off, int
     *n_out = min(b - a, min(limit, kSmallSortCap));
 }
 
+struct SmallSortArgs {
+    const uint32_t *kin, *vin;      // the batch's (row, value) pairs in position order
+    const int32_t* off;
+    int64_t B;
+    int32_t L;
+    int limit;                      // lookups per table the caller stated (<= kSmallSortCap)
+    uint32_t *kout, *vout;          // each table's sorted piece, at the piece's own positions
+    uint32_t *tab_valid, *tab_heads;   // [T] each: the piece's valid pairs and distinct rows
+    int32_t* status;
+};
+
+inline SmallSortArgs small_sort_args(const scars_handle* h, uint32_t* const key[2], uint32_t* const val[2], const int32_t* off,
+                                     int64_t L, int64_t B) {
+    // (the tables' counts take 2 T words of the sort's count matrix, which has kSortMaxBins at least)
+    return SmallSortArgs{key[0], val[0], off, B, (int32_t)L, (int)h->table_lookups_limit, key[1], val[1],
+                         h->ws.sort_hist, h->ws.sort_hist + h->T, h->ws.status};
+}
+
+// Table t's piece, by the calling workgroup (every thread must call).
+__device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ meta, const SmallSortArgs& S) {
+    constexpr int R = kSmallSortCap / kBlock, kTile = kSmallSortCap;
+    constexpr int kMaxBins = kSortMaxBins, kWaves = kBlock / kWave;
+    const uint32_t* __restrict__ kin = S.kin;
+    const uint32_t* __restrict__ vin = S.vin;
+    const int32_t* __restrict__ off = S.off;
+    const int64_t B = S.B;
+    const int32_t L = S.L;
+    const int limit = S.limit;
+    uint32_t* __restrict__ kout = S.kout;
+    uint32_t* __restrict__ vout = S.vout;
+    uint32_t* __restrict__ tab_valid = S.tab_valid;
+    uint32_t* __restrict__ tab_heads = S.tab_heads;
+    int32_t* __restrict__ status = S.status;
+    __shared__ __align__(8) uint32_t s_pairs[2 * kTile];   // the ordered piece; during ranking, the lane sets per wave and digit
+    uint32_t* const s_key = s_pairs;
+    uint32_t* const s_val = s_pairs + kTile;
+    __shared__ uint32_t s_wh[kWaves * kMaxBins];
+    __shared__ uint32_t s_dstart[kMaxBins];
+    __shared__ uint32_t s_scan[8];
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    int32_t a, n;
+    bool over;
+    small_piece(off, B, L, t, limit, &a, &n, &over);
+    if (over && tid == 0) latch_error(status, SCARS_ERR_OFFSETS);   // more lookups in a table than the caller stated
+    // the piece is dealt out evenly: wave w owns positions [w * per_wave, (w + 1) * per_wave) in `rounds` rounds of 64
+    const int rounds = (n + kBlock - 1) / kBlock;            // <= R
+    const int per_wave = rounds * kWave;
+    const uint32_t rbase = (uint32_t)meta->row_base[t];
+    const uint32_t rows = (uint32_t)meta->row_base[t + 1] - rbase;
+    int bits = 1;
+    while (bits < 32 && (1u << bits) <= rows) ++bits;      // 2^bits - 1 >= rows: the key of an invalid lookup stays the largest
+    const int passes = (bits + 8) / 9;
+    const int dbits = (bits + passes - 1) / passes;
+    const int bins = 1 << dbits;
+    const uint32_t mask = (uint32_t)bins - 1u;
+
+    uint32_t key[R], val[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int p = w * per_wave + r * kWave + lane;
+        const bool valid = r < rounds && p < n;
+        const uint32_t k = valid ? kin[a + p] : 0xFFFFFFFFu;
+        key[r] = k == 0xFFFFFFFFu ? k : k - rbase;
+        val[r] = valid ? vin[a + p] : 0u;
+    }
+    uint32_t* wh = s_wh + w * kMaxBins;
+    unsigned long long* const mk = (unsigned long long*)s_pairs + w * kMaxBins;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = pass * dbits;
+        for (int i = tid; i < kWaves * kMaxBins; i += kBlock) s_wh[i] = 0;
+        for (int i = tid; i < 2 * kWaves * kMaxBins; i += kBlock) s_pairs[i] = 0;
+        __syncthreads();
+        // stable rank of every pair among its wave's pairs of the same digit (as in k_sort_scatter; the word of a digit is
+        // read and cleared with atomic accesses: the wave's LDS operations on it are carried out in program order)
+        uint32_t loc[R], old[R];
+        int lead[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            loc[r] = old[r] = 0u;
+            lead[r] = 0;
+            if (r >= rounds) continue;                       // (the same for every lane of the workgroup)
+            const int p = w * per_wave + r * kWave + lane;
+            const bool valid = p < n;
+            const uint32_t d = (key[r] >> shift) & mask;
+            if (valid) atomicOr(&mk[d], 1ull << lane);
+            __builtin_amdgcn_wave_barrier();
+            const uint64_t m = valid ? __hip_atomic_load(&mk[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : (1ull << lane);
+            __builtin_amdgcn_wave_barrier();
+            const int rk = rank_below(m);
+            lead[r] = __ffsll((unsigned long long)m) - 1;
+            loc[r] = (uint32_t)rk;
+            old[r] = 0u;
+            if (valid && rk == 0) {
+                __hip_atomic_store(&mk[d], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                old[r] = atomicAdd(&wh[d], (uint32_t)__popcll(m));
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) loc[r] += __shfl(old[r], lead[r], kWave);
+        __syncthreads();
+        {   // per digit: wave counts -> exclusive wave bases; the piece's count of the digit -> its first position
+            uint32_t carry = 0;
+            for (int base = 0; base < bins; base += kBlock) {
+                const int d = base + tid;
+                uint32_t run = 0;
+                if (d < bins) {
+#pragma unroll
+                    for (int ww = 0; ww < kWaves; ++ww) {
+                        const uint32_t c = s_wh[ww * kMaxBins + d];
+                        s_wh[ww * kMaxBins + d] = run;
+                        run += c;
+                    }
+                }
+                uint32_t total;
+                const uint32_t ex = block_exclusive_scan(run, s_scan, &total);
+                if (d < bins) s_dstart[d] = carry + ex;
+                carry += total;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int p = w * per_wave + r * kWave + lane;
+            if (r < rounds && p < n) {
+                const uint32_t d = (key[r] >> shift) & mask;
+                const uint32_t q = s_dstart[d] + s_wh[w * kMaxBins + d] + loc[r];
+                s_key[q] = key[r];
+                s_val[q] = val[r];
+            }
+        }
+        __syncthreads();
+        if (pass + 1 < passes) {   // the ordered piece back into registers, in position order, for the next digit
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int p = w * per_wave + r * kWave + lane;
+                if (r < rounds && p < n) { key[r] = s_key[p]; val[r] = s_val[p]; }
+            }
+            __syncthreads();
+        }
+    }
+    uint32_t nv = 0, nh = 0;     // valid pairs; distinct rows among them
+    for (int q = tid; q < n; q += kBlock) {
+        const uint32_t k = s_key[q];
+        const bool ok = k != 0xFFFFFFFFu;
+        kout[a + q] = ok ? k + rbase : k;
+        vout[a + q] = s_val[q];
+        nv += ok ? 1u : 0u;
+        nh += (ok && (q == 0 || s_key[q - 1] != k)) ? 1u : 0u;
+    }
+    nv = wave_sum(nv);
+    nh = wave_sum(nh);
+    if (lane == 0) { s_scan[w] = nv; s_scan[4 + w] = nh; }
+    __syncthreads();
+    if (tid == 0) {
+        tab_valid[t] = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
+        tab_heads[t] = s_scan[4] + s_scan[5] + s_scan[6] + s_scan[7];
+    }
+}
+
 // Rows of the pinned host tables -> a staging area in HBM, `lpr` lanes per row (lane gl holds 16-byte piece gl of the
 // `chunks` pieces of a row), kStageUnroll rows in flight per lane group.  list[0 .. min(*d_count, cap_rows)) names the
 // rows (global row ids); row j goes to staging row j.  `flags` (may be null: every row): only rows whose flag equals

@@ -150,6 +150,13 @@ struct scars_handle {
     int64_t update_max_blocks = 0;       // workgroups of the per-row update kernel (it strides over the rows); 0 = by case
     bool pairs_in_remap = true;          // scars_remap also writes the backward pass's (gid, bag) pairs
     int64_t table_lookups_limit = 0;     // > 0: the caller states that no table gets more lookups than this in a batch
+    // the forward pass of this batch has already sorted each table's pairs (in the launch that fetches the missed rows):
+    int64_t n_small_sorted_used = 0;     // backward passes that found their pieces sorted by the forward pass
+    bool small_sorted = false;
+    const int32_t *small_gid = nullptr, *small_off = nullptr;
+    int64_t small_L = 0, small_B = 0;
+    // whether the per-table sort applies to this handle at all
+    bool small_sort_applies() const { return table_lookups_limit > 0 && table_lookups_limit <= scars::kSmallSortCap && 2 * T <= scars::kSortMaxBins; }
     int fused_scan_max_tiles = 4096;     // compaction: up to this many tiles the writer sums the tile counts itself
     int64_t fused_long_max_L = ((int64_t)1 << 31) - 1;   // backward: up to this many lookups long runs and rows share one launch
     // per-kernel timing
@@ -186,7 +193,7 @@ hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key
 // [off[t*B], off[(t+1)*B]) belong to table t): one workgroup per table sorts its piece in LDS, from key[0] / val[0]
 // into the same positions of key[1] / val[1]; per-table counts go to ws.sort_hist (valid pairs [T], distinct rows [T])
 hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                             int64_t L, int64_t B, int limit);
+                             int64_t L, int64_t B);
 // k_build_cache.hip
 hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
 hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,

@@ -235,9 +235,17 @@ def test_more_lookups_in_a_table_than_stated_is_latched_and_stays_in_bounds():
     grad = c.sampler.grads(0).to(c.dev)
     c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 100)
     rm = c.s.remap(d_idx, d_off, wl.batch)
-    c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
-    assert c.s.sync_status() == 0                                   # remap and the forward pass do not depend on it
-    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
+    assert c.s.sync_status() == 0                                   # remap does not depend on it
+    out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    # the fetch's launch carried the per-table sort, which found the statement broken; the pooled sums are not affected
+    assert c.s.sync_status() == binding.ERR_OFFSETS
+    rc, want = oracle.embedding_bag_fwd(wl.rows, c.ora_tables, c.batch[0].numpy(), c.batch[1].numpy(), wl.batch)
+    assert rc == 0
+    assert_close(out.cpu().numpy(), want, "forward pass beside a refused sort")
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)      # in bounds, results unspecified
+    c.s.sync_status()
+    rm = c.s.remap(d_idx, d_off, wl.batch)
+    c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)      # this one sorts for itself
     assert c.s.sync_status() == binding.ERR_OFFSETS
     assert c.s.sync_status() == 0
     c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 10 ** 6)         # beyond what the per-table sort takes: the general sort

@@ -52,9 +52,18 @@ def test_per_table_sort_replaces_the_radix_passes_when_the_caller_states_the_lim
     s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
     s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
     prof = s.profile_read()
+    # remap wrote the pairs, rows can be cold: the forward pass's fetch carried the sort, the backward pass found it done
+    assert prof["stage_misses+small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1
+    assert "small_sort" not in prof and "stage_misses" not in prof
+    assert not any(k.startswith("sort_") or k in ("seg_count", "seg_scan", "seg_write", "bwd_pairs") for k in prof), prof
+    assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 1
+    # a backward pass that does not follow its own forward pass sorts for itself
+    rm = s.remap(d_idx, d_off, wl.batch)
+    s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
+    prof = s.profile_read()
+    assert prof["small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1 and "bwd_pairs" not in prof
+    assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 1
     s.profile_enable(False)
-    assert prof["small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1
-    assert not any(k.startswith("sort_") or k in ("seg_count", "seg_scan", "seg_write") for k in prof), prof
     assert s.sync_status() == 0
     c.close()
 
