@@ -34,6 +34,9 @@ def main(seed: int = 0) -> float:
 
     budget = 400 * D * 4                                  # room for 400 rows on the device
     s.bind_buffers(budget, max_L=T * B * 5, max_G=T * B)  # allocates what scars_query_sizes asks for and binds it
+    # optional: bags hold at most 5 lookups here, so no table gets more than 5 B per batch; stated, the backward pass
+    # of so small a batch sorts each table's lookups in LDS instead of by radix passes over the whole batch
+    s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 5 * B)
     p_idx, p_off = batch()
     s.build_cache(p_idx, p_off, B, budget)                # histogram of the profile stream, top-k, cache fill
 
@@ -78,6 +81,7 @@ def lookahead_loop(seed: int = 1, steps: int = 4) -> float:
     base = np.concatenate([[0], np.cumsum(rows)])[:-1]
     s = binding.Scars(rows, D, binding.DTYPE_F32, [t.ptr for t in tables], binding.OPT_SGD)
     s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
+    s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, 4 * B)    # (bags of at most 4 lookups: see main)
 
     def batch():
         lens = rng.integers(0, 5, T * B)
