@@ -49,14 +49,18 @@ def test_graph_replay_of_remap_and_forward_matches_eager():
     c.close()
 
 
-@pytest.mark.parametrize("presort,name", [(0, "multi_hot"), (1, "multi_hot"), (1, "host_spill")])
+@pytest.mark.parametrize("presort,name", [(0, "multi_hot"), (1, "multi_hot"), (1, "host_spill"), (0, "host_spill/small")])
 def test_graph_replay_of_a_training_step_matches_oracle(presort, name):
     """presort: remap starts the backward sort on the library's side stream, which joins the capture and is joined
     back by bwd_update before the capture ends; with one index per bag the forward pass also pools the cached bags on
-    a stream of its own, forked and joined inside the call."""
+    a stream of its own, forked and joined inside the call.  "/small": the caller states the lookups per table, so the
+    forward pass's fetch launch carries the per-table sort and the backward pass finds it done, replay after replay."""
+    name, _, small = name.partition("/")
     wl = synth.workload("multi_hot", scale=0.004, batch=333) if name == "multi_hot" else synth.workload("host_spill", scale=0.0005, batch=3000)
     c = GpuCase(wl)
     c.s.set_tuning(binding.TUNE_PRESORT, presort)
+    if small:
+        c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, wl.batch)
     c.build()
     d_idx, d_off = c.dev_batch()
     idx, off = c.batch
@@ -88,6 +92,7 @@ def test_graph_replay_of_a_training_step_matches_oracle(presort, name):
     if opt:
         assert_close(c.pinned_state_rows(), np.concatenate(c.ora_state), "state after three replayed steps")
     assert c.s.get_counter(binding.COUNTER_PREPARED_USED) == presort     # decided once, at capture time
+    assert c.s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == (1 if small else 0)
     c.close()
 
 
