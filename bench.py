@@ -891,8 +891,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
 
     leg = run_leg(b, K, W, link, args.graph)
     ahead = None
-    if args.lookahead and not args.coalesce and budget < wl.total_rows * wl.row_bytes:
-        ahead = run_lookahead(b, K, W, leg, link)
+    if args.lookahead and not args.coalesce:     # (with every row cached there is nothing to fetch ahead, but the next
+        ahead = run_lookahead(b, K, W, leg, link)   #  batch's sort is still prepared beside this batch's update)
         log(name, "look-ahead order", {k: ahead[k] for k in ("value", "ms_per_step")})
     split = None
     if wl.bag_lambda is None and not args.coalesce and budget < wl.total_rows * wl.row_bytes:
@@ -908,11 +908,19 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         b.s.build_cache(None, None, 0, b.budget, 0)
         torch.cuda.synchronize()
         r = run_leg(b, K, W, link, args.graph)
-        resident = {"value": r["value"], "unit": "lookups/s", "ms_per_step": r["ms_per_step"],
+        # ... and in the look-ahead order: nothing to fetch, but the next batch's sort and run starts are prepared on
+        # the library's side stream while this batch's update (HBM-bound, several times as long) runs
+        ra = run_lookahead(b, K, W, r, link) if (args.lookahead and not args.coalesce) else None
+        best_r = ra if (ra is not None and ra["value"] > r["value"]) else r
+        resident = {"value": best_r["value"], "unit": "lookups/s", "ms_per_step": best_r["ms_per_step"],
+                    "order": best_r.get("order", "remap(e) -> embedding_bag_fwd(e) -> embedding_bag_bwd_update(e)"),
+                    "plain_order": {"value": r["value"], "ms_per_step": r["ms_per_step"]},
+                    "lookahead": ra and {"value": ra["value"], "ms_per_step": ra["ms_per_step"], "kernels": ra["kernels"]},
                     "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
                     "host_enqueue_ms_per_step": r["host_enqueue_ms_per_step"], "cached_rows": b.s.cache_rows(), "roofline": r["roofline"], "gather": r["gather"],
-                    "calls_alone_ms": r["calls_alone_ms"], "kernels": r["kernels"]}
-        log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step")})
+                    "calls_alone_ms": r["calls_alone_ms"], "kernels": r["kernels"],
+                    "note": "roofline, gather, kernels, median and min are the plain order's"}
+        log(name, "cache-resident leg", {k: resident[k] for k in ("value", "ms_per_step", "plain_order")})
 
     cpu = None
     b.s.flush_cache()           # host tables current again before the oracle reads them

@@ -108,7 +108,10 @@ typedef struct {
 #define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 65536; default 0: 8192 with every row cached, else 1024 (while rows are fetched ahead: 512 for rows of 512 bytes or more, 4096 for rows of 128 bytes or less) */
 /* Non-zero: scars_remap may be called for the next batch before scars_embedding_bag_bwd_update of the current one (it
  * then leaves alone everything that update uses: it writes no pairs and starts no preparation), and
- * scars_embedding_bag_bwd_update_ahead is allowed.  The two batches need remap outputs of their own. */
+ * scars_embedding_bag_bwd_update_ahead is allowed:
+ * with SCARS_TUNE_PRESORT set, that call prepares the next batch's sorted segments on the library's side stream while
+ * its own update runs (also when every row is cached and there is nothing to fetch).  The two batches need remap
+ * outputs of their own. */
 #define SCARS_TUNE_LOOKAHEAD 6                  /* default 0 */
 /* Non-zero: scars_embedding_bag_bwd_update_ahead carries the fetch of the next batch's rows in the first workgroups
  * of its own update launch, on the caller's stream, whenever the update is one launch (see
