@@ -33,6 +33,11 @@ from paper_2411_01611_amd import binding, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 PRESORT_MIN_L = 1 << 17  # batches this large start the backward sort in remap, on the library's side stream
+# With every row cached the threshold gates one thing only, the look-ahead order's preparation of the next batch's sort
+# beside this batch's update.  That pays from about 64k lookups (one index per bag, 26 tables: 0.107 -> 0.085 - 0.093 ms
+# per step at 106k lookups; 0.077 - 0.089 against 0.082 - 0.084 at 53k, no clear gain; at 4k it costs 0.015 ms, the fork
+# and join of the side stream).
+PREPARE_MIN_L_CACHED = 1 << 16
 POOL_KERNELS = ("pool_wave", "pool_group", "pool_short")
 UPDATE_KERNELS = ("seg_rows_long+fetch_ahead", "seg_rows_long", "seg_rows")
 
@@ -532,7 +537,7 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
         alone["remap"] += (c1 - c0) * 1e3 / K
         alone["embedding_bag_fwd"] += (c2 - c1) * 1e3 / K
         alone["embedding_bag_bwd_update"] += (c3 - c2) * 1e3 / K
-    b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
+    b.s.set_tuning(binding.TUNE_PRESORT, b.presort_min_l if b.presort else 0)
     del sweep, sink
     # per-step spread: the same K steps once more, each between its own pair of events
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -801,6 +806,8 @@ def main():
     ap.add_argument("--fetch-on-own-stream", dest="fused_fetch", action="store_false",
                     help="look-ahead order: fetch the next batch's rows in a launch of its own on the library's second "
                          "stream instead of inside the update's launch")
+    ap.add_argument("--presort-min-l", type=int, default=PRESORT_MIN_L,
+                    help="smallest batch (lookups) whose backward sort is started on the library's side stream")
     ap.add_argument("--no-presort", dest="presort", action="store_false",
                     help="sort the backward pass's (row, bag) pairs inside bwd_update instead of starting that sort in "
                          "remap on the library's side stream, beside the forward pass")
@@ -873,8 +880,11 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
 
     b = Bench(wl, budget, pinned, args.coalesce)
     b.presort = bool(args.presort)
+    b.presort_min_l = args.presort_min_l
+    if budget >= wl.total_rows * wl.row_bytes:
+        b.presort_min_l = min(b.presort_min_l, PREPARE_MIN_L_CACHED)
     b.fused_fetch = bool(args.fused_fetch)
-    b.s.set_tuning(binding.TUNE_PRESORT, PRESORT_MIN_L if b.presort else 0)
+    b.s.set_tuning(binding.TUNE_PRESORT, b.presort_min_l if b.presort else 0)
     if args.fused_long_max_l >= 0:
         b.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, args.fused_long_max_l)
     if args.update_max_blocks > 0:
@@ -904,6 +914,8 @@ def run_workload(name: str, args, K: int, W: int, cal: dict, link: dict, with_cp
         b.s.flush_cache()
         torch.cuda.synchronize()
         b.budget = wl.total_rows * wl.row_bytes
+        b.presort_min_l = min(b.presort_min_l, PREPARE_MIN_L_CACHED)
+        b.s.set_tuning(binding.TUNE_PRESORT, b.presort_min_l if b.presort else 0)
         b.prepare(K + W)
         b.s.build_cache(None, None, 0, b.budget, 0)
         torch.cuda.synchronize()
