@@ -105,7 +105,7 @@ typedef struct {
  * value gives the same results).  While it writes cold rows it holds its compute units' memory queues full of host
  * requests, and kernels of other streams that share those units crawl; a few hundred workgroups still saturate the
  * host link and leave room for them. */
-#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 65536; default 0: 8192 with every row cached, else 1024 (while rows are fetched ahead: 512 for rows of 512 bytes or more, 4096 for rows of 128 bytes or less) */
+#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 65536; default 0: 8192 with every row cached, else 1024 (768 for rows of 512 bytes or more; while rows are fetched ahead 4096 for rows of 128 bytes or less) */
 /* Non-zero: scars_remap may be called for the next batch before scars_embedding_bag_bwd_update of the current one (it
  * then leaves alone everything that update uses: it writes no pairs and starts no preparation), and
  * scars_embedding_bag_bwd_update_ahead is allowed:

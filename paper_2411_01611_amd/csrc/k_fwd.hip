@@ -423,7 +423,9 @@ hipError_t launch_fetch_ahead(scars_handle* h, hipStream_t s, const scars_remap_
     const int gpb = kBlock / lpr;
     // (rows of 128 bytes need twice the workgroups to keep as many bytes in flight: 4.30 -> 4.10 ms per step on the
     // bf16 workload, together with more workgroups for the update beside it)
-    const int ahead_blocks = h->R <= 128 ? 2 * kAheadBlocks : kAheadBlocks;
+    // (rows of 512 bytes: 192 beside 768 workgroups of the update against 128 beside 512: 4.57 -> 4.54 ms per step with
+    // most of the batch's rows cold, 1.25 -> 1.23 with one row in five cold)
+    const int ahead_blocks = h->R <= 128 ? 2 * kAheadBlocks : (h->R >= 512 ? kAheadBlocks * 3 / 2 : kAheadBlocks);
     const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(next_L, (int64_t)gpb * kStageUnroll), ahead_blocks));
     {   // on the caller's stream, before the update kernel: beside that kernel it would crawl (see k_stage_misses)
         Timed t(h, s, "mark_ahead");
