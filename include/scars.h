@@ -105,7 +105,9 @@ typedef struct {
  * value gives the same results).  While it writes cold rows it holds its compute units' memory queues full of host
  * requests, and kernels of other streams that share those units crawl; a few hundred workgroups still saturate the
  * host link and leave room for them. */
-#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5          /* at most 65536; default 0: 8192 with every row cached, else 1024 (768 for rows of 512 bytes or more; while rows are fetched ahead 4096 for rows of 128 bytes or less) */
+/* At most 65536; default 0: 8192 with every row cached, else 1024 (768 for rows of 512 bytes or more; while rows are
+ * fetched ahead 4096 for rows of 128 bytes or less). */
+#define SCARS_TUNE_UPDATE_MAX_BLOCKS 5
 /* Non-zero: scars_remap may be called for the next batch before scars_embedding_bag_bwd_update of the current one (it
  * then leaves alone everything that update uses: it writes no pairs and starts no preparation), and
  * scars_embedding_bag_bwd_update_ahead is allowed:
@@ -124,8 +126,9 @@ typedef struct {
  * lists the run starts in a second launch: two launches instead of three per radix pass and two more; the results
  * are the same.  When scars_remap has left the batch's pairs for the backward pass (SCARS_TUNE_PAIRS_IN_REMAP) and
  * rows can be cold, scars_embedding_bag_fwd of the same batch carries the sort in the first workgroups of the launch
- * that fetches the missed rows, and scars_embedding_bag_bwd_update finds it done if it is the next call that sorts.  A batch that breaks the statement latches SCARS_ERR_OFFSETS
- * (reported by scars_sync_status) and its backward results are unspecified (all accesses stay in bounds).
+ * that fetches the missed rows, and scars_embedding_bag_bwd_update finds it done if it is the next call that sorts.
+ * A batch that breaks the statement latches SCARS_ERR_OFFSETS (reported by scars_sync_status) and its backward
+ * results are unspecified (all accesses stay in bounds).
  * 0 (default): nothing is assumed. */
 #define SCARS_TUNE_MAX_TABLE_LOOKUPS 8
 
