@@ -515,6 +515,66 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
     seg_long_body<LPG, kTaskUnroll>((int)blockIdx.x, (int)gridDim.x, key, val, n_unique, seg_start, chunk_run, grad, partial, D, Gm1, shift);
 }
 
+// Runs longer than kLongRun when none can be very long (the caller has stated how many lookups a table gets at most,
+// and a run lies inside one table): the workgroup of the chunk in which such a run starts sums the whole run, a piece
+// per lane group, adds the pieces in LDS in group order and applies the update.  No partial sums in memory and no
+// second launch, which is what counts for the small batches that statement is made for.  Any run length is summed
+// correctly; a long one only takes longer (its positions divided by the workgroup's lane groups, in sequence).
+// One workgroup per chunk; every branch below is taken by the whole workgroup.
+template <int DTYPE, int OPT, int LPG, int UNROLL>
+__device__ __forceinline__ void seg_whole_body(int ch, const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
+                                               const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
+                                               const int32_t* __restrict__ unique_slot, const int32_t* __restrict__ chunk_run,
+                                               const float* __restrict__ grad, const UpdateArgs& A) {
+    constexpr int gpb = kBlock / LPG;
+    __shared__ double s_sum[kBlock * 4];
+    const int32_t Lv = n_unique[1];
+    const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
+    if (ch >= nchunks) return;
+    const int32_t j0 = ch * kLongRun, j1 = min(j0 + kLongRun, Lv);
+    // a long run that starts exactly at the chunk's first position covers the chunk; otherwise one may start inside
+    // and run past the chunk's end: it then holds the next chunk's first position
+    const int32_t U = n_unique[0];
+    int32_t r = chunk_run[ch];
+    if (r < 0 || r >= U) return;             // (only after an offsets error: nothing is dereferenced through it)
+    int32_t a = seg_start[r], b = seg_start[r + 1];
+    if (a != j0 || b - a <= kLongRun) {
+        if (j1 >= Lv) return;
+        r = chunk_run[ch + 1];
+        if (r < 0 || r >= U) return;
+        a = seg_start[r];
+        b = seg_start[r + 1];
+        if (a <= j0 || a >= j1 || b - a <= kLongRun) return;
+    }
+    if (b > Lv) return;
+    const uint32_t gid = (uint32_t)unique_gid[r];
+    if (gid >= A.N) return;
+    const int c = threadIdx.x % LPG, g = threadIdx.x / LPG;
+    const int dq = A.D / 4;
+    const int cc = min(c, dq - 1);
+    RowRef<DTYPE, OPT> ref;
+    float wv[4] = {0.f, 0.f, 0.f, 0.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (g == 0) {   // the row and its accumulator come in while the gradient rows are summed
+        ref.locate(A, A.meta->row_base, A.meta->num_tables, (int32_t)gid, unique_slot[r]);
+        ref.load(cc, wv, sv);
+    }
+    const int32_t piece = (b - a + gpb - 1) / gpb;
+    const int32_t p0 = min(a + g * piece, b), p1 = min(p0 + piece, b);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    sum_grads<LPG, UNROLL>(val, (const float4*)grad, dq, c, p0, p1, A.Gm1, A.shift, acc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s_sum[(g * LPG + c) * 4 + i] = acc[i];
+    __syncthreads();
+    if (g == 0 && c < dq) {
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int q = 0; q < gpb; ++q) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] += s_sum[(q * LPG + c) * 4 + i];
+        }
+        ref.step_and_store(A, c, wv, sv, t);
+    }
+}
+
 // Both of the above in one launch: the first `long_blocks` workgroups take the chunks of long runs, the others the
 // rows.  The two parts touch disjoint rows and share nothing; together the shorter one's chain of dependent memory
 // round trips is hidden behind the other (a whole launch's worth of time for small batches).
@@ -524,7 +584,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
 // rows are copied from host memory into a staging area (rows this update writes are flagged out beforehand), so that
 // the host link's two directions work at once without depending on a second hardware queue.
 template <int DTYPE, int OPT, int LPG, int ULONG, bool FETCH>
-__global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int long_blocks, int rows_first,
+__global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int long_blocks, int rows_first, int whole_runs,
                                                           const uint32_t* __restrict__ key,
                                                           const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                                           const int32_t* __restrict__ seg_start,
@@ -546,7 +606,10 @@ __global__ __launch_bounds__(kBlock) void k_seg_rows_long(int fetch_blocks, int 
     const int rows_blocks = (int)gridDim.x - fetch_blocks - long_blocks;
     const int j = b - fetch_blocks;
     const bool is_long = rows_first ? j >= rows_blocks : j < long_blocks;
-    if (is_long) {
+    if (is_long && whole_runs) {   // (one workgroup per chunk: long_blocks is the number of chunks)
+        seg_whole_body<DTYPE, OPT, LPG, ULONG>(rows_first ? j - rows_blocks : j, val, n_unique, seg_start, unique_gid, unique_slot,
+                                               chunk_run, grad, A);
+    } else if (is_long) {
         seg_long_body<LPG, ULONG>(rows_first ? j - rows_blocks : j, long_blocks, key, val, n_unique, seg_start, chunk_run, grad,
                                   partial, A.D, A.Gm1, A.shift);
     } else {
@@ -623,19 +686,24 @@ static void launch_reduce_t(scars_handle* h, hipStream_t s, hipStream_t s2, cons
     // of a lane group)
     const int64_t max_blocks = h->update_max_blocks > 0 ? h->update_max_blocks : (h->ahead_active ? (h->R >= 512 ? 768 : (h->R <= 128 ? 4096 : 1024)) : (h->k < h->N ? (h->R >= 512 ? 768 : 1024) : 256 * 32));
     const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, gpb), max_blocks));
-    const int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
+    int chunk_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(div_up(L, kLongRun), gpb), 256 * 8));
     if (s2 == s && L <= h->fused_long_max_L) {
+        // no table gets more than a few thousand lookups, by the caller's statement: no run is longer than that, and
+        // the workgroup of the chunk a long run starts in sums all of it (no partial sums, no k_seg_combine)
+        const int whole_runs = h->small_sort_applies() ? 1 : 0;
+        if (whole_runs) chunk_blocks = (int)std::max<int64_t>(1, div_up(L, kLongRun));
         {
             Timed t(h, s, fetch_blocks > 0 ? "seg_rows_long+fetch_ahead" : "seg_rows_long");
             const dim3 grid(fetch_blocks + chunk_blocks + rows_blocks);
             const int rows_first = h->k < h->N ? 1 : 0;   // (rows can be cold)
 #define SCARS_RL(UL, FE)                                                                                                  \
-    hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, UL, FE>), grid, dim3(kBlock), 0, s, fetch_blocks, chunk_blocks, rows_first, key, \
+    hipLaunchKernelGGL((k_seg_rows_long<DTYPE, OPT, LPG, UL, FE>), grid, dim3(kBlock), 0, s, fetch_blocks, chunk_blocks, rows_first, whole_runs, key, \
                        val, nu, seg_start, unique_gid, ws.unique_slot, ws.first_bag, ws.chunk_run, grad, ws.partial, A, F)
             if (L <= kFusedWideMaxL) { if (fetch_blocks > 0) SCARS_RL(kTaskUnroll, true); else SCARS_RL(kTaskUnroll, false); }
             else { if (fetch_blocks > 0) SCARS_RL(kGradUnroll, true); else SCARS_RL(kGradUnroll, false); }
 #undef SCARS_RL
         }
+        if (whole_runs) return;
         Timed t(h, s, "seg_combine");
         hipLaunchKernelGGL((k_seg_combine<DTYPE, OPT, LPG>), dim3(chunk_blocks), dim3(kBlock), 0, s, key, nu, seg_start,
                            unique_gid, ws.unique_slot, ws.chunk_run, ws.partial, A);

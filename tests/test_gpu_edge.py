@@ -49,9 +49,22 @@ def _run_all(c, profile_with_batch=True):
 def test_long_segments(D, dtype, opt, one_launch):
     """Rows looked up thousands of times: runs far above the 64-lookup task size, spanning several sort tiles,
     for lane groups narrower than, equal to and wider than a wave, and a row width that is not a power of two."""
+    _long_segments_case(D, dtype, opt, one_launch, B=6000, budget_rows=100, table_limit=0)
+
+
+@pytest.mark.parametrize("D,dtype,opt", [(32, "f32", "sgd"), (24, "f32", "adagrad"), (256, "f32", "sgd"),
+                                         (512, "bf16", "sgd"), (64, "bf16", "adagrad")])
+@pytest.mark.parametrize("budget_rows", [100, 2, 0])
+def test_long_runs_when_the_caller_has_stated_the_lookups_per_table(D, dtype, opt, budget_rows):
+    """The same runs under SCARS_TUNE_MAX_TABLE_LOOKUPS: each long run is summed by the workgroup of the chunk it starts
+    in (no partial sums, no combining launch), with the long-run rows cached (100), mostly in host memory (2: only
+    the two longest are cached) and all in host memory (0)."""
+    _long_segments_case(D, dtype, opt, True, B=4000, budget_rows=budget_rows, table_limit=4000)
+
+
+def _long_segments_case(D, dtype, opt, one_launch, B, budget_rows, table_limit):
     rng = np.random.default_rng(3)
     rows = [50, 1000]
-    B = 6000
     idx0 = np.where(rng.random(B) < 0.7, 7, rng.integers(0, 50, B))        # 70 % of table 0 hits row 7
     idx1 = np.where(rng.random(B) < 0.3, 999, rng.integers(0, 1000, B))    # long run at the very end of key space
     idx1[:130] = 500                                                         # a run of just over two tasks
@@ -59,12 +72,20 @@ def test_long_segments(D, dtype, opt, one_launch):
     idx1[195:259] = 502                                                      # 64 lookups: the longest short run
     idx = np.concatenate([idx0, idx1]).astype(np.int32)
     off = np.arange(2 * B + 1, dtype=np.int32)
-    _say("D", D, dtype, opt, "one launch" if one_launch else "two launches")
-    c = _custom_case(rows, D, idx, off, B, budget_rows=100, optimizer=opt, dtype=dtype)
+    _say("D", D, dtype, opt, "one launch" if one_launch else "two launches", "B", B, "cached rows", budget_rows,
+         "table limit", table_limit)
+    c = _custom_case(rows, D, idx, off, B, budget_rows=budget_rows, optimizer=opt, dtype=dtype)
     if not one_launch:      # long runs and the other rows in launches of their own, as large batches do
         c.s.set_tuning(binding.TUNE_FUSED_LONG_MAX_L, 0)
+    if table_limit:
+        c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, table_limit)
+        c.s.profile_enable(True)
     rm, out, bo, grad = _run_all(c)
     assert c.s.sync_status() == 0
+    if table_limit:
+        prof = c.s.profile_read()
+        c.s.profile_enable(False)
+        assert "small_segments" in prof and "seg_rows_long" in prof and "seg_combine" not in prof, prof
     wl = c.wl
     rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
     assert_close(out.cpu().numpy(), want, "forward")

@@ -55,6 +55,7 @@ def test_per_table_sort_replaces_the_radix_passes_when_the_caller_states_the_lim
     # remap wrote the pairs, rows can be cold: the forward pass's fetch carried the sort, the backward pass found it done
     assert prof["stage_misses+small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1
     assert "small_sort" not in prof and "stage_misses" not in prof
+    assert prof["seg_rows_long"]["launches"] == 1 and "seg_combine" not in prof   # long runs summed whole, in that launch
     assert not any(k.startswith("sort_") or k in ("seg_count", "seg_scan", "seg_write", "bwd_pairs") for k in prof), prof
     assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 1
     # a backward pass that does not follow its own forward pass sorts for itself
