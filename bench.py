@@ -39,7 +39,7 @@ PRESORT_MIN_L = 1 << 17  # batches this large start the backward sort in remap, 
 # and join of the side stream).
 PREPARE_MIN_L_CACHED = 1 << 16
 POOL_KERNELS = ("pool_wave", "pool_group", "pool_short")
-UPDATE_KERNELS = ("seg_rows_long+fetch_ahead", "seg_rows_long", "seg_rows")
+UPDATE_KERNELS = ("seg_rows_long+fetch_ahead", "seg_rows_long", "seg_rows", "small_update")
 
 
 def log(*a):
@@ -303,6 +303,8 @@ def bytes_model(wl: synth.Workload, L: float, U: float, U_cold: float, n_miss: f
     upd_min = min(L, G) * D * 4 + 8 * L + U * (2 * R + st + 12)
     m = {n: {"alg": pool_alg, "min": pool_min} for n in POOL_KERNELS}
     m.update({n: {"alg": upd_alg, "min": upd_min} for n in UPDATE_KERNELS})
+    # the update by position reads a length and a source per position instead of the 12 bytes per run of a run list
+    m["small_update"] = {"alg": upd_alg + 8 * L - 12 * U, "min": upd_min + 8 * L - 12 * U}
     m.update({
         "stage_misses": {"alg": 2 * n_staged * R + 4 * n_staged, "min": 2 * n_staged * R + 4 * n_staged},   # link read + HBM write
         "remap_probe": {"alg": 16 * L, "min": 16 * L},

@@ -24,7 +24,6 @@ __global__ void k_bwd_empty(int32_t* __restrict__ n_unique, int32_t* __restrict_
 }
 
 // ---- (3) segment heads ----------------------------------------------------------------------------------
-constexpr int64_t kSegViaLocMaxL = 1 << 20;   // up to this many lookups a run's slot is taken from remap's per-lookup arrays
 constexpr int kPerWaveS = kScanTile / (kBlock / kWave);
 constexpr int kRoundsS = kPerWaveS / kWave;
 
@@ -521,13 +520,43 @@ __global__ __launch_bounds__(kBlock) void k_seg_long(const uint32_t* __restrict_
 // second launch, which is what counts for the small batches that statement is made for.  Any run length is summed
 // correctly; a long one only takes longer (its positions divided by the workgroup's lane groups, in sequence).
 // One workgroup per chunk; every branch below is taken by the whole workgroup.
+// The run [a, b) of row gid (found at `slot`, as RowRef::locate reads it), by the whole workgroup.
+template <int DTYPE, int OPT, int LPG, int UNROLL>
+__device__ __forceinline__ void whole_run_apply(int32_t a, int32_t b, uint32_t gid, int32_t slot, const uint32_t* __restrict__ val,
+                                                const float* __restrict__ grad, const UpdateArgs& A) {
+    constexpr int gpb = kBlock / LPG;
+    __shared__ double s_sum[kBlock * 4];
+    const int c = threadIdx.x % LPG, g = threadIdx.x / LPG;
+    const int dq = A.D / 4;
+    const int cc = min(c, dq - 1);
+    RowRef<DTYPE, OPT> ref;
+    float wv[4] = {0.f, 0.f, 0.f, 0.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (g == 0) {   // the row and its accumulator come in while the gradient rows are summed
+        ref.locate(A, A.meta->row_base, A.meta->num_tables, (int32_t)gid, slot);
+        ref.load(cc, wv, sv);
+    }
+    const int32_t piece = (b - a + gpb - 1) / gpb;
+    const int32_t p0 = min(a + g * piece, b), p1 = min(p0 + piece, b);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    sum_grads<LPG, UNROLL>(val, (const float4*)grad, dq, c, p0, p1, A.Gm1, A.shift, acc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s_sum[(g * LPG + c) * 4 + i] = acc[i];
+    __syncthreads();
+    if (g == 0 && c < dq) {
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int q = 0; q < gpb; ++q) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] += s_sum[(q * LPG + c) * 4 + i];
+        }
+        ref.step_and_store(A, c, wv, sv, t);
+    }
+}
+
 template <int DTYPE, int OPT, int LPG, int UNROLL>
 __device__ __forceinline__ void seg_whole_body(int ch, const uint32_t* __restrict__ val, const int32_t* __restrict__ n_unique,
                                                const int32_t* __restrict__ seg_start, const int32_t* __restrict__ unique_gid,
                                                const int32_t* __restrict__ unique_slot, const int32_t* __restrict__ chunk_run,
                                                const float* __restrict__ grad, const UpdateArgs& A) {
-    constexpr int gpb = kBlock / LPG;
-    __shared__ double s_sum[kBlock * 4];
     const int32_t Lv = n_unique[1];
     const int32_t nchunks = (Lv + kLongRun - 1) / kLongRun;
     if (ch >= nchunks) return;
@@ -549,29 +578,63 @@ __device__ __forceinline__ void seg_whole_body(int ch, const uint32_t* __restric
     if (b > Lv) return;
     const uint32_t gid = (uint32_t)unique_gid[r];
     if (gid >= A.N) return;
-    const int c = threadIdx.x % LPG, g = threadIdx.x / LPG;
-    const int dq = A.D / 4;
-    const int cc = min(c, dq - 1);
-    RowRef<DTYPE, OPT> ref;
-    float wv[4] = {0.f, 0.f, 0.f, 0.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (g == 0) {   // the row and its accumulator come in while the gradient rows are summed
-        ref.locate(A, A.meta->row_base, A.meta->num_tables, (int32_t)gid, unique_slot[r]);
-        ref.load(cc, wv, sv);
+    whole_run_apply<DTYPE, OPT, LPG, UNROLL>(a, b, gid, unique_slot[r], val, grad, A);
+}
+
+// ---- the update of a small batch by position ------------------------------------------------------------------------
+// After the per-table sort (small_sort_body with its run outputs) the update needs no list of runs: a lane group per
+// sorted position takes the run that starts there (run_len > 0), and the workgroup of a chunk of kLongRun positions
+// takes the long run that starts in the chunk, if any (at most one can: it is longer than the chunk).  Everything read
+// through run_len / run_src / key is range-checked first: positions that no table's piece covers (after an offsets
+// error) hold whatever an earlier batch left.  cap_staged: rows of the staging area.
+__device__ __forceinline__ bool run_ok(int64_t j, int32_t len, int32_t src, uint32_t gid, int32_t L, const UpdateArgs& A,
+                                       int64_t cap_staged) {
+    return len > 0 && j + len <= L && gid < A.N && (src == -1 || (src >= 0 && (int64_t)src < (int64_t)A.k + cap_staged));
+}
+
+template <int DTYPE, int OPT, int LPG>
+__global__ __launch_bounds__(kBlock) void k_small_update(int long_blocks, int32_t L, int64_t cap_staged,
+                                                         const uint32_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                                         const int32_t* __restrict__ run_len, const int32_t* __restrict__ run_src,
+                                                         const float* __restrict__ grad, UpdateArgs A) {
+    if ((int)blockIdx.x < long_blocks) {      // one workgroup per chunk
+        __shared__ int32_t s_j;
+        if (threadIdx.x == 0) s_j = -1;
+        __syncthreads();
+        const int64_t p = (int64_t)blockIdx.x * kLongRun + threadIdx.x;
+        if (threadIdx.x < kLongRun && p < L && run_len[p] > kLongRun) s_j = (int32_t)p;
+        __syncthreads();
+        const int32_t j = s_j;
+        if (j < 0) return;
+        const int32_t len = run_len[j], src = run_src[j];
+        const uint32_t gid = key[j];
+        if (len <= kLongRun || !run_ok(j, len, src, gid, L, A, cap_staged)) return;
+        whole_run_apply<DTYPE, OPT, LPG, kTaskUnroll>(j, j + len, gid, src, val, grad, A);
+        return;
     }
-    const int32_t piece = (b - a + gpb - 1) / gpb;
-    const int32_t p0 = min(a + g * piece, b), p1 = min(p0 + piece, b);
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    sum_grads<LPG, UNROLL>(val, (const float4*)grad, dq, c, p0, p1, A.Gm1, A.shift, acc);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s_sum[(g * LPG + c) * 4 + i] = acc[i];
+    __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
+    const int T = A.meta->num_tables;
+    for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = A.meta->row_base[t];
     __syncthreads();
-    if (g == 0 && c < dq) {
-        double t[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int q = 0; q < gpb; ++q) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] += s_sum[(q * LPG + c) * 4 + i];
-        }
-        ref.step_and_store(A, c, wv, sv, t);
+    const int c = threadIdx.x % LPG;
+    const int dq = A.D / 4;
+    const bool lane_on = c < dq;
+    const int cc = min(c, dq - 1);
+    const float4* g4 = (const float4*)grad;
+    const int64_t ngroups = (int64_t)((int)gridDim.x - long_blocks) * (kBlock / LPG);
+    for (int64_t j = (int64_t)((int)blockIdx.x - long_blocks) * (kBlock / LPG) + threadIdx.x / LPG; j < L; j += ngroups) {
+        const int32_t len = run_len[j], src = run_src[j];
+        const uint32_t gid = key[j];
+        const uint32_t bag0 = min(val[j] >> A.shift, A.Gm1);
+        if (len > kLongRun || !run_ok(j, len, src, gid, L, A, cap_staged)) continue;
+        RowRef<DTYPE, OPT> ref;
+        ref.locate(A, s_rbase, T, (int32_t)gid, src);
+        float wv[4], sv[4] = {0.f, 0.f, 0.f, 0.f};
+        ref.load(cc, wv, sv);
+        const float4 g0 = g4[(int64_t)bag0 * dq + cc];
+        double acc[4] = {(double)g0.x, (double)g0.y, (double)g0.z, (double)g0.w};
+        if (len > 1) sum_grads<LPG, kGradUnroll>(val, g4, dq, c, (int32_t)j + 1, (int32_t)j + len, A.Gm1, A.shift, acc);
+        if (lane_on) ref.step_and_store(A, c, wv, sv, acc);
     }
 }
 
@@ -738,11 +801,42 @@ static void launch_reduce_o(int lpg, scars_handle* h, hipStream_t s, hipStream_t
     }
 }
 
+template <int DTYPE, int OPT>
+static void launch_small_update_o(int lpg, scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val,
+                                  const float* grad, int64_t L, const UpdateArgs& A) {
+    Timed t(h, s, "small_update");
+    const int long_blocks = (int)div_up(L, kLongRun);
+    switch (lpg) {
+#define SCARS_CASE(N)                                                                                                      \
+    case N: {                                                                                                              \
+        const int rows_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(div_up(L, kBlock / N), 256 * 32));            \
+        hipLaunchKernelGGL((k_small_update<DTYPE, OPT, N>), dim3(long_blocks + rows_blocks), dim3(kBlock), 0, s, long_blocks, \
+                           (int32_t)L, h->buf.max_L, key, val, h->ws.seg_start, h->ws.unique_slot, grad, A);               \
+    } break;
+        SCARS_CASE(1) SCARS_CASE(2) SCARS_CASE(4) SCARS_CASE(8) SCARS_CASE(16) SCARS_CASE(32) SCARS_CASE(64)
+        SCARS_CASE(128)
+#undef SCARS_CASE
+    }
+}
+
+static void launch_small_update(scars_handle* h, hipStream_t s, const uint32_t* key, const uint32_t* val, const float* grad,
+                                int64_t L, const UpdateArgs& A) {
+    const int lpg = next_pow2_host(h->D / 4);
+    if (h->dtype == SCARS_DTYPE_F32) {
+        if (h->optimizer == SCARS_OPT_SGD) launch_small_update_o<SCARS_DTYPE_F32, SCARS_OPT_SGD>(lpg, h, s, key, val, grad, L, A);
+        else launch_small_update_o<SCARS_DTYPE_F32, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, grad, L, A);
+    } else {
+        if (h->optimizer == SCARS_OPT_SGD) launch_small_update_o<SCARS_DTYPE_BF16, SCARS_OPT_SGD>(lpg, h, s, key, val, grad, L, A);
+        else launch_small_update_o<SCARS_DTYPE_BF16, SCARS_OPT_ADAGRAD>(lpg, h, s, key, val, grad, L, A);
+    }
+}
+
 // Integer half of the backward pass: (gid, bag) pairs, their sort, the run starts.  It depends on the remap outputs
 // only, not on the gradient, so it may run on another stream while the forward pass runs.  `staged`: cold rows take
 // their current value from the staging area (the forward pass of the same batch fills it).
 hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
-                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out) {
+                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out,
+                               bool* by_position) {
     Workspace& ws = h->ws;
     int32_t* n_unique = out ? out->n_unique : ws.n_unique;
     int32_t* seg_start = out ? out->seg_start : ws.seg_start;
@@ -768,11 +862,20 @@ hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* of
     // the caller has stated that no table gets more than a few thousand lookups: each table's piece is sorted in LDS
     if (small) {
         const int limit = (int)h->table_lookups_limit;
+        // the caller of this function can update by position (no list of runs wanted): the sort leaves what that needs
+        bool runs = by_position != nullptr;
         if (!pieces_sorted) {
-            hipError_t e = launch_small_sort(h, s, ws.key_buf, ws.val_buf, off, L, B);
+            const SmallRunArgs run = small_run_args(h, rm, staged);
+            hipError_t e = launch_small_sort(h, s, ws.key_buf, ws.val_buf, off, L, B, runs ? &run : nullptr);
             if (e != hipSuccess) return e;
         } else {
             ++h->n_small_sorted_used;
+            runs = runs && h->small_runs && h->small_runs_staged == staged;
+        }
+        if (runs) {      // the sorted pieces stay where they are
+            *res_out = 1;
+            *by_position = true;
+            return hipGetLastError();
         }
         *res_out = 0;
         Timed t(h, s, "small_segments");
@@ -836,8 +939,12 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     }
     int res = h->presort_res;
     if (prepared) ++h->n_prepared_used;
+    bool by_position = false;
     if (!prepared) {
-        hipError_t e = launch_bwd_segments(h, s, off, L, B, rm, use_staged, out, &res);
+        // (a caller who wants the sorted segments, or the look-ahead order, whose fetch leaves out this batch's distinct
+        // rows, needs the list of runs)
+        const bool can_go_by_position = !out && !next_rm && !h->lookahead;
+        hipError_t e = launch_bwd_segments(h, s, off, L, B, rm, use_staged, out, &res, can_go_by_position ? &by_position : nullptr);
         if (e != hipSuccess) return e;
     }
     const uint32_t* key = ws.key_buf[res];
@@ -845,6 +952,13 @@ hipError_t launch_bwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
     UpdateArgs A{ws.meta, h->buf.slot_of, h->buf.cache, h->buf.state_cache, lr, eps, h->D,
                  use_staged ? ws.staging[area] : nullptr, (int32_t)h->k, (uint32_t)h->N,
                  (uint32_t)std::max<int64_t>(G - 1, 0), bag_shift_host(G)};
+    if (by_position) {
+        h->ahead_active = false;
+        const hipError_t e = pf_join(h, s);   // (a fetch still running beside an earlier update reads host rows)
+        if (e != hipSuccess) return e;
+        launch_small_update(h, s, key, val, grad, L, A);
+        return hipGetLastError();
+    }
     // Look-ahead.  (1) The integer half of the next batch's backward pass is prepared beside this update, on the side
     // stream and in the second set of segment arrays (this update still reads the first); the sets change places once
     // the update kernels are enqueued.  It is enqueued before the fetch: should the two library streams share a

@@ -397,8 +397,13 @@ hipError_t launch_fwd(scars_handle* h, hipStream_t s, const int32_t* off, int64_
         const StageArgs S{list, count, (u32x4*)staging, chunks, lpr, h->buf.max_L,
                           ahead ? h->ws.fetched : (const uint8_t*)nullptr, 0};
         if (sort_here) {
-            hipLaunchKernelGGL(k_stage_misses_sort, dim3(grid + h->T), dim3(kBlock), 0, s, h->ws.meta, S, h->T,
-                               small_sort_args(h, h->ws.key_buf, h->ws.val_buf, off, L, B));
+            SmallSortArgs Q = small_sort_args(h, h->ws.key_buf, h->ws.val_buf, off, L, B);
+            // ... and leave the runs for an update by position (cold rows from the staging area this launch fills);
+            // in the look-ahead order the update needs the list of the batch's distinct rows instead
+            h->small_runs = !h->lookahead;
+            h->small_runs_staged = true;
+            if (h->small_runs) Q.run = small_run_args(h, rm, true);
+            hipLaunchKernelGGL(k_stage_misses_sort, dim3(grid + h->T), dim3(kBlock), 0, s, h->ws.meta, S, h->T, Q);
             h->small_sorted = true;
             h->small_gid = rm->gid; h->small_off = off; h->small_L = L; h->small_B = B;
         } else {

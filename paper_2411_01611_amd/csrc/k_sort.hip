@@ -297,9 +297,11 @@ __global__ __launch_bounds__(kBlock) void k_small_sort(const Meta* __restrict__ 
 // The pairs are in key[0] / val[0] (position order); each table's sorted piece is left at the piece's own place in
 // key[1] / val[1], the tables' counts of valid pairs and of distinct rows in the first 2 T words of the sort's count matrix.
 hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                             int64_t L, int64_t B) {
+                             int64_t L, int64_t B, const SmallRunArgs* run) {
     Timed t(h, s, "small_sort");
-    hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, h->ws.meta, small_sort_args(h, key, val, off, L, B));
+    SmallSortArgs Q = small_sort_args(h, key, val, off, L, B);
+    if (run) Q.run = *run;
+    hipLaunchKernelGGL(k_small_sort, dim3(h->T), dim3(kBlock), 0, s, h->ws.meta, Q);
     return hipGetLastError();
 }
 

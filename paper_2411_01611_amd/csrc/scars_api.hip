@@ -147,7 +147,7 @@ hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int
     hipError_t e = side_fork(h, s);
     if (e != hipSuccess) return e;
     const bool staged = h->k < h->N;   // misses are possible: the forward pass stages them
-    e = launch_bwd_segments(h, h->side, off, L, B, rm, staged, nullptr, &h->presort_res);
+    e = launch_bwd_segments(h, h->side, off, L, B, rm, staged, nullptr, &h->presort_res, nullptr);
     if (e == hipSuccess) e = hipEventRecord(h->ev_join, h->side);
     if (e != hipSuccess) return e;
     h->side_pending = true;

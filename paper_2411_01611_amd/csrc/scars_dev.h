@@ -184,6 +184,16 @@ __device__ __forceinline__ void small_piece(const int32_t* __restrict__ off, int
     *n_out = min(b - a, min(limit, kSmallSortCap));
 }
 
+// What the update of a small batch needs of its runs, written by the workgroup that sorted the table, at the position
+// of each run's first pair in the sorted pieces (run_len null: not wanted): the run's length (0 at every other
+// position of the batch) and where its row is found (cache slot, k + row of the staging area, or -1: host memory).
+struct SmallRunArgs {
+    int32_t *run_len, *run_src;     // [L] each
+    const int32_t* loc_of;          // remap's per-lookup locations: cache slot, or k + the lookup's place among the misses
+    int32_t k;
+    int staged;                     // the missed rows of this batch are in the staging area (else they are read from host memory)
+};
+
 struct SmallSortArgs {
     const uint32_t *kin, *vin;      // the batch's (row, value) pairs in position order
     const int32_t* off;
@@ -193,13 +203,19 @@ struct SmallSortArgs {
     uint32_t *kout, *vout;          // each table's sorted piece, at the piece's own positions
     uint32_t *tab_valid, *tab_heads;   // [T] each: the piece's valid pairs and distinct rows
     int32_t* status;
+    SmallRunArgs run;
 };
 
 inline SmallSortArgs small_sort_args(const scars_handle* h, uint32_t* const key[2], uint32_t* const val[2], const int32_t* off,
                                      int64_t L, int64_t B) {
     // (the tables' counts take 2 T words of the sort's count matrix, which has kSortMaxBins at least)
     return SmallSortArgs{key[0], val[0], off, B, (int32_t)L, (int)h->table_lookups_limit, key[1], val[1],
-                         h->ws.sort_hist, h->ws.sort_hist + h->T, h->ws.status};
+                         h->ws.sort_hist, h->ws.sort_hist + h->T, h->ws.status, SmallRunArgs{}};
+}
+
+// The run outputs go to the workspace's own run arrays: seg_start as the lengths, unique_slot as the sources.
+inline SmallRunArgs small_run_args(const scars_handle* h, const scars_remap_out* rm, bool staged) {
+    return SmallRunArgs{h->ws.seg_start, h->ws.unique_slot, rm->loc, (int32_t)h->k, staged ? 1 : 0};
 }
 
 // Table t's piece, by the calling workgroup (every thread must call).
@@ -223,6 +239,8 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
     __shared__ uint32_t s_wh[kWaves * kMaxBins];
     __shared__ uint32_t s_dstart[kMaxBins];
     __shared__ uint32_t s_scan[8];
+    __shared__ int32_t s_loc[kTile];      // with the run outputs: each pair's location, carried along with the pair
+    const bool want_runs = S.run.run_len != nullptr;      // (the same for the whole launch)
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     int32_t a, n;
     bool over;
@@ -241,6 +259,7 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
     const uint32_t mask = (uint32_t)bins - 1u;
 
     uint32_t key[R], val[R];
+    int32_t lc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = w * per_wave + r * kWave + lane;
@@ -248,6 +267,7 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
         const uint32_t k = valid ? kin[a + p] : 0xFFFFFFFFu;
         key[r] = k == 0xFFFFFFFFu ? k : k - rbase;
         val[r] = valid ? vin[a + p] : 0u;
+        lc[r] = (valid && want_runs) ? S.run.loc_of[a + p] : -1;     // (the pair at position a + p is lookup a + p)
     }
     uint32_t* wh = s_wh + w * kMaxBins;
     unsigned long long* const mk = (unsigned long long*)s_pairs + w * kMaxBins;
@@ -313,6 +333,7 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
                 const uint32_t q = s_dstart[d] + s_wh[w * kMaxBins + d] + loc[r];
                 s_key[q] = key[r];
                 s_val[q] = val[r];
+                if (want_runs) s_loc[q] = lc[r];
             }
         }
         __syncthreads();
@@ -320,7 +341,11 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int p = w * per_wave + r * kWave + lane;
-                if (r < rounds && p < n) { key[r] = s_key[p]; val[r] = s_val[p]; }
+                if (r < rounds && p < n) {
+                    key[r] = s_key[p];
+                    val[r] = s_val[p];
+                    if (want_runs) lc[r] = s_loc[p];
+                }
             }
             __syncthreads();
         }
@@ -342,6 +367,58 @@ __device__ __forceinline__ void small_sort_body(int t, const Meta* __restrict__ 
         tab_valid[t] = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
         tab_heads[t] = s_scan[4] + s_scan[5] + s_scan[6] + s_scan[7];
     }
+    if (!want_runs) return;
+    // The runs, for an update that goes by position (k_small_update): the ordered piece is still in LDS.  A run's row is
+    // found where remap found its first pair's lookup: in the cache, or (a miss) in that lookup's row of the staging area
+    // when the batch's missed rows are there, else in host memory.
+    const SmallRunArgs& Q = S.run;
+    // A run's length is the distance to the next run's first position: each thread looks at `per` consecutive positions,
+    // a scan across the threads numbers the runs, their first positions are listed in LDS (in place of the values, which
+    // are in vout by now), and each run reads its successor's.
+    const uint32_t nv_all = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
+    __syncthreads();                                   // (the scan below reuses s_scan)
+    uint32_t* const s_first = s_val;
+    const int per = (n + kBlock - 1) / kBlock;         // <= R
+    const int q0 = tid * per;
+    uint32_t heads = 0, cnt = 0;                       // bit i: position q0 + i starts a run
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int q = q0 + i;
+        if (i < per && q < n) {
+            const uint32_t k = s_key[q];
+            if (k != 0xFFFFFFFFu && (q == 0 || s_key[q - 1] != k)) { heads |= 1u << i; ++cnt; }
+        }
+    }
+    uint32_t total;
+    const uint32_t first_run = block_exclusive_scan(cnt, s_scan, &total);
+    {
+        uint32_t u = first_run;
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+            if (heads & (1u << i)) s_first[u++] = (uint32_t)(q0 + i);
+    }
+    __syncthreads();
+    {
+        uint32_t u = first_run;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int q = q0 + i;
+            if (i >= per || q >= n) continue;
+            int32_t len = 0, src = -1;
+            if (heads & (1u << i)) {
+                const uint32_t next = u + 1 < total ? s_first[u + 1] : nv_all;
+                ++u;
+                len = (int32_t)next - q;
+                const int32_t l = s_loc[q];
+                src = (l >= 0 && (l < Q.k || Q.staged)) ? l : -1;
+            }
+            Q.run_len[a + q] = len;
+            Q.run_src[a + q] = src;
+        }
+    }
+    // positions of this table that the sort did not take (more lookups than the caller stated) hold no run
+    const int32_t b_all = min(max(off[(int64_t)(t + 1) * B], a), L);
+    for (int32_t q = a + n + tid; q < b_all; q += kBlock) Q.run_len[q] = 0;
 }
 
 // Rows of the pinned host tables -> a staging area in HBM, `lpr` lanes per row (lane gl holds 16-byte piece gl of the

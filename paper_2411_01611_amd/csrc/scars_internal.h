@@ -23,6 +23,7 @@ constexpr int kSmallSortCap = 4096;   // pairs per table the one-workgroup-per-t
 constexpr int kSelBins = 2048;       // radix-select bins per pass (11 + 11 + 10 bits)
 constexpr int kPlanBins = 65536;      // count-of-counts bins of the budget chooser; larger counts go to a short list
 constexpr int kPlanBigCap = 4096;
+constexpr int64_t kSegViaLocMaxL = 1 << 20;   // up to this many lookups a run's slot is taken from remap's per-lookup arrays
 constexpr int kLongRunMin = 64;      // runs longer than this are cut into tasks of this many lookups
 constexpr int64_t kStaticRemapMaxL = SCARS_REMAP_STATIC_MAX_L;   // largest batch of scars_remap_static
 
@@ -153,6 +154,8 @@ struct scars_handle {
     // the forward pass of this batch has already sorted each table's pairs (in the launch that fetches the missed rows):
     int64_t n_small_sorted_used = 0;     // backward passes that found their pieces sorted by the forward pass
     bool small_sorted = false;
+    bool small_runs = false;             // ... and left each run's length and row source for an update by position,
+    bool small_runs_staged = false;      //     with cold rows read from the staging area that forward pass filled
     const int32_t *small_gid = nullptr, *small_off = nullptr;
     int64_t small_L = 0, small_B = 0;
     // whether the per-table sort applies to this handle at all
@@ -192,8 +195,10 @@ hipError_t launch_radix_sort_pairs(scars_handle* h, hipStream_t s, uint32_t* key
 // k_sort.hip: for a batch whose tables each hold at most `limit` (<= kSmallSortCap) of the L pairs (positions
 // [off[t*B], off[(t+1)*B]) belong to table t): one workgroup per table sorts its piece in LDS, from key[0] / val[0]
 // into the same positions of key[1] / val[1]; per-table counts go to ws.sort_hist (valid pairs [T], distinct rows [T])
+// `run` (may be null): also write each run's length and row source at its first position (see SmallRunArgs)
+struct SmallRunArgs;
 hipError_t launch_small_sort(scars_handle* h, hipStream_t s, uint32_t* key[2], uint32_t* val[2], const int32_t* off,
-                             int64_t L, int64_t B);
+                             int64_t L, int64_t B, const SmallRunArgs* run);
 // k_build_cache.hip
 hipError_t launch_fill_u32(scars_handle* h, hipStream_t s, uint32_t* p, int64_t n, uint32_t v);
 hipError_t launch_histogram(scars_handle* h, hipStream_t s, const int32_t* idx, const int32_t* off, int64_t L,
@@ -242,6 +247,8 @@ hipError_t pf_join(scars_handle* h, hipStream_t s);
 void swap_segment_sets(scars_handle* h);
 hipError_t start_presort(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B, const scars_remap_out* rm);
 hipError_t launch_bwd_segments(scars_handle* h, hipStream_t s, const int32_t* off, int64_t L, int64_t B,
-                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out);
+                               const scars_remap_out* rm, bool staged, const scars_bwd_out* out, int* res_out,
+                               bool* by_position /*null: the list of runs is wanted; else set when the per-table sort
+                                                   has left the runs by position instead (k_small_update)*/);
 
 }  // namespace scars

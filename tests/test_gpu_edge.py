@@ -25,8 +25,9 @@ def _custom_case(rows, D, idx, off, B, budget_rows, optimizer="sgd", dtype="f32"
     return c
 
 
-def _run_all(c, profile_with_batch=True):
-    """build (profile = the batch itself), remap, fwd, bwd on both sides; returns GPU outputs."""
+def _run_all(c, profile_with_batch=True, with_out=True):
+    """build (profile = the batch itself), remap, fwd, bwd on both sides; returns GPU outputs (with_out False: the
+    backward pass is not asked for its sorted segments, and bo is None)."""
     wl = c.wl
     idx, off = c.batch
     if profile_with_batch:
@@ -37,7 +38,7 @@ def _run_all(c, profile_with_batch=True):
     out = c.s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
     g = torch.Generator().manual_seed(5)
     grad = torch.randn(wl.num_bags, wl.dim, generator=g)
-    bo = c.s.new_bwd_out(max(idx.numel(), 1))
+    bo = c.s.new_bwd_out(max(idx.numel(), 1)) if with_out else None
     c.s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad.to(c.dev), 0.01, 1e-8, bo)
     c.s.flush_cache()
     return rm, out, bo, grad
@@ -55,14 +56,16 @@ def test_long_segments(D, dtype, opt, one_launch):
 @pytest.mark.parametrize("D,dtype,opt", [(32, "f32", "sgd"), (24, "f32", "adagrad"), (256, "f32", "sgd"),
                                          (512, "bf16", "sgd"), (64, "bf16", "adagrad")])
 @pytest.mark.parametrize("budget_rows", [100, 2, 0])
-def test_long_runs_when_the_caller_has_stated_the_lookups_per_table(D, dtype, opt, budget_rows):
+@pytest.mark.parametrize("with_out", [True, False])
+def test_long_runs_when_the_caller_has_stated_the_lookups_per_table(D, dtype, opt, budget_rows, with_out):
     """The same runs under SCARS_TUNE_MAX_TABLE_LOOKUPS: each long run is summed by the workgroup of the chunk it starts
     in (no partial sums, no combining launch), with the long-run rows cached (100), mostly in host memory (2: only
-    the two longest are cached) and all in host memory (0)."""
-    _long_segments_case(D, dtype, opt, True, B=4000, budget_rows=budget_rows, table_limit=4000)
+    the two longest are cached) and all in host memory (0).  Asked for the sorted segments the backward pass lists the
+    runs (k_small_segments) and updates run by run; not asked, it updates by position (k_small_update)."""
+    _long_segments_case(D, dtype, opt, True, B=4000, budget_rows=budget_rows, table_limit=4000, with_out=with_out)
 
 
-def _long_segments_case(D, dtype, opt, one_launch, B, budget_rows, table_limit):
+def _long_segments_case(D, dtype, opt, one_launch, B, budget_rows, table_limit, with_out=True):
     rng = np.random.default_rng(3)
     rows = [50, 1000]
     idx0 = np.where(rng.random(B) < 0.7, 7, rng.integers(0, 50, B))        # 70 % of table 0 hits row 7
@@ -80,19 +83,24 @@ def _long_segments_case(D, dtype, opt, one_launch, B, budget_rows, table_limit):
     if table_limit:
         c.s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, table_limit)
         c.s.profile_enable(True)
-    rm, out, bo, grad = _run_all(c)
+    rm, out, bo, grad = _run_all(c, with_out=with_out)
     assert c.s.sync_status() == 0
     if table_limit:
         prof = c.s.profile_read()
         c.s.profile_enable(False)
-        assert "small_segments" in prof and "seg_rows_long" in prof and "seg_combine" not in prof, prof
+        assert "seg_combine" not in prof, prof
+        if with_out:
+            assert "small_segments" in prof and "seg_rows_long" in prof and "small_update" not in prof, prof
+        else:
+            assert "small_update" in prof and "small_segments" not in prof and "seg_rows_long" not in prof, prof
     wl = c.wl
     rc, want = oracle.embedding_bag_fwd(rows, c.ora_tables, idx, off, B)
     assert_close(out.cpu().numpy(), want, "forward")
     rc, sg, sb, ss, ug = oracle.bwd_segments(wl.rows, idx, off, B)
-    assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
-    assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
-    assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
+    if with_out:
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
+        assert np.array_equal(bo.sorted_bag.cpu().numpy()[: sb.size], sb)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
     o = 1 if opt == "adagrad" else 0
     rc, nr, ns, gr = oracle.embedding_bag_bwd_update(wl.rows, c.ora_tables, c.ora_state, o, idx, off, B, grad.numpy(),
                                                      np.float32(0.01), np.float32(1e-8), report=True, n_unique=ug.size)
@@ -199,7 +207,7 @@ def test_large_counts_use_all_select_passes():
     c.close()
 
 
-@pytest.mark.parametrize("small_sort", [False, True])
+@pytest.mark.parametrize("small_sort", [False, True, "update by position"])
 def test_out_of_range_index_is_latched_and_treated_as_absent(small_sort):
     rows = [40, 30]
     B = 64
@@ -234,14 +242,16 @@ def test_out_of_range_index_is_latched_and_treated_as_absent(small_sort):
     assert rc == oracle.ERR_INDEX_RANGE
     assert_close(out.cpu().numpy(), want, "invalid lookups add nothing")
     grad = torch.ones(2 * B, 4)
-    bo = c.s.new_bwd_out(2 * B)
+    by_position = small_sort == "update by position"    # (not asked for the sorted segments: no list of runs is made)
+    bo = None if by_position else c.s.new_bwd_out(2 * B)
     c.s.embedding_bag_bwd_update(d_idx, d_off, B, rm, grad.to(c.dev), 0.5, 0.0, bo)
     c.s.flush_cache()
     c.s.sync_status()
     rc, sg, sb, ss, ug = oracle.bwd_segments(rows, idx, off, B)
-    assert bo.n_unique.cpu().tolist() == [ug.size, sg.size]
-    assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
-    assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
+    if not by_position:
+        assert bo.n_unique.cpu().tolist() == [ug.size, sg.size]
+        assert np.array_equal(bo.sorted_gid.cpu().numpy()[: sg.size], sg)
+        assert np.array_equal(bo.seg_start.cpu().numpy()[: ss.size], ss)
     oracle.embedding_bag_bwd_update(rows, c.ora_tables, None, 0, idx, off, B, grad.numpy(), np.float32(0.5), np.float32(0))
     assert_close(c.pinned_rows(), np.concatenate(c.ora_tables), "rows after update with invalid lookups")
     c.close()

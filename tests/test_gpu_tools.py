@@ -52,18 +52,27 @@ def test_per_table_sort_replaces_the_radix_passes_when_the_caller_states_the_lim
     s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
     s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
     prof = s.profile_read()
-    # remap wrote the pairs, rows can be cold: the forward pass's fetch carried the sort, the backward pass found it done
-    assert prof["stage_misses+small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1
+    # remap wrote the pairs, rows can be cold: the forward pass's fetch carried the sort, the backward pass found it
+    # done, with each run's length and row at the run's first position, and updated by position: one launch
+    assert prof["stage_misses+small_sort"]["launches"] == 1 and prof["small_update"]["launches"] == 1
     assert "small_sort" not in prof and "stage_misses" not in prof
-    assert prof["seg_rows_long"]["launches"] == 1 and "seg_combine" not in prof   # long runs summed whole, in that launch
+    assert not any(k in prof for k in ("small_segments", "seg_rows_long", "seg_rows", "seg_long", "seg_combine")), prof
     assert not any(k.startswith("sort_") or k in ("seg_count", "seg_scan", "seg_write", "bwd_pairs") for k in prof), prof
     assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 1
     # a backward pass that does not follow its own forward pass sorts for itself
     rm = s.remap(d_idx, d_off, wl.batch)
     s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0)
     prof = s.profile_read()
-    assert prof["small_sort"]["launches"] == 1 and prof["small_segments"]["launches"] == 1 and "bwd_pairs" not in prof
+    assert prof["small_sort"]["launches"] == 1 and prof["small_update"]["launches"] == 1 and "bwd_pairs" not in prof
     assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 1
+    # asked for the sorted segments, it lists the runs and updates run by run (long runs whole, in the same launch)
+    rm = s.remap(d_idx, d_off, wl.batch)
+    s.embedding_bag_fwd(d_idx, d_off, wl.batch, rm)
+    s.embedding_bag_bwd_update(d_idx, d_off, wl.batch, rm, grad, 0.01, 0.0, s.new_bwd_out(int(d_idx.numel())))
+    prof = s.profile_read()
+    assert prof["small_segments"]["launches"] == 1 and prof["seg_rows_long"]["launches"] == 1, prof
+    assert "seg_combine" not in prof and "small_update" not in prof and "small_sort" not in prof, prof
+    assert s.get_counter(binding.COUNTER_SORTED_IN_FWD_USED) == 2
     s.profile_enable(False)
     assert s.sync_status() == 0
     c.close()
