@@ -544,6 +544,7 @@ __device__ __forceinline__ void whole_run_apply(int32_t a, int32_t b, uint32_t g
     __syncthreads();
     if (g == 0 && c < dq) {
         double t[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 2   // (unrolled in full, the loads of all groups' pieces are hoisted: up to 256 registers, for every part of the launch)
         for (int q = 0; q < gpb; ++q) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] += s_sum[(q * LPG + c) * 4 + i];
