@@ -73,7 +73,8 @@ typedef struct {
     float* const* host_state;  /* HOST [T] of PINNED fp32 [rows[t]][D] Adagrad accumulators; NULL for SGD */
 } scars_config;
 
-/* Launch tuning; results never depend on it.  The ordered compactions (hit/miss lists, run starts, sample lists)
+/* Launch tuning; results never depend on it (integer outputs bit for bit; floating-point ones too, except where a
+ * tuning's comment says that the order of an fp64 sum changes).  The ordered compactions (hit/miss lists, run starts, sample lists)
  * count per tile of 2048 items, then need each tile's start: with few tiles the writing kernel adds up the counts
  * of the tiles before its own, beyond the limit a separate scan kernel runs first.  A limit of 0 always scans. */
 #define SCARS_TUNE_FUSED_SCAN_MAX_TILES 1       /* default 4096, which is also the most */
@@ -124,7 +125,11 @@ typedef struct {
  * offsets[t*B] <= n; one index per sample and table with B <= n is the usual case).  For n <= 4096 (and up to 256
  * tables) the backward pass then sorts each table's (row, bag) pairs by itself, one workgroup per table in LDS, and
  * lists the run starts in a second launch: two launches instead of three per radix pass and two more; the results
- * are the same.  When scars_remap has left the batch's pairs for the backward pass (SCARS_TUNE_PAIRS_IN_REMAP) and
+ * are the same.  A scars_embedding_bag_bwd_update that is not asked for its sorted segments (no scars_bwd_out), outside
+ * the look-ahead order, needs no list of runs at all: the sorting workgroup leaves each run's length and row at the
+ * run's first position and the update goes by position, in one launch; runs of more than 64 lookups are then summed
+ * whole by one workgroup each (they cannot be longer than n), in fp64 as always but in another order than the general
+ * path's, so the updated rows of the two can differ in the last bit of a rounding.  When scars_remap has left the batch's pairs for the backward pass (SCARS_TUNE_PAIRS_IN_REMAP) and
  * rows can be cold, scars_embedding_bag_fwd of the same batch carries the sort in the first workgroups of the launch
  * that fetches the missed rows, and scars_embedding_bag_bwd_update finds it done if it is the next call that sorts.
  * A batch that breaks the statement latches SCARS_ERR_OFFSETS (reported by scars_sync_status) and its backward
