@@ -599,22 +599,33 @@ __global__ __launch_bounds__(kBlock) void k_small_update(int long_blocks, int32_
                                                          const int32_t* __restrict__ run_len, const int32_t* __restrict__ run_src,
                                                          const float* __restrict__ grad, UpdateArgs A) {
     if ((int)blockIdx.x < long_blocks) {      // one workgroup per chunk
-        __shared__ int32_t s_j;
-        if (threadIdx.x == 0) s_j = -1;
+        __shared__ int32_t s_run[4];          // position, length, source and row of the long run that starts in the chunk
+        if (threadIdx.x == 0) s_run[0] = -1;
         __syncthreads();
         const int64_t p = (int64_t)blockIdx.x * kLongRun + threadIdx.x;
-        if (threadIdx.x < kLongRun && p < L && run_len[p] > kLongRun) s_j = (int32_t)p;
+        if (threadIdx.x < kLongRun && p < L) {
+            const int32_t len = run_len[p], src = run_src[p];
+            const uint32_t gid = key[p];
+            if (len > kLongRun) {             // (only after an offsets error can more than one lane get here)
+                s_run[1] = len; s_run[2] = src; s_run[3] = (int32_t)gid;
+                s_run[0] = (int32_t)p;
+            }
+        }
         __syncthreads();
-        const int32_t j = s_j;
-        if (j < 0) return;
-        const int32_t len = run_len[j], src = run_src[j];
-        const uint32_t gid = key[j];
-        if (len <= kLongRun || !run_ok(j, len, src, gid, L, A, cap_staged)) return;
-        whole_run_apply<DTYPE, OPT, LPG, kTaskUnroll>(j, j + len, gid, src, val, grad, A);
+        const int32_t j = s_run[0], len = s_run[1], src = s_run[2];
+        const uint32_t gid = (uint32_t)s_run[3];
+        if (j < 0 || len <= kLongRun || !run_ok(j, len, src, gid, L, A, cap_staged)) return;
+        whole_run_apply<DTYPE, OPT, LPG, 8>(j, j + len, gid, src, val, grad, A);
         return;
     }
     __shared__ int32_t s_rbase[SCARS_MAX_TABLES + 1];
     const int T = A.meta->num_tables;
+    const int64_t ngroups = (int64_t)((int)gridDim.x - long_blocks) * (kBlock / LPG);
+    int64_t j = (int64_t)((int)blockIdx.x - long_blocks) * (kBlock / LPG) + threadIdx.x / LPG;
+    // a lane group's first position is read while the table starts are on their way to LDS (most groups have only one)
+    int32_t len = 0, src = -1;
+    uint32_t gid = 0, v = 0;
+    if (j < L) { len = run_len[j]; src = run_src[j]; gid = key[j]; v = val[j]; }
     for (int t = threadIdx.x; t <= T; t += kBlock) s_rbase[t] = A.meta->row_base[t];
     __syncthreads();
     const int c = threadIdx.x % LPG;
@@ -622,11 +633,9 @@ __global__ __launch_bounds__(kBlock) void k_small_update(int long_blocks, int32_
     const bool lane_on = c < dq;
     const int cc = min(c, dq - 1);
     const float4* g4 = (const float4*)grad;
-    const int64_t ngroups = (int64_t)((int)gridDim.x - long_blocks) * (kBlock / LPG);
-    for (int64_t j = (int64_t)((int)blockIdx.x - long_blocks) * (kBlock / LPG) + threadIdx.x / LPG; j < L; j += ngroups) {
-        const int32_t len = run_len[j], src = run_src[j];
-        const uint32_t gid = key[j];
-        const uint32_t bag0 = min(val[j] >> A.shift, A.Gm1);
+    for (bool first = true; j < L; j += ngroups, first = false) {
+        if (!first) { len = run_len[j]; src = run_src[j]; gid = key[j]; v = val[j]; }
+        const uint32_t bag0 = min(v >> A.shift, A.Gm1);
         if (len > kLongRun || !run_ok(j, len, src, gid, L, A, cap_staged)) continue;
         RowRef<DTYPE, OPT> ref;
         ref.locate(A, s_rbase, T, (int32_t)gid, src);
