@@ -190,3 +190,33 @@ def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
     assert r.returncode == 0, r.stderr
     k, cache_bytes, out_bytes = (int(x) for x in r.stdout.split())
     assert k == 100 and cache_bytes >= 100 * 128 and out_bytes >= 512 * 32 * 4
+
+
+def test_update_kernels_keep_their_registers(tmp_path):
+    """The update kernels share a launch between several jobs (rows, long runs, the fetch of the next batch): the
+    widest job sets the registers of all of them.  The compiler's own figures for every instantiation: no spills,
+    and the instantiations that large batches run keep at least five waves per SIMD (a fully unrolled reduction in
+    one job once took that to three, and the bandwidth-bound part of the launch with it)."""
+    import re
+    import subprocess
+    from paper_2411_01611_amd import build
+    src = os.path.join(build.CSRC, "k_bwd.hip")
+    cmd = [build._hipcc(), *build.FLAGS, "--cuda-device-only", "-c", src, "-o", str(tmp_path / "k_bwd.o"),
+           "-Rpass-analysis=kernel-resource-usage"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    seen = 0
+    for block in re.split(r"remark: Function Name: ", r.stderr)[1:]:
+        name = block.split()[0]
+        num = lambda key: int(re.search(key + r": (\d+)", block).group(1))
+        vgprs, waves, scratch = num("VGPRs"), num(r"Occupancy \[waves/SIMD\]"), num(r"ScratchSize \[bytes/lane\]")
+        assert scratch == 0, (name, scratch)
+        m = re.search(r"k_seg_rows_longILi\dELi\dELi\d+ELi(\d+)ELb", name)
+        if m:
+            seen += 1
+            # (4: the instantiation of batches above 131072 lookups; 16: small batches, wide long-run part)
+            assert waves >= (5 if m.group(1) == "4" else 3), (name, vgprs, waves)
+        elif "14k_small_update" in name or "10k_seg_rowsI" in name:
+            seen += 1
+            assert waves >= 5, (name, vgprs, waves)
+    assert seen >= 3 * 32, seen
