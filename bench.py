@@ -575,6 +575,12 @@ def run_leg(b: Bench, K: int, W: int, link: dict, use_graph: bool = False) -> di
     lb = {"fetch": n_staged * wl.row_bytes, "acc": U_cold * state_b, "write": U_cold * (wl.row_bytes + state_b)}
     link_bytes = lambda name: (lb["fetch"], 0) if name == "stage_misses" else (lb["acc"], lb["write"])
     top, gather, host_link = rooflines(wl, prof, K, ms_per_step, model, link, link_bytes, None, b.budget >= wl.total_rows * wl.row_bytes)
+    if prof.get("stage_misses", {}).get("also_carries"):
+        for r in [top] + host_link:
+            if r.get("kernel") == "stage_misses":
+                r["note"] = ("the first workgroups of this launch sort each table's (row, bag) pairs in LDS for the backward pass; "
+                             "for a batch this small the sort, not the fetch, sets the launch's length, so the link figures "
+                             "here are a lower bound on what the fetch reaches")
     pool = gather["kernel"]
     for tag, p in (("forward_alone", prof_fwd), ("forward_cold_caches", prof_cold)):
         t = avg_s(p, pool)
