@@ -68,17 +68,34 @@ def _ora_fwd(c, batch):
 @pytest.mark.parametrize("budget", ["own", "none", "all"])
 @pytest.mark.parametrize("presort", [0, 1, 2])
 def test_lookahead_steps_match_the_calls_made_one_after_the_other(name, budget, presort):
+    _lookahead_case(name, budget, presort, table_limit=False)
+
+
+@pytest.mark.parametrize("name", ["tiny", "dlrm_small", "host_spill_small"])
+@pytest.mark.parametrize("budget", ["own", "all"])
+@pytest.mark.parametrize("presort", [0, 1])
+def test_lookahead_steps_with_the_lookups_per_table_stated(name, budget, presort):
+    """The same with SCARS_TUNE_MAX_TABLE_LOOKUPS (one index per sample and table: the batch size): each table's pairs
+    are sorted by a workgroup of its own, in the forward pass's fetch launch or on the side stream, and the update,
+    which needs the list of the batch's distinct rows for the fetch beside it, goes run by run."""
+    _lookahead_case(name, budget, presort, table_limit=True)
+
+
+def _lookahead_case(name, budget, presort, table_limit):
     # presort 2: as 1, but with the fetch on the library's second stream instead of inside the update's launch
     own_stream = presort == 2
     presort = min(presort, 1)
     wname, kw = CASES[name]
     wl = synth.workload(wname, **kw)
     bb = {"own": None, "none": 0, "all": wl.total_rows * wl.row_bytes}[budget]
-    _say("lookahead", name, budget, "presort", presort, "fetch on its own stream" if own_stream else "fetch inside the update launch")
+    _say("lookahead", name, budget, "presort", presort, "fetch on its own stream" if own_stream else "fetch inside the update launch",
+         "lookups per table stated" if table_limit else "")
     c = GpuCase(wl, budget_bytes=bb, max_L=_room(wl))
     s = c.s
     s.set_tuning(binding.TUNE_LOOKAHEAD, 1)
     s.set_tuning(binding.TUNE_PRESORT, presort)
+    if table_limit:
+        s.set_tuning(binding.TUNE_MAX_TABLE_LOOKUPS, wl.batch)
     if own_stream:
         s.set_tuning(binding.TUNE_FUSED_FETCH, 0)
     c.build()
